@@ -1,0 +1,130 @@
+/*
+ * fasth.h - C ABI of the FastH library for AMD CDNA4 (gfx950).
+ *
+ * FastH (arXiv 2009.13977, Algorithms 1 and 2) computes A = H X and the
+ * gradients of a loss wrt X and the Householder vectors, where
+ * H = H_1 H_2 ... H_n and H_j = I - 2 v_j v_j^T / ||v_j||^2 (Eq. 1). The n
+ * reflections are grouped into n/k blocks P_i of k consecutive reflections
+ * (Eq. 2 with the block size k of Section 3.3 "Trade-off"); every block is
+ * turned into a compact WY form in parallel (Lemma 1, Algorithm 1 Step 1) and
+ * the blocks are then applied one after the other (Algorithm 1 Step 2).
+ *
+ * Conventions shared by every entry point
+ * ---------------------------------------
+ * - All array arguments are DEVICE pointers to dense row-major fp32, at least
+ *   16-byte aligned. Shapes/sizes are plain ints passed by value or in a
+ *   struct that lives in HOST memory.
+ * - V is [n][d]: row j-1 holds v_j. H_1 is the leftmost factor, so v_n is
+ *   applied to X first (Section 2.2 "Multiplication").
+ * - X, A, G, dX, Y are [d][m]: one sample per column (the paper's d x m).
+ * - The caller owns every buffer including the workspace. The library never
+ *   allocates or frees device memory and keeps no pointer after a call
+ *   returns. Outputs are overwritten, not accumulated. Outputs must not alias
+ *   inputs.
+ * - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *   All work is enqueued on it; no entry point synchronises with the host.
+ * - Return value: FASTH_OK (0) or a negative FASTH_E* code. Argument checks
+ *   happen before any GPU call, so they can be exercised on a host without a
+ *   GPU. A zero Householder vector makes Eq. 1 undefined; it is not detected
+ *   and produces Inf/NaN in the outputs.
+ */
+#ifndef FASTH_H
+#define FASTH_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  FASTH_OK = 0,
+  FASTH_EINVAL = -1,       /* null pointer, non-positive size, k does not divide n */
+  FASTH_EWORKSPACE = -2,   /* workspace smaller than *_workspace_bytes() */
+  FASTH_EALIGN = -3,       /* a pointer is not 16-byte aligned */
+  FASTH_EHIP = -4,         /* a HIP runtime call or kernel launch failed */
+  FASTH_EUNSUPPORTED = -5  /* shape outside the supported range (see fasth_shape) */
+};
+
+/* Problem shape. Supported range: 1 <= d <= 16384, 1 <= n, 1 <= m <= 65535,
+ * 1 <= k <= 128 and k divides n (the paper assumes the block size divides
+ * the number of reflections, Section 3.1). n need not equal d. */
+typedef struct fasth_shape {
+  int d;          /* length of each Householder vector = rows of X */
+  int n;          /* number of reflections = rows of V */
+  int m;          /* columns of X (mini-batch size) */
+  int k;          /* reflections per WY block (Section 3.3) */
+  int transpose;  /* 0: A = H X.  1: A = H^T X = H_n ... H_1 X */
+} fasth_shape;
+
+/* Human-readable text for a return code (static storage, never NULL). */
+const char* fasth_strerror(int code);
+
+/* Bytes of device workspace fasth_forward / fasth_backward need for `shape`
+ * (block factors T_i, partial Gram matrices, the saved block inputs A_{i+1}
+ * of Algorithm 1's Remark, the saved gradients dL/dA_i of Algorithm 2 Step 1
+ * and the small per-block coefficient vectors). Returns 0 if the shape is
+ * invalid or unsupported. */
+size_t fasth_workspace_bytes(const fasth_shape* shape);
+
+/* Algorithm 1. A = H X (or H^T X). Step 1 builds, for every block i, the
+ * k x k upper-triangular factor T_i with P_i = I - V_i^T T_i V_i (V_i = the
+ * block's k rows of V); this is the WY form of Lemma 1 with Y = V_i^T and
+ * W = V_i^T T_i / 2. Step 2 applies the blocks sequentially and saves the
+ * input of every block in the workspace for fasth_backward. */
+int fasth_forward(const fasth_shape* shape, const float* V, const float* X, float* A,
+                  void* workspace, size_t workspace_bytes, void* stream);
+
+/* Algorithm 2. Given G = dL/dA [d][m], writes dX = dL/dX [d][m] and
+ * dV [n][d] (row j-1 = dL/dv_j, summed over the m columns, Eq. 5). The
+ * workspace must be exactly as the fasth_forward call with the same shape
+ * and V left it. Step 1 (Eq. 3) is the sequential block chain on G; Step 2 is
+ * evaluated per block as dense matrix products that equal the sum of Eq. 5
+ * over the block's reflections. */
+int fasth_backward(const fasth_shape* shape, const float* V, const float* G,
+                   float* dV, float* dX, void* workspace, size_t workspace_bytes, void* stream);
+
+/* The comparison the paper measures against (Section 2.2, "O(d) sequential
+ * inner products"): the same A, dX and dV computed one reflection at a time
+ * on the GPU. shape->k is ignored. fasth_sequential_backward recomputes the
+ * forward product itself (it needs X, not a forward workspace). */
+size_t fasth_sequential_workspace_bytes(const fasth_shape* shape);
+int fasth_sequential_forward(const fasth_shape* shape, const float* V, const float* X, float* A,
+                             void* stream);
+int fasth_sequential_backward(const fasth_shape* shape, const float* V, const float* X, const float* G,
+                              float* dV, float* dX, void* workspace, size_t workspace_bytes,
+                              void* stream);
+
+/* SVD-reparameterised layer (Section 2.2): W = U diag(sigma) V^T with
+ * U = prod H(u_j) and V = prod H(v_j), each a product of n Householder
+ * reflections of length d given as rows of Uv, Vv [n][d]; sigma is [d].
+ * Table 1, row "Inverse": W^-1 = V diag(1/sigma) U^T. */
+typedef struct fasth_svd_shape {
+  int d, n, m, k;
+} fasth_svd_shape;
+
+size_t svd_layer_workspace_bytes(const fasth_svd_shape* shape);
+
+/* Y = W X = U (sigma * (V^T X)). */
+int svd_layer_apply(const fasth_svd_shape* shape, const float* Uv, const float* sigma,
+                    const float* Vv, const float* X, float* Y,
+                    void* workspace, size_t workspace_bytes, void* stream);
+/* Y = W^-1 X = V ((U^T X) / sigma). sigma must be non-zero. */
+int svd_layer_inverse_apply(const fasth_svd_shape* shape, const float* Uv, const float* sigma,
+                            const float* Vv, const float* X, float* Y,
+                            void* workspace, size_t workspace_bytes, void* stream);
+/* Gradients of L with G = dL/dY, after the matching *_apply call on the same
+ * workspace and arguments: dUv, dVv [n][d], dsigma [d], dX [d][m]. */
+int svd_layer_apply_backward(const fasth_svd_shape* shape, const float* Uv, const float* sigma,
+                             const float* Vv, const float* G,
+                             float* dUv, float* dsigma, float* dVv, float* dX,
+                             void* workspace, size_t workspace_bytes, void* stream);
+int svd_layer_inverse_apply_backward(const fasth_svd_shape* shape, const float* Uv, const float* sigma,
+                                     const float* Vv, const float* G,
+                                     float* dUv, float* dsigma, float* dVv, float* dX,
+                                     void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FASTH_H */

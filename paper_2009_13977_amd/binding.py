@@ -1,0 +1,219 @@
+"""ctypes binding of libfasth.so: the same entry points as include/fasth.h.
+
+Argument marshalling only. torch supplies device memory and the current HIP
+stream; every step of the computation runs in the library's kernels. There is
+no fallback: if the shared library is missing or a call fails, an exception is
+raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+PKG_DIR = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(PKG_DIR, "libfasth.so")
+
+FASTH_OK = 0
+FASTH_EINVAL = -1
+FASTH_EWORKSPACE = -2
+FASTH_EALIGN = -3
+FASTH_EHIP = -4
+FASTH_EUNSUPPORTED = -5
+
+EXPORTED_SYMBOLS = (
+    "fasth_strerror",
+    "fasth_workspace_bytes",
+    "fasth_forward",
+    "fasth_backward",
+    "fasth_sequential_workspace_bytes",
+    "fasth_sequential_forward",
+    "fasth_sequential_backward",
+    "svd_layer_workspace_bytes",
+    "svd_layer_apply",
+    "svd_layer_inverse_apply",
+    "svd_layer_apply_backward",
+    "svd_layer_inverse_apply_backward",
+)
+
+
+class fasth_shape(ctypes.Structure):
+    _fields_ = [("d", ctypes.c_int), ("n", ctypes.c_int), ("m", ctypes.c_int), ("k", ctypes.c_int),
+                ("transpose", ctypes.c_int)]
+
+
+class fasth_svd_shape(ctypes.Structure):
+    _fields_ = [("d", ctypes.c_int), ("n", ctypes.c_int), ("m", ctypes.c_int), ("k", ctypes.c_int)]
+
+
+class FasthError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {strerror(code)} (code {code})")
+
+
+_lib: Optional[ctypes.CDLL] = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Load libfasth.so (built by `python -m paper_2009_13977_amd.build`)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2009_13977_amd.build` "
+            "(there is no CPU fallback)")
+    lib = ctypes.CDLL(LIB_PATH)
+    P, S, I = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
+    shp, sshp = ctypes.POINTER(fasth_shape), ctypes.POINTER(fasth_svd_shape)
+    lib.fasth_strerror.restype = ctypes.c_char_p
+    lib.fasth_strerror.argtypes = [I]
+    lib.fasth_workspace_bytes.restype = S
+    lib.fasth_workspace_bytes.argtypes = [shp]
+    lib.fasth_forward.restype = I
+    lib.fasth_forward.argtypes = [shp, P, P, P, P, S, P]
+    lib.fasth_backward.restype = I
+    lib.fasth_backward.argtypes = [shp, P, P, P, P, P, S, P]
+    lib.fasth_sequential_workspace_bytes.restype = S
+    lib.fasth_sequential_workspace_bytes.argtypes = [shp]
+    lib.fasth_sequential_forward.restype = I
+    lib.fasth_sequential_forward.argtypes = [shp, P, P, P, P]
+    lib.fasth_sequential_backward.restype = I
+    lib.fasth_sequential_backward.argtypes = [shp, P, P, P, P, P, P, S, P]
+    lib.svd_layer_workspace_bytes.restype = S
+    lib.svd_layer_workspace_bytes.argtypes = [sshp]
+    for name in ("svd_layer_apply", "svd_layer_inverse_apply"):
+        fn = getattr(lib, name)
+        fn.restype = I
+        fn.argtypes = [sshp, P, P, P, P, P, P, S, P]
+    for name in ("svd_layer_apply_backward", "svd_layer_inverse_apply_backward"):
+        fn = getattr(lib, name)
+        fn.restype = I
+        fn.argtypes = [sshp, P, P, P, P, P, P, P, P, P, S, P]
+    _lib = lib
+    return lib
+
+
+def strerror(code: int) -> str:
+    return load_library().fasth_strerror(int(code)).decode()
+
+
+def _check(code: int, where: str) -> None:
+    if code != FASTH_OK:
+        raise FasthError(code, where)
+
+
+def _ptr(t, name: str) -> int:
+    import torch
+    if not isinstance(t, torch.Tensor):
+        raise TypeError(f"{name}: expected a torch.Tensor")
+    if not t.is_cuda:
+        raise ValueError(f"{name}: must live in GPU memory")
+    if t.dtype != torch.float32 and name != "workspace":
+        raise ValueError(f"{name}: must be float32")
+    if not t.is_contiguous():
+        raise ValueError(f"{name}: must be contiguous")
+    return t.data_ptr()
+
+
+def _stream() -> int:
+    import torch
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _shape(d, n, m, k, transpose=False) -> fasth_shape:
+    return fasth_shape(int(d), int(n), int(m), int(k), 1 if transpose else 0)
+
+
+def fasth_workspace_bytes(d: int, n: int, m: int, k: int) -> int:
+    return int(load_library().fasth_workspace_bytes(ctypes.byref(_shape(d, n, m, k))))
+
+
+def fasth_sequential_workspace_bytes(d: int, n: int, m: int) -> int:
+    return int(load_library().fasth_sequential_workspace_bytes(ctypes.byref(_shape(d, n, m, 1))))
+
+
+def svd_layer_workspace_bytes(d: int, n: int, m: int, k: int) -> int:
+    return int(load_library().svd_layer_workspace_bytes(ctypes.byref(fasth_svd_shape(int(d), int(n), int(m), int(k)))))
+
+
+def new_workspace(nbytes: int, device="cuda"):
+    import torch
+    return torch.empty(max(int(nbytes), 16), dtype=torch.uint8, device=device)
+
+
+def fasth_forward(V, X, A, workspace, k: int, transpose: bool = False) -> None:
+    n, d = V.shape
+    m = X.shape[1]
+    assert X.shape == (d, m) and A.shape == (d, m)
+    shape = _shape(d, n, m, k, transpose)
+    rc = load_library().fasth_forward(ctypes.byref(shape), _ptr(V, "V"), _ptr(X, "X"), _ptr(A, "A"),
+                                      _ptr(workspace, "workspace"), workspace.numel(), _stream())
+    _check(rc, "fasth_forward")
+
+
+def fasth_backward(V, G, dV, dX, workspace, k: int, transpose: bool = False) -> None:
+    n, d = V.shape
+    m = G.shape[1]
+    assert G.shape == (d, m) and dX.shape == (d, m) and dV.shape == (n, d)
+    shape = _shape(d, n, m, k, transpose)
+    rc = load_library().fasth_backward(ctypes.byref(shape), _ptr(V, "V"), _ptr(G, "G"), _ptr(dV, "dV"),
+                                       _ptr(dX, "dX"), _ptr(workspace, "workspace"), workspace.numel(), _stream())
+    _check(rc, "fasth_backward")
+
+
+def fasth_sequential_forward(V, X, A, transpose: bool = False) -> None:
+    n, d = V.shape
+    m = X.shape[1]
+    shape = _shape(d, n, m, 1, transpose)
+    rc = load_library().fasth_sequential_forward(ctypes.byref(shape), _ptr(V, "V"), _ptr(X, "X"), _ptr(A, "A"),
+                                                 _stream())
+    _check(rc, "fasth_sequential_forward")
+
+
+def fasth_sequential_backward(V, X, G, dV, dX, workspace, transpose: bool = False) -> None:
+    n, d = V.shape
+    m = X.shape[1]
+    shape = _shape(d, n, m, 1, transpose)
+    rc = load_library().fasth_sequential_backward(ctypes.byref(shape), _ptr(V, "V"), _ptr(X, "X"), _ptr(G, "G"),
+                                                  _ptr(dV, "dV"), _ptr(dX, "dX"), _ptr(workspace, "workspace"),
+                                                  workspace.numel(), _stream())
+    _check(rc, "fasth_sequential_backward")
+
+
+def _svd_forward(name, Uv, sigma, Vv, X, Y, workspace, k):
+    n, d = Uv.shape
+    m = X.shape[1]
+    assert Vv.shape == (n, d) and sigma.shape == (d,) and X.shape == (d, m) and Y.shape == (d, m)
+    shape = fasth_svd_shape(d, n, m, int(k))
+    rc = getattr(load_library(), name)(ctypes.byref(shape), _ptr(Uv, "Uv"), _ptr(sigma, "sigma"), _ptr(Vv, "Vv"),
+                                       _ptr(X, "X"), _ptr(Y, "Y"), _ptr(workspace, "workspace"), workspace.numel(),
+                                       _stream())
+    _check(rc, name)
+
+
+def _svd_backward(name, Uv, sigma, Vv, G, dUv, dsigma, dVv, dX, workspace, k):
+    n, d = Uv.shape
+    m = G.shape[1]
+    shape = fasth_svd_shape(d, n, m, int(k))
+    rc = getattr(load_library(), name)(ctypes.byref(shape), _ptr(Uv, "Uv"), _ptr(sigma, "sigma"), _ptr(Vv, "Vv"),
+                                       _ptr(G, "G"), _ptr(dUv, "dUv"), _ptr(dsigma, "dsigma"), _ptr(dVv, "dVv"),
+                                       _ptr(dX, "dX"), _ptr(workspace, "workspace"), workspace.numel(), _stream())
+    _check(rc, name)
+
+
+def svd_layer_apply(Uv, sigma, Vv, X, Y, workspace, k: int) -> None:
+    _svd_forward("svd_layer_apply", Uv, sigma, Vv, X, Y, workspace, k)
+
+
+def svd_layer_inverse_apply(Uv, sigma, Vv, X, Y, workspace, k: int) -> None:
+    _svd_forward("svd_layer_inverse_apply", Uv, sigma, Vv, X, Y, workspace, k)
+
+
+def svd_layer_apply_backward(Uv, sigma, Vv, G, dUv, dsigma, dVv, dX, workspace, k: int) -> None:
+    _svd_backward("svd_layer_apply_backward", Uv, sigma, Vv, G, dUv, dsigma, dVv, dX, workspace, k)
+
+
+def svd_layer_inverse_apply_backward(Uv, sigma, Vv, G, dUv, dsigma, dVv, dX, workspace, k: int) -> None:
+    _svd_backward("svd_layer_inverse_apply_backward", Uv, sigma, Vv, G, dUv, dsigma, dVv, dX, workspace, k)

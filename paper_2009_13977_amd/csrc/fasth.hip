@@ -1,0 +1,951 @@
+// FastH for CDNA4 (gfx950): kernels and the C ABI declared in include/fasth.h.
+//
+// Notation follows the paper (arXiv 2009.13977): d = vector length, n = number of reflections,
+// m = mini-batch columns, k = block size (Section 3.3), nb = n / k blocks P_i (Eq. 2).
+//
+// Block form used here. For the k rows V_i of one block, with S = V_i V_i^T,
+//   P_i = H_{(i-1)k+1} ... H_{ik} = I - V_i^T T_i V_i,   T_i = (diag(S)/2 + striu(S))^-1.
+// This is the WY form of Lemma 1 (Y = V_i^T, W = V_i^T T_i / 2) kept as the k x k factor T_i, so
+// Step 1 of Algorithm 1 is one Gram product per block (matrix cores) plus a k x k triangular
+// inverse, and P_i^T = I - V_i^T T_i^T V_i needs no second factor.
+//
+// Kernels
+//   gram_partial_kernel  Algorithm 1 Step 1a: partial Gram matrices of every block (MFMA)
+//   t_build_kernel       Algorithm 1 Step 1b: T_i by blocked triangular inversion (MFMA)
+//   chain_kernel         Algorithm 1 Step 2 / Algorithm 2 Step 1: the sequential block chain,
+//                        one workgroup per column of X (columns are independent)
+//   dv_kernel            Algorithm 2 Step 2 as dense products per block (MFMA)
+//   seq_*                the one-reflection-at-a-time comparison
+//   dsigma_kernel        the diagonal step of the SVD layer
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <cstdio>
+
+#include "fasth.h"
+#include "fasth_device.h"
+
+namespace fasth {
+
+// ------------------------------------------------------------------------------------------
+// Host-side shape bookkeeping
+// ------------------------------------------------------------------------------------------
+
+constexpr int kMaxBlock = 128;     // largest k: a k x k factor must fit in LDS with scratch
+constexpr int kMaxD = 16384;       // chain kernel: 1024 threads x 16 elements
+constexpr int kGramChunk = 128;    // columns of V per LDS tile in the Gram kernel
+constexpr int kMaxGramSplit = 16;  // partial Gram matrices per block
+constexpr int kDvTile = 64;        // columns of dV per workgroup
+constexpr int kDvMChunk = 32;      // mini-batch columns per LDS tile in the dV kernel
+
+static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+static int padded_block(int k) {
+  int kp = 16;
+  while (kp < k) kp *= 2;
+  return kp;
+}
+
+struct Layout {
+  int kp, nb, gram_split;
+  size_t off_T, off_Spart, off_saveA, off_saveCa, off_saveG, off_saveCg, total;
+};
+
+static Layout make_layout(int d, int n, int m, int k) {
+  Layout L;
+  L.kp = padded_block(k);
+  L.nb = n / k;
+  int split = (d + kGramChunk - 1) / kGramChunk;
+  L.gram_split = split > kMaxGramSplit ? kMaxGramSplit : split;
+  size_t off = 256;  // header, reserved
+  auto take = [&](size_t floats) {
+    size_t o = off;
+    off = align_up(off + floats * sizeof(float), 256);
+    return o;
+  };
+  L.off_T = take((size_t)L.nb * L.kp * L.kp);
+  L.off_Spart = take((size_t)L.nb * L.gram_split * L.kp * L.kp);
+  L.off_saveA = take((size_t)L.nb * m * d);
+  L.off_saveCa = take((size_t)m * n);
+  L.off_saveG = take((size_t)L.nb * m * d);
+  L.off_saveCg = take((size_t)m * n);
+  L.total = off;
+  return L;
+}
+
+static int check_shape(const fasth_shape* s) {
+  if (!s) return FASTH_EINVAL;
+  if (s->d < 1 || s->n < 1 || s->m < 1 || s->k < 1) return FASTH_EINVAL;
+  if (s->n % s->k != 0) return FASTH_EINVAL;
+  if (s->transpose != 0 && s->transpose != 1) return FASTH_EINVAL;
+  if (s->k > kMaxBlock || s->d > kMaxD || s->m > 65535) return FASTH_EUNSUPPORTED;
+  return FASTH_OK;
+}
+
+static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+#define FASTH_HIP(call)                      \
+  do {                                       \
+    hipError_t e_ = (call);                  \
+    if (e_ != hipSuccess) return FASTH_EHIP; \
+  } while (0)
+
+template <typename K>
+static int allow_lds(K kernel, size_t bytes) {
+  if (bytes > 64 * 1024) {
+    FASTH_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes));
+  }
+  return FASTH_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// Algorithm 1 Step 1a: partial Gram matrices S_i = V_i V_i^T, split over d.
+// grid (gram_split, nb), 256 threads. Only the 16x16 tiles on or above the diagonal are formed.
+// ------------------------------------------------------------------------------------------
+
+__global__ void __launch_bounds__(256) gram_partial_kernel(const float* __restrict__ V, float* __restrict__ Spart,
+                                                           int d, int k, int kp, int gram_split) {
+  extern __shared__ float smem[];
+  const int LD = kGramChunk + 4;
+  float* Vs = smem;  // [kp][LD]
+  const int i = blockIdx.y, s = blockIdx.x;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int chunk = ((d + gram_split - 1) / gram_split + 3) & ~3;
+  const int xbeg = s * chunk;
+  const int xend = min(d, xbeg + chunk);
+  const int kt = kp / 16;
+  const int ntiles = kt * (kt + 1) / 2;
+  constexpr int kMaxTilesPerWave = 9;  // kp = 128: 36 upper tiles over 4 waves
+  f32x4 acc[kMaxTilesPerWave];
+#pragma unroll
+  for (int w = 0; w < kMaxTilesPerWave; ++w) acc[w] = f32x4{0.f, 0.f, 0.f, 0.f};
+  const float* Vi = V + (size_t)i * k * d;
+  for (int x0 = xbeg; x0 < xend; x0 += kGramChunk) {
+    for (int idx = tid; idx < kp * kGramChunk; idx += 256) {
+      const int j = idx / kGramChunk, x = idx % kGramChunk;
+      float v = 0.f;
+      if (j < k && x0 + x < xend) v = Vi[(size_t)j * d + x0 + x];
+      Vs[j * LD + x] = v;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int w = 0; w < kMaxTilesPerWave; ++w) {
+      const int t = wave + 4 * w;
+      if (t < ntiles) {
+        int ti = 0, rem = t;
+        while (rem >= kt - ti) { rem -= kt - ti; ++ti; }
+        const int tj = ti + rem;
+        acc[w] = tile_mma(Vs + ti * 16 * LD, LD, 1, Vs + tj * 16 * LD, 1, LD, kGramChunk, acc[w]);
+      }
+    }
+    __syncthreads();
+  }
+  float* out = Spart + ((size_t)i * gram_split + s) * kp * kp;
+  const int li = lane & 15, q = lane >> 4;
+#pragma unroll
+  for (int w = 0; w < kMaxTilesPerWave; ++w) {
+    const int t = wave + 4 * w;
+    if (t < ntiles) {
+      int ti = 0, rem = t;
+      while (rem >= kt - ti) { rem -= kt - ti; ++ti; }
+      const int tj = ti + rem;
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) out[(ti * 16 + 4 * q + jj) * kp + tj * 16 + li] = acc[w][jj];
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Algorithm 1 Step 1b: T_i = (diag(S)/2 + striu(S))^-1, one workgroup per block.
+// 16x16 diagonal blocks by back substitution, then [[T11, -T11 M12 T22], [0, T22]] doubling the
+// block size each level with matrix-core products. Rows/columns >= k (padding) form an identity.
+// ------------------------------------------------------------------------------------------
+
+__global__ void __launch_bounds__(256) t_build_kernel(const float* __restrict__ Spart, float* __restrict__ T,
+                                                      int k, int kp, int gram_split) {
+  extern __shared__ float smem[];
+  const int LDM = kp + 4;
+  float* Ms = smem;                 // [kp][LDM]
+  float* Xs = Ms + kp * LDM;        // level scratch, kp * (kp/2 + 4) / 2 floats at most
+  float* Ds = Xs + kp * (kp / 2 + 4) / 2 + 64;  // [kp/16][16][17] copies of the diagonal blocks
+  const int i = blockIdx.x;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const float* Sp = Spart + (size_t)i * gram_split * kp * kp;
+  for (int idx = tid; idx < kp * kp; idx += 256) {
+    const int j = idx / kp, l = idx % kp;
+    float v = 0.f;
+    if (j < k && l < k && j <= l) {
+      for (int s = 0; s < gram_split; ++s) v += Sp[(size_t)s * kp * kp + idx];
+      if (j == l) v *= 0.5f;
+    } else if (j == l) {
+      v = 1.f;
+    }
+    Ms[j * LDM + l] = v;
+  }
+  __syncthreads();
+  if (tid < kp) {
+    const int blk = tid >> 4, c = tid & 15, base = blk * 16;
+    float* D = Ds + blk * 16 * 17;
+    for (int r = 0; r < 16; ++r) D[r * 17 + c] = Ms[(base + r) * LDM + base + c];
+  }
+  __syncthreads();
+  if (tid < kp) {
+    const int blk = tid >> 4, c = tid & 15, base = blk * 16;
+    const float* D = Ds + blk * 16 * 17;
+    float* col = Ms + base * LDM + base + c;  // col[r * LDM] = T(r, c) of this diagonal block
+    col[c * LDM] = 1.f / D[c * 17 + c];
+    for (int r = c - 1; r >= 0; --r) {
+      float s = 0.f;
+      for (int l = r + 1; l <= c; ++l) s += D[r * 17 + l] * col[l * LDM];
+      col[r * LDM] = -s / D[r * 17 + r];
+    }
+  }
+  __syncthreads();
+  const int li = lane & 15, q = lane >> 4;
+  for (int b = 16; b < kp; b *= 2) {
+    const int tpb = b / 16, per_pair = tpb * tpb, items = (kp / (2 * b)) * per_pair;
+    const int LDX = b + 4;
+    for (int it = wave; it < items; it += 4) {  // X = M12 T22
+      const int pr = it / per_pair, ti = (it % per_pair) / tpb, tj = it % tpb, r0 = pr * 2 * b;
+      f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+      acc = tile_mma(Ms + (r0 + 16 * ti) * LDM + r0 + b, LDM, 1, Ms + (r0 + b) * LDM + r0 + b + 16 * tj, LDM, 1, b, acc);
+      float* X = Xs + pr * b * LDX;
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) X[(16 * ti + 4 * q + jj) * LDX + 16 * tj + li] = acc[jj];
+    }
+    __syncthreads();
+    for (int it = wave; it < items; it += 4) {  // T12 = -T11 X
+      const int pr = it / per_pair, ti = (it % per_pair) / tpb, tj = it % tpb, r0 = pr * 2 * b;
+      f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+      acc = tile_mma(Ms + (r0 + 16 * ti) * LDM + r0, LDM, 1, Xs + pr * b * LDX + 16 * tj, LDX, 1, b, acc);
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) Ms[(r0 + 16 * ti + 4 * q + jj) * LDM + r0 + b + 16 * tj + li] = -acc[jj];
+    }
+    __syncthreads();
+  }
+  float* Ti = T + (size_t)i * kp * kp;
+  for (int idx = tid; idx < kp * kp; idx += 256) Ti[idx] = Ms[(idx / kp) * LDM + idx % kp];
+}
+
+static size_t t_build_lds(int kp) {
+  return sizeof(float) * ((size_t)kp * (kp + 4) + (size_t)kp * (kp / 2 + 4) / 2 + 64 + (size_t)(kp / 16) * 16 * 17);
+}
+
+// ------------------------------------------------------------------------------------------
+// The sequential block chain (Algorithm 1 Step 2; Algorithm 2 Step 1, Eq. 3).
+// One workgroup per column of the d x m input: columns never interact, so no workgroup waits for
+// another. Per block i:  B = V_i a,  C = op(T_i) B,  a <- a - V_i^T C,
+// op(T) = T for P_i (blocks nb..1), T^T for P_i^T (blocks 1..nb).
+// Thread t owns elements x = t + u * blockDim.x of the column. The k inner products of a block are
+// independent, which is the parallelism FastH adds over the one-at-a-time algorithm.
+// Saved for the backward pass: the input column of every block and the coefficient vector C.
+// ------------------------------------------------------------------------------------------
+
+struct ChainArgs {
+  const float* V;         // [n][d]
+  const float* T;         // [nb][kp][kp]
+  const float* in;        // [d][m]
+  float* out;             // [d][m]
+  float* save_in;         // [nb][m][d] or null
+  float* save_c;          // [m][n] or null
+  const float* in_scale;  // [d] or null: the input row x is multiplied (mode 1) or divided (mode 2)
+  int in_scale_mode;
+  int d, n, m, k, kp, nb;
+  int transpose;
+};
+
+template <int U>
+__global__ void __launch_bounds__(1024) chain_kernel(ChainArgs p) {
+  extern __shared__ float smem[];
+  const int nthreads = blockDim.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nw = nthreads >> 6;
+  const int col = blockIdx.x;
+  const int d = p.d, k = p.k, kp = p.kp, m = p.m;
+  const int LDT = kp + 1;
+  float* Ts = smem;               // [kp][LDT]
+  float* Bpart = Ts + kp * LDT;   // [nw][kp]
+  float* Bv = Bpart + nw * kp;    // [kp]
+  float* Cv = Bv + kp;            // [kp]
+  float a[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const int x = tid + u * nthreads;
+    float v = 0.f;
+    if (x < d) {
+      v = p.in[(size_t)x * m + col];
+      if (p.in_scale_mode == 1) v *= p.in_scale[x];
+      else if (p.in_scale_mode == 2) v /= p.in_scale[x];
+    }
+    a[u] = v;
+  }
+  const int sel = reduce_sel<8>(lane);
+  for (int s = 0; s < p.nb; ++s) {
+    const int i = p.transpose ? s : p.nb - 1 - s;
+    const float* Vi = p.V + (size_t)i * k * d;
+    const float* Ti = p.T + (size_t)i * kp * kp;
+    for (int idx = tid; idx < kp * kp; idx += nthreads) Ts[(idx / kp) * LDT + idx % kp] = Ti[idx];
+    if (p.save_in) {
+      float* dst = p.save_in + ((size_t)i * m + col) * d;
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int x = tid + u * nthreads;
+        if (x < d) dst[x] = a[u];
+      }
+    }
+    for (int j0 = 0; j0 < k; j0 += 8) {
+      float pj[8];
+#pragma unroll
+      for (int jj = 0; jj < 8; ++jj) {
+        pj[jj] = 0.f;
+        if (j0 + jj < k) {
+          const float* vr = Vi + (size_t)(j0 + jj) * d;
+#pragma unroll
+          for (int u = 0; u < U; ++u) {
+            const int x = tid + u * nthreads;
+            if (x < d) pj[jj] += vr[x] * a[u];
+          }
+        }
+      }
+      wave_reduce_multi<8>(pj);
+      if ((lane & reduce_writer_mask<8>()) == 0) Bpart[wave * kp + j0 + sel] = pj[0];
+    }
+    __syncthreads();
+    if (tid < kp) {
+      float b = 0.f;
+      if (tid < k)
+        for (int w = 0; w < nw; ++w) b += Bpart[w * kp + tid];
+      Bv[tid] = b;
+    }
+    __syncthreads();
+    if (tid < kp) {
+      float c = 0.f;
+      if (p.transpose) {
+        for (int l = 0; l < kp; ++l) c += Ts[l * LDT + tid] * Bv[l];
+      } else {
+        for (int l = 0; l < kp; ++l) c += Ts[tid * LDT + l] * Bv[l];
+      }
+      Cv[tid] = c;
+      if (p.save_c && tid < k) p.save_c[(size_t)col * p.n + i * k + tid] = c;
+    }
+    __syncthreads();
+    for (int j = 0; j < k; ++j) {
+      const float c = Cv[j];
+      const float* vr = Vi + (size_t)j * d;
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int x = tid + u * nthreads;
+        if (x < d) a[u] -= c * vr[x];
+      }
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const int x = tid + u * nthreads;
+    if (x < d) p.out[(size_t)x * m + col] = a[u];
+  }
+}
+
+static int launch_chain(const ChainArgs& a, hipStream_t stream) {
+  const int d = a.d;
+  int threads = 256;
+  if (d > 256 * 8) threads = 512;
+  if (d > 512 * 8) threads = 1024;
+  const int per = (d + threads - 1) / threads;
+  const int nw = threads / 64;
+  const size_t lds = sizeof(float) * ((size_t)a.kp * (a.kp + 1) + (size_t)nw * a.kp + 2 * a.kp);
+  dim3 grid(a.m), block(threads);
+#define FASTH_LAUNCH_CHAIN(UU)                                                   \
+  do {                                                                           \
+    int rc_ = allow_lds(chain_kernel<UU>, lds);                                  \
+    if (rc_ != FASTH_OK) return rc_;                                             \
+    hipLaunchKernelGGL(chain_kernel<UU>, grid, block, lds, stream, a);           \
+  } while (0)
+  if (per <= 1) FASTH_LAUNCH_CHAIN(1);
+  else if (per <= 2) FASTH_LAUNCH_CHAIN(2);
+  else if (per <= 4) FASTH_LAUNCH_CHAIN(4);
+  else if (per <= 8) FASTH_LAUNCH_CHAIN(8);
+  else FASTH_LAUNCH_CHAIN(16);
+#undef FASTH_LAUNCH_CHAIN
+  FASTH_HIP(hipGetLastError());
+  return FASTH_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// Algorithm 2 Step 2, per block, as dense products (equal to summing Eq. 5 over the block's
+// reflections and the mini-batch). With a = input of block i (saved by the activation chain),
+// g = dL/d(output of block i) (saved by the gradient chain), Ca and Cg the two chains'
+// coefficient matrices (k x m):
+//   Z = Cg Ca^T (k x k);  E = sym(striu(Z)) + diag(Z)   for A = H X
+//                         E = sym(stril(Z)) + diag(Z)   for A = H^T X
+//   dV_i = -(Ca g^T + Cg a^T) + E V_i
+// grid (ceil(d / 64), nb), 256 threads; every workgroup rebuilds the small matrix E.
+// ------------------------------------------------------------------------------------------
+
+struct DvArgs {
+  const float* V;       // [n][d]
+  const float* saveA;   // [nb][m][d]
+  const float* saveCa;  // [m][n]
+  const float* saveG;   // [nb][m][d]
+  const float* saveCg;  // [m][n]
+  float* dV;            // [n][d]
+  int d, n, m, k, kp;
+  int transpose;        // of the forward product
+};
+
+__global__ void __launch_bounds__(256) dv_kernel(DvArgs p) {
+  extern __shared__ float smem[];
+  const int kp = p.kp, k = p.k, d = p.d, m = p.m, n = p.n;
+  const int LDE = kp + 4, LDC = kDvMChunk + 4, LDX = kDvTile + 4;
+  float* Es = smem;                   // [kp][LDE]
+  float* Cas = Es + kp * LDE;         // [kp][LDC]
+  float* Cgs = Cas + kp * LDC;        // [kp][LDC]
+  float* gT = Cgs + kp * LDC;         // [kDvMChunk][LDX]
+  float* aT = gT + kDvMChunk * LDX;   // [kDvMChunk][LDX]
+  float* Vs = Cas;                    // [kp][LDX], reuses Cas/Cgs after the mini-batch loop
+  const int i = blockIdx.y, x0 = blockIdx.x * kDvTile;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, li = lane & 15, q = lane >> 4;
+  const int kt = kp / 16;
+
+  auto load_coeffs = [&](int mc) {
+    for (int idx = tid; idx < kp * kDvMChunk; idx += 256) {
+      const int j = idx % kp, lc = idx / kp;
+      float ca = 0.f, cg = 0.f;
+      if (j < k && mc + lc < m) {
+        const size_t o = (size_t)(mc + lc) * n + (size_t)i * k + j;
+        ca = p.saveCa[o];
+        cg = p.saveCg[o];
+      }
+      Cas[j * LDC + lc] = ca;
+      Cgs[j * LDC + lc] = cg;
+    }
+  };
+
+  // Z = Cg Ca^T, accumulated over the mini-batch in chunks.
+  constexpr int kMaxZ = 16;  // kp = 128: 64 tiles over 4 waves
+  f32x4 z[kMaxZ];
+#pragma unroll
+  for (int w = 0; w < kMaxZ; ++w) z[w] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int mc = 0; mc < m; mc += kDvMChunk) {
+    load_coeffs(mc);
+    __syncthreads();
+#pragma unroll
+    for (int w = 0; w < kMaxZ; ++w) {
+      const int t = wave + 4 * w;
+      if (t < kt * kt) {
+        const int ti = t / kt, tj = t % kt;
+        z[w] = tile_mma(Cgs + ti * 16 * LDC, LDC, 1, Cas + tj * 16 * LDC, 1, LDC, kDvMChunk, z[w]);
+      }
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int w = 0; w < kMaxZ; ++w) {
+    const int t = wave + 4 * w;
+    if (t < kt * kt) {
+      const int ti = t / kt, tj = t % kt;
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) Es[(ti * 16 + 4 * q + jj) * LDE + tj * 16 + li] = z[w][jj];
+    }
+  }
+  __syncthreads();
+  // Mirror the triangle that carries the gradient of T_i^-1 and store -E.
+  for (int idx = tid; idx < kp * kp; idx += 256) {
+    const int r = idx / kp, c = idx % kp;
+    if (r < c) {
+      if (p.transpose) Es[r * LDE + c] = Es[c * LDE + r];
+      else Es[c * LDE + r] = Es[r * LDE + c];
+    }
+  }
+  __syncthreads();
+  for (int idx = tid; idx < kp * kp; idx += 256) Es[(idx / kp) * LDE + idx % kp] *= -1.f;
+
+  // acc = Ca g^T + Cg a^T - E V_i over this workgroup's 64 columns of dV.
+  constexpr int kMaxAcc = 8;  // kp = 128: 8 x 4 tiles over 4 waves
+  f32x4 acc[kMaxAcc];
+#pragma unroll
+  for (int w = 0; w < kMaxAcc; ++w) acc[w] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int mc = 0; mc < m; mc += kDvMChunk) {
+    __syncthreads();
+    load_coeffs(mc);
+    for (int idx = tid; idx < kDvMChunk * kDvTile; idx += 256) {
+      const int lc = idx / kDvTile, x = idx % kDvTile;
+      float g = 0.f, a = 0.f;
+      if (mc + lc < m && x0 + x < d) {
+        const size_t o = ((size_t)i * m + mc + lc) * d + x0 + x;
+        g = p.saveG[o];
+        a = p.saveA[o];
+      }
+      gT[lc * LDX + x] = g;
+      aT[lc * LDX + x] = a;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int w = 0; w < kMaxAcc; ++w) {
+      const int t = wave + 4 * w;
+      if (t < kt * 4) {
+        const int ti = t / 4, tx = t % 4;
+        acc[w] = tile_mma(Cas + ti * 16 * LDC, LDC, 1, gT + tx * 16, LDX, 1, kDvMChunk, acc[w]);
+        acc[w] = tile_mma(Cgs + ti * 16 * LDC, LDC, 1, aT + tx * 16, LDX, 1, kDvMChunk, acc[w]);
+      }
+    }
+  }
+  __syncthreads();
+  for (int idx = tid; idx < kp * kDvTile; idx += 256) {
+    const int j = idx / kDvTile, x = idx % kDvTile;
+    float v = 0.f;
+    if (j < k && x0 + x < d) v = p.V[((size_t)i * k + j) * d + x0 + x];
+    Vs[j * LDX + x] = v;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int w = 0; w < kMaxAcc; ++w) {
+    const int t = wave + 4 * w;
+    if (t < kt * 4) {
+      const int ti = t / 4, tx = t % 4;
+      acc[w] = tile_mma(Es + ti * 16 * LDE, LDE, 1, Vs + tx * 16, LDX, 1, kp, acc[w]);
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) {
+        const int j = ti * 16 + 4 * q + jj, x = x0 + tx * 16 + li;
+        if (j < k && x < d) p.dV[((size_t)i * k + j) * d + x] = -acc[w][jj];
+      }
+    }
+  }
+}
+
+static size_t dv_lds(int kp) {
+  return sizeof(float) * ((size_t)kp * (kp + 4) + 2 * (size_t)kp * (kDvMChunk + 4) + 2 * (size_t)kDvMChunk * (kDvTile + 4));
+}
+
+// ------------------------------------------------------------------------------------------
+// One reflection at a time (Section 2.2): the comparison FastH is measured against.
+// One workgroup per column; every reflection costs a workgroup-wide reduction and a barrier.
+// ------------------------------------------------------------------------------------------
+
+template <int U>
+__global__ void __launch_bounds__(1024) seq_forward_kernel(const float* __restrict__ V, const float* __restrict__ X,
+                                                           float* __restrict__ A, int d, int n, int m, int transpose) {
+  __shared__ float part[2][16][2];
+  const int nthreads = blockDim.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nw = nthreads >> 6;
+  const int col = blockIdx.x;
+  float a[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const int x = tid + u * nthreads;
+    a[u] = x < d ? X[(size_t)x * m + col] : 0.f;
+  }
+  for (int s = 0; s < n; ++s) {
+    const int j = transpose ? s : n - 1 - s;
+    const float* vr = V + (size_t)j * d;
+    float v[U];
+    float r[2] = {0.f, 0.f};
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int x = tid + u * nthreads;
+      v[u] = x < d ? vr[x] : 0.f;
+      r[0] += v[u] * a[u];
+      r[1] += v[u] * v[u];
+    }
+    wave_reduce_multi<2>(r);
+    const int sel = reduce_sel<2>(lane);
+    if ((lane & reduce_writer_mask<2>()) == 0) part[s & 1][wave][sel] = r[0];
+    __syncthreads();
+    float va = 0.f, vv = 0.f;
+    for (int w = 0; w < nw; ++w) {
+      va += part[s & 1][w][0];
+      vv += part[s & 1][w][1];
+    }
+    const float c = 2.f * va / vv;
+#pragma unroll
+    for (int u = 0; u < U; ++u) a[u] -= c * v[u];
+  }
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const int x = tid + u * nthreads;
+    if (x < d) A[(size_t)x * m + col] = a[u];
+  }
+}
+
+// Walks the reflections from the output side (Section 3.2 with blocks of one reflection): recovers the
+// input of H_j from its output (Eq. 4), emits this column's term of Eq. 5 into dVpart[col][j][:], and
+// moves the gradient through H_j.
+template <int U>
+__global__ void __launch_bounds__(1024) seq_backward_kernel(const float* __restrict__ V, const float* __restrict__ A,
+                                                            const float* __restrict__ G, float* __restrict__ dVpart,
+                                                            float* __restrict__ dX, int d, int n, int m, int transpose) {
+  __shared__ float part[2][16][4];
+  const int nthreads = blockDim.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nw = nthreads >> 6;
+  const int col = blockIdx.x;
+  float a[U], g[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const int x = tid + u * nthreads;
+    a[u] = x < d ? A[(size_t)x * m + col] : 0.f;
+    g[u] = x < d ? G[(size_t)x * m + col] : 0.f;
+  }
+  for (int s = 0; s < n; ++s) {
+    const int j = transpose ? n - 1 - s : s;
+    const float* vr = V + (size_t)j * d;
+    float v[U];
+    float r[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int x = tid + u * nthreads;
+      v[u] = x < d ? vr[x] : 0.f;
+      r[0] += v[u] * a[u];
+      r[1] += v[u] * g[u];
+      r[2] += v[u] * v[u];
+    }
+    wave_reduce_multi<4>(r);
+    const int sel = reduce_sel<4>(lane);
+    if ((lane & reduce_writer_mask<4>()) == 0) part[s & 1][wave][sel] = r[0];
+    __syncthreads();
+    float va = 0.f, vg = 0.f, vv = 0.f;
+    for (int w = 0; w < nw; ++w) {
+      va += part[s & 1][w][0];
+      vg += part[s & 1][w][1];
+      vv += part[s & 1][w][2];
+    }
+    const float t = 2.f / vv;
+    const float alpha = -va;  // v^T (input of H_j) = -v^T (output of H_j)
+    float* dst = dVpart + ((size_t)col * n + j) * d;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int x = tid + u * nthreads;
+      a[u] -= t * va * v[u];  // input of H_j
+      if (x < d) dst[x] = -t * (alpha * g[u] + vg * a[u] - t * alpha * vg * v[u]);
+      g[u] -= t * vg * v[u];
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const int x = tid + u * nthreads;
+    if (x < d) dX[(size_t)x * m + col] = g[u];
+  }
+}
+
+__global__ void __launch_bounds__(256) seq_reduce_kernel(const float* __restrict__ dVpart, float* __restrict__ dV,
+                                                         size_t nd, int m) {
+  const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= nd) return;
+  float s = 0.f;
+  for (int c = 0; c < m; ++c) s += dVpart[(size_t)c * nd + idx];
+  dV[idx] = s;
+}
+
+// ------------------------------------------------------------------------------------------
+// Diagonal step of the SVD layer (Section 2.2): with Z2 = s * Z1 (s = sigma or 1/sigma),
+//   ds_r = sum_l dZ2[r][l] Z1[r][l];  for s = 1/sigma, dsigma_r = -ds_r / sigma_r^2.
+// ------------------------------------------------------------------------------------------
+
+__global__ void __launch_bounds__(256) dsigma_kernel(const float* __restrict__ dZ2, const float* __restrict__ Z1,
+                                                     const float* __restrict__ sigma, float* __restrict__ dsigma,
+                                                     int d, int m, int inverse) {
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (row >= d) return;
+  float r[1] = {0.f};
+  for (int l = lane; l < m; l += 64) r[0] += dZ2[(size_t)row * m + l] * Z1[(size_t)row * m + l];
+  wave_reduce_multi<1>(r);
+  if (lane == 0) {
+    float v = r[0];
+    if (inverse) {
+      const float sg = sigma[row];
+      v = -v / (sg * sg);
+    }
+    dsigma[row] = v;
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Host drivers
+// ------------------------------------------------------------------------------------------
+
+struct Product {  // one Householder product bound to its slice of a workspace
+  int d, n, m, k;
+  Layout L;
+  char* ws;
+  float* T() const { return reinterpret_cast<float*>(ws + L.off_T); }
+  float* Spart() const { return reinterpret_cast<float*>(ws + L.off_Spart); }
+  float* saveA() const { return reinterpret_cast<float*>(ws + L.off_saveA); }
+  float* saveCa() const { return reinterpret_cast<float*>(ws + L.off_saveCa); }
+  float* saveG() const { return reinterpret_cast<float*>(ws + L.off_saveG); }
+  float* saveCg() const { return reinterpret_cast<float*>(ws + L.off_saveCg); }
+};
+
+static Product bind(int d, int n, int m, int k, void* ws) {
+  Product P;
+  P.d = d; P.n = n; P.m = m; P.k = k;
+  P.L = make_layout(d, n, m, k);
+  P.ws = static_cast<char*>(ws);
+  return P;
+}
+
+static int build_factors(const Product& P, const float* V, hipStream_t stream) {
+  const int kp = P.L.kp;
+  {
+    const size_t lds = sizeof(float) * (size_t)kp * (kGramChunk + 4);
+    int rc = allow_lds(gram_partial_kernel, lds);
+    if (rc != FASTH_OK) return rc;
+    hipLaunchKernelGGL(gram_partial_kernel, dim3(P.L.gram_split, P.L.nb), dim3(256), lds, stream, V, P.Spart(), P.d,
+                       P.k, kp, P.L.gram_split);
+    FASTH_HIP(hipGetLastError());
+  }
+  {
+    const size_t lds = t_build_lds(kp);
+    int rc = allow_lds(t_build_kernel, lds);
+    if (rc != FASTH_OK) return rc;
+    hipLaunchKernelGGL(t_build_kernel, dim3(P.L.nb), dim3(256), lds, stream, P.Spart(), P.T(), P.k, kp, P.L.gram_split);
+    FASTH_HIP(hipGetLastError());
+  }
+  return FASTH_OK;
+}
+
+// A = H in (transpose = 0) or H^T in (transpose = 1); activation = true saves into the activation
+// slots of the workspace, false into the gradient slots.
+static int run_chain(const Product& P, const float* V, const float* in, float* out, int transpose, bool activation,
+                     const float* in_scale, int in_scale_mode, hipStream_t stream) {
+  ChainArgs a;
+  a.V = V; a.T = P.T(); a.in = in; a.out = out;
+  a.save_in = activation ? P.saveA() : P.saveG();
+  a.save_c = activation ? P.saveCa() : P.saveCg();
+  a.in_scale = in_scale; a.in_scale_mode = in_scale_mode;
+  a.d = P.d; a.n = P.n; a.m = P.m; a.k = P.k; a.kp = P.L.kp; a.nb = P.L.nb;
+  a.transpose = transpose;
+  return launch_chain(a, stream);
+}
+
+static int run_dv(const Product& P, const float* V, float* dV, int transpose, hipStream_t stream) {
+  DvArgs a;
+  a.V = V; a.saveA = P.saveA(); a.saveCa = P.saveCa(); a.saveG = P.saveG(); a.saveCg = P.saveCg(); a.dV = dV;
+  a.d = P.d; a.n = P.n; a.m = P.m; a.k = P.k; a.kp = P.L.kp; a.transpose = transpose;
+  const size_t lds = dv_lds(P.L.kp);
+  int rc = allow_lds(dv_kernel, lds);
+  if (rc != FASTH_OK) return rc;
+  hipLaunchKernelGGL(dv_kernel, dim3((P.d + kDvTile - 1) / kDvTile, P.L.nb), dim3(256), lds, stream, a);
+  FASTH_HIP(hipGetLastError());
+  return FASTH_OK;
+}
+
+static int seq_threads(int d) {
+  int threads = 256;
+  if (d > 256 * 8) threads = 512;
+  if (d > 512 * 8) threads = 1024;
+  return threads;
+}
+
+struct SvdLayout {
+  size_t off_U, off_V, off_Z1, off_dZ2, total;
+};
+
+static SvdLayout make_svd_layout(int d, int n, int m, int k) {
+  SvdLayout S;
+  const size_t one = make_layout(d, n, m, k).total;
+  S.off_U = 0;
+  S.off_V = align_up(one, 256);
+  S.off_Z1 = S.off_V + align_up(one, 256);
+  S.off_dZ2 = S.off_Z1 + align_up((size_t)d * m * sizeof(float), 256);
+  S.total = S.off_dZ2 + align_up((size_t)d * m * sizeof(float), 256);
+  return S;
+}
+
+static int check_svd_shape(const fasth_svd_shape* s, fasth_shape* out) {
+  if (!s) return FASTH_EINVAL;
+  out->d = s->d; out->n = s->n; out->m = s->m; out->k = s->k; out->transpose = 0;
+  return check_shape(out);
+}
+
+// Forward of the layer: first factor transposed, diagonal scale fused into the second chain's load.
+static int svd_forward(const fasth_svd_shape* shape, const float* first, const float* sigma, const float* second,
+                       const float* X, float* Y, void* workspace, size_t workspace_bytes, void* stream, int scale_mode) {
+  fasth_shape fs;
+  int rc = check_svd_shape(shape, &fs);
+  if (rc != FASTH_OK) return rc;
+  if (!first || !sigma || !second || !X || !Y || !workspace) return FASTH_EINVAL;
+  if (!aligned16(first) || !aligned16(sigma) || !aligned16(second) || !aligned16(X) || !aligned16(Y) ||
+      !aligned16(workspace))
+    return FASTH_EALIGN;
+  const SvdLayout S = make_svd_layout(fs.d, fs.n, fs.m, fs.k);
+  if (workspace_bytes < S.total) return FASTH_EWORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  char* ws = static_cast<char*>(workspace);
+  // "first" is the factor applied transposed (V for W, U for W^-1); it owns slot off_V.
+  const Product Pf = bind(fs.d, fs.n, fs.m, fs.k, ws + S.off_V);
+  const Product Ps = bind(fs.d, fs.n, fs.m, fs.k, ws + S.off_U);
+  float* Z1 = reinterpret_cast<float*>(ws + S.off_Z1);
+  if ((rc = build_factors(Pf, first, st)) != FASTH_OK) return rc;
+  if ((rc = build_factors(Ps, second, st)) != FASTH_OK) return rc;
+  if ((rc = run_chain(Pf, first, X, Z1, 1, true, nullptr, 0, st)) != FASTH_OK) return rc;
+  return run_chain(Ps, second, Z1, Y, 0, true, sigma, scale_mode, st);
+}
+
+static int svd_backward(const fasth_svd_shape* shape, const float* first, const float* sigma, const float* second,
+                        const float* G, float* dfirst, float* dsigma, float* dsecond, float* dX, void* workspace,
+                        size_t workspace_bytes, void* stream, int scale_mode) {
+  fasth_shape fs;
+  int rc = check_svd_shape(shape, &fs);
+  if (rc != FASTH_OK) return rc;
+  if (!first || !sigma || !second || !G || !dfirst || !dsigma || !dsecond || !dX || !workspace) return FASTH_EINVAL;
+  if (!aligned16(first) || !aligned16(sigma) || !aligned16(second) || !aligned16(G) || !aligned16(dfirst) ||
+      !aligned16(dsigma) || !aligned16(dsecond) || !aligned16(dX) || !aligned16(workspace))
+    return FASTH_EALIGN;
+  const SvdLayout S = make_svd_layout(fs.d, fs.n, fs.m, fs.k);
+  if (workspace_bytes < S.total) return FASTH_EWORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  char* ws = static_cast<char*>(workspace);
+  const Product Pf = bind(fs.d, fs.n, fs.m, fs.k, ws + S.off_V);
+  const Product Ps = bind(fs.d, fs.n, fs.m, fs.k, ws + S.off_U);
+  const float* Z1 = reinterpret_cast<const float*>(ws + S.off_Z1);
+  float* dZ2 = reinterpret_cast<float*>(ws + S.off_dZ2);
+  // through the second (plain) factor
+  if ((rc = run_chain(Ps, second, G, dZ2, 1, false, nullptr, 0, st)) != FASTH_OK) return rc;
+  if ((rc = run_dv(Ps, second, dsecond, 0, st)) != FASTH_OK) return rc;
+  hipLaunchKernelGGL(dsigma_kernel, dim3((fs.d + 3) / 4), dim3(256), 0, st, dZ2, Z1, sigma, dsigma, fs.d, fs.m,
+                     scale_mode == 2 ? 1 : 0);
+  FASTH_HIP(hipGetLastError());
+  // through the first (transposed) factor; dZ1 = s * dZ2 is fused into the chain's load
+  if ((rc = run_chain(Pf, first, dZ2, dX, 0, false, sigma, scale_mode, st)) != FASTH_OK) return rc;
+  return run_dv(Pf, first, dfirst, 1, st);
+}
+
+}  // namespace fasth
+
+// ------------------------------------------------------------------------------------------
+// C ABI
+// ------------------------------------------------------------------------------------------
+
+using namespace fasth;
+
+extern "C" {
+
+const char* fasth_strerror(int code) {
+  switch (code) {
+    case FASTH_OK: return "success";
+    case FASTH_EINVAL: return "invalid argument (null pointer, non-positive size, or k does not divide n)";
+    case FASTH_EWORKSPACE: return "workspace too small";
+    case FASTH_EALIGN: return "pointer is not 16-byte aligned";
+    case FASTH_EHIP: return "HIP runtime call or kernel launch failed";
+    case FASTH_EUNSUPPORTED: return "shape outside the supported range";
+    default: return "unknown error code";
+  }
+}
+
+size_t fasth_workspace_bytes(const fasth_shape* shape) {
+  if (check_shape(shape) != FASTH_OK) return 0;
+  return make_layout(shape->d, shape->n, shape->m, shape->k).total;
+}
+
+int fasth_forward(const fasth_shape* shape, const float* V, const float* X, float* A, void* workspace,
+                  size_t workspace_bytes, void* stream) {
+  int rc = check_shape(shape);
+  if (rc != FASTH_OK) return rc;
+  if (!V || !X || !A || !workspace) return FASTH_EINVAL;
+  if (!aligned16(V) || !aligned16(X) || !aligned16(A) || !aligned16(workspace)) return FASTH_EALIGN;
+  const Product P = bind(shape->d, shape->n, shape->m, shape->k, workspace);
+  if (workspace_bytes < P.L.total) return FASTH_EWORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if ((rc = build_factors(P, V, st)) != FASTH_OK) return rc;
+  return run_chain(P, V, X, A, shape->transpose, true, nullptr, 0, st);
+}
+
+int fasth_backward(const fasth_shape* shape, const float* V, const float* G, float* dV, float* dX, void* workspace,
+                   size_t workspace_bytes, void* stream) {
+  int rc = check_shape(shape);
+  if (rc != FASTH_OK) return rc;
+  if (!V || !G || !dV || !dX || !workspace) return FASTH_EINVAL;
+  if (!aligned16(V) || !aligned16(G) || !aligned16(dV) || !aligned16(dX) || !aligned16(workspace)) return FASTH_EALIGN;
+  const Product P = bind(shape->d, shape->n, shape->m, shape->k, workspace);
+  if (workspace_bytes < P.L.total) return FASTH_EWORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if ((rc = run_chain(P, V, G, dX, !shape->transpose, false, nullptr, 0, st)) != FASTH_OK) return rc;
+  return run_dv(P, V, dV, shape->transpose, st);
+}
+
+size_t fasth_sequential_workspace_bytes(const fasth_shape* shape) {
+  if (!shape || shape->d < 1 || shape->n < 1 || shape->m < 1) return 0;
+  if (shape->d > kMaxD || shape->m > 65535) return 0;
+  return (size_t)shape->m * shape->n * shape->d * sizeof(float) + (size_t)shape->d * shape->m * sizeof(float);
+}
+
+static int check_seq_shape(const fasth_shape* s) {
+  if (!s) return FASTH_EINVAL;
+  if (s->d < 1 || s->n < 1 || s->m < 1) return FASTH_EINVAL;
+  if (s->transpose != 0 && s->transpose != 1) return FASTH_EINVAL;
+  if (s->d > kMaxD || s->m > 65535) return FASTH_EUNSUPPORTED;
+  return FASTH_OK;
+}
+
+#define FASTH_SEQ_DISPATCH(KERNEL, per, grid, block, stream, ...)                         \
+  do {                                                                                    \
+    if ((per) <= 1) hipLaunchKernelGGL(KERNEL<1>, grid, block, 0, stream, __VA_ARGS__);      \
+    else if ((per) <= 2) hipLaunchKernelGGL(KERNEL<2>, grid, block, 0, stream, __VA_ARGS__); \
+    else if ((per) <= 4) hipLaunchKernelGGL(KERNEL<4>, grid, block, 0, stream, __VA_ARGS__); \
+    else if ((per) <= 8) hipLaunchKernelGGL(KERNEL<8>, grid, block, 0, stream, __VA_ARGS__); \
+    else hipLaunchKernelGGL(KERNEL<16>, grid, block, 0, stream, __VA_ARGS__);                \
+  } while (0)
+
+int fasth_sequential_forward(const fasth_shape* shape, const float* V, const float* X, float* A, void* stream) {
+  int rc = check_seq_shape(shape);
+  if (rc != FASTH_OK) return rc;
+  if (!V || !X || !A) return FASTH_EINVAL;
+  if (!aligned16(V) || !aligned16(X) || !aligned16(A)) return FASTH_EALIGN;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int threads = seq_threads(shape->d), per = (shape->d + threads - 1) / threads;
+  FASTH_SEQ_DISPATCH(seq_forward_kernel, per, dim3(shape->m), dim3(threads), st, V, X, A, shape->d, shape->n, shape->m,
+                     shape->transpose);
+  FASTH_HIP(hipGetLastError());
+  return FASTH_OK;
+}
+
+int fasth_sequential_backward(const fasth_shape* shape, const float* V, const float* X, const float* G, float* dV,
+                              float* dX, void* workspace, size_t workspace_bytes, void* stream) {
+  int rc = check_seq_shape(shape);
+  if (rc != FASTH_OK) return rc;
+  if (!V || !X || !G || !dV || !dX || !workspace) return FASTH_EINVAL;
+  if (!aligned16(V) || !aligned16(X) || !aligned16(G) || !aligned16(dV) || !aligned16(dX) || !aligned16(workspace))
+    return FASTH_EALIGN;
+  if (workspace_bytes < fasth_sequential_workspace_bytes(shape)) return FASTH_EWORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int d = shape->d, n = shape->n, m = shape->m;
+  float* dVpart = static_cast<float*>(workspace);
+  float* A = dVpart + (size_t)m * n * d;
+  const int threads = seq_threads(d), per = (d + threads - 1) / threads;
+  FASTH_SEQ_DISPATCH(seq_forward_kernel, per, dim3(m), dim3(threads), st, V, X, A, d, n, m, shape->transpose);
+  FASTH_HIP(hipGetLastError());
+  FASTH_SEQ_DISPATCH(seq_backward_kernel, per, dim3(m), dim3(threads), st, V, (const float*)A, G, dVpart, dX, d, n, m,
+                     shape->transpose);
+  FASTH_HIP(hipGetLastError());
+  const size_t nd = (size_t)n * d;
+  hipLaunchKernelGGL(seq_reduce_kernel, dim3((unsigned)((nd + 255) / 256)), dim3(256), 0, st, (const float*)dVpart, dV,
+                     nd, m);
+  FASTH_HIP(hipGetLastError());
+  return FASTH_OK;
+}
+
+size_t svd_layer_workspace_bytes(const fasth_svd_shape* shape) {
+  fasth_shape fs;
+  if (check_svd_shape(shape, &fs) != FASTH_OK) return 0;
+  return make_svd_layout(fs.d, fs.n, fs.m, fs.k).total;
+}
+
+int svd_layer_apply(const fasth_svd_shape* shape, const float* Uv, const float* sigma, const float* Vv, const float* X,
+                    float* Y, void* workspace, size_t workspace_bytes, void* stream) {
+  return svd_forward(shape, Vv, sigma, Uv, X, Y, workspace, workspace_bytes, stream, 1);
+}
+
+int svd_layer_inverse_apply(const fasth_svd_shape* shape, const float* Uv, const float* sigma, const float* Vv,
+                            const float* X, float* Y, void* workspace, size_t workspace_bytes, void* stream) {
+  return svd_forward(shape, Uv, sigma, Vv, X, Y, workspace, workspace_bytes, stream, 2);
+}
+
+int svd_layer_apply_backward(const fasth_svd_shape* shape, const float* Uv, const float* sigma, const float* Vv,
+                             const float* G, float* dUv, float* dsigma, float* dVv, float* dX, void* workspace,
+                             size_t workspace_bytes, void* stream) {
+  return svd_backward(shape, Vv, sigma, Uv, G, dVv, dsigma, dUv, dX, workspace, workspace_bytes, stream, 1);
+}
+
+int svd_layer_inverse_apply_backward(const fasth_svd_shape* shape, const float* Uv, const float* sigma,
+                                     const float* Vv, const float* G, float* dUv, float* dsigma, float* dVv,
+                                     float* dX, void* workspace, size_t workspace_bytes, void* stream) {
+  return svd_backward(shape, Uv, sigma, Vv, G, dUv, dsigma, dVv, dX, workspace, workspace_bytes, stream, 2);
+}
+
+}  // extern "C"

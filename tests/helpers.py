@@ -1,0 +1,64 @@
+"""Shared test helpers: error metric and GPU marshalling (no method arithmetic)."""
+import numpy as np
+
+REL_TOL = 1e-4  # relative Frobenius error bar for fp32 GPU results against the fp64 checker
+
+
+def rel_err(got, ref) -> float:
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    den = np.linalg.norm(ref)
+    return float(np.linalg.norm(got - ref) / (den if den > 0 else 1.0))
+
+
+def to_gpu(a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def gpu_fasth(V, X, G, k, transpose=False):
+    """Run fasth_forward + fasth_backward through the C ABI; returns numpy A, dV, dX."""
+    import torch
+    from paper_2009_13977_amd import binding as B
+    n, d = V.shape
+    m = X.shape[1]
+    Vd, Xd, Gd = to_gpu(V), to_gpu(X), to_gpu(G)
+    A = torch.empty_like(Xd); dX = torch.empty_like(Xd); dV = torch.empty_like(Vd)
+    ws = B.new_workspace(B.fasth_workspace_bytes(d, n, m, k))
+    B.fasth_forward(Vd, Xd, A, ws, k, transpose)
+    B.fasth_backward(Vd, Gd, dV, dX, ws, k, transpose)
+    torch.cuda.synchronize()
+    return A.cpu().numpy(), dV.cpu().numpy(), dX.cpu().numpy()
+
+
+def gpu_sequential(V, X, G, transpose=False):
+    import torch
+    from paper_2009_13977_amd import binding as B
+    n, d = V.shape
+    m = X.shape[1]
+    Vd, Xd, Gd = to_gpu(V), to_gpu(X), to_gpu(G)
+    A = torch.empty_like(Xd); dX = torch.empty_like(Xd); dV = torch.empty_like(Vd)
+    ws = B.new_workspace(B.fasth_sequential_workspace_bytes(d, n, m))
+    B.fasth_sequential_forward(Vd, Xd, A, transpose)
+    B.fasth_sequential_backward(Vd, Xd, Gd, dV, dX, ws, transpose)
+    torch.cuda.synchronize()
+    return A.cpu().numpy(), dV.cpu().numpy(), dX.cpu().numpy()
+
+
+def gpu_svd_layer(Uv, sigma, Vv, X, G, k, inverse=False):
+    import torch
+    from paper_2009_13977_amd import binding as B
+    n, d = Uv.shape
+    m = X.shape[1]
+    Ud, sd, Vd, Xd, Gd = (to_gpu(a) for a in (Uv, sigma, Vv, X, G))
+    Y = torch.empty_like(Xd); dX = torch.empty_like(Xd)
+    dU = torch.empty_like(Ud); dVv = torch.empty_like(Vd); ds = torch.empty_like(sd)
+    ws = B.new_workspace(B.svd_layer_workspace_bytes(d, n, m, k))
+    if inverse:
+        B.svd_layer_inverse_apply(Ud, sd, Vd, Xd, Y, ws, k)
+        B.svd_layer_inverse_apply_backward(Ud, sd, Vd, Gd, dU, ds, dVv, dX, ws, k)
+    else:
+        B.svd_layer_apply(Ud, sd, Vd, Xd, Y, ws, k)
+        B.svd_layer_apply_backward(Ud, sd, Vd, Gd, dU, ds, dVv, dX, ws, k)
+    torch.cuda.synchronize()
+    return tuple(t.cpu().numpy() for t in (Y, dU, ds, dVv, dX))

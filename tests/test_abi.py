@@ -1,0 +1,79 @@
+"""Host-only checks of the C ABI: the library loads, exports every symbol include/fasth.h declares,
+and validates its arguments before touching the GPU (so these run without one)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2009_13977_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "fasth.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return set(re.findall(r"\b((?:fasth|svd_layer)_\w+)\s*\(", text))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = B.load_library()
+    declared = _declared_symbols()
+    assert declared == set(B.EXPORTED_SYMBOLS)
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+def test_strerror_texts():
+    for code in (0, -1, -2, -3, -4, -5):
+        assert B.strerror(code)
+    assert "unknown" in B.strerror(-99)
+
+
+def test_workspace_bytes_and_shape_validation():
+    assert B.fasth_workspace_bytes(1024, 1024, 32, 32) > 2 * 32 * 32 * 1024 * 4  # two sets of nb saved d x m matrices
+    assert B.fasth_workspace_bytes(64, 64, 32, 7) == 0       # k does not divide n (Section 3.1)
+    assert B.fasth_workspace_bytes(0, 64, 32, 32) == 0
+    assert B.fasth_workspace_bytes(64, 64, 32, 256) == 0     # beyond the supported block size
+    assert B.svd_layer_workspace_bytes(64, 64, 32, 32) > 2 * B.fasth_workspace_bytes(64, 64, 32, 32)
+    assert B.fasth_sequential_workspace_bytes(64, 64, 32) >= 32 * 64 * 64 * 4
+
+
+def _call_forward(shape, V=256, X=256, A=512, ws=1024, nbytes=1 << 40):
+    return B.load_library().fasth_forward(ctypes.byref(shape), V, X, A, ws, nbytes, None)
+
+
+def test_forward_argument_errors_precede_any_gpu_call():
+    ok = B.fasth_shape(64, 64, 32, 32, 0)
+    assert _call_forward(B.fasth_shape(64, 64, 32, 7, 0)) == B.FASTH_EINVAL
+    assert _call_forward(B.fasth_shape(64, 64, 0, 32, 0)) == B.FASTH_EINVAL
+    assert _call_forward(B.fasth_shape(64, 64, 32, 32, 2)) == B.FASTH_EINVAL
+    assert _call_forward(B.fasth_shape(64, 256, 32, 256, 0)) == B.FASTH_EUNSUPPORTED
+    assert _call_forward(ok, V=None) == B.FASTH_EINVAL
+    assert _call_forward(ok, X=260) == B.FASTH_EALIGN
+    assert _call_forward(ok, nbytes=128) == B.FASTH_EWORKSPACE
+    assert B.load_library().fasth_forward(None, 256, 256, 256, 256, 1 << 40, None) == B.FASTH_EINVAL
+
+
+def test_backward_and_layer_argument_errors():
+    lib = B.load_library()
+    ok = B.fasth_shape(64, 64, 32, 32, 0)
+    assert lib.fasth_backward(ctypes.byref(ok), 256, 256, None, 256, 256, 1 << 40, None) == B.FASTH_EINVAL
+    assert lib.fasth_backward(ctypes.byref(ok), 256, 256, 256, 256, 256, 16, None) == B.FASTH_EWORKSPACE
+    assert lib.fasth_sequential_forward(ctypes.byref(ok), 256, None, 256, None) == B.FASTH_EINVAL
+    assert lib.fasth_sequential_backward(ctypes.byref(ok), 256, 256, 256, 256, 256, 256, 16, None) == B.FASTH_EWORKSPACE
+    s = B.fasth_svd_shape(64, 64, 32, 5)
+    assert lib.svd_layer_apply(ctypes.byref(s), 256, 256, 256, 256, 256, 256, 1 << 40, None) == B.FASTH_EINVAL
+    s = B.fasth_svd_shape(64, 64, 32, 32)
+    assert lib.svd_layer_apply(ctypes.byref(s), 256, 256, 256, 256, 256, 256, 16, None) == B.FASTH_EWORKSPACE
+    assert lib.svd_layer_inverse_apply(ctypes.byref(s), 256, 8, 256, 256, 256, 256, 1 << 40, None) == B.FASTH_EALIGN
+    assert lib.svd_layer_apply_backward(ctypes.byref(s), 256, 256, 256, 256, 256, 256, 256, None, 256, 1 << 40,
+                                        None) == B.FASTH_EINVAL
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    t = torch.zeros(4, 4)
+    with pytest.raises(ValueError):
+        B.fasth_forward(t, t, t, t, 2)
