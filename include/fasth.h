@@ -124,6 +124,27 @@ int svd_layer_inverse_apply_backward(const fasth_svd_shape* shape, const float* 
                                      float* dUv, float* dsigma, float* dVv, float* dX,
                                      void* workspace, size_t workspace_bytes, void* stream);
 
+/* Benchmark aid (not part of the method). While enabled, every kernel this library launches from
+ * the calling process is bracketed by a pair of HIP events on its stream; fasth_profile_collect
+ * waits for them, adds the elapsed milliseconds and the launch count per kernel into the two HOST
+ * arrays of FASTH_KERNEL_COUNT entries, and forgets the records. The extra events perturb
+ * end-to-end timing, so keep profiling off in regions that report throughput. Process-global and
+ * not thread-safe. */
+enum {
+  FASTH_KERNEL_GRAM = 0,
+  FASTH_KERNEL_TBUILD = 1,
+  FASTH_KERNEL_CHAIN = 2,
+  FASTH_KERNEL_DV = 3,
+  FASTH_KERNEL_SEQ_FORWARD = 4,
+  FASTH_KERNEL_SEQ_BACKWARD = 5,
+  FASTH_KERNEL_SEQ_REDUCE = 6,
+  FASTH_KERNEL_DSIGMA = 7,
+  FASTH_KERNEL_COUNT = 8
+};
+const char* fasth_kernel_name(int id);
+int fasth_profile_enable(int on);
+int fasth_profile_collect(float* ms, int* launches);
+
 #ifdef __cplusplus
 }
 #endif

@@ -34,6 +34,9 @@ EXPORTED_SYMBOLS = (
     "svd_layer_inverse_apply",
     "svd_layer_apply_backward",
     "svd_layer_inverse_apply_backward",
+    "fasth_kernel_name",
+    "fasth_profile_enable",
+    "fasth_profile_collect",
 )
 
 
@@ -91,6 +94,12 @@ def load_library() -> ctypes.CDLL:
         fn = getattr(lib, name)
         fn.restype = I
         fn.argtypes = [sshp, P, P, P, P, P, P, P, P, P, S, P]
+    lib.fasth_kernel_name.restype = ctypes.c_char_p
+    lib.fasth_kernel_name.argtypes = [I]
+    lib.fasth_profile_enable.restype = I
+    lib.fasth_profile_enable.argtypes = [I]
+    lib.fasth_profile_collect.restype = I
+    lib.fasth_profile_collect.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_int)]
     _lib = lib
     return lib
 
@@ -217,3 +226,19 @@ def svd_layer_apply_backward(Uv, sigma, Vv, G, dUv, dsigma, dVv, dX, workspace, 
 
 def svd_layer_inverse_apply_backward(Uv, sigma, Vv, G, dUv, dsigma, dVv, dX, workspace, k: int) -> None:
     _svd_backward("svd_layer_inverse_apply_backward", Uv, sigma, Vv, G, dUv, dsigma, dVv, dX, workspace, k)
+
+
+FASTH_KERNEL_COUNT = 8
+
+
+def fasth_profile_enable(on: bool) -> None:
+    _check(load_library().fasth_profile_enable(1 if on else 0), "fasth_profile_enable")
+
+
+def fasth_profile_collect() -> dict:
+    """{kernel name: (total milliseconds, launches)} since profiling was enabled or last collected."""
+    lib = load_library()
+    ms = (ctypes.c_float * FASTH_KERNEL_COUNT)()
+    cnt = (ctypes.c_int * FASTH_KERNEL_COUNT)()
+    _check(lib.fasth_profile_collect(ms, cnt), "fasth_profile_collect")
+    return {lib.fasth_kernel_name(i).decode(): (float(ms[i]), int(cnt[i])) for i in range(FASTH_KERNEL_COUNT)}

@@ -21,6 +21,7 @@
 
 #include <cstdint>
 #include <cstdio>
+#include <vector>
 
 #include "fasth.h"
 #include "fasth_device.h"
@@ -89,6 +90,34 @@ static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
     hipError_t e_ = (call);                  \
     if (e_ != hipSuccess) return FASTH_EHIP; \
   } while (0)
+
+// Optional per-kernel timing for benchmarks: a pair of HIP events around every launch.
+namespace prof {
+struct Rec { int id; hipEvent_t beg, end; };
+static bool enabled = false;
+static std::vector<Rec> recs;
+static std::vector<hipEvent_t> pool;
+static hipEvent_t get_event() {
+  if (!pool.empty()) { hipEvent_t e = pool.back(); pool.pop_back(); return e; }
+  hipEvent_t e = nullptr;
+  if (hipEventCreate(&e) != hipSuccess) return nullptr;
+  return e;
+}
+struct Scope {
+  Rec r{-1, nullptr, nullptr};
+  hipStream_t st;
+  Scope(int id, hipStream_t s) : st(s) {
+    if (!enabled) return;
+    r.id = id; r.beg = get_event(); r.end = get_event();
+    if (r.beg) (void)hipEventRecord(r.beg, st);
+  }
+  ~Scope() {
+    if (r.id < 0) return;
+    if (r.end) (void)hipEventRecord(r.end, st);
+    recs.push_back(r);
+  }
+};
+}  // namespace prof
 
 template <typename K>
 static int allow_lds(K kernel, size_t bytes) {
@@ -345,7 +374,166 @@ __global__ void __launch_bounds__(1024) chain_kernel(ChainArgs p) {
   }
 }
 
+// Register-resident variant for k = K exactly and d a multiple of 4 with d <= 1024 * U4.
+// Thread t owns the float4 chunks c = t + 256 u of every row, so one wave load covers 1 KiB of a
+// row. The k x d block V_i is loaded once into registers and used for both products; the next
+// block (and the thread's entries of T_{i+1}) is loaded while the current one is being applied, and
+// the barriers order LDS traffic only, so those loads stay in flight across them.
+template <int K, int U4>
+struct ChainBlockRegs {
+  float4 v[K][U4];
+  float t[K * K / 256];
+};
+
+template <int K, int U4>
+__global__ void __launch_bounds__(256) chain_fast_kernel(ChainArgs p) {
+  constexpr int NT = 256, NW = 4, G = NT / K, LPT = K / G;  // G threads share one row of T
+  static_assert(K == 16 || K == 32 || K == 64, "block size");
+  __shared__ float Bpart[NW][K];
+  __shared__ __align__(16) float Cv[K];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int col = blockIdx.x, m = p.m, d4 = p.d >> 2;
+  const int trow = tid / G, tg = tid % G;
+  const float4* V4 = reinterpret_cast<const float4*>(p.V);
+  // Threads whose chunk lies beyond d load chunk 0 instead (always valid memory) and keep their
+  // part of the column at zero, so they contribute nothing and need no branch per load.
+  bool ok[U4];
+  int cidx[U4];
+  float4 a[U4];
+#pragma unroll
+  for (int u = 0; u < U4; ++u) {
+    const int c = tid + u * NT;
+    ok[u] = c < d4;
+    cidx[u] = ok[u] ? c : 0;
+    a[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (ok[u]) {
+      float e[4];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int x = 4 * c + r;
+        float v = p.in[(size_t)x * m + col];
+        if (p.in_scale_mode == 1) v *= p.in_scale[x];
+        else if (p.in_scale_mode == 2) v /= p.in_scale[x];
+        e[r] = v;
+      }
+      a[u] = make_float4(e[0], e[1], e[2], e[3]);
+    }
+  }
+  const int sel = reduce_sel<K>(lane);
+
+  auto load_block = [&](int i, ChainBlockRegs<K, U4>& r) {
+    const float4* Vi = V4 + (size_t)i * K * d4;
+#pragma unroll
+    for (int j = 0; j < K; ++j) {
+#pragma unroll
+      for (int u = 0; u < U4; ++u) {
+        r.v[j][u] = Vi[(size_t)j * d4 + cidx[u]];
+      }
+    }
+    const float* Ti = p.T + (size_t)i * K * K;
+#pragma unroll
+    for (int e = 0; e < LPT; ++e) {
+      const int l = tg + G * e;
+      r.t[e] = p.transpose ? Ti[l * K + trow] : Ti[trow * K + l];
+    }
+  };
+
+  auto apply_block = [&](int i, const ChainBlockRegs<K, U4>& r) {
+    if (p.save_in) {
+      float4* dst = reinterpret_cast<float4*>(p.save_in + ((size_t)i * m + col) * p.d);
+#pragma unroll
+      for (int u = 0; u < U4; ++u)
+        if (ok[u]) dst[tid + u * NT] = a[u];
+    }
+    float pj[K];
+#pragma unroll
+    for (int j = 0; j < K; ++j) {
+      float acc = 0.f;
+#pragma unroll
+      for (int u = 0; u < U4; ++u) {
+        acc = fmaf(r.v[j][u].x, a[u].x, acc);
+        acc = fmaf(r.v[j][u].y, a[u].y, acc);
+        acc = fmaf(r.v[j][u].z, a[u].z, acc);
+        acc = fmaf(r.v[j][u].w, a[u].w, acc);
+      }
+      pj[j] = acc;
+    }
+    wave_reduce_multi_reg<K>(pj);
+    if ((lane & reduce_writer_mask<K>()) == 0) Bpart[wave][sel] = pj[0];
+    lds_barrier();
+    float c = 0.f;
+#pragma unroll
+    for (int e = 0; e < LPT; ++e) {
+      const int l = tg + G * e;
+      const float b = (Bpart[0][l] + Bpart[1][l]) + (Bpart[2][l] + Bpart[3][l]);
+      c = fmaf(r.t[e], b, c);
+    }
+    c = group_sum<G>(c);
+    if (tg == 0) {
+      Cv[trow] = c;
+      if (p.save_c) p.save_c[(size_t)col * p.n + (size_t)i * K + trow] = c;
+    }
+    lds_barrier();
+#pragma unroll
+    for (int j4 = 0; j4 < K / 4; ++j4) {
+      const float4 c4 = reinterpret_cast<const float4*>(Cv)[j4];
+      const float cc[4] = {c4.x, c4.y, c4.z, c4.w};
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+#pragma unroll
+        for (int u = 0; u < U4; ++u) {
+          a[u].x = fmaf(-cc[r4], r.v[4 * j4 + r4][u].x, a[u].x);
+          a[u].y = fmaf(-cc[r4], r.v[4 * j4 + r4][u].y, a[u].y);
+          a[u].z = fmaf(-cc[r4], r.v[4 * j4 + r4][u].z, a[u].z);
+          a[u].w = fmaf(-cc[r4], r.v[4 * j4 + r4][u].w, a[u].w);
+        }
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U4; ++u)
+      if (!ok[u]) a[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+  };
+
+  const int nb = p.nb;
+  auto block_of = [&](int s) { return p.transpose ? s : nb - 1 - s; };
+  ChainBlockRegs<K, U4> ra, rb;
+  load_block(block_of(0), ra);
+  for (int s = 0; s < nb; s += 2) {
+    // Drain the loads of `ra` here, before the next block's loads are queued behind them: the
+    // counter is in-order, so waiting any later would also wait for the new prefetch.
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0), other counters untouched
+    if (s + 1 < nb) load_block(block_of(s + 1), rb);
+    apply_block(block_of(s), ra);
+    if (s + 1 < nb) {
+      if (s + 2 < nb) load_block(block_of(s + 2), ra);
+      apply_block(block_of(s + 1), rb);
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < U4; ++u) {
+    if (ok[u]) {
+      const int c = tid + u * NT;
+      const float e[4] = {a[u].x, a[u].y, a[u].z, a[u].w};
+#pragma unroll
+      for (int r = 0; r < 4; ++r) p.out[(size_t)(4 * c + r) * m + col] = e[r];
+    }
+  }
+}
+
+template <int K, int U4>
+static int launch_chain_fast(const ChainArgs& a, hipStream_t stream) {
+  prof::Scope ps_(FASTH_KERNEL_CHAIN, stream);
+  hipLaunchKernelGGL((chain_fast_kernel<K, U4>), dim3(a.m), dim3(256), 0, stream, a);
+  FASTH_HIP(hipGetLastError());
+  return FASTH_OK;
+}
+
 static int launch_chain(const ChainArgs& a, hipStream_t stream) {
+  if (a.d % 4 == 0 && a.k == a.kp) {
+    if (a.k == 32 && a.d <= 1024) return launch_chain_fast<32, 1>(a, stream);
+    if (a.k == 16 && a.d <= 1024) return launch_chain_fast<16, 1>(a, stream);
+    if (a.k == 16 && a.d <= 2048) return launch_chain_fast<16, 2>(a, stream);
+  }
   const int d = a.d;
   int threads = 256;
   if (d > 256 * 8) threads = 512;
@@ -358,6 +546,7 @@ static int launch_chain(const ChainArgs& a, hipStream_t stream) {
   do {                                                                           \
     int rc_ = allow_lds(chain_kernel<UU>, lds);                                  \
     if (rc_ != FASTH_OK) return rc_;                                             \
+    prof::Scope ps_(FASTH_KERNEL_CHAIN, stream);                                 \
     hipLaunchKernelGGL(chain_kernel<UU>, grid, block, lds, stream, a);           \
   } while (0)
   if (per <= 1) FASTH_LAUNCH_CHAIN(1);
@@ -685,6 +874,7 @@ static int build_factors(const Product& P, const float* V, hipStream_t stream) {
     const size_t lds = sizeof(float) * (size_t)kp * (kGramChunk + 4);
     int rc = allow_lds(gram_partial_kernel, lds);
     if (rc != FASTH_OK) return rc;
+    prof::Scope ps_(FASTH_KERNEL_GRAM, stream);
     hipLaunchKernelGGL(gram_partial_kernel, dim3(P.L.gram_split, P.L.nb), dim3(256), lds, stream, V, P.Spart(), P.d,
                        P.k, kp, P.L.gram_split);
     FASTH_HIP(hipGetLastError());
@@ -693,6 +883,7 @@ static int build_factors(const Product& P, const float* V, hipStream_t stream) {
     const size_t lds = t_build_lds(kp);
     int rc = allow_lds(t_build_kernel, lds);
     if (rc != FASTH_OK) return rc;
+    prof::Scope ps_(FASTH_KERNEL_TBUILD, stream);
     hipLaunchKernelGGL(t_build_kernel, dim3(P.L.nb), dim3(256), lds, stream, P.Spart(), P.T(), P.k, kp, P.L.gram_split);
     FASTH_HIP(hipGetLastError());
   }
@@ -720,6 +911,7 @@ static int run_dv(const Product& P, const float* V, float* dV, int transpose, hi
   const size_t lds = dv_lds(P.L.kp);
   int rc = allow_lds(dv_kernel, lds);
   if (rc != FASTH_OK) return rc;
+  prof::Scope ps_(FASTH_KERNEL_DV, stream);
   hipLaunchKernelGGL(dv_kernel, dim3((P.d + kDvTile - 1) / kDvTile, P.L.nb), dim3(256), lds, stream, a);
   FASTH_HIP(hipGetLastError());
   return FASTH_OK;
@@ -798,8 +990,11 @@ static int svd_backward(const fasth_svd_shape* shape, const float* first, const 
   // through the second (plain) factor
   if ((rc = run_chain(Ps, second, G, dZ2, 1, false, nullptr, 0, st)) != FASTH_OK) return rc;
   if ((rc = run_dv(Ps, second, dsecond, 0, st)) != FASTH_OK) return rc;
-  hipLaunchKernelGGL(dsigma_kernel, dim3((fs.d + 3) / 4), dim3(256), 0, st, dZ2, Z1, sigma, dsigma, fs.d, fs.m,
-                     scale_mode == 2 ? 1 : 0);
+  {
+    prof::Scope ps_(FASTH_KERNEL_DSIGMA, st);
+    hipLaunchKernelGGL(dsigma_kernel, dim3((fs.d + 3) / 4), dim3(256), 0, st, dZ2, Z1, sigma, dsigma, fs.d, fs.m,
+                       scale_mode == 2 ? 1 : 0);
+  }
   FASTH_HIP(hipGetLastError());
   // through the first (transposed) factor; dZ1 = s * dZ2 is fused into the chain's load
   if ((rc = run_chain(Pf, first, dZ2, dX, 0, false, sigma, scale_mode, st)) != FASTH_OK) return rc;
@@ -826,6 +1021,45 @@ const char* fasth_strerror(int code) {
     case FASTH_EUNSUPPORTED: return "shape outside the supported range";
     default: return "unknown error code";
   }
+}
+
+const char* fasth_kernel_name(int id) {
+  switch (id) {
+    case FASTH_KERNEL_GRAM: return "gram_partial_kernel";
+    case FASTH_KERNEL_TBUILD: return "t_build_kernel";
+    case FASTH_KERNEL_CHAIN: return "chain_kernel";
+    case FASTH_KERNEL_DV: return "dv_kernel";
+    case FASTH_KERNEL_SEQ_FORWARD: return "seq_forward_kernel";
+    case FASTH_KERNEL_SEQ_BACKWARD: return "seq_backward_kernel";
+    case FASTH_KERNEL_SEQ_REDUCE: return "seq_reduce_kernel";
+    case FASTH_KERNEL_DSIGMA: return "dsigma_kernel";
+    default: return "unknown";
+  }
+}
+
+int fasth_profile_enable(int on) {
+  prof::enabled = on != 0;
+  return FASTH_OK;
+}
+
+int fasth_profile_collect(float* ms, int* launches) {
+  if (!ms || !launches) return FASTH_EINVAL;
+  for (int i = 0; i < FASTH_KERNEL_COUNT; ++i) { ms[i] = 0.f; launches[i] = 0; }
+  int rc = FASTH_OK;
+  for (const prof::Rec& r : prof::recs) {
+    float t = 0.f;
+    if (r.beg && r.end && hipEventSynchronize(r.end) == hipSuccess &&
+        hipEventElapsedTime(&t, r.beg, r.end) == hipSuccess && r.id >= 0 && r.id < FASTH_KERNEL_COUNT) {
+      ms[r.id] += t;
+      launches[r.id] += 1;
+    } else {
+      rc = FASTH_EHIP;
+    }
+    if (r.beg) prof::pool.push_back(r.beg);
+    if (r.end) prof::pool.push_back(r.end);
+  }
+  prof::recs.clear();
+  return rc;
 }
 
 size_t fasth_workspace_bytes(const fasth_shape* shape) {
@@ -889,8 +1123,11 @@ int fasth_sequential_forward(const fasth_shape* shape, const float* V, const flo
   if (!aligned16(V) || !aligned16(X) || !aligned16(A)) return FASTH_EALIGN;
   hipStream_t st = static_cast<hipStream_t>(stream);
   const int threads = seq_threads(shape->d), per = (shape->d + threads - 1) / threads;
-  FASTH_SEQ_DISPATCH(seq_forward_kernel, per, dim3(shape->m), dim3(threads), st, V, X, A, shape->d, shape->n, shape->m,
-                     shape->transpose);
+  {
+    prof::Scope ps_(FASTH_KERNEL_SEQ_FORWARD, st);
+    FASTH_SEQ_DISPATCH(seq_forward_kernel, per, dim3(shape->m), dim3(threads), st, V, X, A, shape->d, shape->n,
+                       shape->m, shape->transpose);
+  }
   FASTH_HIP(hipGetLastError());
   return FASTH_OK;
 }
@@ -908,14 +1145,23 @@ int fasth_sequential_backward(const fasth_shape* shape, const float* V, const fl
   float* dVpart = static_cast<float*>(workspace);
   float* A = dVpart + (size_t)m * n * d;
   const int threads = seq_threads(d), per = (d + threads - 1) / threads;
-  FASTH_SEQ_DISPATCH(seq_forward_kernel, per, dim3(m), dim3(threads), st, V, X, A, d, n, m, shape->transpose);
+  {
+    prof::Scope ps_(FASTH_KERNEL_SEQ_FORWARD, st);
+    FASTH_SEQ_DISPATCH(seq_forward_kernel, per, dim3(m), dim3(threads), st, V, X, A, d, n, m, shape->transpose);
+  }
   FASTH_HIP(hipGetLastError());
-  FASTH_SEQ_DISPATCH(seq_backward_kernel, per, dim3(m), dim3(threads), st, V, (const float*)A, G, dVpart, dX, d, n, m,
-                     shape->transpose);
+  {
+    prof::Scope ps_(FASTH_KERNEL_SEQ_BACKWARD, st);
+    FASTH_SEQ_DISPATCH(seq_backward_kernel, per, dim3(m), dim3(threads), st, V, (const float*)A, G, dVpart, dX, d, n,
+                       m, shape->transpose);
+  }
   FASTH_HIP(hipGetLastError());
   const size_t nd = (size_t)n * d;
-  hipLaunchKernelGGL(seq_reduce_kernel, dim3((unsigned)((nd + 255) / 256)), dim3(256), 0, st, (const float*)dVpart, dV,
-                     nd, m);
+  {
+    prof::Scope ps_(FASTH_KERNEL_SEQ_REDUCE, st);
+    hipLaunchKernelGGL(seq_reduce_kernel, dim3((unsigned)((nd + 255) / 256)), dim3(256), 0, st, (const float*)dVpart,
+                       dV, nd, m);
+  }
   FASTH_HIP(hipGetLastError());
   return FASTH_OK;
 }

@@ -30,7 +30,7 @@ __device__ __forceinline__ f32x4 tile_mma(const float* As, int sai, int sak, con
 // Each exchange halves the number of live values, so NV values cost NV - 1 + log2(64 / NV) shuffles.
 template <int NV>
 __device__ __forceinline__ void wave_reduce_multi(float (&v)[NV]) {
-  static_assert(NV == 1 || NV == 2 || NV == 4 || NV == 8 || NV == 16 || NV == 32, "NV must be a power of two");
+  static_assert(NV == 1 || NV == 2 || NV == 4 || NV == 8 || NV == 16 || NV == 32 || NV == 64, "NV must be a power of two");
   const int lane = threadIdx.x & (kWave - 1);
   int mask = 32;
 #pragma unroll
@@ -46,6 +46,90 @@ __device__ __forceinline__ void wave_reduce_multi(float (&v)[NV]) {
   }
 #pragma unroll
   for (; mask >= 1; mask >>= 1) v[0] += __shfl_xor(v[0], mask, kWave);
+}
+
+// Cross-lane moves used by the register-only reduction below.
+//   swap32 / swap16: v_permlane32_swap / v_permlane16_swap exchange the odd 32-lane half (16-lane
+//   row) of the first operand with the even half (row) of the second, so x + y afterwards is
+//   "what I keep + what my partner sent" for both partners at once.
+//   dpp_*: DPP row_mirror (lane i <-> 15 - i), row_half_mirror (i <-> 7 - i) and quad permutes
+//   (i <-> i ^ 2, i <-> i ^ 1). Each pairs a lane with one whose bit 3 / 2 / 1 / 0 differs.
+typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ float swap32_sum(float keep_lo, float keep_hi) {
+  const u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(keep_lo), __float_as_uint(keep_hi), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+__device__ __forceinline__ float swap16_sum(float keep_lo, float keep_hi) {
+  const u32x2 r = __builtin_amdgcn_permlane16_swap(__float_as_uint(keep_lo), __float_as_uint(keep_hi), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float x) {
+  return __uint_as_float(__builtin_amdgcn_update_dpp(0u, __float_as_uint(x), CTRL, 0xF, 0xF, false));
+}
+constexpr int kDppRowMirror = 0x140, kDppRowHalfMirror = 0x141, kDppQuadXor2 = 0x4E, kDppQuadXor1 = 0xB1;
+
+template <int MASK>
+__device__ __forceinline__ float partner_value(float x) {
+  if constexpr (MASK == 8) return dpp_move<kDppRowMirror>(x);
+  else if constexpr (MASK == 4) return dpp_move<kDppRowHalfMirror>(x);
+  else if constexpr (MASK == 2) return dpp_move<kDppQuadXor2>(x);
+  else return dpp_move<kDppQuadXor1>(x);
+}
+
+// One halving stage of the multi-value reduction: CNT live values -> CNT / 2.
+template <int NV, int CNT, int MASK>
+__device__ __forceinline__ void reduce_stage(float (&v)[NV], int lane) {
+  if constexpr (CNT > 1) {
+#pragma unroll
+    for (int idx = 0; idx < CNT / 2; ++idx) {
+      if constexpr (MASK == 32) v[idx] = swap32_sum(v[idx], v[idx + CNT / 2]);
+      else if constexpr (MASK == 16) v[idx] = swap16_sum(v[idx], v[idx + CNT / 2]);
+      else {
+        const bool upper = (lane & MASK) != 0;
+        const float send = upper ? v[idx] : v[idx + CNT / 2];
+        const float keep = upper ? v[idx + CNT / 2] : v[idx];
+        v[idx] = keep + partner_value<MASK>(send);
+      }
+    }
+  } else {
+    if constexpr (MASK == 32) v[0] = swap32_sum(v[0], v[0]);
+    else if constexpr (MASK == 16) v[0] = swap16_sum(v[0], v[0]);
+    else v[0] += partner_value<MASK>(v[0]);
+  }
+}
+
+// Same contract as wave_reduce_multi (same reduce_sel / reduce_writer_mask), but entirely in
+// vector registers: no LDS crossbar traffic. Lanes that share a `sel` may differ in the last
+// bits (different summation order), so only the writer lanes' copies are to be used.
+template <int NV>
+__device__ __forceinline__ void wave_reduce_multi_reg(float (&v)[NV]) {
+  static_assert(NV == 1 || NV == 2 || NV == 4 || NV == 8 || NV == 16 || NV == 32 || NV == 64, "power of two");
+  const int lane = threadIdx.x & (kWave - 1);
+  reduce_stage<NV, NV, 32>(v, lane);
+  reduce_stage<NV, (NV >= 2 ? NV / 2 : 1), 16>(v, lane);
+  reduce_stage<NV, (NV >= 4 ? NV / 4 : 1), 8>(v, lane);
+  reduce_stage<NV, (NV >= 8 ? NV / 8 : 1), 4>(v, lane);
+  reduce_stage<NV, (NV >= 16 ? NV / 16 : 1), 2>(v, lane);
+  reduce_stage<NV, (NV >= 32 ? NV / 32 : 1), 1>(v, lane);
+}
+
+// Sum over groups of G consecutive lanes (G = 4, 8 or 16); every lane of the group gets the total.
+template <int G>
+__device__ __forceinline__ float group_sum(float x) {
+  x += dpp_move<kDppQuadXor1>(x);
+  x += dpp_move<kDppQuadXor2>(x);
+  if constexpr (G >= 8) x += dpp_move<kDppRowHalfMirror>(x);
+  if constexpr (G >= 16) x += dpp_move<kDppRowMirror>(x);
+  return x;
+}
+
+// Barrier that orders LDS traffic only: global loads issued earlier (prefetches) stay in flight.
+__device__ __forceinline__ void lds_barrier() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
 // Index of the input value whose wave-wide sum wave_reduce_multi<NV> leaves in this lane's v[0].
