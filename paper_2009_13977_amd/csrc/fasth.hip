@@ -21,6 +21,7 @@
 
 #include <cstdint>
 #include <cstdio>
+#include <cstdlib>
 #include <vector>
 
 #include "fasth.h"
@@ -187,8 +188,8 @@ __global__ void __launch_bounds__(256) gram_partial_kernel(const float* __restri
 
 // ------------------------------------------------------------------------------------------
 // Algorithm 1 Step 1b: T_i = (diag(S)/2 + striu(S))^-1, one workgroup per block.
-// 16x16 diagonal blocks by back substitution, then [[T11, -T11 M12 T22], [0, T22]] doubling the
-// block size each level with matrix-core products. Rows/columns >= k (padding) form an identity.
+// From 1x1 diagonal blocks, [[T11, -T11 M12 T22], [0, T22]] doubles the block size each level:
+// plain multiply-adds below 16, matrix-core products from 16 up. Rows/columns >= k (padding) form an identity.
 // ------------------------------------------------------------------------------------------
 
 __global__ void __launch_bounds__(256) t_build_kernel(const float* __restrict__ Spart, float* __restrict__ T,
@@ -196,8 +197,7 @@ __global__ void __launch_bounds__(256) t_build_kernel(const float* __restrict__ 
   extern __shared__ float smem[];
   const int LDM = kp + 4;
   float* Ms = smem;                 // [kp][LDM]
-  float* Xs = Ms + kp * LDM;        // level scratch, kp * (kp/2 + 4) / 2 floats at most
-  float* Ds = Xs + kp * (kp / 2 + 4) / 2 + 64;  // [kp/16][16][17] copies of the diagonal blocks
+  float* Xs = Ms + kp * LDM;        // level scratch: kp * (kp/2 + 4) / 2 floats at most (>= kp * 4 for the small levels)
   const int i = blockIdx.x;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const float* Sp = Spart + (size_t)i * gram_split * kp * kp;
@@ -205,7 +205,11 @@ __global__ void __launch_bounds__(256) t_build_kernel(const float* __restrict__ 
     const int j = idx / kp, l = idx % kp;
     float v = 0.f;
     if (j < k && l < k && j <= l) {
-      for (int s = 0; s < gram_split; ++s) v += Sp[(size_t)s * kp * kp + idx];
+      float part[kMaxGramSplit];  // all partial sums in flight at once
+#pragma unroll
+      for (int s = 0; s < kMaxGramSplit; ++s) part[s] = s < gram_split ? Sp[(size_t)s * kp * kp + idx] : 0.f;
+#pragma unroll
+      for (int s = 0; s < kMaxGramSplit; ++s) v += part[s];
       if (j == l) v *= 0.5f;
     } else if (j == l) {
       v = 1.f;
@@ -213,24 +217,27 @@ __global__ void __launch_bounds__(256) t_build_kernel(const float* __restrict__ 
     Ms[j * LDM + l] = v;
   }
   __syncthreads();
-  if (tid < kp) {
-    const int blk = tid >> 4, c = tid & 15, base = blk * 16;
-    float* D = Ds + blk * 16 * 17;
-    for (int r = 0; r < 16; ++r) D[r * 17 + c] = Ms[(base + r) * LDM + base + c];
-  }
+  // 1x1 diagonal blocks, then the same doubling step with plain multiply-adds (one thread per
+  // output element) while the blocks are smaller than a matrix-core tile.
+  if (tid < kp) Ms[tid * LDM + tid] = 1.f / Ms[tid * LDM + tid];
   __syncthreads();
-  if (tid < kp) {
-    const int blk = tid >> 4, c = tid & 15, base = blk * 16;
-    const float* D = Ds + blk * 16 * 17;
-    float* col = Ms + base * LDM + base + c;  // col[r * LDM] = T(r, c) of this diagonal block
-    col[c * LDM] = 1.f / D[c * 17 + c];
-    for (int r = c - 1; r >= 0; --r) {
-      float s = 0.f;
-      for (int l = r + 1; l <= c; ++l) s += D[r * 17 + l] * col[l * LDM];
-      col[r * LDM] = -s / D[r * 17 + r];
+  for (int b = 1; b < 16; b *= 2) {
+    const int outs = (kp / (2 * b)) * b * b;
+    for (int o = tid; o < outs; o += 256) {  // X = M12 T22
+      const int pr = o / (b * b), r = (o / b) % b, c = o % b, r0 = pr * 2 * b;
+      float acc = 0.f;
+      for (int t = 0; t <= c; ++t) acc += Ms[(r0 + r) * LDM + r0 + b + t] * Ms[(r0 + b + t) * LDM + r0 + b + c];
+      Xs[o] = acc;
     }
+    __syncthreads();
+    for (int o = tid; o < outs; o += 256) {  // T12 = -T11 X
+      const int pr = o / (b * b), r = (o / b) % b, c = o % b, r0 = pr * 2 * b;
+      float acc = 0.f;
+      for (int t = r; t < b; ++t) acc += Ms[(r0 + r) * LDM + r0 + t] * Xs[pr * b * b + t * b + c];
+      Ms[(r0 + r) * LDM + r0 + b + c] = -acc;
+    }
+    __syncthreads();
   }
-  __syncthreads();
   const int li = lane & 15, q = lane >> 4;
   for (int b = 16; b < kp; b *= 2) {
     const int tpb = b / 16, per_pair = tpb * tpb, items = (kp / (2 * b)) * per_pair;
@@ -258,7 +265,7 @@ __global__ void __launch_bounds__(256) t_build_kernel(const float* __restrict__ 
 }
 
 static size_t t_build_lds(int kp) {
-  return sizeof(float) * ((size_t)kp * (kp + 4) + (size_t)kp * (kp / 2 + 4) / 2 + 64 + (size_t)(kp / 16) * 16 * 17);
+  return sizeof(float) * ((size_t)kp * (kp + 4) + (size_t)kp * (kp / 2 + 4) / 2 + 64);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -282,6 +289,7 @@ struct ChainArgs {
   int in_scale_mode;
   int d, n, m, k, kp, nb;
   int transpose;
+  int debug;
 };
 
 template <int U>
@@ -520,6 +528,194 @@ __global__ void __launch_bounds__(256) chain_fast_kernel(ChainArgs p) {
   }
 }
 
+// Second register-resident variant: NT threads (NT / 64 waves, two per SIMD at NT = 512) each own
+// one VW-wide chunk of the column, so a whole k x d block is K * VW registers per thread and two
+// blocks fit without spilling into accumulation registers. With SPREAD the loads of the next block
+// are issued a few at a time between the multiply-adds of the current one, so the address unit
+// (64 B per clock per CU) is fed evenly instead of in one burst that stalls the wave behind it.
+template <int VW> struct VecOf;
+template <> struct VecOf<1> { typedef float type; };
+template <> struct VecOf<2> { typedef float2 type; };
+template <> struct VecOf<4> { typedef float4 type; };
+
+template <int VW>
+struct Chunk {
+  float e[VW];
+};
+
+template <int VW>
+__device__ __forceinline__ Chunk<VW> load_chunk(const float* ptr) {
+  Chunk<VW> c;
+  const typename VecOf<VW>::type v = *reinterpret_cast<const typename VecOf<VW>::type*>(ptr);
+  if constexpr (VW == 1) { c.e[0] = v; }
+  else if constexpr (VW == 2) { c.e[0] = v.x; c.e[1] = v.y; }
+  else { c.e[0] = v.x; c.e[1] = v.y; c.e[2] = v.z; c.e[3] = v.w; }
+  return c;
+}
+
+template <int VW>
+__device__ __forceinline__ void store_chunk(float* ptr, const Chunk<VW>& c) {
+  typename VecOf<VW>::type v;
+  if constexpr (VW == 1) { v = c.e[0]; }
+  else if constexpr (VW == 2) { v.x = c.e[0]; v.y = c.e[1]; }
+  else { v.x = c.e[0]; v.y = c.e[1]; v.z = c.e[2]; v.w = c.e[3]; }
+  *reinterpret_cast<typename VecOf<VW>::type*>(ptr) = v;
+}
+
+template <int K, int VW, int NT>
+struct PipeRegs {
+  static constexpr int G = (NT / K) < 16 ? (NT / K) : 16;  // threads sharing one row of T
+  static constexpr int LPT = K / G;
+  Chunk<VW> v[K];
+  float t[LPT];
+};
+
+template <int K, int VW, int NT, int SPREAD>
+__global__ void __launch_bounds__(NT) chain_pipe_kernel(ChainArgs p) {
+  typedef PipeRegs<K, VW, NT> Regs;
+  constexpr int NW = NT / 64, G = Regs::G, LPT = Regs::LPT;
+  static_assert(K % 2 == 0 && K * G <= NT && LPT >= 1, "shape");
+  __shared__ float Bpart[NW][K];
+  __shared__ __align__(16) float Cv[K];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int col = blockIdx.x, m = p.m, d = p.d;
+  const int trow = tid / G, tg = tid % G;
+  const bool t_active = tid < K * G;
+  const bool ok = VW * tid < d;
+  const unsigned x0 = ok ? VW * tid : 0;  // idle threads read chunk 0 and keep their part at zero
+  Chunk<VW> a;
+#pragma unroll
+  for (int r = 0; r < VW; ++r) {
+    float v = 0.f;
+    if (ok) {
+      v = p.in[(size_t)(x0 + r) * m + col];
+      if (p.in_scale_mode == 1) v *= p.in_scale[x0 + r];
+      else if (p.in_scale_mode == 2) v /= p.in_scale[x0 + r];
+    }
+    a.e[r] = v;
+  }
+  const int sel = reduce_sel<K>(lane);
+  const int nb = p.nb;
+  auto block_of = [&](int s) { return p.transpose ? s : nb - 1 - s; };
+  const int dbg = p.debug;
+  // uniform row base (scalar registers) + 32-bit per-lane offset
+  auto row_ptr = [&](int i, int j) {
+    const float* rowbase = p.V + ((size_t)(dbg == 1 ? 0 : i) * K + (dbg == 2 ? 0 : j)) * (size_t)d;
+    return rowbase + x0;
+  };
+  auto load_t = [&](int i, Regs& r) {
+    const float* Ti = p.T + (size_t)i * K * K;
+#pragma unroll
+    for (int e = 0; e < LPT; ++e) {
+      const int l = tg + G * e;
+      const int row = t_active ? trow : 0;
+      r.t[e] = p.transpose ? Ti[l * K + row] : Ti[row * K + l];
+    }
+  };
+
+  // Applies block i held in `cur` while loading block inext into `nxt`.
+  auto apply_block = [&](int i, const Regs& cur, int inext, Regs& nxt) {
+    if (p.save_in && ok) store_chunk<VW>(p.save_in + ((size_t)i * m + col) * d + x0, a);
+    if constexpr (SPREAD == 0) {
+#pragma unroll
+      for (int j = 0; j < K; ++j) nxt.v[j] = load_chunk<VW>(row_ptr(inext, j));
+    }
+    float pj[K];
+#pragma unroll
+    for (int j = 0; j < K; ++j) {
+      if constexpr (SPREAD == 1) {
+        if (j % 2 == 0) {
+          nxt.v[j / 2] = load_chunk<VW>(row_ptr(inext, j / 2));
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+      if constexpr (SPREAD == 2) {
+        nxt.v[j] = load_chunk<VW>(row_ptr(inext, j));
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      float acc = 0.f;
+#pragma unroll
+      for (int r = 0; r < VW; ++r) acc = fmaf(cur.v[j].e[r], a.e[r], acc);
+      pj[j] = acc;
+    }
+    load_t(inext, nxt);
+    wave_reduce_multi_reg<K>(pj);
+    if ((lane & reduce_writer_mask<K>()) == 0) Bpart[wave][sel] = pj[0];
+    lds_barrier();
+    if (t_active) {
+      float c = 0.f;
+#pragma unroll
+      for (int e = 0; e < LPT; ++e) {
+        const int l = tg + G * e;
+        float b = 0.f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) b += Bpart[w][l];
+        c = fmaf(cur.t[e], b, c);
+      }
+      c = group_sum<G>(c);
+      if (tg == 0) {
+        Cv[trow] = c;
+        if (p.save_c) p.save_c[(size_t)col * p.n + (size_t)i * K + trow] = c;
+      }
+    }
+    lds_barrier();
+    float cc[K];  // the whole coefficient vector in one round trip to LDS
+#pragma unroll
+    for (int j4 = 0; j4 < K / 4; ++j4) {
+      const float4 c4 = reinterpret_cast<const float4*>(Cv)[j4];
+      cc[4 * j4] = c4.x; cc[4 * j4 + 1] = c4.y; cc[4 * j4 + 2] = c4.z; cc[4 * j4 + 3] = c4.w;
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int j = 0; j < K; ++j) {
+      if constexpr (SPREAD == 1) {
+        if (j % 2 == 0) {
+          nxt.v[K / 2 + j / 2] = load_chunk<VW>(row_ptr(inext, K / 2 + j / 2));
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+#pragma unroll
+      for (int r = 0; r < VW; ++r) a.e[r] = fmaf(-cc[j], cur.v[j].e[r], a.e[r]);
+    }
+    if (!ok) {
+#pragma unroll
+      for (int r = 0; r < VW; ++r) a.e[r] = 0.f;
+    }
+  };
+
+  Regs ra, rb;
+#pragma unroll
+  for (int j = 0; j < K; ++j) ra.v[j] = load_chunk<VW>(row_ptr(block_of(0), j));
+  load_t(block_of(0), ra);
+  int s = 0;
+  for (; s + 1 < nb; s += 2) {
+    apply_block(block_of(s), ra, block_of(s + 1), rb);
+    apply_block(block_of(s + 1), rb, block_of(s + 2 < nb ? s + 2 : s + 1), ra);
+  }
+  if (s < nb) apply_block(block_of(s), ra, block_of(s), rb);
+  if (ok) {
+#pragma unroll
+    for (int r = 0; r < VW; ++r) p.out[(size_t)(x0 + r) * m + col] = a.e[r];
+  }
+}
+
+template <int K, int VW, int NT, int SPREAD>
+static int launch_chain_pipe(const ChainArgs& a, hipStream_t stream) {
+  prof::Scope ps_(FASTH_KERNEL_CHAIN, stream);
+  hipLaunchKernelGGL((chain_pipe_kernel<K, VW, NT, SPREAD>), dim3(a.m), dim3(NT), 0, stream, a);
+  FASTH_HIP(hipGetLastError());
+  return FASTH_OK;
+}
+
+static int chain_variant() {
+  static int v = -1;
+  if (v < 0) {
+    const char* e = getenv("FASTH_CHAIN_VARIANT");
+    v = e ? atoi(e) : 3;
+  }
+  return v;
+}
+
 template <int K, int U4>
 static int launch_chain_fast(const ChainArgs& a, hipStream_t stream) {
   prof::Scope ps_(FASTH_KERNEL_CHAIN, stream);
@@ -530,6 +726,12 @@ static int launch_chain_fast(const ChainArgs& a, hipStream_t stream) {
 
 static int launch_chain(const ChainArgs& a, hipStream_t stream) {
   if (a.d % 4 == 0 && a.k == a.kp) {
+    if (a.k == 32 && a.d <= 1024 && chain_variant() == 1) return launch_chain_pipe<32, 2, 512, 0>(a, stream);
+    if (a.k == 32 && a.d <= 1024 && chain_variant() == 2) return launch_chain_pipe<32, 2, 512, 1>(a, stream);
+    if (a.k == 32 && a.d <= 1024 && chain_variant() == 3) return launch_chain_pipe<32, 4, 256, 1>(a, stream);
+    if (a.k == 32 && a.d <= 1024 && chain_variant() == 4) return launch_chain_pipe<32, 4, 256, 2>(a, stream);
+    if (a.k == 32 && a.d <= 1024 && chain_variant() == 5) return launch_chain_pipe<32, 2, 512, 2>(a, stream);
+    if (a.k == 32 && a.d <= 1024 && chain_variant() == 6) return launch_chain_pipe<32, 4, 256, 0>(a, stream);
     if (a.k == 32 && a.d <= 1024) return launch_chain_fast<32, 1>(a, stream);
     if (a.k == 16 && a.d <= 1024) return launch_chain_fast<16, 1>(a, stream);
     if (a.k == 16 && a.d <= 2048) return launch_chain_fast<16, 2>(a, stream);
@@ -581,22 +783,46 @@ struct DvArgs {
   int transpose;        // of the forward product
 };
 
+template <int KT>  // kp = 16 KT
 __global__ void __launch_bounds__(256) dv_kernel(DvArgs p) {
   extern __shared__ float smem[];
-  const int kp = p.kp, k = p.k, d = p.d, m = p.m, n = p.n;
-  const int LDE = kp + 4, LDC = kDvMChunk + 4, LDX = kDvTile + 4;
+  constexpr int kp = 16 * KT;
+  const int k = p.k, d = p.d, m = p.m, n = p.n;
+  constexpr int LDE = kp + 4, LDC = kDvMChunk + 4, LDX = kDvTile + 4;
   float* Es = smem;                   // [kp][LDE]
   float* Cas = Es + kp * LDE;         // [kp][LDC]
   float* Cgs = Cas + kp * LDC;        // [kp][LDC]
   float* gT = Cgs + kp * LDC;         // [kDvMChunk][LDX]
   float* aT = gT + kDvMChunk * LDX;   // [kDvMChunk][LDX]
-  float* Vs = Cas;                    // [kp][LDX], reuses Cas/Cgs after the mini-batch loop
+  float* Vs = aT + kDvMChunk * LDX;   // [kp][LDX]
   const int i = blockIdx.y, x0 = blockIdx.x * kDvTile;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, li = lane & 15, q = lane >> 4;
-  const int kt = kp / 16;
+  constexpr int kt = KT;
 
-  auto load_coeffs = [&](int mc) {
-    for (int idx = tid; idx < kp * kDvMChunk; idx += 256) {
+  // The block's rows of V are needed last; fetch them first so one trip to memory covers them
+  // and the first mini-batch chunk.
+#pragma unroll
+  for (int it = 0; it < kp * kDvTile / 256; ++it) {
+    const int idx = tid + it * 256;
+    const int j = idx / kDvTile, x = idx % kDvTile;
+    float v = 0.f;
+    if (j < k && x0 + x < d) v = p.V[((size_t)i * k + j) * d + x0 + x];
+    Vs[j * LDX + x] = v;
+  }
+
+  // One pass over the mini-batch accumulates both Z = Cg Ca^T and Ca g^T + Cg a^T.
+  constexpr int kMaxZ = (KT * KT + 3) / 4;  // Z tiles per wave
+  constexpr int kMaxAcc = KT;               // KT x 4 output tiles over 4 waves
+  f32x4 z[kMaxZ], acc[kMaxAcc];
+#pragma unroll
+  for (int w = 0; w < kMaxZ; ++w) z[w] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int w = 0; w < kMaxAcc; ++w) acc[w] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int mc = 0; mc < m; mc += kDvMChunk) {
+    if (mc) __syncthreads();
+#pragma unroll
+    for (int it = 0; it < kp * kDvMChunk / 256; ++it) {
+      const int idx = tid + it * 256;
       const int j = idx % kp, lc = idx / kp;
       float ca = 0.f, cg = 0.f;
       if (j < k && mc + lc < m) {
@@ -607,56 +833,9 @@ __global__ void __launch_bounds__(256) dv_kernel(DvArgs p) {
       Cas[j * LDC + lc] = ca;
       Cgs[j * LDC + lc] = cg;
     }
-  };
-
-  // Z = Cg Ca^T, accumulated over the mini-batch in chunks.
-  constexpr int kMaxZ = 16;  // kp = 128: 64 tiles over 4 waves
-  f32x4 z[kMaxZ];
 #pragma unroll
-  for (int w = 0; w < kMaxZ; ++w) z[w] = f32x4{0.f, 0.f, 0.f, 0.f};
-  for (int mc = 0; mc < m; mc += kDvMChunk) {
-    load_coeffs(mc);
-    __syncthreads();
-#pragma unroll
-    for (int w = 0; w < kMaxZ; ++w) {
-      const int t = wave + 4 * w;
-      if (t < kt * kt) {
-        const int ti = t / kt, tj = t % kt;
-        z[w] = tile_mma(Cgs + ti * 16 * LDC, LDC, 1, Cas + tj * 16 * LDC, 1, LDC, kDvMChunk, z[w]);
-      }
-    }
-    __syncthreads();
-  }
-#pragma unroll
-  for (int w = 0; w < kMaxZ; ++w) {
-    const int t = wave + 4 * w;
-    if (t < kt * kt) {
-      const int ti = t / kt, tj = t % kt;
-#pragma unroll
-      for (int jj = 0; jj < 4; ++jj) Es[(ti * 16 + 4 * q + jj) * LDE + tj * 16 + li] = z[w][jj];
-    }
-  }
-  __syncthreads();
-  // Mirror the triangle that carries the gradient of T_i^-1 and store -E.
-  for (int idx = tid; idx < kp * kp; idx += 256) {
-    const int r = idx / kp, c = idx % kp;
-    if (r < c) {
-      if (p.transpose) Es[r * LDE + c] = Es[c * LDE + r];
-      else Es[c * LDE + r] = Es[r * LDE + c];
-    }
-  }
-  __syncthreads();
-  for (int idx = tid; idx < kp * kp; idx += 256) Es[(idx / kp) * LDE + idx % kp] *= -1.f;
-
-  // acc = Ca g^T + Cg a^T - E V_i over this workgroup's 64 columns of dV.
-  constexpr int kMaxAcc = 8;  // kp = 128: 8 x 4 tiles over 4 waves
-  f32x4 acc[kMaxAcc];
-#pragma unroll
-  for (int w = 0; w < kMaxAcc; ++w) acc[w] = f32x4{0.f, 0.f, 0.f, 0.f};
-  for (int mc = 0; mc < m; mc += kDvMChunk) {
-    __syncthreads();
-    load_coeffs(mc);
-    for (int idx = tid; idx < kDvMChunk * kDvTile; idx += 256) {
+    for (int it = 0; it < kDvMChunk * kDvTile / 256; ++it) {
+      const int idx = tid + it * 256;
       const int lc = idx / kDvTile, x = idx % kDvTile;
       float g = 0.f, a = 0.f;
       if (mc + lc < m && x0 + x < d) {
@@ -669,6 +848,14 @@ __global__ void __launch_bounds__(256) dv_kernel(DvArgs p) {
     }
     __syncthreads();
 #pragma unroll
+    for (int w = 0; w < kMaxZ; ++w) {
+      const int t = wave + 4 * w;
+      if (t < kt * kt) {
+        const int ti = t / kt, tj = t % kt;
+        z[w] = tile_mma(Cgs + ti * 16 * LDC, LDC, 1, Cas + tj * 16 * LDC, 1, LDC, kDvMChunk, z[w]);
+      }
+    }
+#pragma unroll
     for (int w = 0; w < kMaxAcc; ++w) {
       const int t = wave + 4 * w;
       if (t < kt * 4) {
@@ -678,31 +865,48 @@ __global__ void __launch_bounds__(256) dv_kernel(DvArgs p) {
       }
     }
   }
-  __syncthreads();
-  for (int idx = tid; idx < kp * kDvTile; idx += 256) {
-    const int j = idx / kDvTile, x = idx % kDvTile;
-    float v = 0.f;
-    if (j < k && x0 + x < d) v = p.V[((size_t)i * k + j) * d + x0 + x];
-    Vs[j * LDX + x] = v;
+  // E: mirror the triangle of Z that carries the gradient of T_i^-1. The matrix-core layout gives
+  // lane (q, li) the entries Z(16 ti + 4 q + jj, 16 tj + li); each is written to its own place and,
+  // if it lies in the carrying triangle, to the mirrored place as well.
+#pragma unroll
+  for (int w = 0; w < kMaxZ; ++w) {
+    const int t = wave + 4 * w;
+    if (t < kt * kt) {
+      const int ti = t / kt, tj = t % kt;
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) {
+        const int r = ti * 16 + 4 * q + jj, c = tj * 16 + li;
+        const bool carries = p.transpose ? (r > c) : (r < c);
+        if (carries) {
+          Es[r * LDE + c] = z[w][jj];
+          Es[c * LDE + r] = z[w][jj];
+        } else if (r == c) {
+          Es[r * LDE + c] = z[w][jj];
+        }
+      }
+    }
   }
   __syncthreads();
+  // dV_i = -(Ca g^T + Cg a^T) + E V_i
 #pragma unroll
   for (int w = 0; w < kMaxAcc; ++w) {
     const int t = wave + 4 * w;
     if (t < kt * 4) {
       const int ti = t / 4, tx = t % 4;
-      acc[w] = tile_mma(Es + ti * 16 * LDE, LDE, 1, Vs + tx * 16, LDX, 1, kp, acc[w]);
+      f32x4 ev = {0.f, 0.f, 0.f, 0.f};
+      ev = tile_mma(Es + ti * 16 * LDE, LDE, 1, Vs + tx * 16, LDX, 1, kp, ev);
 #pragma unroll
       for (int jj = 0; jj < 4; ++jj) {
         const int j = ti * 16 + 4 * q + jj, x = x0 + tx * 16 + li;
-        if (j < k && x < d) p.dV[((size_t)i * k + j) * d + x] = -acc[w][jj];
+        if (j < k && x < d) p.dV[((size_t)i * k + j) * d + x] = ev[jj] - acc[w][jj];
       }
     }
   }
 }
 
 static size_t dv_lds(int kp) {
-  return sizeof(float) * ((size_t)kp * (kp + 4) + 2 * (size_t)kp * (kDvMChunk + 4) + 2 * (size_t)kDvMChunk * (kDvTile + 4));
+  return sizeof(float) * ((size_t)kp * (kp + 4) + 2 * (size_t)kp * (kDvMChunk + 4) +
+                          2 * (size_t)kDvMChunk * (kDvTile + 4) + (size_t)kp * (kDvTile + 4));
 }
 
 // ------------------------------------------------------------------------------------------
@@ -901,6 +1105,7 @@ static int run_chain(const Product& P, const float* V, const float* in, float* o
   a.in_scale = in_scale; a.in_scale_mode = in_scale_mode;
   a.d = P.d; a.n = P.n; a.m = P.m; a.k = P.k; a.kp = P.L.kp; a.nb = P.L.nb;
   a.transpose = transpose;
+  { const char* e = getenv("FASTH_CHAIN_DEBUG"); a.debug = e ? atoi(e) : 0; }
   return launch_chain(a, stream);
 }
 
@@ -909,10 +1114,21 @@ static int run_dv(const Product& P, const float* V, float* dV, int transpose, hi
   a.V = V; a.saveA = P.saveA(); a.saveCa = P.saveCa(); a.saveG = P.saveG(); a.saveCg = P.saveCg(); a.dV = dV;
   a.d = P.d; a.n = P.n; a.m = P.m; a.k = P.k; a.kp = P.L.kp; a.transpose = transpose;
   const size_t lds = dv_lds(P.L.kp);
-  int rc = allow_lds(dv_kernel, lds);
-  if (rc != FASTH_OK) return rc;
+  const dim3 grid((P.d + kDvTile - 1) / kDvTile, P.L.nb);
   prof::Scope ps_(FASTH_KERNEL_DV, stream);
-  hipLaunchKernelGGL(dv_kernel, dim3((P.d + kDvTile - 1) / kDvTile, P.L.nb), dim3(256), lds, stream, a);
+#define FASTH_LAUNCH_DV(KT)                                                  \
+  do {                                                                       \
+    int rc_ = allow_lds(dv_kernel<KT>, lds);                                 \
+    if (rc_ != FASTH_OK) return rc_;                                         \
+    hipLaunchKernelGGL(dv_kernel<KT>, grid, dim3(256), lds, stream, a);      \
+  } while (0)
+  switch (P.L.kp) {
+    case 16: FASTH_LAUNCH_DV(1); break;
+    case 32: FASTH_LAUNCH_DV(2); break;
+    case 64: FASTH_LAUNCH_DV(4); break;
+    default: FASTH_LAUNCH_DV(8); break;
+  }
+#undef FASTH_LAUNCH_DV
   FASTH_HIP(hipGetLastError());
   return FASTH_OK;
 }
