@@ -289,7 +289,6 @@ struct ChainArgs {
   int in_scale_mode;
   int d, n, m, k, kp, nb;
   int transpose;
-  int debug;
 };
 
 template <int U>
@@ -382,157 +381,18 @@ __global__ void __launch_bounds__(1024) chain_kernel(ChainArgs p) {
   }
 }
 
-// Register-resident variant for k = K exactly and d a multiple of 4 with d <= 1024 * U4.
-// Thread t owns the float4 chunks c = t + 256 u of every row, so one wave load covers 1 KiB of a
-// row. The k x d block V_i is loaded once into registers and used for both products; the next
-// block (and the thread's entries of T_{i+1}) is loaded while the current one is being applied, and
-// the barriers order LDS traffic only, so those loads stay in flight across them.
-template <int K, int U4>
-struct ChainBlockRegs {
-  float4 v[K][U4];
-  float t[K * K / 256];
-};
-
-template <int K, int U4>
-__global__ void __launch_bounds__(256) chain_fast_kernel(ChainArgs p) {
-  constexpr int NT = 256, NW = 4, G = NT / K, LPT = K / G;  // G threads share one row of T
-  static_assert(K == 16 || K == 32 || K == 64, "block size");
-  __shared__ float Bpart[NW][K];
-  __shared__ __align__(16) float Cv[K];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int col = blockIdx.x, m = p.m, d4 = p.d >> 2;
-  const int trow = tid / G, tg = tid % G;
-  const float4* V4 = reinterpret_cast<const float4*>(p.V);
-  // Threads whose chunk lies beyond d load chunk 0 instead (always valid memory) and keep their
-  // part of the column at zero, so they contribute nothing and need no branch per load.
-  bool ok[U4];
-  int cidx[U4];
-  float4 a[U4];
-#pragma unroll
-  for (int u = 0; u < U4; ++u) {
-    const int c = tid + u * NT;
-    ok[u] = c < d4;
-    cidx[u] = ok[u] ? c : 0;
-    a[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (ok[u]) {
-      float e[4];
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const int x = 4 * c + r;
-        float v = p.in[(size_t)x * m + col];
-        if (p.in_scale_mode == 1) v *= p.in_scale[x];
-        else if (p.in_scale_mode == 2) v /= p.in_scale[x];
-        e[r] = v;
-      }
-      a[u] = make_float4(e[0], e[1], e[2], e[3]);
-    }
-  }
-  const int sel = reduce_sel<K>(lane);
-
-  auto load_block = [&](int i, ChainBlockRegs<K, U4>& r) {
-    const float4* Vi = V4 + (size_t)i * K * d4;
-#pragma unroll
-    for (int j = 0; j < K; ++j) {
-#pragma unroll
-      for (int u = 0; u < U4; ++u) {
-        r.v[j][u] = Vi[(size_t)j * d4 + cidx[u]];
-      }
-    }
-    const float* Ti = p.T + (size_t)i * K * K;
-#pragma unroll
-    for (int e = 0; e < LPT; ++e) {
-      const int l = tg + G * e;
-      r.t[e] = p.transpose ? Ti[l * K + trow] : Ti[trow * K + l];
-    }
-  };
-
-  auto apply_block = [&](int i, const ChainBlockRegs<K, U4>& r) {
-    if (p.save_in) {
-      float4* dst = reinterpret_cast<float4*>(p.save_in + ((size_t)i * m + col) * p.d);
-#pragma unroll
-      for (int u = 0; u < U4; ++u)
-        if (ok[u]) dst[tid + u * NT] = a[u];
-    }
-    float pj[K];
-#pragma unroll
-    for (int j = 0; j < K; ++j) {
-      float acc = 0.f;
-#pragma unroll
-      for (int u = 0; u < U4; ++u) {
-        acc = fmaf(r.v[j][u].x, a[u].x, acc);
-        acc = fmaf(r.v[j][u].y, a[u].y, acc);
-        acc = fmaf(r.v[j][u].z, a[u].z, acc);
-        acc = fmaf(r.v[j][u].w, a[u].w, acc);
-      }
-      pj[j] = acc;
-    }
-    wave_reduce_multi_reg<K>(pj);
-    if ((lane & reduce_writer_mask<K>()) == 0) Bpart[wave][sel] = pj[0];
-    lds_barrier();
-    float c = 0.f;
-#pragma unroll
-    for (int e = 0; e < LPT; ++e) {
-      const int l = tg + G * e;
-      const float b = (Bpart[0][l] + Bpart[1][l]) + (Bpart[2][l] + Bpart[3][l]);
-      c = fmaf(r.t[e], b, c);
-    }
-    c = group_sum<G>(c);
-    if (tg == 0) {
-      Cv[trow] = c;
-      if (p.save_c) p.save_c[(size_t)col * p.n + (size_t)i * K + trow] = c;
-    }
-    lds_barrier();
-#pragma unroll
-    for (int j4 = 0; j4 < K / 4; ++j4) {
-      const float4 c4 = reinterpret_cast<const float4*>(Cv)[j4];
-      const float cc[4] = {c4.x, c4.y, c4.z, c4.w};
-#pragma unroll
-      for (int r4 = 0; r4 < 4; ++r4) {
-#pragma unroll
-        for (int u = 0; u < U4; ++u) {
-          a[u].x = fmaf(-cc[r4], r.v[4 * j4 + r4][u].x, a[u].x);
-          a[u].y = fmaf(-cc[r4], r.v[4 * j4 + r4][u].y, a[u].y);
-          a[u].z = fmaf(-cc[r4], r.v[4 * j4 + r4][u].z, a[u].z);
-          a[u].w = fmaf(-cc[r4], r.v[4 * j4 + r4][u].w, a[u].w);
-        }
-      }
-    }
-#pragma unroll
-    for (int u = 0; u < U4; ++u)
-      if (!ok[u]) a[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-  };
-
-  const int nb = p.nb;
-  auto block_of = [&](int s) { return p.transpose ? s : nb - 1 - s; };
-  ChainBlockRegs<K, U4> ra, rb;
-  load_block(block_of(0), ra);
-  for (int s = 0; s < nb; s += 2) {
-    // Drain the loads of `ra` here, before the next block's loads are queued behind them: the
-    // counter is in-order, so waiting any later would also wait for the new prefetch.
-    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0), other counters untouched
-    if (s + 1 < nb) load_block(block_of(s + 1), rb);
-    apply_block(block_of(s), ra);
-    if (s + 1 < nb) {
-      if (s + 2 < nb) load_block(block_of(s + 2), ra);
-      apply_block(block_of(s + 1), rb);
-    }
-  }
-#pragma unroll
-  for (int u = 0; u < U4; ++u) {
-    if (ok[u]) {
-      const int c = tid + u * NT;
-      const float e[4] = {a[u].x, a[u].y, a[u].z, a[u].w};
-#pragma unroll
-      for (int r = 0; r < 4; ++r) p.out[(size_t)(4 * c + r) * m + col] = e[r];
-    }
-  }
-}
-
-// Second register-resident variant: NT threads (NT / 64 waves, two per SIMD at NT = 512) each own
-// one VW-wide chunk of the column, so a whole k x d block is K * VW registers per thread and two
-// blocks fit without spilling into accumulation registers. With SPREAD the loads of the next block
-// are issued a few at a time between the multiply-adds of the current one, so the address unit
-// (64 B per clock per CU) is fed evenly instead of in one burst that stalls the wave behind it.
+// ---- Register-resident chain kernels -------------------------------------------------------
+// Thread t owns one VW-wide chunk of the column (x = VW t .. VW t + VW - 1), so a wave load of one
+// row of V covers 64 VW contiguous floats and the whole k x d block V_i is K * VW registers per
+// thread. V_i is read from memory once per block and used for both products.
+//
+// BUFS = 2: two register copies. The rows of block i+1 are loaded a couple at a time between the
+//           multiply-adds of block i (half during B = V_i a, half during a -= V_i^T C), which
+//           feeds the CU's address unit (64 B per clock) evenly instead of in one burst that
+//           stalls the wave behind it.
+// BUFS = 1: one copy; each row is reloaded with the next block's row right after its last use in
+//           the update. Half the registers, so twice the block fits, at a shorter prefetch lead.
+// The barriers order LDS traffic only, so global loads stay in flight across them.
 template <int VW> struct VecOf;
 template <> struct VecOf<1> { typedef float type; };
 template <> struct VecOf<2> { typedef float2 type; };
@@ -562,6 +422,23 @@ __device__ __forceinline__ void store_chunk(float* ptr, const Chunk<VW>& c) {
   *reinterpret_cast<typename VecOf<VW>::type*>(ptr) = v;
 }
 
+// Loads this thread's part of column `col` of a [d][m] matrix, with the optional row scaling.
+template <int VW>
+__device__ __forceinline__ Chunk<VW> load_column_chunk(const ChainArgs& p, int col, unsigned x0, bool ok) {
+  Chunk<VW> a;
+#pragma unroll
+  for (int r = 0; r < VW; ++r) {
+    float v = 0.f;
+    if (ok) {
+      v = p.in[(size_t)(x0 + r) * p.m + col];
+      if (p.in_scale_mode == 1) v *= p.in_scale[x0 + r];
+      else if (p.in_scale_mode == 2) v /= p.in_scale[x0 + r];
+    }
+    a.e[r] = v;
+  }
+  return a;
+}
+
 template <int K, int VW, int NT>
 struct PipeRegs {
   static constexpr int G = (NT / K) < 16 ? (NT / K) : 16;  // threads sharing one row of T
@@ -570,75 +447,55 @@ struct PipeRegs {
   float t[LPT];
 };
 
-template <int K, int VW, int NT, int SPREAD>
+template <int K, int VW, int NT, int BUFS>
 __global__ void __launch_bounds__(NT) chain_pipe_kernel(ChainArgs p) {
   typedef PipeRegs<K, VW, NT> Regs;
   constexpr int NW = NT / 64, G = Regs::G, LPT = Regs::LPT;
-  static_assert(K % 2 == 0 && K * G <= NT && LPT >= 1, "shape");
+  static_assert(K % 4 == 0 && K * G <= NT && LPT >= 1 && (BUFS == 1 || BUFS == 2), "shape");
   __shared__ float Bpart[NW][K];
   __shared__ __align__(16) float Cv[K];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int col = blockIdx.x, m = p.m, d = p.d;
   const int trow = tid / G, tg = tid % G;
   const bool t_active = tid < K * G;
+  // Threads whose chunk lies beyond d read chunk 0 (always valid memory) and keep their part of
+  // the column at zero, so they contribute nothing and need no branch per load.
   const bool ok = VW * tid < d;
-  const unsigned x0 = ok ? VW * tid : 0;  // idle threads read chunk 0 and keep their part at zero
-  Chunk<VW> a;
-#pragma unroll
-  for (int r = 0; r < VW; ++r) {
-    float v = 0.f;
-    if (ok) {
-      v = p.in[(size_t)(x0 + r) * m + col];
-      if (p.in_scale_mode == 1) v *= p.in_scale[x0 + r];
-      else if (p.in_scale_mode == 2) v /= p.in_scale[x0 + r];
-    }
-    a.e[r] = v;
-  }
+  const unsigned x0 = ok ? VW * tid : 0;
+  Chunk<VW> a = load_column_chunk<VW>(p, col, x0, ok);
   const int sel = reduce_sel<K>(lane);
   const int nb = p.nb;
   auto block_of = [&](int s) { return p.transpose ? s : nb - 1 - s; };
-  const int dbg = p.debug;
   // uniform row base (scalar registers) + 32-bit per-lane offset
-  auto row_ptr = [&](int i, int j) {
-    const float* rowbase = p.V + ((size_t)(dbg == 1 ? 0 : i) * K + (dbg == 2 ? 0 : j)) * (size_t)d;
-    return rowbase + x0;
-  };
+  auto row_ptr = [&](int i, int j) { return p.V + ((size_t)i * K + j) * (size_t)d + x0; };
   auto load_t = [&](int i, Regs& r) {
     const float* Ti = p.T + (size_t)i * K * K;
+    const int row = t_active ? trow : 0;
 #pragma unroll
     for (int e = 0; e < LPT; ++e) {
       const int l = tg + G * e;
-      const int row = t_active ? trow : 0;
       r.t[e] = p.transpose ? Ti[l * K + row] : Ti[row * K + l];
     }
   };
 
-  // Applies block i held in `cur` while loading block inext into `nxt`.
-  auto apply_block = [&](int i, const Regs& cur, int inext, Regs& nxt) {
+  // Applies block i held in `cur` while fetching block inext into `nxt` (BUFS = 1: nxt is cur).
+  auto apply_block = [&](int i, Regs& cur, int inext, Regs& nxt) {
     if (p.save_in && ok) store_chunk<VW>(p.save_in + ((size_t)i * m + col) * d + x0, a);
-    if constexpr (SPREAD == 0) {
-#pragma unroll
-      for (int j = 0; j < K; ++j) nxt.v[j] = load_chunk<VW>(row_ptr(inext, j));
-    }
     float pj[K];
 #pragma unroll
     for (int j = 0; j < K; ++j) {
-      if constexpr (SPREAD == 1) {
+      if constexpr (BUFS == 2) {
         if (j % 2 == 0) {
           nxt.v[j / 2] = load_chunk<VW>(row_ptr(inext, j / 2));
           __builtin_amdgcn_sched_barrier(0);
         }
-      }
-      if constexpr (SPREAD == 2) {
-        nxt.v[j] = load_chunk<VW>(row_ptr(inext, j));
-        __builtin_amdgcn_sched_barrier(0);
       }
       float acc = 0.f;
 #pragma unroll
       for (int r = 0; r < VW; ++r) acc = fmaf(cur.v[j].e[r], a.e[r], acc);
       pj[j] = acc;
     }
-    load_t(inext, nxt);
+    if constexpr (BUFS == 2) load_t(inext, nxt);
     wave_reduce_multi_reg<K>(pj);
     if ((lane & reduce_writer_mask<K>()) == 0) Bpart[wave][sel] = pj[0];
     lds_barrier();
@@ -658,6 +515,7 @@ __global__ void __launch_bounds__(NT) chain_pipe_kernel(ChainArgs p) {
         if (p.save_c) p.save_c[(size_t)col * p.n + (size_t)i * K + trow] = c;
       }
     }
+    if constexpr (BUFS == 1) load_t(inext, nxt);
     lds_barrier();
     float cc[K];  // the whole coefficient vector in one round trip to LDS
 #pragma unroll
@@ -668,7 +526,7 @@ __global__ void __launch_bounds__(NT) chain_pipe_kernel(ChainArgs p) {
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int j = 0; j < K; ++j) {
-      if constexpr (SPREAD == 1) {
+      if constexpr (BUFS == 2) {
         if (j % 2 == 0) {
           nxt.v[K / 2 + j / 2] = load_chunk<VW>(row_ptr(inext, K / 2 + j / 2));
           __builtin_amdgcn_sched_barrier(0);
@@ -676,6 +534,10 @@ __global__ void __launch_bounds__(NT) chain_pipe_kernel(ChainArgs p) {
       }
 #pragma unroll
       for (int r = 0; r < VW; ++r) a.e[r] = fmaf(-cc[j], cur.v[j].e[r], a.e[r]);
+      if constexpr (BUFS == 1) {
+        __builtin_amdgcn_sched_barrier(0);
+        nxt.v[j] = load_chunk<VW>(row_ptr(inext, j));
+      }
     }
     if (!ok) {
 #pragma unroll
@@ -683,60 +545,196 @@ __global__ void __launch_bounds__(NT) chain_pipe_kernel(ChainArgs p) {
     }
   };
 
-  Regs ra, rb;
+  if constexpr (BUFS == 2) {
+    Regs ra, rb;
 #pragma unroll
-  for (int j = 0; j < K; ++j) ra.v[j] = load_chunk<VW>(row_ptr(block_of(0), j));
-  load_t(block_of(0), ra);
-  int s = 0;
-  for (; s + 1 < nb; s += 2) {
-    apply_block(block_of(s), ra, block_of(s + 1), rb);
-    apply_block(block_of(s + 1), rb, block_of(s + 2 < nb ? s + 2 : s + 1), ra);
+    for (int j = 0; j < K; ++j) ra.v[j] = load_chunk<VW>(row_ptr(block_of(0), j));
+    load_t(block_of(0), ra);
+    int s = 0;
+    for (; s + 1 < nb; s += 2) {
+      apply_block(block_of(s), ra, block_of(s + 1), rb);
+      apply_block(block_of(s + 1), rb, block_of(s + 2 < nb ? s + 2 : s + 1), ra);
+    }
+    if (s < nb) apply_block(block_of(s), ra, block_of(s), rb);
+  } else {
+    Regs ra;
+#pragma unroll
+    for (int j = 0; j < K; ++j) ra.v[j] = load_chunk<VW>(row_ptr(block_of(0), j));
+    load_t(block_of(0), ra);
+    for (int s = 0; s < nb; ++s) apply_block(block_of(s), ra, block_of(s + 1 < nb ? s + 1 : s), ra);
   }
-  if (s < nb) apply_block(block_of(s), ra, block_of(s), rb);
   if (ok) {
 #pragma unroll
     for (int r = 0; r < VW; ++r) p.out[(size_t)(x0 + r) * m + col] = a.e[r];
   }
 }
 
-template <int K, int VW, int NT, int SPREAD>
+template <int K, int VW, int NT, int BUFS>
 static int launch_chain_pipe(const ChainArgs& a, hipStream_t stream) {
   prof::Scope ps_(FASTH_KERNEL_CHAIN, stream);
-  hipLaunchKernelGGL((chain_pipe_kernel<K, VW, NT, SPREAD>), dim3(a.m), dim3(NT), 0, stream, a);
+  hipLaunchKernelGGL((chain_pipe_kernel<K, VW, NT, BUFS>), dim3(a.m), dim3(NT), 0, stream, a);
   FASTH_HIP(hipGetLastError());
   return FASTH_OK;
 }
 
-static int chain_variant() {
-  static int v = -1;
-  if (v < 0) {
-    const char* e = getenv("FASTH_CHAIN_VARIANT");
-    v = e ? atoi(e) : 3;
+// ---- Streaming chain kernel ----------------------------------------------------------------
+// Any k <= 128 and any d <= VW * NT. The block is too large for registers, so its rows pass
+// through them eight at a time, twice per block (once per product); the second read comes from
+// the L2. The next group of rows is fetched while the current one is used.
+template <int VW, int NT>
+__global__ void __launch_bounds__(NT) chain_stream_kernel(ChainArgs p) {
+  extern __shared__ float smem[];
+  constexpr int NW = NT / 64, R = 8;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int col = blockIdx.x, m = p.m, d = p.d, k = p.k, kp = p.kp;
+  const int LDT = kp + 4;
+  float* Ts = smem;               // [kp][LDT]: op(T_i), row-contiguous
+  float* Bpart = Ts + kp * LDT;   // [NW][kp]
+  float* Bv = Bpart + NW * kp;    // [kp]
+  float* Cpart = Bv + kp;         // [8][kp]
+  float* Cv = Cpart + 8 * kp;     // [kp]
+  const bool ok = VW * tid < d;
+  const unsigned x0 = ok ? VW * tid : 0;
+  Chunk<VW> a = load_column_chunk<VW>(p, col, x0, ok);
+  const int sel = reduce_sel<R>(lane);
+  const int ngroups = (k + R - 1) / R;
+  // matvec work split: mg threads per row of T, each over kp / mg columns
+  int mg = NT / kp < 8 ? NT / kp : 8;
+  if (mg > kp / 4) mg = kp / 4;
+  const int mrow = tid / mg, mpart = tid % mg, mlen = kp / mg;
+  for (int s = 0; s < p.nb; ++s) {
+    const int i = p.transpose ? s : p.nb - 1 - s;
+    const float* Vi = p.V + (size_t)i * k * d + x0;
+    const float* Ti = p.T + (size_t)i * kp * kp;
+    for (int idx = tid; idx < kp * kp; idx += NT) {
+      const int r = idx / kp, c = idx % kp;
+      if (p.transpose) Ts[c * LDT + r] = Ti[idx];
+      else Ts[r * LDT + c] = Ti[idx];
+    }
+    if (p.save_in && ok) store_chunk<VW>(p.save_in + ((size_t)i * m + col) * d + x0, a);
+    auto load_group = [&](int g, Chunk<VW> (&rows)[R]) {
+#pragma unroll
+      for (int jj = 0; jj < R; ++jj) {
+        const int j = min(g * R + jj, k - 1);  // rows past the block repeat its last row; their results are ignored
+        rows[jj] = load_chunk<VW>(Vi + (size_t)j * d);
+      }
+    };
+    auto dots = [&](int g, const Chunk<VW> (&rows)[R]) {
+      float pj[R];
+#pragma unroll
+      for (int jj = 0; jj < R; ++jj) {
+        float acc = 0.f;
+#pragma unroll
+        for (int r = 0; r < VW; ++r) acc = fmaf(rows[jj].e[r], a.e[r], acc);
+        pj[jj] = acc;
+      }
+      wave_reduce_multi_reg<R>(pj);
+      if ((lane & reduce_writer_mask<R>()) == 0) Bpart[wave * kp + g * R + sel] = pj[0];
+    };
+    Chunk<VW> ga[R], gb[R];
+    load_group(0, ga);
+    for (int g = 0; g < ngroups; g += 2) {
+      if (g + 1 < ngroups) load_group(g + 1, gb);
+      dots(g, ga);
+      if (g + 1 < ngroups) {
+        if (g + 2 < ngroups) load_group(g + 2, ga);
+        dots(g + 1, gb);
+      }
+    }
+    load_group(0, ga);  // first group of the second pass, in flight during the small products
+    lds_barrier();
+    if (tid < kp) {
+      float b = 0.f;
+      if (tid < k)
+        for (int w = 0; w < NW; ++w) b += Bpart[w * kp + tid];
+      Bv[tid] = b;
+    }
+    lds_barrier();
+    if (mrow < kp) {
+      const float* trow_ptr = Ts + mrow * LDT + mpart * mlen;
+      const float* bptr = Bv + mpart * mlen;
+      float c = 0.f;
+      for (int l = 0; l < mlen; l += 4) {
+        const float4 t4 = *reinterpret_cast<const float4*>(trow_ptr + l);
+        const float4 b4 = *reinterpret_cast<const float4*>(bptr + l);
+        c = fmaf(t4.x, b4.x, c); c = fmaf(t4.y, b4.y, c); c = fmaf(t4.z, b4.z, c); c = fmaf(t4.w, b4.w, c);
+      }
+      Cpart[mpart * kp + mrow] = c;
+    }
+    lds_barrier();
+    if (tid < kp) {
+      float c = 0.f;
+      for (int g = 0; g < mg; ++g) c += Cpart[g * kp + tid];
+      if (tid >= k) c = 0.f;
+      Cv[tid] = c;
+      if (p.save_c && tid < k) p.save_c[(size_t)col * p.n + (size_t)i * k + tid] = c;
+    }
+    lds_barrier();
+    auto update = [&](int g, const Chunk<VW> (&rows)[R]) {
+#pragma unroll
+      for (int jj = 0; jj < R; ++jj) {
+        const float c = Cv[g * R + jj];  // zero for rows past the block
+#pragma unroll
+        for (int r = 0; r < VW; ++r) a.e[r] = fmaf(-c, rows[jj].e[r], a.e[r]);
+      }
+    };
+    for (int g = 0; g < ngroups; g += 2) {
+      if (g + 1 < ngroups) load_group(g + 1, gb);
+      update(g, ga);
+      if (g + 1 < ngroups) {
+        if (g + 2 < ngroups) load_group(g + 2, ga);
+        update(g + 1, gb);
+      }
+    }
+    if (!ok) {
+#pragma unroll
+      for (int r = 0; r < VW; ++r) a.e[r] = 0.f;
+    }
+    lds_barrier();  // Ts, Bpart and Cv are rewritten by the next block
   }
-  return v;
+  if (ok) {
+#pragma unroll
+    for (int r = 0; r < VW; ++r) p.out[(size_t)(x0 + r) * m + col] = a.e[r];
+  }
 }
 
-template <int K, int U4>
-static int launch_chain_fast(const ChainArgs& a, hipStream_t stream) {
+template <int VW, int NT>
+static int launch_chain_stream(const ChainArgs& a, hipStream_t stream) {
+  const size_t lds = sizeof(float) * ((size_t)a.kp * (a.kp + 4) + (size_t)(NT / 64) * a.kp + 10 * (size_t)a.kp);
+  int rc = allow_lds(chain_stream_kernel<VW, NT>, lds);
+  if (rc != FASTH_OK) return rc;
   prof::Scope ps_(FASTH_KERNEL_CHAIN, stream);
-  hipLaunchKernelGGL((chain_fast_kernel<K, U4>), dim3(a.m), dim3(256), 0, stream, a);
+  hipLaunchKernelGGL((chain_stream_kernel<VW, NT>), dim3(a.m), dim3(NT), lds, stream, a);
   FASTH_HIP(hipGetLastError());
   return FASTH_OK;
+}
+
+template <int VW>
+static int launch_chain_stream_vw(const ChainArgs& a, hipStream_t stream) {
+  const int chunks = a.d / VW;
+  if (chunks <= 256) return launch_chain_stream<VW, 256>(a, stream);
+  if (chunks <= 512) return launch_chain_stream<VW, 512>(a, stream);
+  return launch_chain_stream<VW, 1024>(a, stream);
 }
 
 static int launch_chain(const ChainArgs& a, hipStream_t stream) {
-  if (a.d % 4 == 0 && a.k == a.kp) {
-    if (a.k == 32 && a.d <= 1024 && chain_variant() == 1) return launch_chain_pipe<32, 2, 512, 0>(a, stream);
-    if (a.k == 32 && a.d <= 1024 && chain_variant() == 2) return launch_chain_pipe<32, 2, 512, 1>(a, stream);
-    if (a.k == 32 && a.d <= 1024 && chain_variant() == 3) return launch_chain_pipe<32, 4, 256, 1>(a, stream);
-    if (a.k == 32 && a.d <= 1024 && chain_variant() == 4) return launch_chain_pipe<32, 4, 256, 2>(a, stream);
-    if (a.k == 32 && a.d <= 1024 && chain_variant() == 5) return launch_chain_pipe<32, 2, 512, 2>(a, stream);
-    if (a.k == 32 && a.d <= 1024 && chain_variant() == 6) return launch_chain_pipe<32, 4, 256, 0>(a, stream);
-    if (a.k == 32 && a.d <= 1024) return launch_chain_fast<32, 1>(a, stream);
-    if (a.k == 16 && a.d <= 1024) return launch_chain_fast<16, 1>(a, stream);
-    if (a.k == 16 && a.d <= 2048) return launch_chain_fast<16, 2>(a, stream);
+  const int d = a.d, k = a.k;
+  if (d % 4 == 0 && k == a.kp) {
+    // whole block in registers, two copies
+    if (k == 16 && d <= 1024) return launch_chain_pipe<16, 4, 256, 2>(a, stream);
+    if (k == 16 && d <= 2048) return launch_chain_pipe<16, 4, 512, 2>(a, stream);
+    if (k == 32 && d <= 256) return launch_chain_pipe<32, 1, 256, 2>(a, stream);
+    if (k == 32 && d <= 512) return launch_chain_pipe<32, 2, 256, 2>(a, stream);
+    if (k == 32 && d <= 1024) return launch_chain_pipe<32, 4, 256, 2>(a, stream);
+    if (k == 64 && d <= 256) return launch_chain_pipe<64, 1, 256, 2>(a, stream);
+    if (k == 64 && d <= 512) return launch_chain_pipe<64, 2, 256, 2>(a, stream);
+    // one copy, refilled in place
+    if (k == 32 && d <= 2048) return launch_chain_pipe<32, 4, 512, 1>(a, stream);
+    if (k == 64 && d <= 1024) return launch_chain_pipe<64, 2, 512, 1>(a, stream);
   }
-  const int d = a.d;
+  if (d % 4 == 0 && d <= 4096) return launch_chain_stream_vw<4>(a, stream);
+  if (d % 2 == 0 && d <= 2048) return launch_chain_stream_vw<2>(a, stream);
+  if (d <= 1024) return launch_chain_stream_vw<1>(a, stream);
   int threads = 256;
   if (d > 256 * 8) threads = 512;
   if (d > 512 * 8) threads = 1024;
@@ -1105,7 +1103,6 @@ static int run_chain(const Product& P, const float* V, const float* in, float* o
   a.in_scale = in_scale; a.in_scale_mode = in_scale_mode;
   a.d = P.d; a.n = P.n; a.m = P.m; a.k = P.k; a.kp = P.L.kp; a.nb = P.L.nb;
   a.transpose = transpose;
-  { const char* e = getenv("FASTH_CHAIN_DEBUG"); a.debug = e ? atoi(e) : 0; }
   return launch_chain(a, stream);
 }
 

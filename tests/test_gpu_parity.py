@@ -46,6 +46,31 @@ def test_fasth_small_cases(d, n, m, k, transpose):
     assert rel_err(dV, dV0) <= REL_TOL
 
 
+# One case per chain-kernel variant the launcher can pick: blocks held in registers once or twice
+# for k in {16, 32, 64}, the streaming kernel at every vector width and workgroup size, and the
+# generic kernel for very long vectors. Few reflections and columns keep the checker fast.
+DISPATCH = [
+    (1024, 32, 3, 16), (2048, 32, 3, 16),
+    (256, 64, 3, 32), (512, 64, 3, 32), (1024, 96, 3, 32), (2048, 64, 3, 32), (1500, 64, 3, 32),
+    (256, 128, 3, 64), (512, 128, 3, 64), (1024, 128, 3, 64), (1000, 128, 2, 64),
+    (1024, 256, 3, 128), (2048, 128, 2, 64), (4096, 64, 2, 32), (3000, 48, 2, 24),
+    (2046, 32, 2, 32), (1022, 40, 2, 8), (1023, 32, 2, 16), (777, 21, 2, 7),
+    (4100, 32, 2, 16), (5001, 16, 2, 8),
+]
+
+
+@pytest.mark.parametrize("transpose", [False, True])
+@pytest.mark.parametrize("d,n,m,k", DISPATCH)
+def test_fasth_every_chain_kernel(d, n, m, k, transpose):
+    _say(f"fasth dispatch d={d} n={n} m={m} k={k} transpose={transpose}")
+    p = synthetic.householder_problem(d, n, m, seed=4000 + d + n + m + k)
+    A, dV, dX = gpu_fasth(p["V"], p["X"], p["G"], k, transpose)
+    A0, dV0, dX0 = orc.product_gradients(p["V"], p["X"], p["G"], transpose=transpose)
+    assert rel_err(A, A0) <= REL_TOL
+    assert rel_err(dX, dX0) <= REL_TOL
+    assert rel_err(dV, dV0) <= REL_TOL
+
+
 @pytest.mark.parametrize("name", ["d64_m32_k32", "d256_m32_k32", "d1024_m32_k32",
                                   "d2048_m64_k32", "d2048_m64_k64", "d2048_m64_k128"])
 def test_fasth_benchmark_configs(name):
