@@ -26,6 +26,7 @@ if ROOT not in sys.path:
 
 FP32_MATRIX_PEAK_TFLOPS = 157.3  # MI355X published dense fp32 matrix (MFMA) and packed-vector peak
 HBM_PEAK_GBS = 8000.0
+CHAIN_TRAFFIC_BYTES = {"d1024_m32_k32": 17499.0 * 1024 * 2.0 + 5248.0 * 1024}
 
 
 def f_paper(d, n, m, k):
@@ -54,6 +55,10 @@ def main() -> int:
     ap.add_argument("--workload", default=None, help="name in paper_2009_13977_amd.synthetic.WORKLOADS")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sequential", action="store_true")
+    ap.add_argument("--copy-calibration-mib", type=int, default=0,
+                    help="also run a plain device-to-device copy of this many MiB (three times) so that a "
+                         "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE run of this command can be scaled by a kernel "
+                         "of known traffic")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (the path shards over mini-batch columns; "
@@ -96,6 +101,14 @@ def main() -> int:
         e1.record()
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / reps  # ms per call
+
+    if args.copy_calibration_mib > 0:
+        src = torch.ones(args.copy_calibration_mib * 1024 * 1024 // 4, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         step()
@@ -152,7 +165,10 @@ def main() -> int:
             "peak": FP32_MATRIX_PEAK_TFLOPS,
             "unit": "TFLOP/s",
             "frac": chain_tflops / FP32_MATRIX_PEAK_TFLOPS,
-            "traffic": None,
+            # HBM bytes per launch from rocprofv3 FETCH_SIZE (x2.0) + WRITE_SIZE (x1.0), scaled by a 256 MiB
+            # copy in the same run; measured for the headline workload only
+            # (profiles/hbm_traffic_d1024_m32_k32.txt).
+            "traffic": CHAIN_TRAFFIC_BYTES.get(name),
         },
     }
 
