@@ -139,7 +139,8 @@ enum {
   FASTH_KERNEL_SEQ_BACKWARD = 5,
   FASTH_KERNEL_SEQ_REDUCE = 6,
   FASTH_KERNEL_DSIGMA = 7,
-  FASTH_KERNEL_COUNT = 8
+  FASTH_KERNEL_FACTOR = 8,
+  FASTH_KERNEL_COUNT = 9
 };
 const char* fasth_kernel_name(int id);
 int fasth_profile_enable(int on);

@@ -228,7 +228,7 @@ def svd_layer_inverse_apply_backward(Uv, sigma, Vv, G, dUv, dsigma, dVv, dX, wor
     _svd_backward("svd_layer_inverse_apply_backward", Uv, sigma, Vv, G, dUv, dsigma, dVv, dX, workspace, k)
 
 
-FASTH_KERNEL_COUNT = 8
+FASTH_KERNEL_COUNT = 9
 
 
 def fasth_profile_enable(on: bool) -> None:

@@ -12,6 +12,7 @@
 // Kernels
 //   gram_partial_kernel  Algorithm 1 Step 1a: partial Gram matrices of every block (MFMA)
 //   t_build_kernel       Algorithm 1 Step 1b: T_i by blocked triangular inversion (MFMA)
+//   factor_fused_kernel  Algorithm 1 Step 1 in one kernel for block sizes up to 32
 //   chain_kernel         Algorithm 1 Step 2 / Algorithm 2 Step 1: the sequential block chain,
 //                        one workgroup per column of X (columns are independent)
 //   dv_kernel            Algorithm 2 Step 2 as dense products per block (MFMA)
@@ -192,14 +193,64 @@ __global__ void __launch_bounds__(256) gram_partial_kernel(const float* __restri
 // plain multiply-adds below 16, matrix-core products from 16 up. Rows/columns >= k (padding) form an identity.
 // ------------------------------------------------------------------------------------------
 
+// In-place inverse of the upper-triangular kp x kp matrix Ms (row stride LDM) in LDS by block
+// doubling; Xs is scratch of kp * (kp/2 + 4) / 2 + 64 floats. Called by every thread of the workgroup
+// (a multiple of 64 threads); Ms must be complete (barrier) on entry and is complete on return.
+__device__ __forceinline__ void invert_upper_lds(float* Ms, float* Xs, int kp, int LDM) {
+  const int tid = threadIdx.x, nthreads = blockDim.x, wave = tid >> 6, nwaves = nthreads >> 6, lane = tid & 63;
+  // 1x1 diagonal blocks, then the same doubling step with plain multiply-adds (one thread per
+  // output element) while the blocks are smaller than a matrix-core tile.
+  if (tid < kp) Ms[tid * LDM + tid] = 1.f / Ms[tid * LDM + tid];
+  __syncthreads();
+  for (int b = 1; b < 16; b *= 2) {
+    const int outs = (kp / (2 * b)) * b * b;
+    for (int o = tid; o < outs; o += nthreads) {  // X = M12 T22
+      const int pr = o / (b * b), r = (o / b) % b, c = o % b, r0 = pr * 2 * b;
+      float acc = 0.f;
+      for (int t = 0; t <= c; ++t) acc += Ms[(r0 + r) * LDM + r0 + b + t] * Ms[(r0 + b + t) * LDM + r0 + b + c];
+      Xs[o] = acc;
+    }
+    __syncthreads();
+    for (int o = tid; o < outs; o += nthreads) {  // T12 = -T11 X
+      const int pr = o / (b * b), r = (o / b) % b, c = o % b, r0 = pr * 2 * b;
+      float acc = 0.f;
+      for (int t = r; t < b; ++t) acc += Ms[(r0 + r) * LDM + r0 + t] * Xs[pr * b * b + t * b + c];
+      Ms[(r0 + r) * LDM + r0 + b + c] = -acc;
+    }
+    __syncthreads();
+  }
+  const int li = lane & 15, q = lane >> 4;
+  for (int b = 16; b < kp; b *= 2) {
+    const int tpb = b / 16, per_pair = tpb * tpb, items = (kp / (2 * b)) * per_pair;
+    const int LDX = b + 4;
+    for (int it = wave; it < items; it += nwaves) {  // X = M12 T22
+      const int pr = it / per_pair, ti = (it % per_pair) / tpb, tj = it % tpb, r0 = pr * 2 * b;
+      f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+      acc = tile_mma(Ms + (r0 + 16 * ti) * LDM + r0 + b, LDM, 1, Ms + (r0 + b) * LDM + r0 + b + 16 * tj, LDM, 1, b, acc);
+      float* X = Xs + pr * b * LDX;
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) X[(16 * ti + 4 * q + jj) * LDX + 16 * tj + li] = acc[jj];
+    }
+    __syncthreads();
+    for (int it = wave; it < items; it += nwaves) {  // T12 = -T11 X
+      const int pr = it / per_pair, ti = (it % per_pair) / tpb, tj = it % tpb, r0 = pr * 2 * b;
+      f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+      acc = tile_mma(Ms + (r0 + 16 * ti) * LDM + r0, LDM, 1, Xs + pr * b * LDX + 16 * tj, LDX, 1, b, acc);
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) Ms[(r0 + 16 * ti + 4 * q + jj) * LDM + r0 + b + 16 * tj + li] = -acc[jj];
+    }
+    __syncthreads();
+  }
+}
+
 __global__ void __launch_bounds__(256) t_build_kernel(const float* __restrict__ Spart, float* __restrict__ T,
                                                       int k, int kp, int gram_split) {
   extern __shared__ float smem[];
   const int LDM = kp + 4;
   float* Ms = smem;                 // [kp][LDM]
-  float* Xs = Ms + kp * LDM;        // level scratch: kp * (kp/2 + 4) / 2 floats at most (>= kp * 4 for the small levels)
+  float* Xs = Ms + kp * LDM;        // scratch of the inversion
   const int i = blockIdx.x;
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int tid = threadIdx.x;
   const float* Sp = Spart + (size_t)i * gram_split * kp * kp;
   for (int idx = tid; idx < kp * kp; idx += 256) {
     const int j = idx / kp, l = idx % kp;
@@ -217,51 +268,82 @@ __global__ void __launch_bounds__(256) t_build_kernel(const float* __restrict__ 
     Ms[j * LDM + l] = v;
   }
   __syncthreads();
-  // 1x1 diagonal blocks, then the same doubling step with plain multiply-adds (one thread per
-  // output element) while the blocks are smaller than a matrix-core tile.
-  if (tid < kp) Ms[tid * LDM + tid] = 1.f / Ms[tid * LDM + tid];
-  __syncthreads();
-  for (int b = 1; b < 16; b *= 2) {
-    const int outs = (kp / (2 * b)) * b * b;
-    for (int o = tid; o < outs; o += 256) {  // X = M12 T22
-      const int pr = o / (b * b), r = (o / b) % b, c = o % b, r0 = pr * 2 * b;
-      float acc = 0.f;
-      for (int t = 0; t <= c; ++t) acc += Ms[(r0 + r) * LDM + r0 + b + t] * Ms[(r0 + b + t) * LDM + r0 + b + c];
-      Xs[o] = acc;
-    }
-    __syncthreads();
-    for (int o = tid; o < outs; o += 256) {  // T12 = -T11 X
-      const int pr = o / (b * b), r = (o / b) % b, c = o % b, r0 = pr * 2 * b;
-      float acc = 0.f;
-      for (int t = r; t < b; ++t) acc += Ms[(r0 + r) * LDM + r0 + t] * Xs[pr * b * b + t * b + c];
-      Ms[(r0 + r) * LDM + r0 + b + c] = -acc;
-    }
-    __syncthreads();
-  }
-  const int li = lane & 15, q = lane >> 4;
-  for (int b = 16; b < kp; b *= 2) {
-    const int tpb = b / 16, per_pair = tpb * tpb, items = (kp / (2 * b)) * per_pair;
-    const int LDX = b + 4;
-    for (int it = wave; it < items; it += 4) {  // X = M12 T22
-      const int pr = it / per_pair, ti = (it % per_pair) / tpb, tj = it % tpb, r0 = pr * 2 * b;
-      f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-      acc = tile_mma(Ms + (r0 + 16 * ti) * LDM + r0 + b, LDM, 1, Ms + (r0 + b) * LDM + r0 + b + 16 * tj, LDM, 1, b, acc);
-      float* X = Xs + pr * b * LDX;
-#pragma unroll
-      for (int jj = 0; jj < 4; ++jj) X[(16 * ti + 4 * q + jj) * LDX + 16 * tj + li] = acc[jj];
-    }
-    __syncthreads();
-    for (int it = wave; it < items; it += 4) {  // T12 = -T11 X
-      const int pr = it / per_pair, ti = (it % per_pair) / tpb, tj = it % tpb, r0 = pr * 2 * b;
-      f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-      acc = tile_mma(Ms + (r0 + 16 * ti) * LDM + r0, LDM, 1, Xs + pr * b * LDX + 16 * tj, LDX, 1, b, acc);
-#pragma unroll
-      for (int jj = 0; jj < 4; ++jj) Ms[(r0 + 16 * ti + 4 * q + jj) * LDM + r0 + b + 16 * tj + li] = -acc[jj];
-    }
-    __syncthreads();
-  }
+  invert_upper_lds(Ms, Xs, kp, LDM);
   float* Ti = T + (size_t)i * kp * kp;
   for (int idx = tid; idx < kp * kp; idx += 256) Ti[idx] = Ms[(idx / kp) * LDM + idx % kp];
+}
+
+// Algorithm 1 Step 1 in one kernel for small blocks (kp = 16 KT <= 32): one workgroup of 8 waves per
+// block streams the block's rows through LDS in 128-column slabs; wave w multiplies columns
+// [16 w, 16 w + 16) of each slab, the 8 partial Gram matrices are added through LDS, and the same
+// workgroup inverts. Saves a launch and the round trip of the partial sums through memory.
+template <int KT>
+__global__ void __launch_bounds__(512) factor_fused_kernel(const float* __restrict__ V, float* __restrict__ T,
+                                                           int d, int k) {
+  constexpr int kp = 16 * KT, LD = kGramChunk + 4, NTILE = KT * (KT + 1) / 2, NW = 8, LDM = kp + 4;
+  constexpr int PER = kp * kGramChunk / 512;  // slab elements per thread
+  __shared__ float Vs[kp * LD];
+  __shared__ float Red[NW * NTILE * 256];
+  __shared__ float Ms[kp * LDM];
+  __shared__ float Xs[kp * (kp / 2 + 4) / 2 + 64];
+  const int i = blockIdx.x;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, li = lane & 15, q = lane >> 4;
+  const float* Vi = V + (size_t)i * k * d;
+  f32x4 acc[NTILE];
+#pragma unroll
+  for (int t = 0; t < NTILE; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+  float stage[PER];
+  auto fetch = [&](int x0) {
+#pragma unroll
+    for (int it = 0; it < PER; ++it) {
+      const int idx = tid + it * 512, j = idx / kGramChunk, x = idx % kGramChunk;
+      stage[it] = (j < k && x0 + x < d) ? Vi[(size_t)j * d + x0 + x] : 0.f;
+    }
+  };
+  fetch(0);
+  for (int x0 = 0; x0 < d; x0 += kGramChunk) {
+#pragma unroll
+    for (int it = 0; it < PER; ++it) {
+      const int idx = tid + it * 512;
+      Vs[(idx / kGramChunk) * LD + idx % kGramChunk] = stage[it];
+    }
+    __syncthreads();
+    if (x0 + kGramChunk < d) fetch(x0 + kGramChunk);  // next slab in flight during the products
+    int t = 0;
+#pragma unroll
+    for (int ti = 0; ti < KT; ++ti) {
+#pragma unroll
+      for (int tj = ti; tj < KT; ++tj) {
+        acc[t] = tile_mma(Vs + ti * 16 * LD + 16 * wave, LD, 1, Vs + tj * 16 * LD + 16 * wave, 1, LD, 16, acc[t]);
+        ++t;
+      }
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int t = 0; t < NTILE; ++t) {
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) Red[(wave * NTILE + t) * 256 + (4 * q + jj) * 16 + li] = acc[t][jj];
+  }
+  __syncthreads();
+  for (int idx = tid; idx < kp * kp; idx += 512) {
+    const int j = idx / kp, l = idx % kp;
+    float v = 0.f;
+    if (j < k && l < k && j <= l) {
+      const int ti = j / 16, tj = l / 16;
+      const int t = ti * KT - ti * (ti - 1) / 2 + (tj - ti);  // index of tile (ti, tj) in the upper-triangle order
+#pragma unroll
+      for (int w = 0; w < NW; ++w) v += Red[(w * NTILE + t) * 256 + (j % 16) * 16 + l % 16];
+      if (j == l) v *= 0.5f;
+    } else if (j == l) {
+      v = 1.f;
+    }
+    Ms[j * LDM + l] = v;
+  }
+  __syncthreads();
+  invert_upper_lds(Ms, Xs, kp, LDM);
+  float* Ti = T + (size_t)i * kp * kp;
+  for (int idx = tid; idx < kp * kp; idx += 512) Ti[idx] = Ms[(idx / kp) * LDM + idx % kp];
 }
 
 static size_t t_build_lds(int kp) {
@@ -447,11 +529,13 @@ struct PipeRegs {
   float t[LPT];
 };
 
-template <int K, int VW, int NT, int BUFS>
+template <int K, int VW, int NT, int BUFS, int RL = 0>  // RL: rows of the next block fetched during the reduction
 __global__ void __launch_bounds__(NT) chain_pipe_kernel(ChainArgs p) {
   typedef PipeRegs<K, VW, NT> Regs;
   constexpr int NW = NT / 64, G = Regs::G, LPT = Regs::LPT;
+  constexpr int PR = (K - RL) / 2;  // rows of the next block fetched during each of the two products
   static_assert(K % 4 == 0 && K * G <= NT && LPT >= 1 && (BUFS == 1 || BUFS == 2), "shape");
+  static_assert(RL % 2 == 0 && RL <= K / 4 && (RL == 0 || K >= 8), "prefetch split");
   __shared__ float Bpart[NW][K];
   __shared__ __align__(16) float Cv[K];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -485,7 +569,7 @@ __global__ void __launch_bounds__(NT) chain_pipe_kernel(ChainArgs p) {
 #pragma unroll
     for (int j = 0; j < K; ++j) {
       if constexpr (BUFS == 2) {
-        if (j % 2 == 0) {
+        if (j % 2 == 0 && j / 2 < PR) {
           nxt.v[j / 2] = load_chunk<VW>(row_ptr(inext, j / 2));
           __builtin_amdgcn_sched_barrier(0);
         }
@@ -496,7 +580,18 @@ __global__ void __launch_bounds__(NT) chain_pipe_kernel(ChainArgs p) {
       pj[j] = acc;
     }
     if constexpr (BUFS == 2) load_t(inext, nxt);
-    wave_reduce_multi_reg<K>(pj);
+    if constexpr (BUFS == 2 && RL > 0) {
+      auto prefetch = [&](int t) {
+        if (t % 4 == 0 && t / 4 < RL) {
+          __builtin_amdgcn_sched_barrier(0);
+          nxt.v[PR + t / 4] = load_chunk<VW>(row_ptr(inext, PR + t / 4));
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      };
+      wave_reduce_multi_reg<K>(pj, prefetch);
+    } else {
+      wave_reduce_multi_reg<K>(pj);
+    }
     if ((lane & reduce_writer_mask<K>()) == 0) Bpart[wave][sel] = pj[0];
     lds_barrier();
     if (t_active) {
@@ -527,8 +622,8 @@ __global__ void __launch_bounds__(NT) chain_pipe_kernel(ChainArgs p) {
 #pragma unroll
     for (int j = 0; j < K; ++j) {
       if constexpr (BUFS == 2) {
-        if (j % 2 == 0) {
-          nxt.v[K / 2 + j / 2] = load_chunk<VW>(row_ptr(inext, K / 2 + j / 2));
+        if (j % 2 == 0 && j / 2 < PR) {
+          nxt.v[PR + RL + j / 2] = load_chunk<VW>(row_ptr(inext, PR + RL + j / 2));
           __builtin_amdgcn_sched_barrier(0);
         }
       }
@@ -569,10 +664,10 @@ __global__ void __launch_bounds__(NT) chain_pipe_kernel(ChainArgs p) {
   }
 }
 
-template <int K, int VW, int NT, int BUFS>
+template <int K, int VW, int NT, int BUFS, int RL = 0>
 static int launch_chain_pipe(const ChainArgs& a, hipStream_t stream) {
   prof::Scope ps_(FASTH_KERNEL_CHAIN, stream);
-  hipLaunchKernelGGL((chain_pipe_kernel<K, VW, NT, BUFS>), dim3(a.m), dim3(NT), 0, stream, a);
+  hipLaunchKernelGGL((chain_pipe_kernel<K, VW, NT, BUFS, RL>), dim3(a.m), dim3(NT), 0, stream, a);
   FASTH_HIP(hipGetLastError());
   return FASTH_OK;
 }
@@ -720,14 +815,14 @@ static int launch_chain_stream_vw(const ChainArgs& a, hipStream_t stream) {
 static int launch_chain(const ChainArgs& a, hipStream_t stream) {
   const int d = a.d, k = a.k;
   if (d % 4 == 0 && k == a.kp) {
-    // whole block in registers, two copies
-    if (k == 16 && d <= 1024) return launch_chain_pipe<16, 4, 256, 2>(a, stream);
-    if (k == 16 && d <= 2048) return launch_chain_pipe<16, 4, 512, 2>(a, stream);
-    if (k == 32 && d <= 256) return launch_chain_pipe<32, 1, 256, 2>(a, stream);
-    if (k == 32 && d <= 512) return launch_chain_pipe<32, 2, 256, 2>(a, stream);
-    if (k == 32 && d <= 1024) return launch_chain_pipe<32, 4, 256, 2>(a, stream);
-    if (k == 64 && d <= 256) return launch_chain_pipe<64, 1, 256, 2>(a, stream);
-    if (k == 64 && d <= 512) return launch_chain_pipe<64, 2, 256, 2>(a, stream);
+    // whole block in registers, two copies; a quarter of the next block is fetched during the reduction
+    if (k == 16 && d <= 1024) return launch_chain_pipe<16, 4, 256, 2, 4>(a, stream);
+    if (k == 16 && d <= 2048) return launch_chain_pipe<16, 4, 512, 2, 4>(a, stream);
+    if (k == 32 && d <= 256) return launch_chain_pipe<32, 1, 256, 2, 8>(a, stream);
+    if (k == 32 && d <= 512) return launch_chain_pipe<32, 2, 256, 2, 8>(a, stream);
+    if (k == 32 && d <= 1024) return launch_chain_pipe<32, 4, 256, 2, 8>(a, stream);
+    if (k == 64 && d <= 256) return launch_chain_pipe<64, 1, 256, 2, 16>(a, stream);
+    if (k == 64 && d <= 512) return launch_chain_pipe<64, 2, 256, 2, 16>(a, stream);
     // one copy, refilled in place
     if (k == 32 && d <= 2048) return launch_chain_pipe<32, 4, 512, 1>(a, stream);
     if (k == 64 && d <= 1024) return launch_chain_pipe<64, 2, 512, 1>(a, stream);
@@ -1072,6 +1167,13 @@ static Product bind(int d, int n, int m, int k, void* ws) {
 
 static int build_factors(const Product& P, const float* V, hipStream_t stream) {
   const int kp = P.L.kp;
+  if (kp <= 32) {
+    prof::Scope ps_(FASTH_KERNEL_FACTOR, stream);
+    if (kp == 16) hipLaunchKernelGGL(factor_fused_kernel<1>, dim3(P.L.nb), dim3(512), 0, stream, V, P.T(), P.d, P.k);
+    else hipLaunchKernelGGL(factor_fused_kernel<2>, dim3(P.L.nb), dim3(512), 0, stream, V, P.T(), P.d, P.k);
+    FASTH_HIP(hipGetLastError());
+    return FASTH_OK;
+  }
   {
     const size_t lds = sizeof(float) * (size_t)kp * (kGramChunk + 4);
     int rc = allow_lds(gram_partial_kernel, lds);
@@ -1246,6 +1348,7 @@ const char* fasth_kernel_name(int id) {
     case FASTH_KERNEL_SEQ_BACKWARD: return "seq_backward_kernel";
     case FASTH_KERNEL_SEQ_REDUCE: return "seq_reduce_kernel";
     case FASTH_KERNEL_DSIGMA: return "dsigma_kernel";
+    case FASTH_KERNEL_FACTOR: return "factor_fused_kernel";
     default: return "unknown";
   }
 }

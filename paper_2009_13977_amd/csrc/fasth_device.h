@@ -79,11 +79,14 @@ __device__ __forceinline__ float partner_value(float x) {
 }
 
 // One halving stage of the multi-value reduction: CNT live values -> CNT / 2.
-template <int NV, int CNT, int MASK>
-__device__ __forceinline__ void reduce_stage(float (&v)[NV], int lane) {
+// `hook(t)` is called once before each exchange with a running index t (compile-time after
+// unrolling); callers use it to slip independent work (e.g. a prefetch) between the exchanges.
+template <int NV, int CNT, int MASK, int T0, typename Hook>
+__device__ __forceinline__ void reduce_stage(float (&v)[NV], int lane, Hook& hook) {
   if constexpr (CNT > 1) {
 #pragma unroll
     for (int idx = 0; idx < CNT / 2; ++idx) {
+      hook(T0 + idx);
       if constexpr (MASK == 32) v[idx] = swap32_sum(v[idx], v[idx + CNT / 2]);
       else if constexpr (MASK == 16) v[idx] = swap16_sum(v[idx], v[idx + CNT / 2]);
       else {
@@ -100,19 +103,30 @@ __device__ __forceinline__ void reduce_stage(float (&v)[NV], int lane) {
   }
 }
 
+struct NoHook {
+  __device__ __forceinline__ void operator()(int) const {}
+};
+
 // Same contract as wave_reduce_multi (same reduce_sel / reduce_writer_mask), but entirely in
 // vector registers: no LDS crossbar traffic. Lanes that share a `sel` may differ in the last
 // bits (different summation order), so only the writer lanes' copies are to be used.
-template <int NV>
-__device__ __forceinline__ void wave_reduce_multi_reg(float (&v)[NV]) {
+template <int NV, typename Hook>
+__device__ __forceinline__ void wave_reduce_multi_reg(float (&v)[NV], Hook& hook) {
   static_assert(NV == 1 || NV == 2 || NV == 4 || NV == 8 || NV == 16 || NV == 32 || NV == 64, "power of two");
   const int lane = threadIdx.x & (kWave - 1);
-  reduce_stage<NV, NV, 32>(v, lane);
-  reduce_stage<NV, (NV >= 2 ? NV / 2 : 1), 16>(v, lane);
-  reduce_stage<NV, (NV >= 4 ? NV / 4 : 1), 8>(v, lane);
-  reduce_stage<NV, (NV >= 8 ? NV / 8 : 1), 4>(v, lane);
-  reduce_stage<NV, (NV >= 16 ? NV / 16 : 1), 2>(v, lane);
-  reduce_stage<NV, (NV >= 32 ? NV / 32 : 1), 1>(v, lane);
+  // exchanges before each stage: NV/2, NV/4, ... (stages with one live value make none)
+  reduce_stage<NV, NV, 32, 0>(v, lane, hook);
+  reduce_stage<NV, (NV >= 2 ? NV / 2 : 1), 16, NV / 2>(v, lane, hook);
+  reduce_stage<NV, (NV >= 4 ? NV / 4 : 1), 8, NV / 2 + NV / 4>(v, lane, hook);
+  reduce_stage<NV, (NV >= 8 ? NV / 8 : 1), 4, NV / 2 + NV / 4 + NV / 8>(v, lane, hook);
+  reduce_stage<NV, (NV >= 16 ? NV / 16 : 1), 2, NV / 2 + NV / 4 + NV / 8 + NV / 16>(v, lane, hook);
+  reduce_stage<NV, (NV >= 32 ? NV / 32 : 1), 1, NV / 2 + NV / 4 + NV / 8 + NV / 16 + NV / 32>(v, lane, hook);
+}
+
+template <int NV>
+__device__ __forceinline__ void wave_reduce_multi_reg(float (&v)[NV]) {
+  NoHook h;
+  wave_reduce_multi_reg<NV>(v, h);
 }
 
 // Sum over groups of G consecutive lanes (G = 4, 8 or 16); every lane of the group gets the total.
