@@ -189,36 +189,39 @@ __global__ void __launch_bounds__(256) gram_partial_kernel(const float* __restri
 
 // ------------------------------------------------------------------------------------------
 // Algorithm 1 Step 1b: T_i = (diag(S)/2 + striu(S))^-1, one workgroup per block.
-// From 1x1 diagonal blocks, [[T11, -T11 M12 T22], [0, T22]] doubles the block size each level:
-// plain multiply-adds below 16, matrix-core products from 16 up. Rows/columns >= k (padding) form an identity.
+// 16x16 diagonal blocks by unrolled back substitution, then [[T11, -T11 M12 T22], [0, T22]] doubles
+// the block size each level with matrix-core products. Rows/columns >= k (padding) form an identity.
 // ------------------------------------------------------------------------------------------
 
 // In-place inverse of the upper-triangular kp x kp matrix Ms (row stride LDM) in LDS by block
-// doubling; Xs is scratch of kp * (kp/2 + 4) / 2 + 64 floats. Called by every thread of the workgroup
+// doubling; Xs is scratch of max(kp * (kp/2 + 4) / 2 + 64, kp * 17) floats. Called by every thread of the workgroup
 // (a multiple of 64 threads); Ms must be complete (barrier) on entry and is complete on return.
 __device__ __forceinline__ void invert_upper_lds(float* Ms, float* Xs, int kp, int LDM) {
   const int tid = threadIdx.x, nthreads = blockDim.x, wave = tid >> 6, nwaves = nthreads >> 6, lane = tid & 63;
-  // 1x1 diagonal blocks, then the same doubling step with plain multiply-adds (one thread per
-  // output element) while the blocks are smaller than a matrix-core tile.
-  if (tid < kp) Ms[tid * LDM + tid] = 1.f / Ms[tid * LDM + tid];
-  __syncthreads();
-  for (int b = 1; b < 16; b *= 2) {
-    const int outs = (kp / (2 * b)) * b * b;
-    for (int o = tid; o < outs; o += nthreads) {  // X = M12 T22
-      const int pr = o / (b * b), r = (o / b) % b, c = o % b, r0 = pr * 2 * b;
-      float acc = 0.f;
-      for (int t = 0; t <= c; ++t) acc += Ms[(r0 + r) * LDM + r0 + b + t] * Ms[(r0 + b + t) * LDM + r0 + b + c];
-      Xs[o] = acc;
-    }
-    __syncthreads();
-    for (int o = tid; o < outs; o += nthreads) {  // T12 = -T11 X
-      const int pr = o / (b * b), r = (o / b) % b, c = o % b, r0 = pr * 2 * b;
-      float acc = 0.f;
-      for (int t = r; t < b; ++t) acc += Ms[(r0 + r) * LDM + r0 + t] * Xs[pr * b * b + t * b + c];
-      Ms[(r0 + r) * LDM + r0 + b + c] = -acc;
-    }
-    __syncthreads();
+  // 16x16 diagonal blocks: thread c of a block solves for column c by back substitution, fully
+  // unrolled so that the reads of M (a copy in Xs) are independent of the values being computed.
+  float* Ds = Xs;  // [kp/16][16][17]
+  if (tid < kp) {
+    const int base = tid & ~15, c = tid & 15;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) Ds[(base + r) * 17 + c] = Ms[(base + r) * LDM + base + c];
   }
+  __syncthreads();
+  if (tid < kp) {
+    const int base = tid & ~15, c = tid & 15;
+    const float* D = Ds + base * 17;
+    float x[16];
+#pragma unroll
+    for (int r = 15; r >= 0; --r) {
+      float sum = r == c ? 1.f : 0.f;
+#pragma unroll
+      for (int l = r + 1; l < 16; ++l) sum -= D[r * 17 + l] * x[l];
+      x[r] = sum / D[r * 17 + r];  // rows below c stay exactly zero
+    }
+#pragma unroll
+    for (int r = 0; r < 16; ++r) Ms[(base + r) * LDM + base + c] = x[r];
+  }
+  __syncthreads();
   const int li = lane & 15, q = lane >> 4;
   for (int b = 16; b < kp; b *= 2) {
     const int tpb = b / 16, per_pair = tpb * tpb, items = (kp / (2 * b)) * per_pair;
@@ -285,40 +288,47 @@ __global__ void __launch_bounds__(512) factor_fused_kernel(const float* __restri
   __shared__ float Vs[kp * LD];
   __shared__ float Red[NW * NTILE * 256];
   __shared__ float Ms[kp * LDM];
-  __shared__ float Xs[kp * (kp / 2 + 4) / 2 + 64];
+  __shared__ float Xs[(kp * (kp / 2 + 4) / 2 + 64) > kp * 17 ? (kp * (kp / 2 + 4) / 2 + 64) : kp * 17];
   const int i = blockIdx.x;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, li = lane & 15, q = lane >> 4;
   const float* Vi = V + (size_t)i * k * d;
   f32x4 acc[NTILE];
 #pragma unroll
   for (int t = 0; t < NTILE; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
-  float stage[PER];
-  auto fetch = [&](int x0) {
+  // Eight slabs (1024 columns) are fetched at once, so the trip to memory is paid once per 1024
+  // columns of V instead of once per slab.
+  constexpr int NS = 8;
+  float stage[NS][PER];
+  for (int xs = 0; xs < d; xs += NS * kGramChunk) {
 #pragma unroll
-    for (int it = 0; it < PER; ++it) {
-      const int idx = tid + it * 512, j = idx / kGramChunk, x = idx % kGramChunk;
-      stage[it] = (j < k && x0 + x < d) ? Vi[(size_t)j * d + x0 + x] : 0.f;
-    }
-  };
-  fetch(0);
-  for (int x0 = 0; x0 < d; x0 += kGramChunk) {
+    for (int sl = 0; sl < NS; ++sl) {
 #pragma unroll
-    for (int it = 0; it < PER; ++it) {
-      const int idx = tid + it * 512;
-      Vs[(idx / kGramChunk) * LD + idx % kGramChunk] = stage[it];
-    }
-    __syncthreads();
-    if (x0 + kGramChunk < d) fetch(x0 + kGramChunk);  // next slab in flight during the products
-    int t = 0;
-#pragma unroll
-    for (int ti = 0; ti < KT; ++ti) {
-#pragma unroll
-      for (int tj = ti; tj < KT; ++tj) {
-        acc[t] = tile_mma(Vs + ti * 16 * LD + 16 * wave, LD, 1, Vs + tj * 16 * LD + 16 * wave, 1, LD, 16, acc[t]);
-        ++t;
+      for (int it = 0; it < PER; ++it) {
+        const int idx = tid + it * 512, j = idx / kGramChunk, x = xs + sl * kGramChunk + idx % kGramChunk;
+        stage[sl][it] = (j < k && x < d) ? Vi[(size_t)j * d + x] : 0.f;
       }
     }
-    __syncthreads();
+#pragma unroll
+    for (int sl = 0; sl < NS; ++sl) {
+      if (xs + sl * kGramChunk < d) {  // uniform across the workgroup
+#pragma unroll
+        for (int it = 0; it < PER; ++it) {
+          const int idx = tid + it * 512;
+          Vs[(idx / kGramChunk) * LD + idx % kGramChunk] = stage[sl][it];
+        }
+        __syncthreads();
+        int t = 0;
+#pragma unroll
+        for (int ti = 0; ti < KT; ++ti) {
+#pragma unroll
+          for (int tj = ti; tj < KT; ++tj) {
+            acc[t] = tile_mma(Vs + ti * 16 * LD + 16 * wave, LD, 1, Vs + tj * 16 * LD + 16 * wave, 1, LD, 16, acc[t]);
+            ++t;
+          }
+        }
+        __syncthreads();
+      }
+    }
   }
 #pragma unroll
   for (int t = 0; t < NTILE; ++t) {
@@ -347,7 +357,9 @@ __global__ void __launch_bounds__(512) factor_fused_kernel(const float* __restri
 }
 
 static size_t t_build_lds(int kp) {
-  return sizeof(float) * ((size_t)kp * (kp + 4) + (size_t)kp * (kp / 2 + 4) / 2 + 64);
+  size_t scratch = (size_t)kp * (kp / 2 + 4) / 2 + 64;
+  if (scratch < (size_t)kp * 17) scratch = (size_t)kp * 17;
+  return sizeof(float) * ((size_t)kp * (kp + 4) + scratch);
 }
 
 // ------------------------------------------------------------------------------------------
