@@ -89,6 +89,59 @@ def test_fasth_benchmark_configs(name):
     assert np.max(row / scale) < 1e-3
 
 
+def test_limits_of_the_supported_range():
+    """Longest supported vector (generic chain kernel, 1024 threads x 16 elements), the largest block
+    size, and a mini-batch wider than several LDS chunks of the dV kernel."""
+    for (d, n, m, k) in [(16384, 16, 1, 16), (16384, 8, 2, 8), (200, 128, 3, 128), (64, 64, 100, 32), (48, 32, 257, 16)]:
+        _say(f"limits d={d} n={n} m={m} k={k}")
+        p = synthetic.householder_problem(d, n, m, seed=6000 + d + n + m + k)
+        got = gpu_fasth(p["V"], p["X"], p["G"], k)
+        ref = orc.product_gradients(p["V"], p["X"], p["G"])
+        for g, r in zip(got, ref):
+            assert rel_err(g, r) <= REL_TOL
+
+
+def test_workspace_reuse_and_repeated_backward():
+    """One workspace serves calls of different shapes; backward may be called again with a new G."""
+    import torch
+    from paper_2009_13977_amd import binding as B
+    from helpers import to_gpu
+    ws = B.new_workspace(B.fasth_workspace_bytes(256, 256, 32, 32))
+    for (d, n, m, k) in [(256, 256, 32, 32), (100, 60, 5, 12), (256, 128, 16, 16)]:
+        assert B.fasth_workspace_bytes(d, n, m, k) <= ws.numel()
+        p = synthetic.householder_problem(d, n, m, seed=7000 + d)
+        Vd, Xd = to_gpu(p["V"]), to_gpu(p["X"])
+        A = torch.empty_like(Xd); dX = torch.empty_like(Xd); dV = torch.empty_like(Vd)
+        B.fasth_forward(Vd, Xd, A, ws, k)
+        for seed in (1, 2):
+            G = np.random.default_rng(seed).standard_normal((d, m)).astype(np.float32)
+            B.fasth_backward(Vd, to_gpu(G), dV, dX, ws, k)
+            torch.cuda.synchronize()
+            A0, dV0, dX0 = orc.product_gradients(p["V"], p["X"], G)
+            assert rel_err(A.cpu().numpy(), A0) <= REL_TOL
+            assert rel_err(dV.cpu().numpy(), dV0) <= REL_TOL
+            assert rel_err(dX.cpu().numpy(), dX0) <= REL_TOL
+
+
+def test_runs_on_a_side_stream():
+    import torch
+    from paper_2009_13977_amd import binding as B
+    from helpers import to_gpu
+    p = synthetic.householder_problem(128, 128, 8, seed=11)
+    Vd, Xd, Gd = (to_gpu(p[a]) for a in ("V", "X", "G"))
+    A = torch.empty_like(Xd); dX = torch.empty_like(Xd); dV = torch.empty_like(Vd)
+    ws = B.new_workspace(B.fasth_workspace_bytes(128, 128, 8, 32))
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        B.fasth_forward(Vd, Xd, A, ws, 32)
+        B.fasth_backward(Vd, Gd, dV, dX, ws, 32)
+    side.synchronize()
+    A0, dV0, dX0 = orc.product_gradients(p["V"], p["X"], p["G"])
+    assert rel_err(A.cpu().numpy(), A0) <= REL_TOL and rel_err(dV.cpu().numpy(), dV0) <= REL_TOL
+    assert rel_err(dX.cpu().numpy(), dX0) <= REL_TOL
+
+
 def test_block_size_independence():
     """Theorem 1 correctness: the result does not depend on how reflections are grouped."""
     p = synthetic.householder_problem(96, 96, 8, seed=77)
