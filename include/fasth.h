@@ -75,6 +75,17 @@ size_t fasth_workspace_bytes(const fasth_shape* shape);
 int fasth_forward(const fasth_shape* shape, const float* V, const float* X, float* A,
                   void* workspace, size_t workspace_bytes, void* stream);
 
+/* The two steps of Algorithm 1 as separate calls, for the uses of Section 3.3 ("Recurrent Layers")
+ * where one H is applied many times: fasth_prepare runs Step 1 (block factors into the workspace)
+ * once; fasth_apply runs Step 2 only and may be called any number of times, with any X of the
+ * shape's size, while V and the workspace are unchanged. With save_for_backward != 0 it also saves
+ * the block inputs, so fasth_prepare + fasth_apply(save) is exactly fasth_forward; with 0 nothing
+ * but A is written (inference). */
+int fasth_prepare(const fasth_shape* shape, const float* V, void* workspace, size_t workspace_bytes,
+                  void* stream);
+int fasth_apply(const fasth_shape* shape, const float* V, const float* X, float* A,
+                void* workspace, size_t workspace_bytes, int save_for_backward, void* stream);
+
 /* Algorithm 2. Given G = dL/dA [d][m], writes dX = dL/dX [d][m] and
  * dV [n][d] (row j-1 = dL/dv_j, summed over the m columns, Eq. 5). The
  * workspace must be exactly as the fasth_forward call with the same shape

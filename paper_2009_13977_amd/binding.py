@@ -25,6 +25,8 @@ EXPORTED_SYMBOLS = (
     "fasth_strerror",
     "fasth_workspace_bytes",
     "fasth_forward",
+    "fasth_prepare",
+    "fasth_apply",
     "fasth_backward",
     "fasth_sequential_workspace_bytes",
     "fasth_sequential_forward",
@@ -78,6 +80,10 @@ def load_library() -> ctypes.CDLL:
     lib.fasth_forward.argtypes = [shp, P, P, P, P, S, P]
     lib.fasth_backward.restype = I
     lib.fasth_backward.argtypes = [shp, P, P, P, P, P, S, P]
+    lib.fasth_prepare.restype = I
+    lib.fasth_prepare.argtypes = [shp, P, P, S, P]
+    lib.fasth_apply.restype = I
+    lib.fasth_apply.argtypes = [shp, P, P, P, P, S, I, P]
     lib.fasth_sequential_workspace_bytes.restype = S
     lib.fasth_sequential_workspace_bytes.argtypes = [shp]
     lib.fasth_sequential_forward.restype = I
@@ -160,6 +166,25 @@ def fasth_forward(V, X, A, workspace, k: int, transpose: bool = False) -> None:
     rc = load_library().fasth_forward(ctypes.byref(shape), _ptr(V, "V"), _ptr(X, "X"), _ptr(A, "A"),
                                       _ptr(workspace, "workspace"), workspace.numel(), _stream())
     _check(rc, "fasth_forward")
+
+
+def fasth_prepare(V, m: int, workspace, k: int) -> None:
+    n, d = V.shape
+    shape = _shape(d, n, m, k, False)
+    rc = load_library().fasth_prepare(ctypes.byref(shape), _ptr(V, "V"), _ptr(workspace, "workspace"),
+                                      workspace.numel(), _stream())
+    _check(rc, "fasth_prepare")
+
+
+def fasth_apply(V, X, A, workspace, k: int, transpose: bool = False, save_for_backward: bool = False) -> None:
+    n, d = V.shape
+    m = X.shape[1]
+    assert X.shape == (d, m) and A.shape == (d, m)
+    shape = _shape(d, n, m, k, transpose)
+    rc = load_library().fasth_apply(ctypes.byref(shape), _ptr(V, "V"), _ptr(X, "X"), _ptr(A, "A"),
+                                    _ptr(workspace, "workspace"), workspace.numel(),
+                                    1 if save_for_backward else 0, _stream())
+    _check(rc, "fasth_apply")
 
 
 def fasth_backward(V, G, dV, dX, workspace, k: int, transpose: bool = False) -> None:

@@ -1209,11 +1209,11 @@ static int build_factors(const Product& P, const float* V, hipStream_t stream) {
 // A = H in (transpose = 0) or H^T in (transpose = 1); activation = true saves into the activation
 // slots of the workspace, false into the gradient slots.
 static int run_chain(const Product& P, const float* V, const float* in, float* out, int transpose, bool activation,
-                     const float* in_scale, int in_scale_mode, hipStream_t stream) {
+                     const float* in_scale, int in_scale_mode, hipStream_t stream, bool save = true) {
   ChainArgs a;
   a.V = V; a.T = P.T(); a.in = in; a.out = out;
-  a.save_in = activation ? P.saveA() : P.saveG();
-  a.save_c = activation ? P.saveCa() : P.saveCg();
+  a.save_in = !save ? nullptr : activation ? P.saveA() : P.saveG();
+  a.save_c = !save ? nullptr : activation ? P.saveCa() : P.saveCg();
   a.in_scale = in_scale; a.in_scale_mode = in_scale_mode;
   a.d = P.d; a.n = P.n; a.m = P.m; a.k = P.k; a.kp = P.L.kp; a.nb = P.L.nb;
   a.transpose = transpose;
@@ -1406,6 +1406,28 @@ int fasth_forward(const fasth_shape* shape, const float* V, const float* X, floa
   hipStream_t st = static_cast<hipStream_t>(stream);
   if ((rc = build_factors(P, V, st)) != FASTH_OK) return rc;
   return run_chain(P, V, X, A, shape->transpose, true, nullptr, 0, st);
+}
+
+int fasth_prepare(const fasth_shape* shape, const float* V, void* workspace, size_t workspace_bytes, void* stream) {
+  int rc = check_shape(shape);
+  if (rc != FASTH_OK) return rc;
+  if (!V || !workspace) return FASTH_EINVAL;
+  if (!aligned16(V) || !aligned16(workspace)) return FASTH_EALIGN;
+  const Product P = bind(shape->d, shape->n, shape->m, shape->k, workspace);
+  if (workspace_bytes < P.L.total) return FASTH_EWORKSPACE;
+  return build_factors(P, V, static_cast<hipStream_t>(stream));
+}
+
+int fasth_apply(const fasth_shape* shape, const float* V, const float* X, float* A, void* workspace,
+                size_t workspace_bytes, int save_for_backward, void* stream) {
+  int rc = check_shape(shape);
+  if (rc != FASTH_OK) return rc;
+  if (!V || !X || !A || !workspace) return FASTH_EINVAL;
+  if (!aligned16(V) || !aligned16(X) || !aligned16(A) || !aligned16(workspace)) return FASTH_EALIGN;
+  const Product P = bind(shape->d, shape->n, shape->m, shape->k, workspace);
+  if (workspace_bytes < P.L.total) return FASTH_EWORKSPACE;
+  return run_chain(P, V, X, A, shape->transpose, true, nullptr, 0, static_cast<hipStream_t>(stream),
+                   save_for_backward != 0);
 }
 
 int fasth_backward(const fasth_shape* shape, const float* V, const float* G, float* dV, float* dX, void* workspace,

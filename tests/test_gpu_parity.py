@@ -142,6 +142,34 @@ def test_runs_on_a_side_stream():
     assert rel_err(dX.cpu().numpy(), dX0) <= REL_TOL
 
 
+def test_prepare_once_apply_many():
+    """Section 3.3 "Recurrent Layers": the block factors are built once and the same H is applied
+    r times (here H, then H^T, then H twice, then a saved apply followed by backward)."""
+    import torch
+    from paper_2009_13977_amd import binding as B
+    from helpers import to_gpu
+    d = n = 256; m = 32; k = 32
+    p = synthetic.householder_problem(d, n, m, seed=21)
+    Vd, Xd, Gd = (to_gpu(p[a]) for a in ("V", "X", "G"))
+    Y1 = torch.empty_like(Xd); Y2 = torch.empty_like(Xd); Y3 = torch.empty_like(Xd)
+    dX = torch.empty_like(Xd); dV = torch.empty_like(Vd)
+    ws = B.new_workspace(B.fasth_workspace_bytes(d, n, m, k))
+    B.fasth_prepare(Vd, m, ws, k)
+    B.fasth_apply(Vd, Xd, Y1, ws, k)                      # H X
+    B.fasth_apply(Vd, Y1, Y2, ws, k, transpose=True)      # H^T H X = X
+    B.fasth_apply(Vd, Y1, Y3, ws, k)                      # H H X
+    torch.cuda.synchronize()
+    HX = orc.product_apply(p["V"], p["X"])
+    assert rel_err(Y1.cpu().numpy(), HX) <= REL_TOL
+    assert rel_err(Y2.cpu().numpy(), p["X"]) <= REL_TOL
+    assert rel_err(Y3.cpu().numpy(), orc.product_apply(p["V"], HX)) <= REL_TOL
+    B.fasth_apply(Vd, Xd, Y1, ws, k, save_for_backward=True)
+    B.fasth_backward(Vd, Gd, dV, dX, ws, k)
+    torch.cuda.synchronize()
+    _, dV0, dX0 = orc.product_gradients(p["V"], p["X"], p["G"])
+    assert rel_err(dV.cpu().numpy(), dV0) <= REL_TOL and rel_err(dX.cpu().numpy(), dX0) <= REL_TOL
+
+
 def test_block_size_independence():
     """Theorem 1 correctness: the result does not depend on how reflections are grouped."""
     p = synthetic.householder_problem(96, 96, 8, seed=77)
