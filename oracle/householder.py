@@ -15,7 +15,8 @@ definition written out, one reflection at a time, in numpy fp64:
 * Supplement 8.1:  dL/dX = H_n^T ... H_1^T dL/dA_1
 * Eq. 4:           the input of H_j is recovered from its output, H_j^-1 = H_j^T
 * Eq. 5:           dL/dv_j, summed over the m columns of the mini-batch
-* Section 2.2 / Table 1:  W = U diag(sigma) V^T,  W^-1 = V diag(1/sigma) U^T
+* Section 2.2 / Table 1:  W = U diag(sigma) V^T,  W^-1 = V diag(1/sigma) U^T,
+                          exp(U S U^T) = U e^S U^T,  Cayley(U S U^T) = U (I - S)(I + S)^-1 U^T
 
 Layout: V is [n][d], row j-1 holding v_j; X, A, G are [d][m], one sample per
 column. Every function promotes its inputs to float64.
@@ -186,3 +187,43 @@ def svd_layer_inverse_gradients(Uv, sigma, Vv, X, G):
 def log_abs_det(sigma) -> float:
     """Table 1 row "Determinant": sum_i log |sigma_i| = log |det W|."""
     return float(np.sum(np.log(np.abs(_f64(sigma)))))
+
+
+# --------------------------------------------------------------------------
+# Symmetric forms of Table 1 (rows "Matrix Exponential" and "Cayley map"): one
+# orthogonal factor U and a diagonal, W = U diag(sigma) U^T.
+# --------------------------------------------------------------------------
+
+def diagonal_function(sigma, kind: str):
+    """f(sigma) and f'(sigma) for the diagonal of U f(Sigma) U^T.
+    'identity': W itself; 'exp': e^W = U e^Sigma U^T; 'cayley': (I - W)(I + W)^-1 =
+    U (I - Sigma)(I + Sigma)^-1 U^T."""
+    sigma = _f64(sigma)
+    if kind == "identity":
+        return sigma.copy(), np.ones_like(sigma)
+    if kind == "exp":
+        e = np.exp(sigma)
+        return e, e
+    if kind == "cayley":
+        return (1.0 - sigma) / (1.0 + sigma), -2.0 / (1.0 + sigma) ** 2
+    raise ValueError(kind)
+
+
+def symmetric_apply(Uv, sigma, X, kind: str = "identity") -> np.ndarray:
+    """U f(Sigma) U^T X."""
+    s, _ = diagonal_function(sigma, kind)
+    Z1 = product_apply(Uv, X, transpose=True)
+    return product_apply(Uv, s[:, None] * Z1)
+
+
+def symmetric_gradients(Uv, sigma, X, G, kind: str = "identity"):
+    """Y = U f(Sigma) U^T X and the gradients of L = <G, Y> wrt (Uv, sigma, X). U enters twice
+    (as U^T on X and as U on the scaled result); its two gradient contributions add."""
+    s, ds_dsigma = diagonal_function(sigma, kind)
+    Z1 = product_apply(Uv, X, transpose=True)
+    Z2 = s[:, None] * Z1
+    Y, dU_outer, dZ2 = product_gradients(Uv, Z2, G)
+    dsigma = np.sum(dZ2 * Z1, axis=1) * ds_dsigma
+    dZ1 = s[:, None] * dZ2
+    _, dU_inner, dX = product_gradients(Uv, X, dZ1, transpose=True)
+    return Y, dU_outer + dU_inner, dsigma, dX

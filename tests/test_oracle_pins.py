@@ -269,3 +269,56 @@ def test_svd_layer_gradients_against_central_differences(inverse):
             p[idx][it.multi_index] += h; q[idx][it.multi_index] -= h
             fd[it.multi_index] = (loss(*p) - loss(*q)) / (2 * h)
         assert np.linalg.norm(grad - fd) <= 1e-6 * np.linalg.norm(fd), idx
+
+
+# ------------------------------------------------------- symmetric forms (Table 1)
+
+def _dense_symmetric(Uv, sigma):
+    U = _dense_product(Uv)
+    return U @ np.diag(sigma) @ U.T
+
+
+def test_symmetric_forms_against_dense_expm_and_cayley():
+    """Table 1: e^W = U e^Sigma U^T and (I - W)(I + W)^-1 = U (I - Sigma)(I + Sigma)^-1 U^T for
+    W = U Sigma U^T, against scipy's Pade expm and a dense solve."""
+    r = _rng(14)
+    d = 10; m = 4
+    Uv = r.standard_normal((d, d)); sigma = r.uniform(-0.8, 0.9, d); X = r.standard_normal((d, m))
+    W = _dense_symmetric(Uv, sigma)
+    np.testing.assert_allclose(orc.symmetric_apply(Uv, sigma, X), W @ X, atol=1e-12)
+    np.testing.assert_allclose(orc.symmetric_apply(Uv, sigma, X, "exp"), scipy.linalg.expm(W) @ X, atol=1e-11)
+    cay = np.linalg.solve(np.eye(d) + W, (np.eye(d) - W) @ X)
+    np.testing.assert_allclose(orc.symmetric_apply(Uv, sigma, X, "cayley"), cay, atol=1e-11)
+    # the Cayley map of a symmetric matrix is its own inverse map: applying it twice returns W X
+    s_c, _ = orc.diagonal_function(sigma, "cayley")
+    np.testing.assert_allclose(orc.symmetric_apply(Uv, s_c, X, "cayley"), W @ X, atol=1e-11)
+
+
+@pytest.mark.parametrize("kind", ["identity", "exp", "cayley"])
+def test_symmetric_gradients_against_central_differences(kind):
+    r = _rng(15)
+    d = 7; m = 3
+    Uv = r.standard_normal((d, d)); sigma = r.uniform(-0.6, 0.8, d)
+    X = r.standard_normal((d, m)); G = r.standard_normal((d, m))
+
+    def loss(Uv_, sigma_, X_):
+        W = _dense_symmetric(Uv_, sigma_)
+        if kind == "exp":
+            M = scipy.linalg.expm(W)
+        elif kind == "cayley":
+            M = np.linalg.solve(np.eye(d) + W, np.eye(d) - W)
+        else:
+            M = W
+        return float(np.sum(G * (M @ X_)))
+
+    Y, dUv, dsigma, dX = orc.symmetric_gradients(Uv, sigma, X, G, kind)
+    h = 1e-6
+    args = [Uv, sigma, X]
+    for idx, grad in ((0, dUv), (1, dsigma), (2, dX)):
+        fd = np.zeros_like(grad)
+        it = np.nditer(grad, flags=["multi_index"])
+        for _ in it:
+            p = [a.copy() for a in args]; q = [a.copy() for a in args]
+            p[idx][it.multi_index] += h; q[idx][it.multi_index] -= h
+            fd[it.multi_index] = (loss(*p) - loss(*q)) / (2 * h)
+        assert np.linalg.norm(grad - fd) <= 2e-6 * np.linalg.norm(fd), (kind, idx)
