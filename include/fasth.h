@@ -135,6 +135,25 @@ int svd_layer_inverse_apply_backward(const fasth_svd_shape* shape, const float* 
                                      float* dUv, float* dsigma, float* dVv, float* dX,
                                      void* workspace, size_t workspace_bytes, void* stream);
 
+/* The symmetric forms of Table 1 (rows "Matrix Exponential" and "Cayley map"): with one orthogonal
+ * factor U (n reflections, rows of Uv) and W = U diag(sigma) U^T,
+ *   FASTH_DIAG_IDENTITY: Y = W X
+ *   FASTH_DIAG_EXP:      Y = e^W X            = U diag(e^sigma) U^T X
+ *   FASTH_DIAG_CAYLEY:   Y = (I - W)(I + W)^-1 X = U diag((1 - sigma)/(1 + sigma)) U^T X   (sigma != -1)
+ * The block factors of U are built once and used by both products. The workspace has the size
+ * svd_layer_workspace_bytes() returns. The backward call follows the apply call on the same workspace
+ * and arguments and writes dUv [n][d] (both uses of U added), dsigma [d] and dX [d][m]. */
+enum { FASTH_DIAG_IDENTITY = 0, FASTH_DIAG_EXP = 1, FASTH_DIAG_CAYLEY = 2 };
+int svd_sym_apply(const fasth_svd_shape* shape, int function, const float* Uv, const float* sigma,
+                  const float* X, float* Y, void* workspace, size_t workspace_bytes, void* stream);
+int svd_sym_apply_backward(const fasth_svd_shape* shape, int function, const float* Uv, const float* sigma,
+                           const float* G, float* dUv, float* dsigma, float* dX,
+                           void* workspace, size_t workspace_bytes, void* stream);
+
+/* Table 1, row "Determinant": *log_abs_det (one float in device memory) = sum_i log|sigma_i| =
+ * log|det(U diag(sigma) V^T)|; if dsigma is not NULL it receives the gradient 1/sigma_i. */
+int svd_layer_log_abs_det(int d, const float* sigma, float* log_abs_det, float* dsigma, void* stream);
+
 /* Benchmark aid (not part of the method). While enabled, every kernel this library launches from
  * the calling process is bracketed by a pair of HIP events on its stream; fasth_profile_collect
  * waits for them, adds the elapsed milliseconds and the launch count per kernel into the two HOST

@@ -36,6 +36,9 @@ EXPORTED_SYMBOLS = (
     "svd_layer_inverse_apply",
     "svd_layer_apply_backward",
     "svd_layer_inverse_apply_backward",
+    "svd_sym_apply",
+    "svd_sym_apply_backward",
+    "svd_layer_log_abs_det",
     "fasth_kernel_name",
     "fasth_profile_enable",
     "fasth_profile_collect",
@@ -100,6 +103,12 @@ def load_library() -> ctypes.CDLL:
         fn = getattr(lib, name)
         fn.restype = I
         fn.argtypes = [sshp, P, P, P, P, P, P, P, P, P, S, P]
+    lib.svd_sym_apply.restype = I
+    lib.svd_sym_apply.argtypes = [sshp, I, P, P, P, P, P, S, P]
+    lib.svd_sym_apply_backward.restype = I
+    lib.svd_sym_apply_backward.argtypes = [sshp, I, P, P, P, P, P, P, P, S, P]
+    lib.svd_layer_log_abs_det.restype = I
+    lib.svd_layer_log_abs_det.argtypes = [I, P, P, P, P]
     lib.fasth_kernel_name.restype = ctypes.c_char_p
     lib.fasth_kernel_name.argtypes = [I]
     lib.fasth_profile_enable.restype = I
@@ -251,6 +260,37 @@ def svd_layer_apply_backward(Uv, sigma, Vv, G, dUv, dsigma, dVv, dX, workspace, 
 
 def svd_layer_inverse_apply_backward(Uv, sigma, Vv, G, dUv, dsigma, dVv, dX, workspace, k: int) -> None:
     _svd_backward("svd_layer_inverse_apply_backward", Uv, sigma, Vv, G, dUv, dsigma, dVv, dX, workspace, k)
+
+
+DIAG_FUNCTIONS = {"identity": 0, "exp": 1, "cayley": 2}
+
+
+def svd_sym_apply(Uv, sigma, X, Y, workspace, k: int, function: str = "identity") -> None:
+    n, d = Uv.shape
+    m = X.shape[1]
+    assert sigma.shape == (d,) and X.shape == (d, m) and Y.shape == (d, m)
+    shape = fasth_svd_shape(d, n, m, int(k))
+    rc = load_library().svd_sym_apply(ctypes.byref(shape), DIAG_FUNCTIONS[function], _ptr(Uv, "Uv"),
+                                      _ptr(sigma, "sigma"), _ptr(X, "X"), _ptr(Y, "Y"),
+                                      _ptr(workspace, "workspace"), workspace.numel(), _stream())
+    _check(rc, "svd_sym_apply")
+
+
+def svd_sym_apply_backward(Uv, sigma, G, dUv, dsigma, dX, workspace, k: int, function: str = "identity") -> None:
+    n, d = Uv.shape
+    m = G.shape[1]
+    shape = fasth_svd_shape(d, n, m, int(k))
+    rc = load_library().svd_sym_apply_backward(ctypes.byref(shape), DIAG_FUNCTIONS[function], _ptr(Uv, "Uv"),
+                                               _ptr(sigma, "sigma"), _ptr(G, "G"), _ptr(dUv, "dUv"),
+                                               _ptr(dsigma, "dsigma"), _ptr(dX, "dX"),
+                                               _ptr(workspace, "workspace"), workspace.numel(), _stream())
+    _check(rc, "svd_sym_apply_backward")
+
+
+def svd_layer_log_abs_det(sigma, out, dsigma=None) -> None:
+    rc = load_library().svd_layer_log_abs_det(int(sigma.shape[0]), _ptr(sigma, "sigma"), _ptr(out, "out"),
+                                              _ptr(dsigma, "dsigma") if dsigma is not None else None, _stream())
+    _check(rc, "svd_layer_log_abs_det")
 
 
 FASTH_KERNEL_COUNT = 9

@@ -372,6 +372,18 @@ static size_t t_build_lds(int kp) {
 // Saved for the backward pass: the input column of every block and the coefficient vector C.
 // ------------------------------------------------------------------------------------------
 
+// Diagonal factor applied to row x of a chain's input (Section 2.2 and Table 1):
+// 1: sigma, 2: 1/sigma (inverse), 3: e^sigma (matrix exponential), 4: (1 - sigma)/(1 + sigma) (Cayley map).
+__device__ __forceinline__ float diag_factor(int mode, float sigma) {
+  switch (mode) {
+    case 1: return sigma;
+    case 2: return 1.f / sigma;
+    case 3: return expf(sigma);
+    case 4: return (1.f - sigma) / (1.f + sigma);
+    default: return 1.f;
+  }
+}
+
 struct ChainArgs {
   const float* V;         // [n][d]
   const float* T;         // [nb][kp][kp]
@@ -379,7 +391,7 @@ struct ChainArgs {
   float* out;             // [d][m]
   float* save_in;         // [nb][m][d] or null
   float* save_c;          // [m][n] or null
-  const float* in_scale;  // [d] or null: the input row x is multiplied (mode 1) or divided (mode 2)
+  const float* in_scale;  // [d] or null: input row x is multiplied by diag_factor(in_scale_mode, in_scale[x])
   int in_scale_mode;
   int d, n, m, k, kp, nb;
   int transpose;
@@ -403,8 +415,7 @@ __global__ void __launch_bounds__(1024) chain_kernel(ChainArgs p) {
     float v = 0.f;
     if (x < d) {
       v = p.in[(size_t)x * m + col];
-      if (p.in_scale_mode == 1) v *= p.in_scale[x];
-      else if (p.in_scale_mode == 2) v /= p.in_scale[x];
+      if (p.in_scale_mode) v *= diag_factor(p.in_scale_mode, p.in_scale[x]);
     }
     a[u] = v;
   }
@@ -525,8 +536,7 @@ __device__ __forceinline__ Chunk<VW> load_column_chunk(const ChainArgs& p, int c
     float v = 0.f;
     if (ok) {
       v = p.in[(size_t)(x0 + r) * p.m + col];
-      if (p.in_scale_mode == 1) v *= p.in_scale[x0 + r];
-      else if (p.in_scale_mode == 2) v /= p.in_scale[x0 + r];
+      if (p.in_scale_mode) v *= diag_factor(p.in_scale_mode, p.in_scale[x0 + r]);
     }
     a.e[r] = v;
   }
@@ -886,6 +896,7 @@ struct DvArgs {
   float* dV;            // [n][d]
   int d, n, m, k, kp;
   int transpose;        // of the forward product
+  int accumulate;       // add to dV instead of overwriting it (a factor that enters a layer twice)
 };
 
 template <int KT>  // kp = 16 KT
@@ -1003,7 +1014,11 @@ __global__ void __launch_bounds__(256) dv_kernel(DvArgs p) {
 #pragma unroll
       for (int jj = 0; jj < 4; ++jj) {
         const int j = ti * 16 + 4 * q + jj, x = x0 + tx * 16 + li;
-        if (j < k && x < d) p.dV[((size_t)i * k + j) * d + x] = ev[jj] - acc[w][jj];
+        if (j < k && x < d) {
+          float* dst = p.dV + ((size_t)i * k + j) * d + x;
+          const float val = ev[jj] - acc[w][jj];
+          *dst = p.accumulate ? *dst + val : val;
+        }
       }
     }
   }
@@ -1132,25 +1147,44 @@ __global__ void __launch_bounds__(256) seq_reduce_kernel(const float* __restrict
 
 // ------------------------------------------------------------------------------------------
 // Diagonal step of the SVD layer (Section 2.2): with Z2 = s * Z1 (s = sigma or 1/sigma),
-//   ds_r = sum_l dZ2[r][l] Z1[r][l];  for s = 1/sigma, dsigma_r = -ds_r / sigma_r^2.
+//   ds_r = sum_l dZ2[r][l] Z1[r][l];  dsigma_r = ds_r * s'(sigma_r)  (e.g. -ds_r / sigma_r^2 for s = 1/sigma).
 // ------------------------------------------------------------------------------------------
 
 __global__ void __launch_bounds__(256) dsigma_kernel(const float* __restrict__ dZ2, const float* __restrict__ Z1,
                                                      const float* __restrict__ sigma, float* __restrict__ dsigma,
-                                                     int d, int m, int inverse) {
+                                                     int d, int m, int mode) {
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
   if (row >= d) return;
   float r[1] = {0.f};
   for (int l = lane; l < m; l += 64) r[0] += dZ2[(size_t)row * m + l] * Z1[(size_t)row * m + l];
   wave_reduce_multi<1>(r);
   if (lane == 0) {
+    // chain rule from the diagonal factor s(sigma) to sigma: mode = diag_factor mode
     float v = r[0];
-    if (inverse) {
-      const float sg = sigma[row];
-      v = -v / (sg * sg);
-    }
+    const float sg = sigma[row];
+    if (mode == 2) v = -v / (sg * sg);
+    else if (mode == 3) v *= expf(sg);
+    else if (mode == 4) v *= -2.f / ((1.f + sg) * (1.f + sg));
     dsigma[row] = v;
   }
+}
+
+// Table 1, row "Determinant": log|det W| = sum_i log|sigma_i| and its gradient 1/sigma_i. One workgroup,
+// fixed summation order.
+__global__ void __launch_bounds__(256) logabsdet_kernel(const float* __restrict__ sigma, float* __restrict__ out,
+                                                        float* __restrict__ dsigma, int d) {
+  __shared__ float part[4];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  float r[1] = {0.f};
+  for (int x = tid; x < d; x += 256) {
+    const float sg = sigma[x];
+    r[0] += logf(fabsf(sg));
+    if (dsigma) dsigma[x] = 1.f / sg;
+  }
+  wave_reduce_multi<1>(r);
+  if (lane == 0) part[wave] = r[0];
+  __syncthreads();
+  if (tid == 0) out[0] = (part[0] + part[1]) + (part[2] + part[3]);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1209,9 +1243,10 @@ static int build_factors(const Product& P, const float* V, hipStream_t stream) {
 // A = H in (transpose = 0) or H^T in (transpose = 1); activation = true saves into the activation
 // slots of the workspace, false into the gradient slots.
 static int run_chain(const Product& P, const float* V, const float* in, float* out, int transpose, bool activation,
-                     const float* in_scale, int in_scale_mode, hipStream_t stream, bool save = true) {
+                     const float* in_scale, int in_scale_mode, hipStream_t stream, bool save = true,
+                     const float* factors = nullptr) {
   ChainArgs a;
-  a.V = V; a.T = P.T(); a.in = in; a.out = out;
+  a.V = V; a.T = factors ? factors : P.T(); a.in = in; a.out = out;
   a.save_in = !save ? nullptr : activation ? P.saveA() : P.saveG();
   a.save_c = !save ? nullptr : activation ? P.saveCa() : P.saveCg();
   a.in_scale = in_scale; a.in_scale_mode = in_scale_mode;
@@ -1220,8 +1255,10 @@ static int run_chain(const Product& P, const float* V, const float* in, float* o
   return launch_chain(a, stream);
 }
 
-static int run_dv(const Product& P, const float* V, float* dV, int transpose, hipStream_t stream) {
+static int run_dv(const Product& P, const float* V, float* dV, int transpose, hipStream_t stream,
+                  bool accumulate = false) {
   DvArgs a;
+  a.accumulate = accumulate ? 1 : 0;
   a.V = V; a.saveA = P.saveA(); a.saveCa = P.saveCa(); a.saveG = P.saveG(); a.saveCg = P.saveCg(); a.dV = dV;
   a.d = P.d; a.n = P.n; a.m = P.m; a.k = P.k; a.kp = P.L.kp; a.transpose = transpose;
   const size_t lds = dv_lds(P.L.kp);
@@ -1320,12 +1357,21 @@ static int svd_backward(const fasth_svd_shape* shape, const float* first, const 
   {
     prof::Scope ps_(FASTH_KERNEL_DSIGMA, st);
     hipLaunchKernelGGL(dsigma_kernel, dim3((fs.d + 3) / 4), dim3(256), 0, st, dZ2, Z1, sigma, dsigma, fs.d, fs.m,
-                       scale_mode == 2 ? 1 : 0);
+                       scale_mode);
   }
   FASTH_HIP(hipGetLastError());
   // through the first (transposed) factor; dZ1 = s * dZ2 is fused into the chain's load
   if ((rc = run_chain(Pf, first, dZ2, dX, 0, false, sigma, scale_mode, st)) != FASTH_OK) return rc;
   return run_dv(Pf, first, dfirst, 1, st);
+}
+
+static int sym_scale_mode(int function) {
+  switch (function) {
+    case FASTH_DIAG_IDENTITY: return 1;
+    case FASTH_DIAG_EXP: return 3;
+    case FASTH_DIAG_CAYLEY: return 4;
+    default: return -1;
+  }
 }
 
 }  // namespace fasth
@@ -1520,6 +1566,66 @@ size_t svd_layer_workspace_bytes(const fasth_svd_shape* shape) {
   fasth_shape fs;
   if (check_svd_shape(shape, &fs) != FASTH_OK) return 0;
   return make_svd_layout(fs.d, fs.n, fs.m, fs.k).total;
+}
+
+int svd_sym_apply(const fasth_svd_shape* shape, int function, const float* Uv, const float* sigma, const float* X,
+                  float* Y, void* workspace, size_t workspace_bytes, void* stream) {
+  fasth_shape fs;
+  int rc = check_svd_shape(shape, &fs);
+  if (rc != FASTH_OK) return rc;
+  const int mode = sym_scale_mode(function);
+  if (mode < 0 || !Uv || !sigma || !X || !Y || !workspace) return FASTH_EINVAL;
+  if (!aligned16(Uv) || !aligned16(sigma) || !aligned16(X) || !aligned16(Y) || !aligned16(workspace)) return FASTH_EALIGN;
+  const SvdLayout S = make_svd_layout(fs.d, fs.n, fs.m, fs.k);
+  if (workspace_bytes < S.total) return FASTH_EWORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  char* ws = static_cast<char*>(workspace);
+  const Product Pin = bind(fs.d, fs.n, fs.m, fs.k, ws + S.off_V);   // U^T X; owns the factors
+  const Product Pout = bind(fs.d, fs.n, fs.m, fs.k, ws + S.off_U);  // U (s * Z1); saves only
+  float* Z1 = reinterpret_cast<float*>(ws + S.off_Z1);
+  if ((rc = build_factors(Pin, Uv, st)) != FASTH_OK) return rc;
+  if ((rc = run_chain(Pin, Uv, X, Z1, 1, true, nullptr, 0, st)) != FASTH_OK) return rc;
+  return run_chain(Pout, Uv, Z1, Y, 0, true, sigma, mode, st, true, Pin.T());
+}
+
+int svd_sym_apply_backward(const fasth_svd_shape* shape, int function, const float* Uv, const float* sigma,
+                           const float* G, float* dUv, float* dsigma, float* dX, void* workspace,
+                           size_t workspace_bytes, void* stream) {
+  fasth_shape fs;
+  int rc = check_svd_shape(shape, &fs);
+  if (rc != FASTH_OK) return rc;
+  const int mode = sym_scale_mode(function);
+  if (mode < 0 || !Uv || !sigma || !G || !dUv || !dsigma || !dX || !workspace) return FASTH_EINVAL;
+  if (!aligned16(Uv) || !aligned16(sigma) || !aligned16(G) || !aligned16(dUv) || !aligned16(dsigma) ||
+      !aligned16(dX) || !aligned16(workspace))
+    return FASTH_EALIGN;
+  const SvdLayout S = make_svd_layout(fs.d, fs.n, fs.m, fs.k);
+  if (workspace_bytes < S.total) return FASTH_EWORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  char* ws = static_cast<char*>(workspace);
+  const Product Pin = bind(fs.d, fs.n, fs.m, fs.k, ws + S.off_V);
+  const Product Pout = bind(fs.d, fs.n, fs.m, fs.k, ws + S.off_U);
+  const float* Z1 = reinterpret_cast<const float*>(ws + S.off_Z1);
+  float* dZ2 = reinterpret_cast<float*>(ws + S.off_dZ2);
+  if ((rc = run_chain(Pout, Uv, G, dZ2, 1, false, nullptr, 0, st, true, Pin.T())) != FASTH_OK) return rc;
+  if ((rc = run_dv(Pout, Uv, dUv, 0, st)) != FASTH_OK) return rc;
+  {
+    prof::Scope ps_(FASTH_KERNEL_DSIGMA, st);
+    hipLaunchKernelGGL(dsigma_kernel, dim3((fs.d + 3) / 4), dim3(256), 0, st, (const float*)dZ2, Z1, sigma, dsigma,
+                       fs.d, fs.m, mode);
+  }
+  FASTH_HIP(hipGetLastError());
+  if ((rc = run_chain(Pin, Uv, dZ2, dX, 0, false, sigma, mode, st)) != FASTH_OK) return rc;
+  return run_dv(Pin, Uv, dUv, 1, st, true);
+}
+
+int svd_layer_log_abs_det(int d, const float* sigma, float* log_abs_det, float* dsigma, void* stream) {
+  if (d < 1 || !sigma || !log_abs_det) return FASTH_EINVAL;
+  if (!aligned16(sigma) || (dsigma && !aligned16(dsigma))) return FASTH_EALIGN;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  hipLaunchKernelGGL(logabsdet_kernel, dim3(1), dim3(256), 0, st, sigma, log_abs_det, dsigma, d);
+  FASTH_HIP(hipGetLastError());
+  return FASTH_OK;
 }
 
 int svd_layer_apply(const fasth_svd_shape* shape, const float* Uv, const float* sigma, const float* Vv, const float* X,

@@ -62,3 +62,17 @@ def gpu_svd_layer(Uv, sigma, Vv, X, G, k, inverse=False):
         B.svd_layer_apply_backward(Ud, sd, Vd, Gd, dU, ds, dVv, dX, ws, k)
     torch.cuda.synchronize()
     return tuple(t.cpu().numpy() for t in (Y, dU, ds, dVv, dX))
+
+
+def gpu_svd_sym(Uv, sigma, X, G, k, function="identity"):
+    import torch
+    from paper_2009_13977_amd import binding as B
+    n, d = Uv.shape
+    m = X.shape[1]
+    Ud, sd, Xd, Gd = (to_gpu(a) for a in (Uv, sigma, X, G))
+    Y = torch.empty_like(Xd); dX = torch.empty_like(Xd); dU = torch.empty_like(Ud); ds = torch.empty_like(sd)
+    ws = B.new_workspace(B.svd_layer_workspace_bytes(d, n, m, k))
+    B.svd_sym_apply(Ud, sd, Xd, Y, ws, k, function)
+    B.svd_sym_apply_backward(Ud, sd, Gd, dU, ds, dX, ws, k, function)
+    torch.cuda.synchronize()
+    return tuple(t.cpu().numpy() for t in (Y, dU, ds, dX))

@@ -14,7 +14,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def _declared_symbols():
     text = open(os.path.join(ROOT, "include", "fasth.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return set(re.findall(r"\b((?:fasth|svd_layer)_\w+)\s*\(", text))
+    return set(re.findall(r"\b((?:fasth|svd_layer|svd_sym)_\w+)\s*\(", text))
 
 
 def test_library_exports_every_declared_symbol():

@@ -7,7 +7,7 @@ import pytest
 
 from oracle import householder as orc
 from paper_2009_13977_amd import synthetic
-from helpers import REL_TOL, gpu_fasth, gpu_sequential, gpu_svd_layer, rel_err
+from helpers import REL_TOL, gpu_fasth, gpu_sequential, gpu_svd_layer, gpu_svd_sym, rel_err
 
 pytestmark = pytest.mark.gpu
 
@@ -240,3 +240,36 @@ def test_svd_layer_inverse_round_trip():
     B.svd_layer_inverse_apply(Ud, sd, Vd, Y, Xr, ws, 32)
     torch.cuda.synchronize()
     assert rel_err(Xr.cpu().numpy(), p["X"]) <= REL_TOL
+
+
+@pytest.mark.parametrize("function", ["identity", "exp", "cayley"])
+@pytest.mark.parametrize("d,n,m,k", [(64, 64, 32, 32), (100, 60, 5, 12), (256, 256, 32, 32), (1024, 1024, 32, 32)])
+def test_symmetric_forms(d, n, m, k, function):
+    """Table 1: U f(Sigma) U^T X for f = identity, exp, Cayley, with gradients wrt U (both uses), sigma, X."""
+    _say(f"svd sym d={d} n={n} m={m} k={k} f={function}")
+    rng = np.random.default_rng(8000 + d + n + m + k)
+    Uv = rng.standard_normal((n, d)).astype(np.float32)
+    sigma = rng.uniform(-0.8, 0.9, d).astype(np.float32)
+    X = rng.standard_normal((d, m)).astype(np.float32)
+    G = rng.standard_normal((d, m)).astype(np.float32)
+    got = gpu_svd_sym(Uv, sigma, X, G, k, function)
+    ref = orc.symmetric_gradients(Uv, sigma, X, G, function)
+    for name, g, r in zip(("Y", "dUv", "dsigma", "dX"), got, ref):
+        assert rel_err(g, r) <= REL_TOL, (name, rel_err(g, r))
+
+
+def test_log_abs_det():
+    """Table 1: sum_i log|sigma_i| and its gradient."""
+    import torch
+    from paper_2009_13977_amd import binding as B
+    from helpers import to_gpu
+    for d in (1, 7, 256, 1024, 5000):
+        rng = np.random.default_rng(9000 + d)
+        sigma = (rng.uniform(0.5, 2.0, d) * rng.choice([-1.0, 1.0], d)).astype(np.float32)
+        sd = to_gpu(sigma)
+        out = torch.zeros(4, dtype=torch.float32, device="cuda"); ds = torch.empty_like(sd)
+        B.svd_layer_log_abs_det(sd, out, ds)
+        torch.cuda.synchronize()
+        ref = orc.log_abs_det(sigma)
+        assert abs(float(out[0]) - ref) <= 1e-5 * max(1.0, abs(ref)) + 1e-4
+        assert rel_err(ds.cpu().numpy(), 1.0 / sigma.astype(np.float64)) <= 1e-6
