@@ -95,6 +95,20 @@ int fasth_apply(const fasth_shape* shape, const float* V, const float* X, float*
 int fasth_backward(const fasth_shape* shape, const float* V, const float* G,
                    float* dV, float* dX, void* workspace, size_t workspace_bytes, void* stream);
 
+/* Section 3.3 "Trade-off": the block size k trades total work against the number of sequential
+ * steps, and the paper picks it by trying the candidates once on the hardware at hand. This call
+ * times fasth_forward + fasth_backward (`repetitions` >= 1 timed passes after one untimed pass) for
+ * every candidate block size and writes the fastest to *best_k and its milliseconds per pass to
+ * *best_ms (may be NULL); both are HOST pointers. `candidates` is a HOST array of ncandidates block
+ * sizes, or NULL for every divisor of n in [2, 128]. Candidates that do not divide n, are out of
+ * range, or need more workspace than given are skipped; FASTH_EUNSUPPORTED if none is left.
+ * shape->k is ignored. Unlike every other entry point this one waits for the stream (it reads
+ * event times). On return A, dV, dX hold the results of the last candidate run, which do not
+ * depend on k beyond rounding. */
+int fasth_tune_block_size(const fasth_shape* shape, const int* candidates, int ncandidates, int repetitions,
+                          const float* V, const float* X, const float* G, float* A, float* dV, float* dX,
+                          void* workspace, size_t workspace_bytes, int* best_k, float* best_ms, void* stream);
+
 /* The comparison the paper measures against (Section 2.2, "O(d) sequential
  * inner products"): the same A, dX and dV computed one reflection at a time
  * on the GPU. shape->k is ignored. fasth_sequential_backward recomputes the

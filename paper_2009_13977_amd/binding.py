@@ -28,6 +28,7 @@ EXPORTED_SYMBOLS = (
     "fasth_prepare",
     "fasth_apply",
     "fasth_backward",
+    "fasth_tune_block_size",
     "fasth_sequential_workspace_bytes",
     "fasth_sequential_forward",
     "fasth_sequential_backward",
@@ -83,6 +84,9 @@ def load_library() -> ctypes.CDLL:
     lib.fasth_forward.argtypes = [shp, P, P, P, P, S, P]
     lib.fasth_backward.restype = I
     lib.fasth_backward.argtypes = [shp, P, P, P, P, P, S, P]
+    lib.fasth_tune_block_size.restype = I
+    lib.fasth_tune_block_size.argtypes = [shp, ctypes.POINTER(ctypes.c_int), I, I, P, P, P, P, P, P, P, S,
+                                          ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_float), P]
     lib.fasth_prepare.restype = I
     lib.fasth_prepare.argtypes = [shp, P, P, S, P]
     lib.fasth_apply.restype = I
@@ -204,6 +208,27 @@ def fasth_backward(V, G, dV, dX, workspace, k: int, transpose: bool = False) -> 
     rc = load_library().fasth_backward(ctypes.byref(shape), _ptr(V, "V"), _ptr(G, "G"), _ptr(dV, "dV"),
                                        _ptr(dX, "dX"), _ptr(workspace, "workspace"), workspace.numel(), _stream())
     _check(rc, "fasth_backward")
+
+
+def fasth_tune_block_size(V, X, G, A, dV, dX, workspace, candidates=None, repetitions: int = 5,
+                          transpose: bool = False):
+    """Returns (best k, milliseconds per forward+backward pass at that k)."""
+    n, d = V.shape
+    m = X.shape[1]
+    shape = _shape(d, n, m, 1, transpose)
+    if candidates is None:
+        cand, ncand = None, 0
+    else:
+        cand = (ctypes.c_int * len(candidates))(*[int(c) for c in candidates])
+        ncand = len(candidates)
+    best_k = ctypes.c_int(0)
+    best_ms = ctypes.c_float(0.0)
+    rc = load_library().fasth_tune_block_size(ctypes.byref(shape), cand, ncand, int(repetitions), _ptr(V, "V"),
+                                              _ptr(X, "X"), _ptr(G, "G"), _ptr(A, "A"), _ptr(dV, "dV"),
+                                              _ptr(dX, "dX"), _ptr(workspace, "workspace"), workspace.numel(),
+                                              ctypes.byref(best_k), ctypes.byref(best_ms), _stream())
+    _check(rc, "fasth_tune_block_size")
+    return best_k.value, best_ms.value
 
 
 def fasth_sequential_forward(V, X, A, transpose: bool = False) -> None:

@@ -1489,6 +1489,63 @@ int fasth_backward(const fasth_shape* shape, const float* V, const float* G, flo
   return run_dv(P, V, dV, shape->transpose, st);
 }
 
+int fasth_tune_block_size(const fasth_shape* shape, const int* candidates, int ncandidates, int repetitions,
+                          const float* V, const float* X, const float* G, float* A, float* dV, float* dX,
+                          void* workspace, size_t workspace_bytes, int* best_k, float* best_ms, void* stream) {
+  if (!shape || !best_k) return FASTH_EINVAL;
+  if (shape->d < 1 || shape->n < 1 || shape->m < 1 || repetitions < 1) return FASTH_EINVAL;
+  if ((candidates && ncandidates < 1) || (shape->transpose != 0 && shape->transpose != 1)) return FASTH_EINVAL;
+  if (!V || !X || !G || !A || !dV || !dX || !workspace) return FASTH_EINVAL;
+  if (!aligned16(V) || !aligned16(X) || !aligned16(G) || !aligned16(A) || !aligned16(dV) || !aligned16(dX) ||
+      !aligned16(workspace))
+    return FASTH_EALIGN;
+  std::vector<int> ks;
+  if (candidates) {
+    ks.assign(candidates, candidates + ncandidates);
+  } else {
+    for (int k = 2; k <= kMaxBlock && k <= shape->n; ++k)
+      if (shape->n % k == 0) ks.push_back(k);
+    if (ks.empty()) ks.push_back(1);
+  }
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  FASTH_HIP(hipEventCreate(&e0));
+  if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return FASTH_EHIP; }
+  int rc = FASTH_OK, found = 0;
+  float best = 0.f;
+  for (int k : ks) {
+    fasth_shape s = *shape;
+    s.k = k;
+    if (check_shape(&s) != FASTH_OK || fasth_workspace_bytes(&s) > workspace_bytes) continue;  // not a usable candidate
+    // one untimed pass, then `repetitions` timed ones
+    for (int pass = 0; pass < 2 && rc == FASTH_OK; ++pass) {
+      const int reps = pass == 0 ? 1 : repetitions;
+      if (pass == 1 && hipEventRecord(e0, st) != hipSuccess) { rc = FASTH_EHIP; break; }
+      for (int r = 0; r < reps && rc == FASTH_OK; ++r) {
+        rc = fasth_forward(&s, V, X, A, workspace, workspace_bytes, stream);
+        if (rc == FASTH_OK) rc = fasth_backward(&s, V, G, dV, dX, workspace, workspace_bytes, stream);
+      }
+      if (pass == 1 && rc == FASTH_OK) {
+        float ms = 0.f;
+        if (hipEventRecord(e1, st) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
+            hipEventElapsedTime(&ms, e0, e1) != hipSuccess) {
+          rc = FASTH_EHIP;
+          break;
+        }
+        ms /= repetitions;
+        if (!found || ms < best) { best = ms; *best_k = k; found = 1; }
+      }
+    }
+    if (rc != FASTH_OK) break;
+  }
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  if (rc != FASTH_OK) return rc;
+  if (!found) return FASTH_EUNSUPPORTED;
+  if (best_ms) *best_ms = best;
+  return FASTH_OK;
+}
+
 size_t fasth_sequential_workspace_bytes(const fasth_shape* shape) {
   if (!shape || shape->d < 1 || shape->n < 1 || shape->m < 1) return 0;
   if (shape->d > kMaxD || shape->m > 65535) return 0;

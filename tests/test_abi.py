@@ -77,3 +77,16 @@ def test_binding_refuses_cpu_tensors():
     t = torch.zeros(4, 4)
     with pytest.raises(ValueError):
         B.fasth_forward(t, t, t, t, 2)
+
+
+def test_block_size_search_argument_errors():
+    lib = B.load_library()
+    ok = B.fasth_shape(64, 64, 32, 0, 0)
+    best = ctypes.c_int(0)
+    call = lambda **kw: lib.fasth_tune_block_size(ctypes.byref(kw.get("shape", ok)), None, 0, kw.get("reps", 3),
+                                                  kw.get("V", 256), 256, 256, 256, 256, 256, 256, 1 << 40,
+                                                  ctypes.byref(best), None, None)
+    assert call(reps=0) == B.FASTH_EINVAL
+    assert call(V=None) == B.FASTH_EINVAL
+    assert call(V=260) == B.FASTH_EALIGN
+    assert call(shape=B.fasth_shape(64, 64, 0, 0, 0)) == B.FASTH_EINVAL

@@ -273,3 +273,28 @@ def test_log_abs_det():
         ref = orc.log_abs_det(sigma)
         assert abs(float(out[0]) - ref) <= 1e-5 * max(1.0, abs(ref)) + 1e-4
         assert rel_err(ds.cpu().numpy(), 1.0 / sigma.astype(np.float64)) <= 1e-6
+
+
+def test_block_size_search():
+    """Section 3.3: the search tries the candidates once and returns the fastest; the paper's own
+    example size d = 784 (all divisors of 784 up to 128)."""
+    import time
+    import torch
+    from paper_2009_13977_amd import binding as B
+    from helpers import to_gpu
+    d = n = 784; m = 32
+    p = synthetic.householder_problem(d, n, m, seed=31)
+    Vd, Xd, Gd = (to_gpu(p[a]) for a in ("V", "X", "G"))
+    A = torch.empty_like(Xd); dX = torch.empty_like(Xd); dV = torch.empty_like(Vd)
+    divisors = [k for k in range(2, 129) if n % k == 0]
+    ws = B.new_workspace(max(B.fasth_workspace_bytes(d, n, m, k) for k in divisors))
+    t0 = time.perf_counter()
+    k, ms = B.fasth_tune_block_size(Vd, Xd, Gd, A, dV, dX, ws, repetitions=3)
+    elapsed = time.perf_counter() - t0
+    _say(f"  block-size search at d=784: best k={k}, {ms * 1e3:.1f} us per pass, search took {elapsed:.3f} s")
+    assert k in divisors and ms > 0
+    A0, dV0, dX0 = orc.product_gradients(p["V"], p["X"], p["G"])
+    assert rel_err(A.cpu().numpy(), A0) <= REL_TOL and rel_err(dV.cpu().numpy(), dV0) <= REL_TOL
+    assert rel_err(dX.cpu().numpy(), dX0) <= REL_TOL
+    k2, _ = B.fasth_tune_block_size(Vd, Xd, Gd, A, dV, dX, ws, candidates=[5, 16, 28, 300], repetitions=2)
+    assert k2 in (16, 28)
