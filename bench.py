@@ -47,6 +47,60 @@ def chain_flops(d, n, m):
     return 4.0 * d * n * m  # B = V_i a and a -= V_i^T C over all blocks: 2 * 2dnm
 
 
+def bench_svd_layer(args, name, w) -> int:
+    """Non-default workload: the SVD-reparameterised layer (Section 2.2, Table 1 "Inverse"). A step is
+    apply + backward, once for W X and once for W^-1 X; each is two Householder products forward and
+    two backward plus the diagonal steps, i.e. 2 x F_paper FLOPs on the paper's count."""
+    import torch
+    from paper_2009_13977_amd import binding as B
+    from paper_2009_13977_amd import synthetic
+    d, n, m, k = w.d, w.n, w.m, w.k
+    p = synthetic.workload_inputs(name)
+    dev = torch.device("cuda:0")
+    Uv, sg, Vv, X, G = (torch.from_numpy(p[a]).to(dev) for a in ("Uv", "sigma", "Vv", "X", "G"))
+    Y = torch.empty_like(X); dX = torch.empty_like(X)
+    dU = torch.empty_like(Uv); dVv = torch.empty_like(Vv); ds = torch.empty_like(sg)
+    ws = B.new_workspace(B.svd_layer_workspace_bytes(d, n, m, k))
+
+    def step_apply():
+        B.svd_layer_apply(Uv, sg, Vv, X, Y, ws, k)
+        B.svd_layer_apply_backward(Uv, sg, Vv, G, dU, ds, dVv, dX, ws, k)
+
+    def step_inverse():
+        B.svd_layer_inverse_apply(Uv, sg, Vv, X, Y, ws, k)
+        B.svd_layer_inverse_apply_backward(Uv, sg, Vv, G, dU, ds, dVv, dX, ws, k)
+
+    def timed(fn, reps):
+        e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    for _ in range(args.warmup):
+        step_apply(); step_inverse()
+    ms_apply = timed(step_apply, args.steps)
+    ms_inverse = timed(step_inverse, args.steps)
+    flops = 2.0 * f_paper(d, n, m, k)
+    out = {
+        "metric": "svd_layer_fwd_bwd_gflops_paper_count",
+        "value": flops / (ms_apply * 1e-3) / 1e9,
+        "unit": "GFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_apply,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": name, "d": d, "n": n, "m": m, "k": k, "seed": w.seed},
+        "ms_inverse_apply_step": ms_inverse,
+        "gflops_inverse": flops / (ms_inverse * 1e-3) / 1e9,
+        "flops": {"paper": flops},
+    }
+    print(json.dumps(out))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -77,8 +131,7 @@ def main() -> int:
     name = args.workload or synthetic.HEADLINE
     w = synthetic.WORKLOADS[name]
     if w.svd_layer:
-        print("bench.py: use a Householder-product workload", file=sys.stderr)
-        return 2
+        return bench_svd_layer(args, name, w)
     d, n, m, k = w.d, w.n, w.m, w.k
     p = synthetic.workload_inputs(name)
     dev = torch.device("cuda:0")
