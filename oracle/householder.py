@@ -17,6 +17,7 @@ definition written out, one reflection at a time, in numpy fp64:
 * Eq. 5:           dL/dv_j, summed over the m columns of the mini-batch
 * Section 2.2 / Table 1:  W = U diag(sigma) V^T,  W^-1 = V diag(1/sigma) U^T,
                           exp(U S U^T) = U e^S U^T,  Cayley(U S U^T) = U (I - S)(I + S)^-1 U^T
+* Section 3.3 "Rectangular Matrices":  W (p x q) = U Sigma V^T with U p x p, V q x q, Sigma p x q
 
 Layout: V is [n][d], row j-1 holding v_j; X, A, G are [d][m], one sample per
 column. Every function promotes its inputs to float64.
@@ -227,3 +228,38 @@ def symmetric_gradients(Uv, sigma, X, G, kind: str = "identity"):
     dZ1 = s[:, None] * dZ2
     _, dU_inner, dX = product_gradients(Uv, X, dZ1, transpose=True)
     return Y, dU_outer + dU_inner, dsigma, dX
+
+
+# --------------------------------------------------------------------------
+# Rectangular W (Section 3.3 "Rectangular Matrices"): W in R^{p x q}, U in R^{p x p},
+# V in R^{q x q}, Sigma in R^{p x q} with sigma on its main diagonal (min(p, q) values).
+# --------------------------------------------------------------------------
+
+def _rect_scale(sigma, Z, p):
+    """Sigma Z for Z with q rows: row i < min(p, q) is scaled by sigma_i, the result has p rows."""
+    sigma = _f64(sigma)
+    r = sigma.shape[0]
+    out = np.zeros((p, Z.shape[1]))
+    out[:r] = sigma[:, None] * Z[:r]
+    return out
+
+
+def rectangular_apply(Uv, sigma, Vv, X) -> np.ndarray:
+    p = _f64(Uv).shape[1]
+    Z1 = product_apply(Vv, X, transpose=True)
+    return product_apply(Uv, _rect_scale(sigma, Z1, p))
+
+
+def rectangular_gradients(Uv, sigma, Vv, X, G):
+    """Y = U Sigma V^T X and the gradients of L = <G, Y> wrt (Uv, sigma, Vv, X)."""
+    sigma = _f64(sigma)
+    p = _f64(Uv).shape[1]
+    q = _f64(Vv).shape[1]
+    r = sigma.shape[0]
+    Z1 = product_apply(Vv, X, transpose=True)
+    Z2 = _rect_scale(sigma, Z1, p)
+    Y, dUv, dZ2 = product_gradients(Uv, Z2, G)
+    dsigma = np.sum(dZ2[:r] * Z1[:r], axis=1)
+    dZ1 = _rect_scale(sigma, dZ2, q)  # Sigma^T dZ2
+    _, dVv, dX = product_gradients(Vv, X, dZ1, transpose=True)
+    return Y, dUv, dsigma, dVv, dX

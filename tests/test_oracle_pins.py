@@ -322,3 +322,40 @@ def test_symmetric_gradients_against_central_differences(kind):
             p[idx][it.multi_index] += h; q[idx][it.multi_index] -= h
             fd[it.multi_index] = (loss(*p) - loss(*q)) / (2 * h)
         assert np.linalg.norm(grad - fd) <= 2e-6 * np.linalg.norm(fd), (kind, idx)
+
+
+# ----------------------------------------------------------- rectangular W (Section 3.3)
+
+def _dense_rect(Uv, sigma, Vv):
+    p, q = Uv.shape[1], Vv.shape[1]
+    S = np.zeros((p, q))
+    S[np.arange(sigma.size), np.arange(sigma.size)] = sigma
+    return _dense_product(Uv) @ S @ _dense_product(Vv).T
+
+
+@pytest.mark.parametrize("p,q", [(9, 5), (5, 9), (7, 7)])
+def test_rectangular_layer_against_dense(p, q):
+    """Section 3.3: W = U Sigma V^T with a rectangular diagonal Sigma; its singular values are sigma."""
+    r = _rng(16 + p + q)
+    Uv = r.standard_normal((p, p)); Vv = r.standard_normal((q, q))
+    sigma = r.uniform(0.5, 2.0, min(p, q)); X = r.standard_normal((q, 4)); G = r.standard_normal((p, 4))
+    W = _dense_rect(Uv, sigma, Vv)
+    assert W.shape == (p, q)
+    np.testing.assert_allclose(orc.rectangular_apply(Uv, sigma, Vv, X), W @ X, atol=1e-12)
+    np.testing.assert_allclose(np.linalg.svd(W, compute_uv=False), np.sort(sigma)[::-1], atol=1e-12)
+
+    def loss(Uv_, sigma_, Vv_, X_):
+        return float(np.sum(G * (_dense_rect(Uv_, sigma_, Vv_) @ X_)))
+
+    Y, dUv, dsigma, dVv, dX = orc.rectangular_gradients(Uv, sigma, Vv, X, G)
+    np.testing.assert_allclose(dX, W.T @ G, atol=1e-12)
+    h = 1e-6
+    args = [Uv, sigma, Vv, X]
+    for idx, grad in ((0, dUv), (1, dsigma), (2, dVv), (3, dX)):
+        fd = np.zeros_like(grad)
+        it = np.nditer(grad, flags=["multi_index"])
+        for _ in it:
+            a = [x.copy() for x in args]; b = [x.copy() for x in args]
+            a[idx][it.multi_index] += h; b[idx][it.multi_index] -= h
+            fd[it.multi_index] = (loss(*a) - loss(*b)) / (2 * h)
+        assert np.linalg.norm(grad - fd) <= 1e-6 * np.linalg.norm(fd), idx
