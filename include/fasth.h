@@ -164,6 +164,22 @@ int svd_sym_apply_backward(const fasth_svd_shape* shape, int function, const flo
                            const float* G, float* dUv, float* dsigma, float* dX,
                            void* workspace, size_t workspace_bytes, void* stream);
 
+/* Section 3.3 "Rectangular Matrices": W [rows][cols] = U Sigma V^T with U = prod H(u_j) of size
+ * rows x rows (Uv is [n_u][rows]), V = prod H(v_j) of size cols x cols (Vv is [n_v][cols]) and Sigma
+ * rows x cols, zero except Sigma_ii = sigma[i] for i < min(rows, cols). X and dX are [cols][m]; Y and G
+ * are [rows][m]; k must divide both n_u and n_v; each of (rows, n_u) and (cols, n_v) obeys the limits
+ * of fasth_shape. Y = U (Sigma (V^T X)); the backward call follows the apply call on the same
+ * workspace and arguments and writes dUv [n_u][rows], dsigma [min(rows, cols)], dVv [n_v][cols], dX. */
+typedef struct fasth_rect_shape {
+  int rows, cols, n_u, n_v, m, k;
+} fasth_rect_shape;
+size_t svd_rect_workspace_bytes(const fasth_rect_shape* shape);
+int svd_rect_apply(const fasth_rect_shape* shape, const float* Uv, const float* sigma, const float* Vv,
+                   const float* X, float* Y, void* workspace, size_t workspace_bytes, void* stream);
+int svd_rect_apply_backward(const fasth_rect_shape* shape, const float* Uv, const float* sigma, const float* Vv,
+                            const float* G, float* dUv, float* dsigma, float* dVv, float* dX,
+                            void* workspace, size_t workspace_bytes, void* stream);
+
 /* Table 1, row "Determinant": *log_abs_det (one float in device memory) = sum_i log|sigma_i| =
  * log|det(U diag(sigma) V^T)|; if dsigma is not NULL it receives the gradient 1/sigma_i. */
 int svd_layer_log_abs_det(int d, const float* sigma, float* log_abs_det, float* dsigma, void* stream);

@@ -39,6 +39,9 @@ EXPORTED_SYMBOLS = (
     "svd_layer_inverse_apply_backward",
     "svd_sym_apply",
     "svd_sym_apply_backward",
+    "svd_rect_workspace_bytes",
+    "svd_rect_apply",
+    "svd_rect_apply_backward",
     "svd_layer_log_abs_det",
     "fasth_kernel_name",
     "fasth_profile_enable",
@@ -53,6 +56,11 @@ class fasth_shape(ctypes.Structure):
 
 class fasth_svd_shape(ctypes.Structure):
     _fields_ = [("d", ctypes.c_int), ("n", ctypes.c_int), ("m", ctypes.c_int), ("k", ctypes.c_int)]
+
+
+class fasth_rect_shape(ctypes.Structure):
+    _fields_ = [("rows", ctypes.c_int), ("cols", ctypes.c_int), ("n_u", ctypes.c_int), ("n_v", ctypes.c_int),
+                ("m", ctypes.c_int), ("k", ctypes.c_int)]
 
 
 class FasthError(RuntimeError):
@@ -111,6 +119,13 @@ def load_library() -> ctypes.CDLL:
     lib.svd_sym_apply.argtypes = [sshp, I, P, P, P, P, P, S, P]
     lib.svd_sym_apply_backward.restype = I
     lib.svd_sym_apply_backward.argtypes = [sshp, I, P, P, P, P, P, P, P, S, P]
+    rshp = ctypes.POINTER(fasth_rect_shape)
+    lib.svd_rect_workspace_bytes.restype = S
+    lib.svd_rect_workspace_bytes.argtypes = [rshp]
+    lib.svd_rect_apply.restype = I
+    lib.svd_rect_apply.argtypes = [rshp, P, P, P, P, P, P, S, P]
+    lib.svd_rect_apply_backward.restype = I
+    lib.svd_rect_apply_backward.argtypes = [rshp, P, P, P, P, P, P, P, P, P, S, P]
     lib.svd_layer_log_abs_det.restype = I
     lib.svd_layer_log_abs_det.argtypes = [I, P, P, P, P]
     lib.fasth_kernel_name.restype = ctypes.c_char_p
@@ -310,6 +325,37 @@ def svd_sym_apply_backward(Uv, sigma, G, dUv, dsigma, dX, workspace, k: int, fun
                                                _ptr(dsigma, "dsigma"), _ptr(dX, "dX"),
                                                _ptr(workspace, "workspace"), workspace.numel(), _stream())
     _check(rc, "svd_sym_apply_backward")
+
+
+def _rect_shape(Uv, Vv, m, k) -> fasth_rect_shape:
+    return fasth_rect_shape(int(Uv.shape[1]), int(Vv.shape[1]), int(Uv.shape[0]), int(Vv.shape[0]), int(m), int(k))
+
+
+def svd_rect_workspace_bytes(rows: int, cols: int, n_u: int, n_v: int, m: int, k: int) -> int:
+    shape = fasth_rect_shape(int(rows), int(cols), int(n_u), int(n_v), int(m), int(k))
+    return int(load_library().svd_rect_workspace_bytes(ctypes.byref(shape)))
+
+
+def svd_rect_apply(Uv, sigma, Vv, X, Y, workspace, k: int) -> None:
+    m = X.shape[1]
+    shape = _rect_shape(Uv, Vv, m, k)
+    assert sigma.shape == (min(shape.rows, shape.cols),) and X.shape == (shape.cols, m) and Y.shape == (shape.rows, m)
+    rc = load_library().svd_rect_apply(ctypes.byref(shape), _ptr(Uv, "Uv"), _ptr(sigma, "sigma"), _ptr(Vv, "Vv"),
+                                       _ptr(X, "X"), _ptr(Y, "Y"), _ptr(workspace, "workspace"), workspace.numel(),
+                                       _stream())
+    _check(rc, "svd_rect_apply")
+
+
+def svd_rect_apply_backward(Uv, sigma, Vv, G, dUv, dsigma, dVv, dX, workspace, k: int) -> None:
+    m = G.shape[1]
+    shape = _rect_shape(Uv, Vv, m, k)
+    assert G.shape == (shape.rows, m) and dX.shape == (shape.cols, m) and dsigma.shape == sigma.shape
+    assert dUv.shape == Uv.shape and dVv.shape == Vv.shape
+    rc = load_library().svd_rect_apply_backward(ctypes.byref(shape), _ptr(Uv, "Uv"), _ptr(sigma, "sigma"),
+                                                _ptr(Vv, "Vv"), _ptr(G, "G"), _ptr(dUv, "dUv"),
+                                                _ptr(dsigma, "dsigma"), _ptr(dVv, "dVv"), _ptr(dX, "dX"),
+                                                _ptr(workspace, "workspace"), workspace.numel(), _stream())
+    _check(rc, "svd_rect_apply_backward")
 
 
 def svd_layer_log_abs_det(sigma, out, dsigma=None) -> None:

@@ -393,6 +393,7 @@ struct ChainArgs {
   float* save_c;          // [m][n] or null
   const float* in_scale;  // [d] or null: input row x is multiplied by diag_factor(in_scale_mode, in_scale[x])
   int in_scale_mode;
+  int in_rows;            // rows of `in` that exist; rows in_rows..d-1 of the chain's input are zero
   int d, n, m, k, kp, nb;
   int transpose;
 };
@@ -413,7 +414,7 @@ __global__ void __launch_bounds__(1024) chain_kernel(ChainArgs p) {
   for (int u = 0; u < U; ++u) {
     const int x = tid + u * nthreads;
     float v = 0.f;
-    if (x < d) {
+    if (x < d && x < p.in_rows) {
       v = p.in[(size_t)x * m + col];
       if (p.in_scale_mode) v *= diag_factor(p.in_scale_mode, p.in_scale[x]);
     }
@@ -534,7 +535,7 @@ __device__ __forceinline__ Chunk<VW> load_column_chunk(const ChainArgs& p, int c
 #pragma unroll
   for (int r = 0; r < VW; ++r) {
     float v = 0.f;
-    if (ok) {
+    if (ok && x0 + r < (unsigned)p.in_rows) {
       v = p.in[(size_t)(x0 + r) * p.m + col];
       if (p.in_scale_mode) v *= diag_factor(p.in_scale_mode, p.in_scale[x0 + r]);
     }
@@ -1244,12 +1245,13 @@ static int build_factors(const Product& P, const float* V, hipStream_t stream) {
 // slots of the workspace, false into the gradient slots.
 static int run_chain(const Product& P, const float* V, const float* in, float* out, int transpose, bool activation,
                      const float* in_scale, int in_scale_mode, hipStream_t stream, bool save = true,
-                     const float* factors = nullptr) {
+                     const float* factors = nullptr, int in_rows = -1) {
   ChainArgs a;
   a.V = V; a.T = factors ? factors : P.T(); a.in = in; a.out = out;
   a.save_in = !save ? nullptr : activation ? P.saveA() : P.saveG();
   a.save_c = !save ? nullptr : activation ? P.saveCa() : P.saveCg();
   a.in_scale = in_scale; a.in_scale_mode = in_scale_mode;
+  a.in_rows = in_rows < 0 ? P.d : in_rows;
   a.d = P.d; a.n = P.n; a.m = P.m; a.k = P.k; a.kp = P.L.kp; a.nb = P.L.nb;
   a.transpose = transpose;
   return launch_chain(a, stream);
@@ -1372,6 +1374,30 @@ static int sym_scale_mode(int function) {
     case FASTH_DIAG_CAYLEY: return 4;
     default: return -1;
   }
+}
+
+// Rectangular layer (Section 3.3 "Rectangular Matrices"): U is rows x rows, V is cols x cols and
+// Sigma is rows x cols with min(rows, cols) diagonal entries.
+struct RectLayout {
+  size_t off_U, off_V, off_Z1, off_dZ2, total;
+};
+
+static int check_rect_shape(const fasth_rect_shape* s, fasth_shape* u, fasth_shape* v) {
+  if (!s) return FASTH_EINVAL;
+  u->d = s->rows; u->n = s->n_u; u->m = s->m; u->k = s->k; u->transpose = 0;
+  v->d = s->cols; v->n = s->n_v; v->m = s->m; v->k = s->k; v->transpose = 0;
+  const int rc = check_shape(u);
+  return rc != FASTH_OK ? rc : check_shape(v);
+}
+
+static RectLayout make_rect_layout(const fasth_shape& u, const fasth_shape& v) {
+  RectLayout S;
+  S.off_U = 0;
+  S.off_V = align_up(make_layout(u.d, u.n, u.m, u.k).total, 256);
+  S.off_Z1 = S.off_V + align_up(make_layout(v.d, v.n, v.m, v.k).total, 256);
+  S.off_dZ2 = S.off_Z1 + align_up((size_t)v.d * v.m * sizeof(float), 256);
+  S.total = S.off_dZ2 + align_up((size_t)u.d * u.m * sizeof(float), 256);
+  return S;
 }
 
 }  // namespace fasth
@@ -1705,6 +1731,67 @@ int svd_layer_inverse_apply_backward(const fasth_svd_shape* shape, const float* 
                                      const float* Vv, const float* G, float* dUv, float* dsigma, float* dVv,
                                      float* dX, void* workspace, size_t workspace_bytes, void* stream) {
   return svd_backward(shape, Uv, sigma, Vv, G, dUv, dsigma, dVv, dX, workspace, workspace_bytes, stream, 2);
+}
+
+size_t svd_rect_workspace_bytes(const fasth_rect_shape* shape) {
+  fasth_shape fu, fv;
+  if (check_rect_shape(shape, &fu, &fv) != FASTH_OK) return 0;
+  return make_rect_layout(fu, fv).total;
+}
+
+int svd_rect_apply(const fasth_rect_shape* shape, const float* Uv, const float* sigma, const float* Vv, const float* X,
+                   float* Y, void* workspace, size_t workspace_bytes, void* stream) {
+  fasth_shape fu, fv;
+  int rc = check_rect_shape(shape, &fu, &fv);
+  if (rc != FASTH_OK) return rc;
+  if (!Uv || !sigma || !Vv || !X || !Y || !workspace) return FASTH_EINVAL;
+  if (!aligned16(Uv) || !aligned16(sigma) || !aligned16(Vv) || !aligned16(X) || !aligned16(Y) || !aligned16(workspace))
+    return FASTH_EALIGN;
+  const RectLayout S = make_rect_layout(fu, fv);
+  if (workspace_bytes < S.total) return FASTH_EWORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  char* ws = static_cast<char*>(workspace);
+  const Product Pu = bind(fu.d, fu.n, fu.m, fu.k, ws + S.off_U);
+  const Product Pv = bind(fv.d, fv.n, fv.m, fv.k, ws + S.off_V);
+  float* Z1 = reinterpret_cast<float*>(ws + S.off_Z1);
+  const int r = fu.d < fv.d ? fu.d : fv.d;
+  if ((rc = build_factors(Pv, Vv, st)) != FASTH_OK) return rc;
+  if ((rc = build_factors(Pu, Uv, st)) != FASTH_OK) return rc;
+  if ((rc = run_chain(Pv, Vv, X, Z1, 1, true, nullptr, 0, st)) != FASTH_OK) return rc;
+  // Sigma Z1: the first r rows of Z1 scaled by sigma, rows r..rows-1 zero; fused into the chain's load
+  return run_chain(Pu, Uv, Z1, Y, 0, true, sigma, 1, st, true, nullptr, r);
+}
+
+int svd_rect_apply_backward(const fasth_rect_shape* shape, const float* Uv, const float* sigma, const float* Vv,
+                            const float* G, float* dUv, float* dsigma, float* dVv, float* dX, void* workspace,
+                            size_t workspace_bytes, void* stream) {
+  fasth_shape fu, fv;
+  int rc = check_rect_shape(shape, &fu, &fv);
+  if (rc != FASTH_OK) return rc;
+  if (!Uv || !sigma || !Vv || !G || !dUv || !dsigma || !dVv || !dX || !workspace) return FASTH_EINVAL;
+  if (!aligned16(Uv) || !aligned16(sigma) || !aligned16(Vv) || !aligned16(G) || !aligned16(dUv) ||
+      !aligned16(dsigma) || !aligned16(dVv) || !aligned16(dX) || !aligned16(workspace))
+    return FASTH_EALIGN;
+  const RectLayout S = make_rect_layout(fu, fv);
+  if (workspace_bytes < S.total) return FASTH_EWORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  char* ws = static_cast<char*>(workspace);
+  const Product Pu = bind(fu.d, fu.n, fu.m, fu.k, ws + S.off_U);
+  const Product Pv = bind(fv.d, fv.n, fv.m, fv.k, ws + S.off_V);
+  const float* Z1 = reinterpret_cast<const float*>(ws + S.off_Z1);
+  float* dZ2 = reinterpret_cast<float*>(ws + S.off_dZ2);
+  const int r = fu.d < fv.d ? fu.d : fv.d;
+  if ((rc = run_chain(Pu, Uv, G, dZ2, 1, false, nullptr, 0, st)) != FASTH_OK) return rc;
+  if ((rc = run_dv(Pu, Uv, dUv, 0, st)) != FASTH_OK) return rc;
+  {
+    prof::Scope ps_(FASTH_KERNEL_DSIGMA, st);
+    hipLaunchKernelGGL(dsigma_kernel, dim3((r + 3) / 4), dim3(256), 0, st, (const float*)dZ2, Z1, sigma, dsigma, r,
+                       fu.m, 1);
+  }
+  FASTH_HIP(hipGetLastError());
+  // Sigma^T dZ2: first r rows scaled, rows r..cols-1 zero
+  if ((rc = run_chain(Pv, Vv, dZ2, dX, 0, false, sigma, 1, st, true, nullptr, r)) != FASTH_OK) return rc;
+  return run_dv(Pv, Vv, dVv, 1, st);
 }
 
 }  // extern "C"

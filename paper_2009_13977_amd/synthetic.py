@@ -79,6 +79,17 @@ def svd_layer_problem(d: int, n: int, m: int, seed: int) -> Dict[str, np.ndarray
     return {"Uv": _f32(Uv), "Vv": _f32(Vv), "sigma": _f32(sigma), "X": _f32(X), "G": _f32(G)}
 
 
+def rect_layer_problem(rows: int, cols: int, n_u: int, n_v: int, m: int, seed: int) -> Dict[str, np.ndarray]:
+    """Uv [n_u][rows], Vv [n_v][cols], sigma [min(rows, cols)] in [0.5, 2], X [cols][m], G [rows][m]."""
+    rng = np.random.default_rng(seed)
+    Uv = rng.standard_normal((n_u, rows))
+    Vv = rng.standard_normal((n_v, cols))
+    sigma = rng.uniform(0.5, 2.0, size=min(rows, cols))
+    X = rng.standard_normal((cols, m))
+    G = rng.standard_normal((rows, m))
+    return {"Uv": _f32(Uv), "Vv": _f32(Vv), "sigma": _f32(sigma), "X": _f32(X), "G": _f32(G)}
+
+
 def workload_inputs(name: str) -> Dict[str, np.ndarray]:
     w = WORKLOADS[name]
     if w.svd_layer:

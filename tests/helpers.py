@@ -76,3 +76,17 @@ def gpu_svd_sym(Uv, sigma, X, G, k, function="identity"):
     B.svd_sym_apply_backward(Ud, sd, Gd, dU, ds, dX, ws, k, function)
     torch.cuda.synchronize()
     return tuple(t.cpu().numpy() for t in (Y, dU, ds, dX))
+
+
+def gpu_svd_rect(Uv, sigma, Vv, X, G, k):
+    import torch
+    from paper_2009_13977_amd import binding as B
+    (n_u, rows), (n_v, cols), m = Uv.shape, Vv.shape, X.shape[1]
+    Ud, sd, Vd, Xd, Gd = (to_gpu(a) for a in (Uv, sigma, Vv, X, G))
+    Y = torch.empty_like(Gd); dX = torch.empty_like(Xd)
+    dU = torch.empty_like(Ud); dVv = torch.empty_like(Vd); ds = torch.empty_like(sd)
+    ws = B.new_workspace(B.svd_rect_workspace_bytes(rows, cols, n_u, n_v, m, k))
+    B.svd_rect_apply(Ud, sd, Vd, Xd, Y, ws, k)
+    B.svd_rect_apply_backward(Ud, sd, Vd, Gd, dU, ds, dVv, dX, ws, k)
+    torch.cuda.synchronize()
+    return tuple(t.cpu().numpy() for t in (Y, dU, ds, dVv, dX))

@@ -14,7 +14,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def _declared_symbols():
     text = open(os.path.join(ROOT, "include", "fasth.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return set(re.findall(r"\b((?:fasth|svd_layer|svd_sym)_\w+)\s*\(", text))
+    return set(re.findall(r"\b((?:fasth|svd_layer|svd_sym|svd_rect)_\w+)\s*\(", text))
 
 
 def test_library_exports_every_declared_symbol():
@@ -90,3 +90,20 @@ def test_block_size_search_argument_errors():
     assert call(V=None) == B.FASTH_EINVAL
     assert call(V=260) == B.FASTH_EALIGN
     assert call(shape=B.fasth_shape(64, 64, 0, 0, 0)) == B.FASTH_EINVAL
+
+
+def test_rectangular_layer_argument_errors():
+    lib = B.load_library()
+    ok = B.fasth_rect_shape(96, 64, 96, 64, 8, 32)
+    assert B.svd_rect_workspace_bytes(96, 64, 96, 64, 8, 32) > 0
+    assert B.svd_rect_workspace_bytes(96, 64, 96, 60, 8, 32) == 0      # k does not divide n_v
+    assert B.svd_rect_workspace_bytes(96, 20000, 96, 64, 8, 32) == 0   # cols beyond the supported range
+    bad = B.fasth_rect_shape(96, 64, 96, 60, 8, 32)
+    assert lib.svd_rect_apply(ctypes.byref(bad), 256, 256, 256, 256, 256, 256, 1 << 40, None) == B.FASTH_EINVAL
+    assert lib.svd_rect_apply(ctypes.byref(ok), 256, None, 256, 256, 256, 256, 1 << 40, None) == B.FASTH_EINVAL
+    assert lib.svd_rect_apply(ctypes.byref(ok), 256, 256, 256, 260, 256, 256, 1 << 40, None) == B.FASTH_EALIGN
+    assert lib.svd_rect_apply(ctypes.byref(ok), 256, 256, 256, 256, 256, 256, 16, None) == B.FASTH_EWORKSPACE
+    assert lib.svd_rect_apply_backward(ctypes.byref(ok), 256, 256, 256, 256, 256, None, 256, 256, 256, 1 << 40,
+                                       None) == B.FASTH_EINVAL
+    assert lib.svd_rect_apply_backward(ctypes.byref(ok), 256, 256, 256, 256, 256, 256, 256, 256, 256, 16,
+                                       None) == B.FASTH_EWORKSPACE

@@ -7,7 +7,7 @@ import pytest
 
 from oracle import householder as orc
 from paper_2009_13977_amd import synthetic
-from helpers import REL_TOL, gpu_fasth, gpu_sequential, gpu_svd_layer, gpu_svd_sym, rel_err
+from helpers import REL_TOL, gpu_fasth, gpu_sequential, gpu_svd_layer, gpu_svd_rect, gpu_svd_sym, rel_err
 
 pytestmark = pytest.mark.gpu
 
@@ -255,6 +255,25 @@ def test_symmetric_forms(d, n, m, k, function):
     got = gpu_svd_sym(Uv, sigma, X, G, k, function)
     ref = orc.symmetric_gradients(Uv, sigma, X, G, function)
     for name, g, r in zip(("Y", "dUv", "dsigma", "dX"), got, ref):
+        assert rel_err(g, r) <= REL_TOL, (name, rel_err(g, r))
+
+
+RECT = [  # rows, cols, n_u, n_v, m, k: both orientations, every family of chain kernel, ragged min(rows, cols)
+    (64, 48, 64, 48, 8, 16), (96, 256, 96, 256, 32, 32), (1024, 512, 1024, 512, 32, 32),
+    (512, 1024, 512, 1024, 32, 32), (100, 37, 60, 24, 5, 12), (3000, 1000, 64, 64, 3, 32),
+    (1024, 510, 64, 64, 4, 32), (5001, 64, 24, 32, 2, 8), (7, 7, 7, 7, 1, 7),
+]
+
+
+@pytest.mark.parametrize("rows,cols,n_u,n_v,m,k", RECT)
+def test_rectangular_layer(rows, cols, n_u, n_v, m, k):
+    """Section 3.3 "Rectangular Matrices": W = U Sigma V^T with a rows x cols diagonal Sigma."""
+    _say(f"svd rect rows={rows} cols={cols} n_u={n_u} n_v={n_v} m={m} k={k}")
+    p = synthetic.rect_layer_problem(rows, cols, n_u, n_v, m, seed=11000 + rows + cols + m + k)
+    got = gpu_svd_rect(p["Uv"], p["sigma"], p["Vv"], p["X"], p["G"], k)
+    ref = orc.rectangular_gradients(p["Uv"], p["sigma"], p["Vv"], p["X"], p["G"])
+    for name, g, r in zip(("Y", "dUv", "dsigma", "dVv", "dX"), got, ref):
+        assert g.shape == r.shape, name
         assert rel_err(g, r) <= REL_TOL, (name, rel_err(g, r))
 
 
