@@ -280,32 +280,34 @@ __global__ void __launch_bounds__(256) t_build_kernel(const float* __restrict__ 
 // block streams the block's rows through LDS in 128-column slabs; wave w multiplies columns
 // [16 w, 16 w + 16) of each slab, the 8 partial Gram matrices are added through LDS, and the same
 // workgroup inverts. Saves a launch and the round trip of the partial sums through memory.
-template <int KT>
+template <int KT, int VEC>  // VEC = 4 when d is a multiple of 4 (16-byte loads), else 1
 __global__ void __launch_bounds__(512) factor_fused_kernel(const float* __restrict__ V, float* __restrict__ T,
                                                            int d, int k) {
   constexpr int kp = 16 * KT, LD = kGramChunk + 4, NTILE = KT * (KT + 1) / 2, NW = 8, LDM = kp + 4;
-  constexpr int PER = kp * kGramChunk / 512;  // slab elements per thread
-  __shared__ float Vs[kp * LD];
+  constexpr int PER = kp * kGramChunk / 512 / VEC;  // loads per thread and slab
+  constexpr int XV = kGramChunk / VEC;              // loads per slab row
+  __shared__ __align__(16) float Vs[kp * LD];
   __shared__ float Red[NW * NTILE * 256];
   __shared__ float Ms[kp * LDM];
   __shared__ float Xs[(kp * (kp / 2 + 4) / 2 + 64) > kp * 17 ? (kp * (kp / 2 + 4) / 2 + 64) : kp * 17];
   const int i = blockIdx.x;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, li = lane & 15, q = lane >> 4;
-  const float* Vi = V + (size_t)i * k * d;
+  // the block's k rows as one buffer: rows k .. kp - 1 of the padded block lie beyond it and read as zero
+  const BufferDesc vdesc = make_buffer(V + (size_t)i * k * d, (size_t)k * d * sizeof(float));
   f32x4 acc[NTILE];
 #pragma unroll
   for (int t = 0; t < NTILE; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
   // Eight slabs (1024 columns) are fetched at once, so the trip to memory is paid once per 1024
   // columns of V instead of once per slab.
   constexpr int NS = 8;
-  float stage[NS][PER];
+  BufVec<VEC> stage[NS][PER];
   for (int xs = 0; xs < d; xs += NS * kGramChunk) {
 #pragma unroll
     for (int sl = 0; sl < NS; ++sl) {
 #pragma unroll
       for (int it = 0; it < PER; ++it) {
-        const int idx = tid + it * 512, j = idx / kGramChunk, x = xs + sl * kGramChunk + idx % kGramChunk;
-        stage[sl][it] = (j < k && x < d) ? Vi[(size_t)j * d + x] : 0.f;
+        const int idx = tid + it * 512, j = idx / XV, x = xs + sl * kGramChunk + (idx % XV) * VEC;
+        stage[sl][it] = buffer_load<VEC>(vdesc, x < d ? (unsigned)(j * d + x) * 4u : kOob, 0);
       }
     }
 #pragma unroll
@@ -314,7 +316,7 @@ __global__ void __launch_bounds__(512) factor_fused_kernel(const float* __restri
 #pragma unroll
         for (int it = 0; it < PER; ++it) {
           const int idx = tid + it * 512;
-          Vs[(idx / kGramChunk) * LD + idx % kGramChunk] = stage[sl][it];
+          lds_store<VEC>(Vs + (idx / XV) * LD + (idx % XV) * VEC, stage[sl][it]);
         }
         __syncthreads();
         int t = 0;
@@ -900,9 +902,9 @@ struct DvArgs {
   int accumulate;       // add to dV instead of overwriting it (a factor that enters a layer twice)
 };
 
-template <int KT>  // kp = 16 KT
+template <int KT, int VEC>  // kp = 16 KT; VEC = 4 when d is a multiple of 4 (16-byte loads along x), else 1
 __global__ void __launch_bounds__(256) dv_kernel(DvArgs p) {
-  extern __shared__ float smem[];
+  extern __shared__ __align__(16) float smem[];
   constexpr int kp = 16 * KT;
   const int k = p.k, d = p.d, m = p.m, n = p.n;
   constexpr int LDE = kp + 4, LDC = kDvMChunk + 4, LDX = kDvTile + 4;
@@ -915,16 +917,68 @@ __global__ void __launch_bounds__(256) dv_kernel(DvArgs p) {
   const int i = blockIdx.y, x0 = blockIdx.x * kDvTile;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, li = lane & 15, q = lane >> 4;
   constexpr int kt = KT;
+  constexpr int XV = kDvTile / VEC;                    // loads per tile row
+  constexpr int V_PER = kp * kDvTile / VEC / 256;      // loads of the V tile per thread
+  constexpr int X_PER = kDvMChunk * kDvTile / VEC / 256;  // loads of the a^T / g^T tile per thread
+  constexpr int C_PER = kp * kDvMChunk / 256;          // loads of each coefficient tile per thread
 
-  // The block's rows of V are needed last; fetch them first so one trip to memory covers them
-  // and the first mini-batch chunk.
+  // All fetches go through buffers whose size is the valid extent, so nothing branches on a bound
+  // and the fetches of a tile are in flight together. The block's rows of V are needed last; they
+  // are fetched first so that one trip to memory covers them and the first mini-batch chunk.
+  BufVec<VEC> vreg[V_PER];
+  {
+    const BufferDesc vdesc = make_buffer(p.V + (size_t)i * k * d, (size_t)k * d * sizeof(float));
 #pragma unroll
-  for (int it = 0; it < kp * kDvTile / 256; ++it) {
+    for (int it = 0; it < V_PER; ++it) {
+      const int idx = tid + it * 256, j = idx / XV, x = x0 + (idx % XV) * VEC;
+      vreg[it] = buffer_load<VEC>(vdesc, x < d ? (unsigned)(j * d + x) * 4u : kOob, 0);  // rows >= k lie beyond the buffer
+    }
+  }
+  struct Chunk {
+    BufVec<VEC> g[X_PER], a[X_PER];
+    float ca[C_PER], cg[C_PER];
+  };
+  auto fetch = [&](int mc, Chunk& c) {
+    const int rows = min(kDvMChunk, m - mc);  // mini-batch columns in this chunk
+    const BufferDesc gdesc = make_buffer(p.saveG + ((size_t)i * m + mc) * d, (size_t)rows * d * sizeof(float));
+    const BufferDesc adesc = make_buffer(p.saveA + ((size_t)i * m + mc) * d, (size_t)rows * d * sizeof(float));
+    const BufferDesc cadesc = make_buffer(p.saveCa + (size_t)mc * n, (size_t)rows * n * sizeof(float));
+    const BufferDesc cgdesc = make_buffer(p.saveCg + (size_t)mc * n, (size_t)rows * n * sizeof(float));
+#pragma unroll
+    for (int it = 0; it < X_PER; ++it) {
+      const int idx = tid + it * 256, lc = idx / XV, x = x0 + (idx % XV) * VEC;
+      const unsigned off = x < d ? (unsigned)(lc * d + x) * 4u : kOob;
+      c.g[it] = buffer_load<VEC>(gdesc, off, 0);
+      c.a[it] = buffer_load<VEC>(adesc, off, 0);
+    }
+#pragma unroll
+    for (int it = 0; it < C_PER; ++it) {
+      const int idx = tid + it * 256, j = idx % kp, lc = idx / kp;
+      const unsigned off = j < k ? (unsigned)(lc * n + i * k + j) * 4u : kOob;
+      c.ca[it] = buffer_load<1>(cadesc, off, 0).e[0];
+      c.cg[it] = buffer_load<1>(cgdesc, off, 0).e[0];
+    }
+  };
+  auto to_lds = [&](const Chunk& c) {
+#pragma unroll
+    for (int it = 0; it < X_PER; ++it) {
+      const int idx = tid + it * 256, lc = idx / XV, xv = (idx % XV) * VEC;
+      lds_store<VEC>(gT + lc * LDX + xv, c.g[it]);
+      lds_store<VEC>(aT + lc * LDX + xv, c.a[it]);
+    }
+#pragma unroll
+    for (int it = 0; it < C_PER; ++it) {
+      const int idx = tid + it * 256, j = idx % kp, lc = idx / kp;
+      Cas[j * LDC + lc] = c.ca[it];
+      Cgs[j * LDC + lc] = c.cg[it];
+    }
+  };
+  Chunk cur;
+  fetch(0, cur);
+#pragma unroll
+  for (int it = 0; it < V_PER; ++it) {
     const int idx = tid + it * 256;
-    const int j = idx / kDvTile, x = idx % kDvTile;
-    float v = 0.f;
-    if (j < k && x0 + x < d) v = p.V[((size_t)i * k + j) * d + x0 + x];
-    Vs[j * LDX + x] = v;
+    lds_store<VEC>(Vs + (idx / XV) * LDX + (idx % XV) * VEC, vreg[it]);
   }
 
   // One pass over the mini-batch accumulates both Z = Cg Ca^T and Ca g^T + Cg a^T.
@@ -937,33 +991,9 @@ __global__ void __launch_bounds__(256) dv_kernel(DvArgs p) {
   for (int w = 0; w < kMaxAcc; ++w) acc[w] = f32x4{0.f, 0.f, 0.f, 0.f};
   for (int mc = 0; mc < m; mc += kDvMChunk) {
     if (mc) __syncthreads();
-#pragma unroll
-    for (int it = 0; it < kp * kDvMChunk / 256; ++it) {
-      const int idx = tid + it * 256;
-      const int j = idx % kp, lc = idx / kp;
-      float ca = 0.f, cg = 0.f;
-      if (j < k && mc + lc < m) {
-        const size_t o = (size_t)(mc + lc) * n + (size_t)i * k + j;
-        ca = p.saveCa[o];
-        cg = p.saveCg[o];
-      }
-      Cas[j * LDC + lc] = ca;
-      Cgs[j * LDC + lc] = cg;
-    }
-#pragma unroll
-    for (int it = 0; it < kDvMChunk * kDvTile / 256; ++it) {
-      const int idx = tid + it * 256;
-      const int lc = idx / kDvTile, x = idx % kDvTile;
-      float g = 0.f, a = 0.f;
-      if (mc + lc < m && x0 + x < d) {
-        const size_t o = ((size_t)i * m + mc + lc) * d + x0 + x;
-        g = p.saveG[o];
-        a = p.saveA[o];
-      }
-      gT[lc * LDX + x] = g;
-      aT[lc * LDX + x] = a;
-    }
+    to_lds(cur);
     __syncthreads();
+    if (mc + kDvMChunk < m) fetch(mc + kDvMChunk, cur);  // in flight during this chunk's products
 #pragma unroll
     for (int w = 0; w < kMaxZ; ++w) {
       const int t = wave + 4 * w;
@@ -1216,8 +1246,14 @@ static int build_factors(const Product& P, const float* V, hipStream_t stream) {
   const int kp = P.L.kp;
   if (kp <= 32) {
     prof::Scope ps_(FASTH_KERNEL_FACTOR, stream);
-    if (kp == 16) hipLaunchKernelGGL(factor_fused_kernel<1>, dim3(P.L.nb), dim3(512), 0, stream, V, P.T(), P.d, P.k);
-    else hipLaunchKernelGGL(factor_fused_kernel<2>, dim3(P.L.nb), dim3(512), 0, stream, V, P.T(), P.d, P.k);
+    const dim3 grid(P.L.nb), block(512);
+    if (P.d % 4 == 0) {
+      if (kp == 16) hipLaunchKernelGGL((factor_fused_kernel<1, 4>), grid, block, 0, stream, V, P.T(), P.d, P.k);
+      else hipLaunchKernelGGL((factor_fused_kernel<2, 4>), grid, block, 0, stream, V, P.T(), P.d, P.k);
+    } else {
+      if (kp == 16) hipLaunchKernelGGL((factor_fused_kernel<1, 1>), grid, block, 0, stream, V, P.T(), P.d, P.k);
+      else hipLaunchKernelGGL((factor_fused_kernel<2, 1>), grid, block, 0, stream, V, P.T(), P.d, P.k);
+    }
     FASTH_HIP(hipGetLastError());
     return FASTH_OK;
   }
@@ -1266,11 +1302,17 @@ static int run_dv(const Product& P, const float* V, float* dV, int transpose, hi
   const size_t lds = dv_lds(P.L.kp);
   const dim3 grid((P.d + kDvTile - 1) / kDvTile, P.L.nb);
   prof::Scope ps_(FASTH_KERNEL_DV, stream);
-#define FASTH_LAUNCH_DV(KT)                                                  \
-  do {                                                                       \
-    int rc_ = allow_lds(dv_kernel<KT>, lds);                                 \
-    if (rc_ != FASTH_OK) return rc_;                                         \
-    hipLaunchKernelGGL(dv_kernel<KT>, grid, dim3(256), lds, stream, a);      \
+#define FASTH_LAUNCH_DV(KT)                                                            \
+  do {                                                                                 \
+    if (P.d % 4 == 0) {                                                                \
+      int rc_ = allow_lds(dv_kernel<KT, 4>, lds);                                      \
+      if (rc_ != FASTH_OK) return rc_;                                                 \
+      hipLaunchKernelGGL((dv_kernel<KT, 4>), grid, dim3(256), lds, stream, a);         \
+    } else {                                                                           \
+      int rc_ = allow_lds(dv_kernel<KT, 1>, lds);                                      \
+      if (rc_ != FASTH_OK) return rc_;                                                 \
+      hipLaunchKernelGGL((dv_kernel<KT, 1>), grid, dim3(256), lds, stream, a);         \
+    }                                                                                  \
   } while (0)
   switch (P.L.kp) {
     case 16: FASTH_LAUNCH_DV(1); break;

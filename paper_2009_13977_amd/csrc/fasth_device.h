@@ -8,6 +8,43 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kWave = 64;
 
+// Buffer addressing: the descriptor (scalar registers) holds base and size; a load takes a per-lane
+// byte offset and a scalar byte offset. A lane whose offset lies beyond the buffer (kOob is beyond
+// every buffer used here, all < 2 GiB) gets zeros and causes no memory traffic, so bounds checks
+// need no branch and the loads of a tile can all be in flight together.
+typedef __amdgpu_buffer_rsrc_t BufferDesc;
+constexpr unsigned kOob = 0x80000000u;
+
+__device__ __forceinline__ BufferDesc make_buffer(const float* base, size_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(base), 0, (int)bytes, 0x00020000);
+}
+
+// VEC consecutive floats (1 or 4) at byte offset lane_bytes + uniform_bytes of the buffer.
+template <int VEC>
+struct BufVec {
+  float e[VEC];
+};
+template <int VEC>
+__device__ __forceinline__ BufVec<VEC> buffer_load(BufferDesc desc, unsigned lane_bytes, unsigned uniform_bytes) {
+  BufVec<VEC> r;
+  if constexpr (VEC == 4) {
+    const float4 v = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(desc, lane_bytes, uniform_bytes, 0));
+    r.e[0] = v.x; r.e[1] = v.y; r.e[2] = v.z; r.e[3] = v.w;
+  } else {
+    static_assert(VEC == 1, "1 or 4 floats");
+    r.e[0] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(desc, lane_bytes, uniform_bytes, 0));
+  }
+  return r;
+}
+template <int VEC>
+__device__ __forceinline__ void lds_store(float* dst, const BufVec<VEC>& v) {
+  if constexpr (VEC == 4) {
+    *reinterpret_cast<float4*>(dst) = make_float4(v.e[0], v.e[1], v.e[2], v.e[3]);
+  } else {
+    dst[0] = v.e[0];
+  }
+}
+
 // One 16x16 output tile of a matrix product on the fp32 matrix cores, operands in LDS.
 //   acc(r, c) += sum_{kk < K} A(r, kk) * B(kk, c),   K a multiple of 4
 //   A(r, kk) = As[r * sai + kk * sak],  B(kk, c) = Bs[kk * sbk + c * sbj]
