@@ -210,13 +210,16 @@ __device__ __forceinline__ void invert_upper_lds(float* Ms, float* Xs, int kp, i
   if (tid < kp) {
     const int base = tid & ~15, c = tid & 15;
     const float* D = Ds + base * 17;
-    float x[16];
+    float x[16], rdiag[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) rdiag[r] = 1.f / D[r * 17 + r];  // all sixteen at once, off the dependent chain
 #pragma unroll
     for (int r = 15; r >= 0; --r) {
       float sum = r == c ? 1.f : 0.f;
+      // oldest x first: the value computed last enters last, so each row adds one multiply-add to the chain
 #pragma unroll
-      for (int l = r + 1; l < 16; ++l) sum -= D[r * 17 + l] * x[l];
-      x[r] = sum / D[r * 17 + r];  // rows below c stay exactly zero
+      for (int l = 15; l > r; --l) sum = fmaf(-D[r * 17 + l], x[l], sum);
+      x[r] = sum * rdiag[r];  // rows below c stay exactly zero
     }
 #pragma unroll
     for (int r = 0; r < 16; ++r) Ms[(base + r) * LDM + base + c] = x[r];
@@ -319,13 +322,25 @@ __global__ void __launch_bounds__(512) factor_fused_kernel(const float* __restri
           lds_store<VEC>(Vs + (idx / XV) * LD + (idx % XV) * VEC, stage[sl][it]);
         }
         __syncthreads();
-        int t = 0;
+        // This wave's 16 columns of the slab, one 16-byte read per 16-row group: lane (i, q) holds
+        // columns 4 q .. 4 q + 3 of row i, which serves as the A fragment of row group ti and as the
+        // B fragment of row group tj alike (the matrix cores sum over q; product u takes element u).
+        float4 frag[KT];
 #pragma unroll
-        for (int ti = 0; ti < KT; ++ti) {
+        for (int tt = 0; tt < KT; ++tt)
+          frag[tt] = *reinterpret_cast<const float4*>(Vs + (16 * tt + li) * LD + 16 * wave + 4 * q);
 #pragma unroll
-          for (int tj = ti; tj < KT; ++tj) {
-            acc[t] = tile_mma(Vs + ti * 16 * LD + 16 * wave, LD, 1, Vs + tj * 16 * LD + 16 * wave, 1, LD, 16, acc[t]);
-            ++t;
+        for (int u = 0; u < 4; ++u) {
+          int t = 0;
+#pragma unroll
+          for (int ti = 0; ti < KT; ++ti) {
+            const float av = u == 0 ? frag[ti].x : u == 1 ? frag[ti].y : u == 2 ? frag[ti].z : frag[ti].w;
+#pragma unroll
+            for (int tj = ti; tj < KT; ++tj) {
+              const float bv = u == 0 ? frag[tj].x : u == 1 ? frag[tj].y : u == 2 ? frag[tj].z : frag[tj].w;
+              acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, bv, acc[t], 0, 0, 0);
+              ++t;
+            }
           }
         }
         __syncthreads();
