@@ -135,9 +135,10 @@ static int allow_lds(K kernel, size_t bytes) {
 // grid (gram_split, nb), 256 threads. Only the 16x16 tiles on or above the diagonal are formed.
 // ------------------------------------------------------------------------------------------
 
+template <int VEC>  // VEC = 4 when d is a multiple of 4 (16-byte loads), else 1
 __global__ void __launch_bounds__(256) gram_partial_kernel(const float* __restrict__ V, float* __restrict__ Spart,
                                                            int d, int k, int kp, int gram_split) {
-  extern __shared__ float smem[];
+  extern __shared__ __align__(16) float smem[];
   const int LD = kGramChunk + 4;
   float* Vs = smem;  // [kp][LD]
   const int i = blockIdx.y, s = blockIdx.x;
@@ -151,13 +152,26 @@ __global__ void __launch_bounds__(256) gram_partial_kernel(const float* __restri
   f32x4 acc[kMaxTilesPerWave];
 #pragma unroll
   for (int w = 0; w < kMaxTilesPerWave; ++w) acc[w] = f32x4{0.f, 0.f, 0.f, 0.f};
-  const float* Vi = V + (size_t)i * k * d;
+  // the block's k rows as one buffer: rows k .. kp - 1 of the padded block lie beyond it and read as zero
+  const BufferDesc vdesc = make_buffer(V + (size_t)i * k * d, (size_t)k * d * sizeof(float));
+  constexpr int XV = kGramChunk / VEC;             // loads per slab row
+  constexpr int kMaxPer = kMaxBlock * XV / 256;    // loads per thread and slab at the largest block
+  const int per = kp * XV / 256;
   for (int x0 = xbeg; x0 < xend; x0 += kGramChunk) {
-    for (int idx = tid; idx < kp * kGramChunk; idx += 256) {
-      const int j = idx / kGramChunk, x = idx % kGramChunk;
-      float v = 0.f;
-      if (j < k && x0 + x < xend) v = Vi[(size_t)j * d + x0 + x];
-      Vs[j * LD + x] = v;
+    BufVec<VEC> stage[kMaxPer];
+#pragma unroll
+    for (int it = 0; it < kMaxPer; ++it) {
+      if (it < per) {  // uniform
+        const int idx = tid + it * 256, j = idx / XV, x = x0 + (idx % XV) * VEC;
+        stage[it] = buffer_load<VEC>(vdesc, x < xend ? (unsigned)(j * d + x) * 4u : kOob, 0);
+      }
+    }
+#pragma unroll
+    for (int it = 0; it < kMaxPer; ++it) {
+      if (it < per) {
+        const int idx = tid + it * 256;
+        lds_store<VEC>(Vs + (idx / XV) * LD + (idx % XV) * VEC, stage[it]);
+      }
     }
     __syncthreads();
 #pragma unroll
@@ -258,20 +272,31 @@ __global__ void __launch_bounds__(256) t_build_kernel(const float* __restrict__ 
   const int i = blockIdx.x;
   const int tid = threadIdx.x;
   const float* Sp = Spart + (size_t)i * gram_split * kp * kp;
-  for (int idx = tid; idx < kp * kp; idx += 256) {
-    const int j = idx / kp, l = idx % kp;
-    float v = 0.f;
-    if (j < k && l < k && j <= l) {
-      float part[kMaxGramSplit];  // all partial sums in flight at once
+  // Four neighbouring entries of a row at a time (kp is a multiple of 16, so they share a 16 x 16 tile); tiles
+  // below the diagonal hold nothing and are not read. All partial sums of an entry are in flight at once.
+  for (int idx4 = tid; idx4 < kp * kp / 4; idx4 += 256) {
+    const int j = idx4 / (kp / 4), l0 = (idx4 % (kp / 4)) * 4;
+    float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (j / 16 <= l0 / 16 && j < k) {
+      float4 part[kMaxGramSplit];
 #pragma unroll
-      for (int s = 0; s < kMaxGramSplit; ++s) part[s] = s < gram_split ? Sp[(size_t)s * kp * kp + idx] : 0.f;
+      for (int s = 0; s < kMaxGramSplit; ++s)
+        part[s] = s < gram_split ? *reinterpret_cast<const float4*>(Sp + (size_t)s * kp * kp + 4 * (size_t)idx4)
+                                 : make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
-      for (int s = 0; s < kMaxGramSplit; ++s) v += part[s];
-      if (j == l) v *= 0.5f;
-    } else if (j == l) {
-      v = 1.f;
+      for (int s = 0; s < kMaxGramSplit; ++s) {
+        sum.x += part[s].x; sum.y += part[s].y; sum.z += part[s].z; sum.w += part[s].w;
+      }
     }
-    Ms[j * LDM + l] = v;
+    const float e[4] = {sum.x, sum.y, sum.z, sum.w};
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int l = l0 + u;
+      float v = 0.f;
+      if (j < k && l < k && j <= l) v = j == l ? 0.5f * e[u] : e[u];
+      else if (j == l) v = 1.f;
+      Ms[j * LDM + l] = v;
+    }
   }
   __syncthreads();
   invert_upper_lds(Ms, Xs, kp, LDM);
@@ -1274,11 +1299,15 @@ static int build_factors(const Product& P, const float* V, hipStream_t stream) {
   }
   {
     const size_t lds = sizeof(float) * (size_t)kp * (kGramChunk + 4);
-    int rc = allow_lds(gram_partial_kernel, lds);
+    int rc = allow_lds(gram_partial_kernel<4>, lds);
+    if (rc == FASTH_OK) rc = allow_lds(gram_partial_kernel<1>, lds);
     if (rc != FASTH_OK) return rc;
     prof::Scope ps_(FASTH_KERNEL_GRAM, stream);
-    hipLaunchKernelGGL(gram_partial_kernel, dim3(P.L.gram_split, P.L.nb), dim3(256), lds, stream, V, P.Spart(), P.d,
-                       P.k, kp, P.L.gram_split);
+    const dim3 grid(P.L.gram_split, P.L.nb);
+    if (P.d % 4 == 0)
+      hipLaunchKernelGGL(gram_partial_kernel<4>, grid, dim3(256), lds, stream, V, P.Spart(), P.d, P.k, kp, P.L.gram_split);
+    else
+      hipLaunchKernelGGL(gram_partial_kernel<1>, grid, dim3(256), lds, stream, V, P.Spart(), P.d, P.k, kp, P.L.gram_split);
     FASTH_HIP(hipGetLastError());
   }
   {
