@@ -263,18 +263,18 @@ __device__ __forceinline__ void invert_upper_lds(float* Ms, float* Xs, int kp, i
   }
 }
 
-__global__ void __launch_bounds__(256) t_build_kernel(const float* __restrict__ Spart, float* __restrict__ T,
+__global__ void __launch_bounds__(1024) t_build_kernel(const float* __restrict__ Spart, float* __restrict__ T,
                                                       int k, int kp, int gram_split) {
   extern __shared__ float smem[];
   const int LDM = kp + 4;
   float* Ms = smem;                 // [kp][LDM]
   float* Xs = Ms + kp * LDM;        // scratch of the inversion
   const int i = blockIdx.x;
-  const int tid = threadIdx.x;
+  const int tid = threadIdx.x, nthreads = blockDim.x;
   const float* Sp = Spart + (size_t)i * gram_split * kp * kp;
   // Four neighbouring entries of a row at a time (kp is a multiple of 16, so they share a 16 x 16 tile); tiles
   // below the diagonal hold nothing and are not read. All partial sums of an entry are in flight at once.
-  for (int idx4 = tid; idx4 < kp * kp / 4; idx4 += 256) {
+  for (int idx4 = tid; idx4 < kp * kp / 4; idx4 += nthreads) {
     const int j = idx4 / (kp / 4), l0 = (idx4 % (kp / 4)) * 4;
     float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
     if (j / 16 <= l0 / 16 && j < k) {
@@ -301,7 +301,7 @@ __global__ void __launch_bounds__(256) t_build_kernel(const float* __restrict__ 
   __syncthreads();
   invert_upper_lds(Ms, Xs, kp, LDM);
   float* Ti = T + (size_t)i * kp * kp;
-  for (int idx = tid; idx < kp * kp; idx += 256) Ti[idx] = Ms[(idx / kp) * LDM + idx % kp];
+  for (int idx = tid; idx < kp * kp; idx += nthreads) Ti[idx] = Ms[(idx / kp) * LDM + idx % kp];
 }
 
 // Algorithm 1 Step 1 in one kernel for small blocks (kp = 16 KT <= 32): one workgroup of 8 waves per
@@ -1315,7 +1315,7 @@ static int build_factors(const Product& P, const float* V, hipStream_t stream) {
     int rc = allow_lds(t_build_kernel, lds);
     if (rc != FASTH_OK) return rc;
     prof::Scope ps_(FASTH_KERNEL_TBUILD, stream);
-    hipLaunchKernelGGL(t_build_kernel, dim3(P.L.nb), dim3(256), lds, stream, P.Spart(), P.T(), P.k, kp, P.L.gram_split);
+    hipLaunchKernelGGL(t_build_kernel, dim3(P.L.nb), dim3(kp >= 128 ? 1024 : kp >= 64 ? 512 : 256), lds, stream, P.Spart(), P.T(), P.k, kp, P.L.gram_split);
     FASTH_HIP(hipGetLastError());
   }
   return FASTH_OK;
