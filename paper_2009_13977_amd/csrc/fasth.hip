@@ -20,6 +20,7 @@
 //   dsigma_kernel        the diagonal step of the SVD layer
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cstdint>
 #include <cstdio>
 #include <cstdlib>
@@ -308,9 +309,21 @@ __global__ void __launch_bounds__(1024) t_build_kernel(const float* __restrict__
 // block streams the block's rows through LDS in 128-column slabs; wave w multiplies columns
 // [16 w, 16 w + 16) of each slab, the 8 partial Gram matrices are added through LDS, and the same
 // workgroup inverts. Saves a launch and the round trip of the partial sums through memory.
+// Up to two products (the two orthogonal factors of an SVD layer) are factored by one launch:
+// blockIdx.y picks the product, blockIdx.x its block.
+struct FactorPair {
+  const float* V[2];  // [n][d]
+  float* T[2];        // [nb][kp][kp]
+  int d[2], k[2], nb[2];
+};
+
 template <int KT, int VEC>  // VEC = 4 when d is a multiple of 4 (16-byte loads), else 1
-__global__ void __launch_bounds__(512) factor_fused_kernel(const float* __restrict__ V, float* __restrict__ T,
-                                                           int d, int k) {
+__global__ void __launch_bounds__(512) factor_fused_kernel(FactorPair fp) {
+  const int which = blockIdx.y;
+  if ((int)blockIdx.x >= fp.nb[which]) return;  // whole workgroup, before any barrier
+  const float* __restrict__ V = fp.V[which];
+  float* __restrict__ T = fp.T[which];
+  const int d = fp.d[which], k = fp.k[which];
   constexpr int kp = 16 * KT, LD = kGramChunk + 4, NTILE = KT * (KT + 1) / 2, NW = 8, LDM = kp + 4;
   constexpr int PER = kp * kGramChunk / 512 / VEC;  // loads per thread and slab
   constexpr int XV = kGramChunk / VEC;              // loads per slab row
@@ -942,11 +955,18 @@ struct DvArgs {
   int accumulate;       // add to dV instead of overwriting it (a factor that enters a layer twice)
 };
 
+// Up to two products per launch (the two factors of an SVD layer): blockIdx.z picks the product.
+struct DvPair {
+  DvArgs a[2];
+};
+
 template <int KT, int VEC>  // kp = 16 KT; VEC = 4 when d is a multiple of 4 (16-byte loads along x), else 1
-__global__ void __launch_bounds__(256) dv_kernel(DvArgs p) {
+__global__ void __launch_bounds__(256) dv_kernel(DvPair pair) {
   extern __shared__ __align__(16) float smem[];
   constexpr int kp = 16 * KT;
+  const DvArgs p = pair.a[blockIdx.z];
   const int k = p.k, d = p.d, m = p.m, n = p.n;
+  if ((int)blockIdx.y * k >= n || (int)blockIdx.x * kDvTile >= d) return;  // whole workgroup, before any barrier
   constexpr int LDE = kp + 4, LDC = kDvMChunk + 4, LDX = kDvTile + 4;
   float* Es = smem;                   // [kp][LDE]
   float* Cas = Es + kp * LDE;         // [kp][LDC]
@@ -1282,20 +1302,31 @@ static Product bind(int d, int n, int m, int k, void* ws) {
   return P;
 }
 
+static int launch_factor_fused(const FactorPair& fp, int count, int kp, bool vec4, hipStream_t stream) {
+  prof::Scope ps_(FASTH_KERNEL_FACTOR, stream);
+  const dim3 grid(count == 2 && fp.nb[1] > fp.nb[0] ? fp.nb[1] : fp.nb[0], count), block(512);
+  if (vec4) {
+    if (kp == 16) hipLaunchKernelGGL((factor_fused_kernel<1, 4>), grid, block, 0, stream, fp);
+    else hipLaunchKernelGGL((factor_fused_kernel<2, 4>), grid, block, 0, stream, fp);
+  } else {
+    if (kp == 16) hipLaunchKernelGGL((factor_fused_kernel<1, 1>), grid, block, 0, stream, fp);
+    else hipLaunchKernelGGL((factor_fused_kernel<2, 1>), grid, block, 0, stream, fp);
+  }
+  FASTH_HIP(hipGetLastError());
+  return FASTH_OK;
+}
+
+static void set_factor_slot(FactorPair& fp, int slot, const Product& P, const float* V) {
+  fp.V[slot] = V; fp.T[slot] = P.T(); fp.d[slot] = P.d; fp.k[slot] = P.k; fp.nb[slot] = P.L.nb;
+}
+
 static int build_factors(const Product& P, const float* V, hipStream_t stream) {
   const int kp = P.L.kp;
   if (kp <= 32) {
-    prof::Scope ps_(FASTH_KERNEL_FACTOR, stream);
-    const dim3 grid(P.L.nb), block(512);
-    if (P.d % 4 == 0) {
-      if (kp == 16) hipLaunchKernelGGL((factor_fused_kernel<1, 4>), grid, block, 0, stream, V, P.T(), P.d, P.k);
-      else hipLaunchKernelGGL((factor_fused_kernel<2, 4>), grid, block, 0, stream, V, P.T(), P.d, P.k);
-    } else {
-      if (kp == 16) hipLaunchKernelGGL((factor_fused_kernel<1, 1>), grid, block, 0, stream, V, P.T(), P.d, P.k);
-      else hipLaunchKernelGGL((factor_fused_kernel<2, 1>), grid, block, 0, stream, V, P.T(), P.d, P.k);
-    }
-    FASTH_HIP(hipGetLastError());
-    return FASTH_OK;
+    FactorPair fp;
+    set_factor_slot(fp, 0, P, V);
+    set_factor_slot(fp, 1, P, V);  // unused
+    return launch_factor_fused(fp, 1, kp, P.d % 4 == 0, stream);
   }
   {
     const size_t lds = sizeof(float) * (size_t)kp * (kGramChunk + 4);
@@ -1321,6 +1352,20 @@ static int build_factors(const Product& P, const float* V, hipStream_t stream) {
   return FASTH_OK;
 }
 
+// Factors of two products (independent of each other) in one launch when both take the fused
+// kernel with the same template arguments; otherwise one after the other.
+static int build_factors_pair(const Product& P0, const float* V0, const Product& P1, const float* V1,
+                              hipStream_t stream) {
+  if (P0.L.kp <= 32 && P0.L.kp == P1.L.kp && (P0.d % 4 == 0) == (P1.d % 4 == 0)) {
+    FactorPair fp;
+    set_factor_slot(fp, 0, P0, V0);
+    set_factor_slot(fp, 1, P1, V1);
+    return launch_factor_fused(fp, 2, P0.L.kp, P0.d % 4 == 0, stream);
+  }
+  const int rc = build_factors(P0, V0, stream);
+  return rc != FASTH_OK ? rc : build_factors(P1, V1, stream);
+}
+
 // A = H in (transpose = 0) or H^T in (transpose = 1); activation = true saves into the activation
 // slots of the workspace, false into the gradient slots.
 static int run_chain(const Product& P, const float* V, const float* in, float* out, int transpose, bool activation,
@@ -1337,28 +1382,36 @@ static int run_chain(const Product& P, const float* V, const float* in, float* o
   return launch_chain(a, stream);
 }
 
-static int run_dv(const Product& P, const float* V, float* dV, int transpose, hipStream_t stream,
-                  bool accumulate = false) {
+static DvArgs dv_args(const Product& P, const float* V, float* dV, int transpose, bool accumulate) {
   DvArgs a;
   a.accumulate = accumulate ? 1 : 0;
   a.V = V; a.saveA = P.saveA(); a.saveCa = P.saveCa(); a.saveG = P.saveG(); a.saveCg = P.saveCg(); a.dV = dV;
   a.d = P.d; a.n = P.n; a.m = P.m; a.k = P.k; a.kp = P.L.kp; a.transpose = transpose;
-  const size_t lds = dv_lds(P.L.kp);
-  const dim3 grid((P.d + kDvTile - 1) / kDvTile, P.L.nb);
+  return a;
+}
+
+static int launch_dv(const DvPair& pair, int count, int kp, bool vec4, hipStream_t stream) {
+  const size_t lds = dv_lds(kp);
+  int xt = (pair.a[0].d + kDvTile - 1) / kDvTile, nb = pair.a[0].n / pair.a[0].k;
+  if (count == 2) {
+    xt = std::max(xt, (pair.a[1].d + kDvTile - 1) / kDvTile);
+    nb = std::max(nb, pair.a[1].n / pair.a[1].k);
+  }
+  const dim3 grid(xt, nb, count);
   prof::Scope ps_(FASTH_KERNEL_DV, stream);
-#define FASTH_LAUNCH_DV(KT)                                                            \
-  do {                                                                                 \
-    if (P.d % 4 == 0) {                                                                \
-      int rc_ = allow_lds(dv_kernel<KT, 4>, lds);                                      \
-      if (rc_ != FASTH_OK) return rc_;                                                 \
-      hipLaunchKernelGGL((dv_kernel<KT, 4>), grid, dim3(256), lds, stream, a);         \
-    } else {                                                                           \
-      int rc_ = allow_lds(dv_kernel<KT, 1>, lds);                                      \
-      if (rc_ != FASTH_OK) return rc_;                                                 \
-      hipLaunchKernelGGL((dv_kernel<KT, 1>), grid, dim3(256), lds, stream, a);         \
-    }                                                                                  \
+#define FASTH_LAUNCH_DV(KT)                                                               \
+  do {                                                                                    \
+    if (vec4) {                                                                           \
+      int rc_ = allow_lds(dv_kernel<KT, 4>, lds);                                         \
+      if (rc_ != FASTH_OK) return rc_;                                                    \
+      hipLaunchKernelGGL((dv_kernel<KT, 4>), grid, dim3(256), lds, stream, pair);         \
+    } else {                                                                              \
+      int rc_ = allow_lds(dv_kernel<KT, 1>, lds);                                         \
+      if (rc_ != FASTH_OK) return rc_;                                                    \
+      hipLaunchKernelGGL((dv_kernel<KT, 1>), grid, dim3(256), lds, stream, pair);         \
+    }                                                                                     \
   } while (0)
-  switch (P.L.kp) {
+  switch (kp) {
     case 16: FASTH_LAUNCH_DV(1); break;
     case 32: FASTH_LAUNCH_DV(2); break;
     case 64: FASTH_LAUNCH_DV(4); break;
@@ -1367,6 +1420,27 @@ static int run_dv(const Product& P, const float* V, float* dV, int transpose, hi
 #undef FASTH_LAUNCH_DV
   FASTH_HIP(hipGetLastError());
   return FASTH_OK;
+}
+
+static int run_dv(const Product& P, const float* V, float* dV, int transpose, hipStream_t stream,
+                  bool accumulate = false) {
+  DvPair pair;
+  pair.a[0] = pair.a[1] = dv_args(P, V, dV, transpose, accumulate);
+  return launch_dv(pair, 1, P.L.kp, P.d % 4 == 0, stream);
+}
+
+// dV of two products with different outputs in one launch when both take the same template
+// arguments; otherwise one after the other.
+static int run_dv_pair(const Product& P0, const float* V0, float* dV0, int transpose0, const Product& P1,
+                       const float* V1, float* dV1, int transpose1, hipStream_t stream) {
+  if (P0.L.kp == P1.L.kp && (P0.d % 4 == 0) == (P1.d % 4 == 0)) {
+    DvPair pair;
+    pair.a[0] = dv_args(P0, V0, dV0, transpose0, false);
+    pair.a[1] = dv_args(P1, V1, dV1, transpose1, false);
+    return launch_dv(pair, 2, P0.L.kp, P0.d % 4 == 0, stream);
+  }
+  const int rc = run_dv(P0, V0, dV0, transpose0, stream);
+  return rc != FASTH_OK ? rc : run_dv(P1, V1, dV1, transpose1, stream);
 }
 
 static int seq_threads(int d) {
@@ -1415,8 +1489,7 @@ static int svd_forward(const fasth_svd_shape* shape, const float* first, const f
   const Product Pf = bind(fs.d, fs.n, fs.m, fs.k, ws + S.off_V);
   const Product Ps = bind(fs.d, fs.n, fs.m, fs.k, ws + S.off_U);
   float* Z1 = reinterpret_cast<float*>(ws + S.off_Z1);
-  if ((rc = build_factors(Pf, first, st)) != FASTH_OK) return rc;
-  if ((rc = build_factors(Ps, second, st)) != FASTH_OK) return rc;
+  if ((rc = build_factors_pair(Pf, first, Ps, second, st)) != FASTH_OK) return rc;
   if ((rc = run_chain(Pf, first, X, Z1, 1, true, nullptr, 0, st)) != FASTH_OK) return rc;
   return run_chain(Ps, second, Z1, Y, 0, true, sigma, scale_mode, st);
 }
@@ -1441,7 +1514,6 @@ static int svd_backward(const fasth_svd_shape* shape, const float* first, const 
   float* dZ2 = reinterpret_cast<float*>(ws + S.off_dZ2);
   // through the second (plain) factor
   if ((rc = run_chain(Ps, second, G, dZ2, 1, false, nullptr, 0, st)) != FASTH_OK) return rc;
-  if ((rc = run_dv(Ps, second, dsecond, 0, st)) != FASTH_OK) return rc;
   {
     prof::Scope ps_(FASTH_KERNEL_DSIGMA, st);
     hipLaunchKernelGGL(dsigma_kernel, dim3((fs.d + 3) / 4), dim3(256), 0, st, dZ2, Z1, sigma, dsigma, fs.d, fs.m,
@@ -1450,7 +1522,8 @@ static int svd_backward(const fasth_svd_shape* shape, const float* first, const 
   FASTH_HIP(hipGetLastError());
   // through the first (transposed) factor; dZ1 = s * dZ2 is fused into the chain's load
   if ((rc = run_chain(Pf, first, dZ2, dX, 0, false, sigma, scale_mode, st)) != FASTH_OK) return rc;
-  return run_dv(Pf, first, dfirst, 1, st);
+  // both factors' vector gradients in one launch: each reads only its own saved slots
+  return run_dv_pair(Ps, second, dsecond, 0, Pf, first, dfirst, 1, st);
 }
 
 static int sym_scale_mode(int function) {
@@ -1841,8 +1914,7 @@ int svd_rect_apply(const fasth_rect_shape* shape, const float* Uv, const float* 
   const Product Pv = bind(fv.d, fv.n, fv.m, fv.k, ws + S.off_V);
   float* Z1 = reinterpret_cast<float*>(ws + S.off_Z1);
   const int r = fu.d < fv.d ? fu.d : fv.d;
-  if ((rc = build_factors(Pv, Vv, st)) != FASTH_OK) return rc;
-  if ((rc = build_factors(Pu, Uv, st)) != FASTH_OK) return rc;
+  if ((rc = build_factors_pair(Pv, Vv, Pu, Uv, st)) != FASTH_OK) return rc;
   if ((rc = run_chain(Pv, Vv, X, Z1, 1, true, nullptr, 0, st)) != FASTH_OK) return rc;
   // Sigma Z1: the first r rows of Z1 scaled by sigma, rows r..rows-1 zero; fused into the chain's load
   return run_chain(Pu, Uv, Z1, Y, 0, true, sigma, 1, st, true, nullptr, r);
@@ -1868,7 +1940,6 @@ int svd_rect_apply_backward(const fasth_rect_shape* shape, const float* Uv, cons
   float* dZ2 = reinterpret_cast<float*>(ws + S.off_dZ2);
   const int r = fu.d < fv.d ? fu.d : fv.d;
   if ((rc = run_chain(Pu, Uv, G, dZ2, 1, false, nullptr, 0, st)) != FASTH_OK) return rc;
-  if ((rc = run_dv(Pu, Uv, dUv, 0, st)) != FASTH_OK) return rc;
   {
     prof::Scope ps_(FASTH_KERNEL_DSIGMA, st);
     hipLaunchKernelGGL(dsigma_kernel, dim3((r + 3) / 4), dim3(256), 0, st, (const float*)dZ2, Z1, sigma, dsigma, r,
@@ -1877,7 +1948,7 @@ int svd_rect_apply_backward(const fasth_rect_shape* shape, const float* Uv, cons
   FASTH_HIP(hipGetLastError());
   // Sigma^T dZ2: first r rows scaled, rows r..cols-1 zero
   if ((rc = run_chain(Pv, Vv, dZ2, dX, 0, false, sigma, 1, st, true, nullptr, r)) != FASTH_OK) return rc;
-  return run_dv(Pv, Vv, dVv, 1, st);
+  return run_dv_pair(Pu, Uv, dUv, 0, Pv, Vv, dVv, 1, st);
 }
 
 }  // extern "C"
