@@ -607,7 +607,11 @@ struct PipeRegs {
   float t[LPT];
 };
 
-template <int K, int VW, int NT, int BUFS, int RL = 0>  // RL: rows of the next block fetched during the reduction
+// SUB > 1: a block of SUB K rows is applied as SUB steps of K rows. The diagonal K x K blocks of its factor T_i
+// are the factors of the row groups (T_i is triangular and the groups are consecutive reflections), the
+// coefficients of the steps put together are T_i V_i a, and the block's input is saved at its first step,
+// so nothing downstream sees the difference; p.nb counts the K-row steps.
+template <int K, int VW, int NT, int BUFS, int RL = 0, int SUB = 1>  // RL: rows of the next block fetched during the reduction
 __global__ void __launch_bounds__(NT) chain_pipe_kernel(ChainArgs p) {
   typedef PipeRegs<K, VW, NT> Regs;
   constexpr int NW = NT / 64, G = Regs::G, LPT = Regs::LPT;
@@ -631,18 +635,20 @@ __global__ void __launch_bounds__(NT) chain_pipe_kernel(ChainArgs p) {
   // uniform row base (scalar registers) + 32-bit per-lane offset
   auto row_ptr = [&](int i, int j) { return p.V + ((size_t)i * K + j) * (size_t)d + x0; };
   auto load_t = [&](int i, Regs& r) {
-    const float* Ti = p.T + (size_t)i * K * K;
+    constexpr int LDT = K * SUB;  // row stride of the stored factor
+    const float* Ti = p.T + (size_t)(i / SUB) * LDT * LDT + (size_t)(i % SUB) * (K * LDT + K);
     const int row = t_active ? trow : 0;
 #pragma unroll
     for (int e = 0; e < LPT; ++e) {
       const int l = tg + G * e;
-      r.t[e] = p.transpose ? Ti[l * K + row] : Ti[row * K + l];
+      r.t[e] = p.transpose ? Ti[l * LDT + row] : Ti[row * LDT + l];
     }
   };
 
   // Applies block i held in `cur` while fetching block inext into `nxt` (BUFS = 1: nxt is cur).
   auto apply_block = [&](int i, Regs& cur, int inext, Regs& nxt) {
-    if (p.save_in && ok) store_chunk<VW>(p.save_in + ((size_t)i * m + col) * d + x0, a);
+    if (p.save_in && ok && (SUB == 1 || i % SUB == (p.transpose ? 0 : SUB - 1)))
+      store_chunk<VW>(p.save_in + ((size_t)(i / SUB) * m + col) * d + x0, a);
     float pj[K];
 #pragma unroll
     for (int j = 0; j < K; ++j) {
@@ -742,10 +748,12 @@ __global__ void __launch_bounds__(NT) chain_pipe_kernel(ChainArgs p) {
   }
 }
 
-template <int K, int VW, int NT, int BUFS, int RL = 0>
-static int launch_chain_pipe(const ChainArgs& a, hipStream_t stream) {
+template <int K, int VW, int NT, int BUFS, int RL = 0, int SUB = 1>
+static int launch_chain_pipe(const ChainArgs& args, hipStream_t stream) {
+  ChainArgs a = args;
+  a.nb = args.nb * SUB;
   prof::Scope ps_(FASTH_KERNEL_CHAIN, stream);
-  hipLaunchKernelGGL((chain_pipe_kernel<K, VW, NT, BUFS, RL>), dim3(a.m), dim3(NT), 0, stream, a);
+  hipLaunchKernelGGL((chain_pipe_kernel<K, VW, NT, BUFS, RL, SUB>), dim3(a.m), dim3(NT), 0, stream, a);
   FASTH_HIP(hipGetLastError());
   return FASTH_OK;
 }
@@ -902,7 +910,9 @@ static int launch_chain(const ChainArgs& a, hipStream_t stream) {
     if (k == 64 && d <= 256) return launch_chain_pipe<64, 1, 256, 2, 16>(a, stream);
     if (k == 64 && d <= 512) return launch_chain_pipe<64, 2, 256, 2, 16>(a, stream);
     // one copy, refilled in place
-    if (k == 32 && d <= 2048) return launch_chain_pipe<32, 4, 512, 1>(a, stream);
+    // 1024 < d <= 2048: two register copies of 32 rows do not fit two waves per SIMD; 16-row steps do, and are
+    // faster than one copy of 32 rows refilled in place (178 vs 222 us at d = n = 2048)
+    if (k == 32 && d <= 2048) return launch_chain_pipe<16, 4, 512, 2, 4, 2>(a, stream);
     if (k == 64 && d <= 1024) return launch_chain_pipe<64, 2, 512, 1>(a, stream);
   }
   if (d % 4 == 0 && d <= 4096) return launch_chain_stream_vw<4>(a, stream);
