@@ -909,11 +909,18 @@ static int launch_chain(const ChainArgs& a, hipStream_t stream) {
     if (k == 32 && d <= 1024) return launch_chain_pipe<32, 4, 256, 2, 8>(a, stream);
     if (k == 64 && d <= 256) return launch_chain_pipe<64, 1, 256, 2, 16>(a, stream);
     if (k == 64 && d <= 512) return launch_chain_pipe<64, 2, 256, 2, 16>(a, stream);
-    // one copy, refilled in place
-    // 1024 < d <= 2048: two register copies of 32 rows do not fit two waves per SIMD; 16-row steps do, and are
-    // faster than one copy of 32 rows refilled in place (178 vs 222 us at d = n = 2048)
-    if (k == 32 && d <= 2048) return launch_chain_pipe<16, 4, 512, 2, 4, 2>(a, stream);
-    if (k == 64 && d <= 1024) return launch_chain_pipe<64, 2, 512, 1>(a, stream);
+    // Larger blocks and longer vectors: two register copies of the whole block do not fit, but the block can be
+    // applied as steps of 32 rows (d <= 1024) or 16 rows (d <= 2048, two waves per SIMD), which is faster than
+    // one copy refilled in place or rows streamed twice (d = n = 2048: 178 us for k = 32, 64 and 128 alike,
+    // against 222, 359 and 406 us)
+    if (d <= 1024) {
+      if (k == 64) return launch_chain_pipe<32, 4, 256, 2, 8, 2>(a, stream);
+      if (k == 128) return launch_chain_pipe<32, 4, 256, 2, 8, 4>(a, stream);
+    } else if (d <= 2048) {
+      if (k == 32) return launch_chain_pipe<16, 4, 512, 2, 4, 2>(a, stream);
+      if (k == 64) return launch_chain_pipe<16, 4, 512, 2, 4, 4>(a, stream);
+      if (k == 128) return launch_chain_pipe<16, 4, 512, 2, 4, 8>(a, stream);
+    }
   }
   if (d % 4 == 0 && d <= 4096) return launch_chain_stream_vw<4>(a, stream);
   if (d % 2 == 0 && d <= 2048) return launch_chain_stream_vw<2>(a, stream);
