@@ -547,12 +547,10 @@ __global__ void __launch_bounds__(1024) chain_kernel(ChainArgs p) {
 // row of V covers 64 VW contiguous floats and the whole k x d block V_i is K * VW registers per
 // thread. V_i is read from memory once per block and used for both products.
 //
-// BUFS = 2: two register copies. The rows of block i+1 are loaded a couple at a time between the
-//           multiply-adds of block i (half during B = V_i a, half during a -= V_i^T C), which
-//           feeds the CU's address unit (64 B per clock) evenly instead of in one burst that
-//           stalls the wave behind it.
-// BUFS = 1: one copy; each row is reloaded with the next block's row right after its last use in
-//           the update. Half the registers, so twice the block fits, at a shorter prefetch lead.
+// Two register copies: the rows of block i+1 are loaded a couple at a time between the multiply-adds
+// of block i (during B = V_i a, during the reduction and during a -= V_i^T C), which feeds the CU's
+// address unit (64 B per clock) evenly instead of in one burst that stalls the wave behind it.
+// Blocks too large for two copies are applied as steps of fewer rows (SUB below).
 // The barriers order LDS traffic only, so global loads stay in flight across them.
 template <int VW> struct VecOf;
 template <> struct VecOf<1> { typedef float type; };
@@ -611,12 +609,12 @@ struct PipeRegs {
 // are the factors of the row groups (T_i is triangular and the groups are consecutive reflections), the
 // coefficients of the steps put together are T_i V_i a, and the block's input is saved at its first step,
 // so nothing downstream sees the difference; p.nb counts the K-row steps.
-template <int K, int VW, int NT, int BUFS, int RL = 0, int SUB = 1>  // RL: rows of the next block fetched during the reduction
+template <int K, int VW, int NT, int RL = 0, int SUB = 1>  // RL: rows of the next block fetched during the reduction
 __global__ void __launch_bounds__(NT) chain_pipe_kernel(ChainArgs p) {
   typedef PipeRegs<K, VW, NT> Regs;
   constexpr int NW = NT / 64, G = Regs::G, LPT = Regs::LPT;
   constexpr int PR = (K - RL) / 2;  // rows of the next block fetched during each of the two products
-  static_assert(K % 4 == 0 && K * G <= NT && LPT >= 1 && (BUFS == 1 || BUFS == 2), "shape");
+  static_assert(K % 4 == 0 && K * G <= NT && LPT >= 1, "shape");
   static_assert(RL % 2 == 0 && RL <= K / 4 && (RL == 0 || K >= 8), "prefetch split");
   __shared__ float Bpart[NW][K];
   __shared__ __align__(16) float Cv[K];
@@ -645,26 +643,24 @@ __global__ void __launch_bounds__(NT) chain_pipe_kernel(ChainArgs p) {
     }
   };
 
-  // Applies block i held in `cur` while fetching block inext into `nxt` (BUFS = 1: nxt is cur).
+  // Applies block i held in `cur` while fetching block inext into `nxt`.
   auto apply_block = [&](int i, Regs& cur, int inext, Regs& nxt) {
     if (p.save_in && ok && (SUB == 1 || i % SUB == (p.transpose ? 0 : SUB - 1)))
       store_chunk<VW>(p.save_in + ((size_t)(i / SUB) * m + col) * d + x0, a);
     float pj[K];
 #pragma unroll
     for (int j = 0; j < K; ++j) {
-      if constexpr (BUFS == 2) {
-        if (j % 2 == 0 && j / 2 < PR) {
-          nxt.v[j / 2] = load_chunk<VW>(row_ptr(inext, j / 2));
-          __builtin_amdgcn_sched_barrier(0);
-        }
+      if (j % 2 == 0 && j / 2 < PR) {
+        nxt.v[j / 2] = load_chunk<VW>(row_ptr(inext, j / 2));
+        __builtin_amdgcn_sched_barrier(0);
       }
       float acc = 0.f;
 #pragma unroll
       for (int r = 0; r < VW; ++r) acc = fmaf(cur.v[j].e[r], a.e[r], acc);
       pj[j] = acc;
     }
-    if constexpr (BUFS == 2) load_t(inext, nxt);
-    if constexpr (BUFS == 2 && RL > 0) {
+    load_t(inext, nxt);
+    if constexpr (RL > 0) {
       auto prefetch = [&](int t) {
         if (t % 4 == 0 && t / 4 < RL) {
           __builtin_amdgcn_sched_barrier(0);
@@ -694,7 +690,6 @@ __global__ void __launch_bounds__(NT) chain_pipe_kernel(ChainArgs p) {
         if (p.save_c) p.save_c[(size_t)col * p.n + (size_t)i * K + trow] = c;
       }
     }
-    if constexpr (BUFS == 1) load_t(inext, nxt);
     lds_barrier();
     float cc[K];  // the whole coefficient vector in one round trip to LDS
 #pragma unroll
@@ -705,18 +700,12 @@ __global__ void __launch_bounds__(NT) chain_pipe_kernel(ChainArgs p) {
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int j = 0; j < K; ++j) {
-      if constexpr (BUFS == 2) {
-        if (j % 2 == 0 && j / 2 < PR) {
-          nxt.v[PR + RL + j / 2] = load_chunk<VW>(row_ptr(inext, PR + RL + j / 2));
-          __builtin_amdgcn_sched_barrier(0);
-        }
+      if (j % 2 == 0 && j / 2 < PR) {
+        nxt.v[PR + RL + j / 2] = load_chunk<VW>(row_ptr(inext, PR + RL + j / 2));
+        __builtin_amdgcn_sched_barrier(0);
       }
 #pragma unroll
       for (int r = 0; r < VW; ++r) a.e[r] = fmaf(-cc[j], cur.v[j].e[r], a.e[r]);
-      if constexpr (BUFS == 1) {
-        __builtin_amdgcn_sched_barrier(0);
-        nxt.v[j] = load_chunk<VW>(row_ptr(inext, j));
-      }
     }
     if (!ok) {
 #pragma unroll
@@ -724,36 +713,28 @@ __global__ void __launch_bounds__(NT) chain_pipe_kernel(ChainArgs p) {
     }
   };
 
-  if constexpr (BUFS == 2) {
-    Regs ra, rb;
+  Regs ra, rb;
 #pragma unroll
-    for (int j = 0; j < K; ++j) ra.v[j] = load_chunk<VW>(row_ptr(block_of(0), j));
-    load_t(block_of(0), ra);
-    int s = 0;
-    for (; s + 1 < nb; s += 2) {
-      apply_block(block_of(s), ra, block_of(s + 1), rb);
-      apply_block(block_of(s + 1), rb, block_of(s + 2 < nb ? s + 2 : s + 1), ra);
-    }
-    if (s < nb) apply_block(block_of(s), ra, block_of(s), rb);
-  } else {
-    Regs ra;
-#pragma unroll
-    for (int j = 0; j < K; ++j) ra.v[j] = load_chunk<VW>(row_ptr(block_of(0), j));
-    load_t(block_of(0), ra);
-    for (int s = 0; s < nb; ++s) apply_block(block_of(s), ra, block_of(s + 1 < nb ? s + 1 : s), ra);
+  for (int j = 0; j < K; ++j) ra.v[j] = load_chunk<VW>(row_ptr(block_of(0), j));
+  load_t(block_of(0), ra);
+  int s = 0;
+  for (; s + 1 < nb; s += 2) {
+    apply_block(block_of(s), ra, block_of(s + 1), rb);
+    apply_block(block_of(s + 1), rb, block_of(s + 2 < nb ? s + 2 : s + 1), ra);
   }
+  if (s < nb) apply_block(block_of(s), ra, block_of(s), rb);
   if (ok) {
 #pragma unroll
     for (int r = 0; r < VW; ++r) p.out[(size_t)(x0 + r) * m + col] = a.e[r];
   }
 }
 
-template <int K, int VW, int NT, int BUFS, int RL = 0, int SUB = 1>
+template <int K, int VW, int NT, int RL = 0, int SUB = 1>
 static int launch_chain_pipe(const ChainArgs& args, hipStream_t stream) {
   ChainArgs a = args;
   a.nb = args.nb * SUB;
   prof::Scope ps_(FASTH_KERNEL_CHAIN, stream);
-  hipLaunchKernelGGL((chain_pipe_kernel<K, VW, NT, BUFS, RL, SUB>), dim3(a.m), dim3(NT), 0, stream, a);
+  hipLaunchKernelGGL((chain_pipe_kernel<K, VW, NT, RL, SUB>), dim3(a.m), dim3(NT), 0, stream, a);
   FASTH_HIP(hipGetLastError());
   return FASTH_OK;
 }
@@ -902,24 +883,24 @@ static int launch_chain(const ChainArgs& a, hipStream_t stream) {
   const int d = a.d, k = a.k;
   if (d % 4 == 0 && k == a.kp) {
     // whole block in registers, two copies; a quarter of the next block is fetched during the reduction
-    if (k == 16 && d <= 1024) return launch_chain_pipe<16, 4, 256, 2, 4>(a, stream);
-    if (k == 16 && d <= 2048) return launch_chain_pipe<16, 4, 512, 2, 4>(a, stream);
-    if (k == 32 && d <= 256) return launch_chain_pipe<32, 1, 256, 2, 8>(a, stream);
-    if (k == 32 && d <= 512) return launch_chain_pipe<32, 2, 256, 2, 8>(a, stream);
-    if (k == 32 && d <= 1024) return launch_chain_pipe<32, 4, 256, 2, 8>(a, stream);
-    if (k == 64 && d <= 256) return launch_chain_pipe<64, 1, 256, 2, 16>(a, stream);
-    if (k == 64 && d <= 512) return launch_chain_pipe<64, 2, 256, 2, 16>(a, stream);
+    if (k == 16 && d <= 1024) return launch_chain_pipe<16, 4, 256, 4>(a, stream);
+    if (k == 16 && d <= 2048) return launch_chain_pipe<16, 4, 512, 4>(a, stream);
+    if (k == 32 && d <= 256) return launch_chain_pipe<32, 1, 256, 8>(a, stream);
+    if (k == 32 && d <= 512) return launch_chain_pipe<32, 2, 256, 8>(a, stream);
+    if (k == 32 && d <= 1024) return launch_chain_pipe<32, 4, 256, 8>(a, stream);
+    if (k == 64 && d <= 256) return launch_chain_pipe<64, 1, 256, 16>(a, stream);
+    if (k == 64 && d <= 512) return launch_chain_pipe<64, 2, 256, 16>(a, stream);
     // Larger blocks and longer vectors: two register copies of the whole block do not fit, but the block can be
     // applied as steps of 32 rows (d <= 1024) or 16 rows (d <= 2048, two waves per SIMD), which is faster than
     // one copy refilled in place or rows streamed twice (d = n = 2048: 178 us for k = 32, 64 and 128 alike,
     // against 222, 359 and 406 us)
     if (d <= 1024) {
-      if (k == 64) return launch_chain_pipe<32, 4, 256, 2, 8, 2>(a, stream);
-      if (k == 128) return launch_chain_pipe<32, 4, 256, 2, 8, 4>(a, stream);
+      if (k == 64) return launch_chain_pipe<32, 4, 256, 8, 2>(a, stream);
+      if (k == 128) return launch_chain_pipe<32, 4, 256, 8, 4>(a, stream);
     } else if (d <= 2048) {
-      if (k == 32) return launch_chain_pipe<16, 4, 512, 2, 4, 2>(a, stream);
-      if (k == 64) return launch_chain_pipe<16, 4, 512, 2, 4, 4>(a, stream);
-      if (k == 128) return launch_chain_pipe<16, 4, 512, 2, 4, 8>(a, stream);
+      if (k == 32) return launch_chain_pipe<16, 4, 512, 4, 2>(a, stream);
+      if (k == 64) return launch_chain_pipe<16, 4, 512, 4, 4>(a, stream);
+      if (k == 128) return launch_chain_pipe<16, 4, 512, 4, 8>(a, stream);
     }
   }
   if (d % 4 == 0 && d <= 4096) return launch_chain_stream_vw<4>(a, stream);
