@@ -451,6 +451,7 @@ struct ChainArgs {
   int in_rows;            // rows of `in` that exist; rows in_rows..d-1 of the chain's input are zero
   int d, n, m, k, kp, nb;
   int transpose;
+  int sub;                // chain_pipe_kernel: steps per block (set by its launcher)
 };
 
 template <int U>
@@ -599,42 +600,68 @@ __device__ __forceinline__ Chunk<VW> load_column_chunk(const ChainArgs& p, int c
 
 template <int K, int VW, int NT>
 struct PipeRegs {
-  static constexpr int G = (NT / K) < 16 ? (NT / K) : 16;  // threads sharing one row of T
+  static constexpr int G0 = (NT / K) < 16 ? (NT / K) : 16;
+  static constexpr int G = G0 < K ? G0 : K;  // threads sharing one row of T
   static constexpr int LPT = K / G;
   Chunk<VW> v[K];
   float t[LPT];
 };
 
-// SUB > 1: a block of SUB K rows is applied as SUB steps of K rows. The diagonal K x K blocks of its factor T_i
+// A block of more than K rows is applied as several steps of K rows. The diagonal K x K blocks of its factor T_i
 // are the factors of the row groups (T_i is triangular and the groups are consecutive reflections), the
 // coefficients of the steps put together are T_i V_i a, and the block's input is saved at its first step,
-// so nothing downstream sees the difference; p.nb counts the K-row steps.
-template <int K, int VW, int NT, int RL = 0, int SUB = 1>  // RL: rows of the next block fetched during the reduction
+// so nothing downstream sees the difference; p.nb counts the steps. SUB is the number of steps per block
+// (0: taken from p.sub at run time). PAD: k is not a multiple of K, so a block's last step has fewer than K
+// rows; the missing rows repeat the last one and their inner products and coefficients are forced to zero.
+template <int K, int VW, int NT, int RL = 0, int SUB = 1, bool PAD = false>  // RL: rows of the next block fetched during the reduction
 __global__ void __launch_bounds__(NT) chain_pipe_kernel(ChainArgs p) {
   typedef PipeRegs<K, VW, NT> Regs;
   constexpr int NW = NT / 64, G = Regs::G, LPT = Regs::LPT;
   constexpr int PR = (K - RL) / 2;  // rows of the next block fetched during each of the two products
   static_assert(K % 4 == 0 && K * G <= NT && LPT >= 1, "shape");
   static_assert(RL % 2 == 0 && RL <= K / 4 && (RL == 0 || K >= 8), "prefetch split");
+  static_assert(!PAD || SUB == 0, "ragged steps take the step count at run time");
   __shared__ float Bpart[NW][K];
   __shared__ __align__(16) float Cv[K];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int col = blockIdx.x, m = p.m, d = p.d;
   const int trow = tid / G, tg = tid % G;
   const bool t_active = tid < K * G;
+  const int nb = p.nb;
+  // A wave whose chunks all lie beyond d and that has no row of T to multiply only keeps the barrier count:
+  // it issues no loads, which would cost the compute unit's address unit as much as useful ones.
+  if (wave * 64 * VW >= d && wave * 64 >= K * G) {
+    if (lane < K) Bpart[wave][lane] = 0.f;
+    for (int s = 0; s < nb; ++s) {
+      lds_barrier();
+      lds_barrier();
+    }
+    return;
+  }
   // Threads whose chunk lies beyond d read chunk 0 (always valid memory) and keep their part of
   // the column at zero, so they contribute nothing and need no branch per load.
   const bool ok = VW * tid < d;
   const unsigned x0 = ok ? VW * tid : 0;
   Chunk<VW> a = load_column_chunk<VW>(p, col, x0, ok);
   const int sel = reduce_sel<K>(lane);
-  const int nb = p.nb;
   auto block_of = [&](int s) { return p.transpose ? s : nb - 1 - s; };
+  const int sub = SUB > 0 ? SUB : p.sub;
+  auto step_block = [&](int i) { return SUB == 1 ? i : i / sub; };
+  auto step_part = [&](int i) { return SUB == 1 ? 0 : i % sub; };
+  auto rows_valid = [&](int i) { return PAD ? min(K, p.k - step_part(i) * K) : K; };
   // uniform row base (scalar registers) + 32-bit per-lane offset
-  auto row_ptr = [&](int i, int j) { return p.V + ((size_t)i * K + j) * (size_t)d + x0; };
+  auto row_ptr = [&](int i, int j) {
+    if constexpr (PAD) {
+      const int row = step_block(i) * p.k + step_part(i) * K + min(j, rows_valid(i) - 1);
+      return p.V + (size_t)row * (size_t)d + x0;
+    } else {
+      return p.V + ((size_t)i * K + j) * (size_t)d + x0;
+    }
+  };
   auto load_t = [&](int i, Regs& r) {
-    constexpr int LDT = K * SUB;  // row stride of the stored factor
-    const float* Ti = p.T + (size_t)(i / SUB) * LDT * LDT + (size_t)(i % SUB) * (K * LDT + K);
+    const int LDT = (SUB > 0 && K * SUB >= 16) ? K * SUB : p.kp;  // row stride of the stored factor
+    const float* Ti = p.T + (size_t)step_block(i) * LDT * LDT + (size_t)step_part(i) * (K * LDT + K);
     const int row = t_active ? trow : 0;
 #pragma unroll
     for (int e = 0; e < LPT; ++e) {
@@ -645,8 +672,9 @@ __global__ void __launch_bounds__(NT) chain_pipe_kernel(ChainArgs p) {
 
   // Applies block i held in `cur` while fetching block inext into `nxt`.
   auto apply_block = [&](int i, Regs& cur, int inext, Regs& nxt) {
-    if (p.save_in && ok && (SUB == 1 || i % SUB == (p.transpose ? 0 : SUB - 1)))
-      store_chunk<VW>(p.save_in + ((size_t)(i / SUB) * m + col) * d + x0, a);
+    if (p.save_in && ok && (SUB == 1 || step_part(i) == (p.transpose ? 0 : sub - 1)))
+      store_chunk<VW>(p.save_in + ((size_t)step_block(i) * m + col) * d + x0, a);
+    const int kv = rows_valid(i);
     float pj[K];
 #pragma unroll
     for (int j = 0; j < K; ++j) {
@@ -657,7 +685,7 @@ __global__ void __launch_bounds__(NT) chain_pipe_kernel(ChainArgs p) {
       float acc = 0.f;
 #pragma unroll
       for (int r = 0; r < VW; ++r) acc = fmaf(cur.v[j].e[r], a.e[r], acc);
-      pj[j] = acc;
+      pj[j] = (PAD && j >= kv) ? 0.f : acc;
     }
     load_t(inext, nxt);
     if constexpr (RL > 0) {
@@ -685,9 +713,14 @@ __global__ void __launch_bounds__(NT) chain_pipe_kernel(ChainArgs p) {
         c = fmaf(cur.t[e], b, c);
       }
       c = group_sum<G>(c);
+      if (PAD && trow >= kv) c = 0.f;
       if (tg == 0) {
         Cv[trow] = c;
-        if (p.save_c) p.save_c[(size_t)col * p.n + (size_t)i * K + trow] = c;
+        if constexpr (PAD) {
+          if (p.save_c && trow < kv) p.save_c[(size_t)col * p.n + (size_t)step_block(i) * p.k + step_part(i) * K + trow] = c;
+        } else {
+          if (p.save_c) p.save_c[(size_t)col * p.n + (size_t)i * K + trow] = c;
+        }
       }
     }
     lds_barrier();
@@ -729,12 +762,14 @@ __global__ void __launch_bounds__(NT) chain_pipe_kernel(ChainArgs p) {
   }
 }
 
-template <int K, int VW, int NT, int RL = 0, int SUB = 1>
+template <int K, int VW, int NT, int RL = 0, int SUB = 1, bool PAD = false>
 static int launch_chain_pipe(const ChainArgs& args, hipStream_t stream) {
   ChainArgs a = args;
-  a.nb = args.nb * SUB;
+  a.sub = SUB > 0 ? SUB : (args.k + K - 1) / K;
+  a.nb = args.nb * a.sub;
+  if ((size_t)VW * NT < (size_t)a.d || (PAD ? a.sub * K > a.kp : a.sub * K != a.k)) return FASTH_EINVAL;
   prof::Scope ps_(FASTH_KERNEL_CHAIN, stream);
-  hipLaunchKernelGGL((chain_pipe_kernel<K, VW, NT, RL, SUB>), dim3(a.m), dim3(NT), 0, stream, a);
+  hipLaunchKernelGGL((chain_pipe_kernel<K, VW, NT, RL, SUB, PAD>), dim3(a.m), dim3(NT), 0, stream, a);
   FASTH_HIP(hipGetLastError());
   return FASTH_OK;
 }
@@ -881,7 +916,7 @@ static int launch_chain_stream_vw(const ChainArgs& a, hipStream_t stream) {
 
 static int launch_chain(const ChainArgs& a, hipStream_t stream) {
   const int d = a.d, k = a.k;
-  if (d % 4 == 0 && k == a.kp) {
+  if (d % 4 == 0 && d <= 4096) {
     // whole block in registers, two copies; a quarter of the next block is fetched during the reduction
     if (k == 16 && d <= 1024) return launch_chain_pipe<16, 4, 256, 4>(a, stream);
     if (k == 16 && d <= 2048) return launch_chain_pipe<16, 4, 512, 4>(a, stream);
@@ -897,13 +932,24 @@ static int launch_chain(const ChainArgs& a, hipStream_t stream) {
     if (d <= 1024) {
       if (k == 64) return launch_chain_pipe<32, 4, 256, 8, 2>(a, stream);
       if (k == 128) return launch_chain_pipe<32, 4, 256, 8, 4>(a, stream);
+      if (k == 8) return launch_chain_pipe<8, 4, 256, 2>(a, stream);
+      // any other block size: steps of 8, 16 or 32 rows, the last one of a block short
+      if (k < 8) return launch_chain_pipe<8, 4, 256, 2, 0, true>(a, stream);
+      if (k < 16) return launch_chain_pipe<16, 4, 256, 4, 0, true>(a, stream);
+      return launch_chain_pipe<32, 4, 256, 8, 0, true>(a, stream);
     } else if (d <= 2048) {
       if (k == 32) return launch_chain_pipe<16, 4, 512, 4, 2>(a, stream);
       if (k == 64) return launch_chain_pipe<16, 4, 512, 4, 4>(a, stream);
       if (k == 128) return launch_chain_pipe<16, 4, 512, 4, 8>(a, stream);
+      if (k == 8) return launch_chain_pipe<8, 4, 512, 2>(a, stream);
+      if (k < 8) return launch_chain_pipe<8, 4, 512, 2, 0, true>(a, stream);
+      return launch_chain_pipe<16, 4, 512, 4, 0, true>(a, stream);
+    } else {
+      // 16 waves share 512 registers per lane: two copies of 8 rows
+      if (k % 8 == 0) return launch_chain_pipe<8, 4, 1024, 2, 0>(a, stream);
+      return launch_chain_pipe<8, 4, 1024, 2, 0, true>(a, stream);
     }
   }
-  if (d % 4 == 0 && d <= 4096) return launch_chain_stream_vw<4>(a, stream);
   if (d % 2 == 0 && d <= 2048) return launch_chain_stream_vw<2>(a, stream);
   if (d <= 1024) return launch_chain_stream_vw<1>(a, stream);
   int threads = 256;

@@ -46,9 +46,11 @@ def test_fasth_small_cases(d, n, m, k, transpose):
     assert rel_err(dV, dV0) <= REL_TOL
 
 
-# One case per chain-kernel variant the launcher can pick: blocks held in registers once or twice
-# for k in {16, 32, 64}, the streaming kernel at every vector width and workgroup size, and the
-# generic kernel for very long vectors. Few reflections and columns keep the checker fast.
+# One case per chain-kernel variant the launcher can pick: blocks held in registers and applied whole or
+# as steps of 8, 16 or 32 rows (with a short last step when k is not a multiple of the step), at every
+# workgroup size including shapes that leave whole waves without work, the streaming kernel at the
+# narrower vector widths, and the generic kernel for very long vectors. Few reflections and columns
+# keep the checker fast.
 DISPATCH = [
     (1024, 32, 3, 16), (2048, 32, 3, 16),
     (256, 64, 3, 32), (512, 64, 3, 32), (1024, 96, 3, 32), (2048, 64, 3, 32), (1500, 64, 3, 32),
@@ -56,6 +58,9 @@ DISPATCH = [
     (1024, 256, 3, 128), (2048, 128, 2, 64), (4096, 64, 2, 32), (3000, 48, 2, 24),
     (2046, 32, 2, 32), (1022, 40, 2, 8), (1023, 32, 2, 16), (777, 21, 2, 7),
     (4100, 32, 2, 16), (5001, 16, 2, 8),
+    (3072, 64, 3, 32), (2304, 48, 2, 24), (4096, 56, 2, 28), (4096, 256, 1, 128), (2052, 10, 2, 5),
+    (1024, 56, 3, 28), (784, 112, 2, 56), (1024, 36, 2, 12), (1024, 15, 2, 5), (1024, 40, 2, 8),
+    (2048, 40, 2, 8), (2048, 20, 2, 5), (1536, 72, 2, 24), (1280, 200, 2, 100),
 ]
 
 
