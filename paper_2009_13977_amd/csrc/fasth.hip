@@ -452,7 +452,41 @@ struct ChainArgs {
   int d, n, m, k, kp, nb;
   int transpose;
   int sub;                // chain_pipe_kernel: steps per block (set by its launcher)
+  // Optional side product of the SVD layers' backward pass, which has the chain's input as one operand:
+  // ds_out[r] = s'(in_scale[r]) sum_l in[r][l] ds_z1[r][l] for r < ds_rows (s = diag_factor(in_scale_mode, .)).
+  // Null ds_out: not wanted. Kernels that cannot take it along leave it to a launch of dsigma_kernel.
+  const float* ds_z1;     // [ds_rows][m]
+  float* ds_out;          // [ds_rows]
+  int ds_rows;
 };
+
+// Gradient of the diagonal step of the SVD layer (Section 2.2), one wave per row: with Z2 = s * Z1 row-wise
+// (s = sigma, 1/sigma or a function of sigma),
+//   ds_r = sum_l dZ2[r][l] Z1[r][l];  dsigma_r = ds_r * s'(sigma_r)  (e.g. -ds_r / sigma_r^2 for s = 1/sigma).
+__device__ __forceinline__ void dsigma_row(const float* __restrict__ dZ2, const float* __restrict__ Z1,
+                                           const float* __restrict__ sigma, float* __restrict__ dsigma, int row,
+                                           int m, int mode) {
+  const int lane = threadIdx.x & 63;
+  float r[1] = {0.f};
+  for (int l = lane; l < m; l += 64) r[0] += dZ2[(size_t)row * m + l] * Z1[(size_t)row * m + l];
+  wave_reduce_multi<1>(r);
+  if (lane == 0) {
+    // chain rule from the diagonal factor s(sigma) to sigma: mode = diag_factor mode
+    float v = r[0];
+    const float sg = sigma[row];
+    if (mode == 2) v = -v / (sg * sg);
+    else if (mode == 3) v *= expf(sg);
+    else if (mode == 4) v *= -2.f / ((1.f + sg) * (1.f + sg));
+    dsigma[row] = v;
+  }
+}
+
+__global__ void __launch_bounds__(256) dsigma_kernel(const float* __restrict__ dZ2, const float* __restrict__ Z1,
+                                                     const float* __restrict__ sigma, float* __restrict__ dsigma,
+                                                     int d, int m, int mode) {
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row < d) dsigma_row(dZ2, Z1, sigma, dsigma, row, m, mode);
+}
 
 template <int U>
 __global__ void __launch_bounds__(1024) chain_kernel(ChainArgs p) {
@@ -626,6 +660,11 @@ __global__ void __launch_bounds__(NT) chain_pipe_kernel(ChainArgs p) {
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int col = blockIdx.x, m = p.m, d = p.d;
+  if (col >= m) {  // workgroups beyond the columns: the side product, on compute units the chain leaves idle
+    const int row = (col - m) * NW + wave;
+    if (row < p.ds_rows) dsigma_row(p.in, p.ds_z1, p.in_scale, p.ds_out, row, m, p.in_scale_mode);
+    return;
+  }
   const int trow = tid / G, tg = tid % G;
   const bool t_active = tid < K * G;
   const int nb = p.nb;
@@ -768,8 +807,9 @@ static int launch_chain_pipe(const ChainArgs& args, hipStream_t stream) {
   a.sub = SUB > 0 ? SUB : (args.k + K - 1) / K;
   a.nb = args.nb * a.sub;
   if ((size_t)VW * NT < (size_t)a.d || (PAD ? a.sub * K > a.kp : a.sub * K != a.k)) return FASTH_EINVAL;
+  const int side = a.ds_out ? (a.ds_rows + NT / 64 - 1) / (NT / 64) : 0;
   prof::Scope ps_(FASTH_KERNEL_CHAIN, stream);
-  hipLaunchKernelGGL((chain_pipe_kernel<K, VW, NT, RL, SUB, PAD>), dim3(a.m), dim3(NT), 0, stream, a);
+  hipLaunchKernelGGL((chain_pipe_kernel<K, VW, NT, RL, SUB, PAD>), dim3(a.m + side), dim3(NT), 0, stream, a);
   FASTH_HIP(hipGetLastError());
   return FASTH_OK;
 }
@@ -914,9 +954,11 @@ static int launch_chain_stream_vw(const ChainArgs& a, hipStream_t stream) {
   return launch_chain_stream<VW, 1024>(a, stream);
 }
 
-static int launch_chain(const ChainArgs& a, hipStream_t stream) {
+static bool chain_takes_side_product(const ChainArgs& a) { return a.d % 4 == 0 && a.d <= 4096; }
+
+static int launch_chain_kernel(const ChainArgs& a, hipStream_t stream) {
   const int d = a.d, k = a.k;
-  if (d % 4 == 0 && d <= 4096) {
+  if (chain_takes_side_product(a)) {  // every launch in this branch is a chain_pipe_kernel
     // whole block in registers, two copies; a quarter of the next block is fetched during the reduction
     if (k == 16 && d <= 1024) return launch_chain_pipe<16, 4, 256, 4>(a, stream);
     if (k == 16 && d <= 2048) return launch_chain_pipe<16, 4, 512, 4>(a, stream);
@@ -972,6 +1014,16 @@ static int launch_chain(const ChainArgs& a, hipStream_t stream) {
   else if (per <= 8) FASTH_LAUNCH_CHAIN(8);
   else FASTH_LAUNCH_CHAIN(16);
 #undef FASTH_LAUNCH_CHAIN
+  FASTH_HIP(hipGetLastError());
+  return FASTH_OK;
+}
+
+static int launch_chain(const ChainArgs& a, hipStream_t stream) {
+  const int rc = launch_chain_kernel(a, stream);
+  if (rc != FASTH_OK || !a.ds_out || chain_takes_side_product(a)) return rc;
+  prof::Scope ps_(FASTH_KERNEL_DSIGMA, stream);
+  hipLaunchKernelGGL(dsigma_kernel, dim3((a.ds_rows + 3) / 4), dim3(256), 0, stream, a.in, a.ds_z1, a.in_scale, a.ds_out,
+                     a.ds_rows, a.m, a.in_scale_mode);
   FASTH_HIP(hipGetLastError());
   return FASTH_OK;
 }
@@ -1281,29 +1333,6 @@ __global__ void __launch_bounds__(256) seq_reduce_kernel(const float* __restrict
 }
 
 // ------------------------------------------------------------------------------------------
-// Diagonal step of the SVD layer (Section 2.2): with Z2 = s * Z1 (s = sigma or 1/sigma),
-//   ds_r = sum_l dZ2[r][l] Z1[r][l];  dsigma_r = ds_r * s'(sigma_r)  (e.g. -ds_r / sigma_r^2 for s = 1/sigma).
-// ------------------------------------------------------------------------------------------
-
-__global__ void __launch_bounds__(256) dsigma_kernel(const float* __restrict__ dZ2, const float* __restrict__ Z1,
-                                                     const float* __restrict__ sigma, float* __restrict__ dsigma,
-                                                     int d, int m, int mode) {
-  const int row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
-  if (row >= d) return;
-  float r[1] = {0.f};
-  for (int l = lane; l < m; l += 64) r[0] += dZ2[(size_t)row * m + l] * Z1[(size_t)row * m + l];
-  wave_reduce_multi<1>(r);
-  if (lane == 0) {
-    // chain rule from the diagonal factor s(sigma) to sigma: mode = diag_factor mode
-    float v = r[0];
-    const float sg = sigma[row];
-    if (mode == 2) v = -v / (sg * sg);
-    else if (mode == 3) v *= expf(sg);
-    else if (mode == 4) v *= -2.f / ((1.f + sg) * (1.f + sg));
-    dsigma[row] = v;
-  }
-}
-
 // Table 1, row "Determinant": log|det W| = sum_i log|sigma_i| and its gradient 1/sigma_i. One workgroup,
 // fixed summation order.
 __global__ void __launch_bounds__(256) logabsdet_kernel(const float* __restrict__ sigma, float* __restrict__ out,
@@ -1414,7 +1443,8 @@ static int build_factors_pair(const Product& P0, const float* V0, const Product&
 // slots of the workspace, false into the gradient slots.
 static int run_chain(const Product& P, const float* V, const float* in, float* out, int transpose, bool activation,
                      const float* in_scale, int in_scale_mode, hipStream_t stream, bool save = true,
-                     const float* factors = nullptr, int in_rows = -1) {
+                     const float* factors = nullptr, int in_rows = -1, const float* ds_z1 = nullptr,
+                     float* ds_out = nullptr, int ds_rows = 0) {
   ChainArgs a;
   a.V = V; a.T = factors ? factors : P.T(); a.in = in; a.out = out;
   a.save_in = !save ? nullptr : activation ? P.saveA() : P.saveG();
@@ -1423,6 +1453,8 @@ static int run_chain(const Product& P, const float* V, const float* in, float* o
   a.in_rows = in_rows < 0 ? P.d : in_rows;
   a.d = P.d; a.n = P.n; a.m = P.m; a.k = P.k; a.kp = P.L.kp; a.nb = P.L.nb;
   a.transpose = transpose;
+  a.sub = 1;
+  a.ds_z1 = ds_z1; a.ds_out = ds_out; a.ds_rows = ds_rows;
   return launch_chain(a, stream);
 }
 
@@ -1558,14 +1590,11 @@ static int svd_backward(const fasth_svd_shape* shape, const float* first, const 
   float* dZ2 = reinterpret_cast<float*>(ws + S.off_dZ2);
   // through the second (plain) factor
   if ((rc = run_chain(Ps, second, G, dZ2, 1, false, nullptr, 0, st)) != FASTH_OK) return rc;
-  {
-    prof::Scope ps_(FASTH_KERNEL_DSIGMA, st);
-    hipLaunchKernelGGL(dsigma_kernel, dim3((fs.d + 3) / 4), dim3(256), 0, st, dZ2, Z1, sigma, dsigma, fs.d, fs.m,
-                       scale_mode);
-  }
-  FASTH_HIP(hipGetLastError());
-  // through the first (transposed) factor; dZ1 = s * dZ2 is fused into the chain's load
-  if ((rc = run_chain(Pf, first, dZ2, dX, 0, false, sigma, scale_mode, st)) != FASTH_OK) return rc;
+  // through the first (transposed) factor; dZ1 = s * dZ2 is fused into the chain's load, and the gradient of
+  // sigma, which needs the same dZ2, rides along in the same launch
+  if ((rc = run_chain(Pf, first, dZ2, dX, 0, false, sigma, scale_mode, st, true, nullptr, -1, Z1, dsigma, fs.d)) !=
+      FASTH_OK)
+    return rc;
   // both factors' vector gradients in one launch: each reads only its own saved slots
   return run_dv_pair(Ps, second, dsecond, 0, Pf, first, dfirst, 1, st);
 }
@@ -1895,13 +1924,8 @@ int svd_sym_apply_backward(const fasth_svd_shape* shape, int function, const flo
   float* dZ2 = reinterpret_cast<float*>(ws + S.off_dZ2);
   if ((rc = run_chain(Pout, Uv, G, dZ2, 1, false, nullptr, 0, st, true, Pin.T())) != FASTH_OK) return rc;
   if ((rc = run_dv(Pout, Uv, dUv, 0, st)) != FASTH_OK) return rc;
-  {
-    prof::Scope ps_(FASTH_KERNEL_DSIGMA, st);
-    hipLaunchKernelGGL(dsigma_kernel, dim3((fs.d + 3) / 4), dim3(256), 0, st, (const float*)dZ2, Z1, sigma, dsigma,
-                       fs.d, fs.m, mode);
-  }
-  FASTH_HIP(hipGetLastError());
-  if ((rc = run_chain(Pin, Uv, dZ2, dX, 0, false, sigma, mode, st)) != FASTH_OK) return rc;
+  if ((rc = run_chain(Pin, Uv, dZ2, dX, 0, false, sigma, mode, st, true, nullptr, -1, Z1, dsigma, fs.d)) != FASTH_OK)
+    return rc;
   return run_dv(Pin, Uv, dUv, 1, st, true);
 }
 
@@ -1984,14 +2008,8 @@ int svd_rect_apply_backward(const fasth_rect_shape* shape, const float* Uv, cons
   float* dZ2 = reinterpret_cast<float*>(ws + S.off_dZ2);
   const int r = fu.d < fv.d ? fu.d : fv.d;
   if ((rc = run_chain(Pu, Uv, G, dZ2, 1, false, nullptr, 0, st)) != FASTH_OK) return rc;
-  {
-    prof::Scope ps_(FASTH_KERNEL_DSIGMA, st);
-    hipLaunchKernelGGL(dsigma_kernel, dim3((r + 3) / 4), dim3(256), 0, st, (const float*)dZ2, Z1, sigma, dsigma, r,
-                       fu.m, 1);
-  }
-  FASTH_HIP(hipGetLastError());
   // Sigma^T dZ2: first r rows scaled, rows r..cols-1 zero
-  if ((rc = run_chain(Pv, Vv, dZ2, dX, 0, false, sigma, 1, st, true, nullptr, r)) != FASTH_OK) return rc;
+  if ((rc = run_chain(Pv, Vv, dZ2, dX, 0, false, sigma, 1, st, true, nullptr, r, Z1, dsigma, r)) != FASTH_OK) return rc;
   return run_dv_pair(Pu, Uv, dUv, 0, Pv, Vv, dVv, 1, st);
 }
 
