@@ -29,6 +29,10 @@ def build_library(verbose: bool = True) -> str:
     cmd = [
         hipcc_path(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+        # matrix-instruction results stay in the ordinary vector registers: the chain kernel for wide mini-batches
+        # uses its accumulators as the next product's operand, and copies between the two register files
+        # would cost more than the products' bookkeeping
+        "-mllvm", "-amdgpu-mfma-vgpr-form=1",
         "-I", os.path.join(ROOT, "include"), "-I", os.path.join(PKG_DIR, "csrc"),
         "-o", LIB_PATH, *SOURCES,
     ]

@@ -36,6 +36,18 @@ __device__ __forceinline__ BufVec<VEC> buffer_load(BufferDesc desc, unsigned lan
   }
   return r;
 }
+// Store of VEC consecutive floats; a lane whose offset lies beyond the buffer stores nothing.
+template <int VEC>
+__device__ __forceinline__ void buffer_store(BufferDesc desc, unsigned lane_bytes, unsigned uniform_bytes, const BufVec<VEC>& v) {
+  if constexpr (VEC == 4) {
+    typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+    const u32x4 w = {__float_as_uint(v.e[0]), __float_as_uint(v.e[1]), __float_as_uint(v.e[2]), __float_as_uint(v.e[3])};
+    __builtin_amdgcn_raw_buffer_store_b128(w, desc, lane_bytes, uniform_bytes, 0);
+  } else {
+    static_assert(VEC == 1, "1 or 4 floats");
+    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v.e[0]), desc, lane_bytes, uniform_bytes, 0);
+  }
+}
 template <int VEC>
 __device__ __forceinline__ void lds_store(float* dst, const BufVec<VEC>& v) {
   if constexpr (VEC == 4) {

@@ -76,6 +76,58 @@ def test_fasth_every_chain_kernel(d, n, m, k, transpose):
     assert rel_err(dV, dV0) <= REL_TOL
 
 
+# Wide mini-batches (more than 768 columns) take the matrix-core chain kernel: 16 columns per workgroup, rows in
+# steps of 16. Cases: every groups-per-wave variant (d <= 256, 512, 768, 1024), d and m with ragged tails, blocks
+# of one and of several steps, n != d; few reflections keep the checker fast.
+WIDE = [
+    (256, 64, 800, 32), (512, 32, 1030, 16), (768, 96, 770, 48), (1024, 64, 780, 32), (1000, 128, 1100, 64),
+    (100, 32, 769, 16), (320, 256, 900, 128),
+]
+
+
+@pytest.mark.parametrize("transpose", [False, True])
+@pytest.mark.parametrize("d,n,m,k", WIDE)
+def test_fasth_wide_minibatch(d, n, m, k, transpose):
+    _say(f"fasth wide d={d} n={n} m={m} k={k} transpose={transpose}")
+    p = synthetic.householder_problem(d, n, m, seed=5000 + d + n + m + k)
+    A, dV, dX = gpu_fasth(p["V"], p["X"], p["G"], k, transpose)
+    A0, dV0, dX0 = orc.product_gradients(p["V"], p["X"], p["G"], transpose=transpose)
+    assert rel_err(A, A0) <= REL_TOL
+    assert rel_err(dX, dX0) <= REL_TOL
+    assert rel_err(dV, dV0) <= REL_TOL
+
+
+def test_layers_wide_minibatch():
+    """The layers on the matrix-core chain kernel: the diagonal factor fused into its input fetch (every mode),
+    a rectangular Sigma (rows of the chain's input that do not exist), and the gradient of sigma from a launch of
+    its own."""
+    d, n, m, k = 256, 64, 800, 32
+    p = synthetic.svd_layer_problem(d, n, m, seed=5100)
+    for inverse in (False, True):
+        _say(f"svd layer wide inverse={inverse}")
+        got = gpu_svd_layer(p["Uv"], p["sigma"], p["Vv"], p["X"], p["G"], k, inverse)
+        fn = orc.svd_layer_inverse_gradients if inverse else orc.svd_layer_gradients
+        ref = fn(p["Uv"], p["sigma"], p["Vv"], p["X"], p["G"])
+        for name, g, r in zip(("Y", "dUv", "dsigma", "dVv", "dX"), got, ref):
+            assert rel_err(g, r) <= REL_TOL, (name, rel_err(g, r))
+    rng = np.random.default_rng(5200)
+    sigma = rng.uniform(-0.8, 0.9, d).astype(np.float32)
+    for function in ("exp", "cayley"):
+        _say(f"svd sym wide f={function}")
+        got = gpu_svd_sym(p["Uv"], sigma, p["X"], p["G"], k, function)
+        ref = orc.symmetric_gradients(p["Uv"], sigma, p["X"], p["G"], function)
+        for name, g, r in zip(("Y", "dUv", "dsigma", "dX"), got, ref):
+            assert rel_err(g, r) <= REL_TOL, (name, rel_err(g, r))
+    for rows, cols in ((256, 192), (192, 256)):
+        _say(f"svd rect wide rows={rows} cols={cols}")
+        q = synthetic.rect_layer_problem(rows, cols, 32, 32, 800, seed=5300 + rows)
+        got = gpu_svd_rect(q["Uv"], q["sigma"], q["Vv"], q["X"], q["G"], 16)
+        ref = orc.rectangular_gradients(q["Uv"], q["sigma"], q["Vv"], q["X"], q["G"])
+        for name, g, r in zip(("Y", "dUv", "dsigma", "dVv", "dX"), got, ref):
+            assert g.shape == r.shape, name
+            assert rel_err(g, r) <= REL_TOL, (name, rel_err(g, r))
+
+
 @pytest.mark.parametrize("name", ["d64_m32_k32", "d256_m32_k32", "d1024_m32_k32",
                                   "d2048_m64_k32", "d2048_m64_k64", "d2048_m64_k128"])
 def test_fasth_benchmark_configs(name):
