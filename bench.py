@@ -174,6 +174,9 @@ def main() -> int:
         per.append(timed(step, 1))
     per = np.array(per)
     ms_fwd = timed(lambda: B.fasth_forward(V, X, A, ws, k), args.steps)
+    # factors built once and reused (Section 3.3: recurrent and convolutional layers, inference): chain only
+    B.fasth_prepare(V, m, ws, k)
+    ms_apply = timed(lambda: B.fasth_apply(V, X, A, ws, k, False, False), args.steps)
     B.fasth_forward(V, X, A, ws, k)
     ms_bwd = timed(lambda: B.fasth_backward(V, G, dV, dX, ws, k), args.steps)
 
@@ -188,6 +191,9 @@ def main() -> int:
     kernels = {kn: {"ms_avg": t / c, "launches_per_step": c / args.steps} for kn, (t, c) in prof.items() if c}
     chain_ms = kernels["chain_kernel"]["ms_avg"]
     chain_tflops = chain_flops(d, n, m) / (chain_ms * 1e-3) / 1e12
+    # More than 768 columns (d <= 1024) run the chain on the matrix cores; below that it is one workgroup per
+    # column on the vector units.
+    chain_on_matrix_cores = m > 768 and d <= 1024 and d % 4 == 0 and k % 16 == 0
 
     out = {
         "metric": "fasth_fwd_bwd_gflops_paper_count",
@@ -209,11 +215,13 @@ def main() -> int:
         "flops": {"paper": f_paper(d, n, m, k), "exec": f_exec(d, n, m, k), "sequential": f_seq(d, n, m)},
         "ms_forward": ms_fwd,
         "ms_backward": ms_bwd,
+        "ms_apply_prepared": ms_apply,
+        "tflops_apply_prepared": chain_flops(d, n, m) / (ms_apply * 1e-3) / 1e12,
         "ms_step_single": {"mean": float(per.mean()), "std": float(per.std()), "min": float(per.min())},
         "kernels": kernels,
         "roofline": {
             "kernel": "chain_kernel",
-            "bound": "alu",
+            "bound": "mfma" if chain_on_matrix_cores else "alu",
             "achieved": chain_tflops,
             "peak": FP32_MATRIX_PEAK_TFLOPS,
             "unit": "TFLOP/s",

@@ -976,15 +976,25 @@ __global__ void __launch_bounds__(256) chain_tile_kernel(ChainArgs p) {
     f32x4 acc[4];
 #pragma unroll
     for (int r = 0; r < 4; ++r) acc[r] = f32x4{0.f, 0.f, 0.f, 0.f};
+    // operand fetches run two ahead of the matrix instructions that use them
+    auto v1_at = [&](int t) {  // t = 4 g + j
+      return *reinterpret_cast<const float4*>(Vc + i * kTileLd + 64 * (t >> 2) + 16 * q + 4 * (t & 3));
+    };
+    {
+      float4 va = v1_at(0), vb = v1_at(1);
+      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
 #pragma unroll
-    for (int g = 0; g < kTileGroups; ++g) {
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const float4 v4 = *reinterpret_cast<const float4*>(Vc + i * kTileLd + 64 * g + 16 * q + 4 * j);
+      for (int t = 0; t < 4 * kTileGroups; ++t) {
+        const int g = t >> 2, j = t & 3;
+        const float4 v4 = va;
+        va = vb;
+        if (t + 2 < 4 * kTileGroups) vb = v1_at(t + 2);
         acc[0] = __builtin_amdgcn_mfma_f32_16x16x4f32(v4.x, A[4 * g][j], acc[0], 0, 0, 0);
         acc[1] = __builtin_amdgcn_mfma_f32_16x16x4f32(v4.y, A[4 * g + 1][j], acc[1], 0, 0, 0);
         acc[2] = __builtin_amdgcn_mfma_f32_16x16x4f32(v4.z, A[4 * g + 2][j], acc[2], 0, 0, 0);
         acc[3] = __builtin_amdgcn_mfma_f32_16x16x4f32(v4.w, A[4 * g + 3][j], acc[3], 0, 0, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // one LDS read ...
+        __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);  // ... then four matrix instructions
       }
     }
     const f32x4 bpart = (acc[0] + acc[1]) + (acc[2] + acc[3]);
@@ -1009,16 +1019,25 @@ __global__ void __launch_bounds__(256) chain_tile_kernel(ChainArgs p) {
     if (p.save_c && wave == 0 && col_ok)
       *reinterpret_cast<float4*>(p.save_c + (size_t)col * n + row0 + 4 * q) = make_float4(C[0], C[1], C[2], C[3]);
     // A -= V_rows^T C: contraction slice s2 pairs K index q with row 4 q + s2, which is where lane (q, i) holds C
+    auto v2_at = [&](int t) {  // t = 4 g + s2
+      return *reinterpret_cast<const float4*>(Vc + (4 * q + (t & 3)) * kTileLd + 64 * (t >> 2) + 4 * i);
+    };
+    {
+      const float cn[4] = {-C[0], -C[1], -C[2], -C[3]};
+      float4 va = v2_at(0), vb = v2_at(1);
+      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
 #pragma unroll
-    for (int g = 0; g < kTileGroups; ++g) {
-#pragma unroll
-      for (int s2 = 0; s2 < 4; ++s2) {
-        const float4 v4 = *reinterpret_cast<const float4*>(Vc + (4 * q + s2) * kTileLd + 64 * g + 4 * i);
-        const float c = -C[s2];
-        A[4 * g] = __builtin_amdgcn_mfma_f32_16x16x4f32(v4.x, c, A[4 * g], 0, 0, 0);
-        A[4 * g + 1] = __builtin_amdgcn_mfma_f32_16x16x4f32(v4.y, c, A[4 * g + 1], 0, 0, 0);
-        A[4 * g + 2] = __builtin_amdgcn_mfma_f32_16x16x4f32(v4.z, c, A[4 * g + 2], 0, 0, 0);
-        A[4 * g + 3] = __builtin_amdgcn_mfma_f32_16x16x4f32(v4.w, c, A[4 * g + 3], 0, 0, 0);
+      for (int t = 0; t < 4 * kTileGroups; ++t) {
+        const int g = t >> 2, s2 = t & 3;
+        const float4 v4 = va;
+        va = vb;
+        if (t + 2 < 4 * kTileGroups) vb = v2_at(t + 2);
+        A[4 * g] = __builtin_amdgcn_mfma_f32_16x16x4f32(v4.x, cn[s2], A[4 * g], 0, 0, 0);
+        A[4 * g + 1] = __builtin_amdgcn_mfma_f32_16x16x4f32(v4.y, cn[s2], A[4 * g + 1], 0, 0, 0);
+        A[4 * g + 2] = __builtin_amdgcn_mfma_f32_16x16x4f32(v4.z, cn[s2], A[4 * g + 2], 0, 0, 0);
+        A[4 * g + 3] = __builtin_amdgcn_mfma_f32_16x16x4f32(v4.w, cn[s2], A[4 * g + 3], 0, 0, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
       }
     }
     stash_rows();

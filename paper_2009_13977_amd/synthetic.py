@@ -48,6 +48,9 @@ WORKLOADS: Dict[str, Workload] = {
         Workload("d2048_m64_k64", 2048, 2048, 64, 64, SEED_BASE + 4),
         Workload("d2048_m64_k128", 2048, 2048, 64, 128, SEED_BASE + 4),
         Workload("svd_d1024_m32_k32", 1024, 1024, 32, 32, SEED_BASE + 5, True),
+        # Section 3.3, convolutional and recurrent uses: one V applied to m * h * w (or m * r) columns
+        Workload("d1024_m4096_k32", 1024, 1024, 4096, 32, SEED_BASE + 6),
+        Workload("d1024_m16384_k32", 1024, 1024, 16384, 32, SEED_BASE + 7),
     )
 }
 

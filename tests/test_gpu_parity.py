@@ -97,6 +97,20 @@ def test_fasth_wide_minibatch(d, n, m, k, transpose):
     assert rel_err(dV, dV0) <= REL_TOL
 
 
+def test_fasth_wide_benchmark_config():
+    """The wide workload at full size (4096 columns) against the checker on every output."""
+    name = "d1024_m4096_k32"
+    w = synthetic.WORKLOADS[name]
+    _say(f"fasth config {name}")
+    p = synthetic.workload_inputs(name)
+    A, dV, dX = gpu_fasth(p["V"], p["X"], p["G"], w.k)
+    _say("  checker")
+    A0, dV0, dX0 = orc.product_gradients(p["V"], p["X"], p["G"])
+    errs = (rel_err(A, A0), rel_err(dV, dV0), rel_err(dX, dX0))
+    _say(f"  rel errors A/dV/dX: {errs}")
+    assert max(errs) <= REL_TOL
+
+
 def test_layers_wide_minibatch():
     """The layers on the matrix-core chain kernel: the diagonal factor fused into its input fetch (every mode),
     a rectangular Sigma (rows of the chain's input that do not exist), and the gradient of sigma from a launch of
