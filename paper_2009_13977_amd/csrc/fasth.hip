@@ -817,9 +817,9 @@ static int launch_chain_pipe(const ChainArgs& args, hipStream_t stream) {
 
 // ---- Matrix-core chain kernel for wide mini-batches ------------------------------------------
 // With many columns the two products of a block step, B = V_i A and A -= V_i^T C, are dense contractions with a
-// real N dimension, so they go to the fp32 matrix cores: one workgroup of 4 waves per tile of 16 columns.
+// real N dimension, so they go to the fp32 matrix cores: one workgroup of 4 (d <= 1024) or 8 waves per tile of 16 columns.
 //  * The d x 16 tile of A lives in the accumulator registers for the whole chain. The x axis is cut into groups
-//    of 64; wave w owns groups w, w + 4, ... Within a group, accumulator tile r (0..3), register j of lane
+//    of 64; wave w of NW owns groups w, w + NW, ... Within a group, accumulator tile r (0..3), register j of lane
 //    (q, i) = (lane / 16, lane % 16) holds A(x = 64 g + 16 q + 4 j + r, column i): the order in which a
 //    contraction runs over x is free, and this one lets the same registers serve as the product's output tile
 //    (A -= V^T C) and as the B operand of the next step's first product without any shuffle, while every fetch
@@ -833,16 +833,17 @@ static int launch_chain_pipe(const ChainArgs& args, hipStream_t stream) {
 //    C = op(T) B itself (4 matrix instructions), which is already laid out as the B operand of the update.
 constexpr int kTileCols = 16;           // columns per workgroup
 constexpr int kTileRows = 16;           // rows of V per step
-constexpr int kTileMaxGroups = 4;       // groups of 64 x per wave: d <= 4 waves * 4 * 64
-constexpr int kTileMaxD = 4 * kTileMaxGroups * 64;
-static constexpr size_t tile_lds_bytes(int groups) {
-  return sizeof(float) * (size_t)(4 * kTileRows * (64 * groups + 4) + 2 * 4 * 256);
+constexpr int kTileMaxGroups = 4;       // groups of 64 x per wave
+constexpr int kTileMaxD = 8 * kTileMaxGroups * 64;  // with 8 waves
+static constexpr size_t tile_lds_bytes(int waves, int groups) {
+  return sizeof(float) * (size_t)(waves * kTileRows * (64 * groups + 4) + 2 * waves * 256);
 }
 
 // kTileGroups: groups per wave, the same for all four waves (a group that lies beyond d is all zeros: its
 // fetches are out of the buffers' range, so it costs matrix instructions but no branch).
-template <int kTileGroups>
-__global__ void __launch_bounds__(256) chain_tile_kernel(ChainArgs p) {
+// NW: waves per workgroup, 4 for d <= 1024, 8 (two per SIMD) for d <= 2048.
+template <int NW, int kTileGroups>
+__global__ void __launch_bounds__(64 * NW) chain_tile_kernel(ChainArgs p) {
   constexpr int kTileLd = 64 * kTileGroups + 4;  // row stride of a wave's slice in LDS (floats)
   extern __shared__ float smem[];
   const int tid = threadIdx.x, lane = tid & 63;
@@ -852,8 +853,8 @@ __global__ void __launch_bounds__(256) chain_tile_kernel(ChainArgs p) {
   const int col = blockIdx.x * kTileCols + i;
   const bool col_ok = col < m;
   float* Vw = smem + (size_t)wave * kTileRows * kTileLd;         // this wave's slice of the step's rows: [16][kTileLd]
-  float* Bp = smem + (size_t)4 * kTileRows * kTileLd;            // partial products: [2][4 waves][256]
-  auto group_x = [&](int g) { return 64 * (wave + 4 * g); };
+  float* Bp = smem + (size_t)NW * kTileRows * kTileLd;           // partial products: [2][NW][256]
+  auto group_x = [&](int g) { return 64 * (wave + NW * g); };
 
   // Input tile through a buffer bounded by the rows that exist: rows beyond them, columns beyond m and groups
   // this wave does not own read as zero without a branch, so all fetches are in flight together.
@@ -1000,14 +1001,14 @@ __global__ void __launch_bounds__(256) chain_tile_kernel(ChainArgs p) {
     const f32x4 bpart = (acc[0] + acc[1]) + (acc[2] + acc[3]);
     // element (row 4 kk + qq, column i) of a wave's partial sits at ((qq * 16 + i) * 4 + kk): the writes of a
     // wave hit 64 different banks and the operand fetch below is one 16-byte read per wave summed over
-    float* bw = Bp + (size_t)(cur * 4 + wave) * 256;
+    float* bw = Bp + (size_t)(cur * NW + wave) * 256;
 #pragma unroll
     for (int jj = 0; jj < 4; ++jj) bw[(jj * 16 + i) * 4 + q] = bpart[jj];
     lds_barrier();
-    const float* br = Bp + (size_t)cur * 4 * 256 + (q * 16 + i) * 4;
+    const float* br = Bp + (size_t)cur * NW * 256 + (q * 16 + i) * 4;
     float4 b = *reinterpret_cast<const float4*>(br);
 #pragma unroll
-    for (int w = 1; w < 4; ++w) {
+    for (int w = 1; w < NW; ++w) {
       const float4 t4 = *reinterpret_cast<const float4*>(br + w * 256);
       b.x += t4.x; b.y += t4.y; b.z += t4.z; b.w += t4.w;
     }
@@ -1076,19 +1077,25 @@ static int launch_chain_tile(const ChainArgs& a, hipStream_t stream) {
   if (a.d > kTileMaxD || a.d % 4 != 0 || a.k % kTileRows != 0 || a.n % a.k != 0 ||
       (size_t)a.d * a.m * sizeof(float) >= kOob || (size_t)a.n * a.d * sizeof(float) >= kOob)
     return FASTH_EINVAL;
-  const int groups = (a.d + 255) / 256;  // per wave
   const dim3 grid((a.m + kTileCols - 1) / kTileCols);
-#define FASTH_LAUNCH_TILE(GG)                                                                      \
-  do {                                                                                             \
-    int rc_ = allow_lds(chain_tile_kernel<GG>, tile_lds_bytes(GG));                                \
-    if (rc_ != FASTH_OK) return rc_;                                                               \
-    prof::Scope ps_(FASTH_KERNEL_CHAIN, stream);                                                   \
-    hipLaunchKernelGGL(chain_tile_kernel<GG>, grid, dim3(256), tile_lds_bytes(GG), stream, a);     \
+#define FASTH_LAUNCH_TILE(WW, GG)                                                                           \
+  do {                                                                                                      \
+    int rc_ = allow_lds(chain_tile_kernel<WW, GG>, tile_lds_bytes(WW, GG));                                 \
+    if (rc_ != FASTH_OK) return rc_;                                                                        \
+    prof::Scope ps_(FASTH_KERNEL_CHAIN, stream);                                                            \
+    hipLaunchKernelGGL((chain_tile_kernel<WW, GG>), grid, dim3(64 * WW), tile_lds_bytes(WW, GG), stream, a); \
   } while (0)
-  if (groups <= 1) FASTH_LAUNCH_TILE(1);
-  else if (groups == 2) FASTH_LAUNCH_TILE(2);
-  else if (groups == 3) FASTH_LAUNCH_TILE(3);
-  else FASTH_LAUNCH_TILE(4);
+  if (a.d <= 1024) {
+    const int groups = (a.d + 255) / 256;  // per wave
+    if (groups <= 1) FASTH_LAUNCH_TILE(4, 1);
+    else if (groups == 2) FASTH_LAUNCH_TILE(4, 2);
+    else if (groups == 3) FASTH_LAUNCH_TILE(4, 3);
+    else FASTH_LAUNCH_TILE(4, 4);
+  } else {
+    const int groups = (a.d + 511) / 512;
+    if (groups <= 3) FASTH_LAUNCH_TILE(8, 3);
+    else FASTH_LAUNCH_TILE(8, 4);
+  }
 #undef FASTH_LAUNCH_TILE
   FASTH_HIP(hipGetLastError());
   return FASTH_OK;

@@ -77,11 +77,12 @@ def test_fasth_every_chain_kernel(d, n, m, k, transpose):
 
 
 # Wide mini-batches (more than 768 columns) take the matrix-core chain kernel: 16 columns per workgroup, rows in
-# steps of 16. Cases: every groups-per-wave variant (d <= 256, 512, 768, 1024), d and m with ragged tails, blocks
+# steps of 16. Cases: every groups-per-wave variant (d <= 256, 512, 768, 1024; 1536, 2048), d and m with ragged tails, blocks
 # of one and of several steps, n != d; few reflections keep the checker fast.
 WIDE = [
     (256, 64, 800, 32), (512, 32, 1030, 16), (768, 96, 770, 48), (1024, 64, 780, 32), (1000, 128, 1100, 64),
     (100, 32, 769, 16), (320, 256, 900, 128),
+    (2048, 32, 780, 16), (1500, 48, 770, 48), (1280, 64, 800, 64),  # 8 waves per workgroup
 ]
 
 
