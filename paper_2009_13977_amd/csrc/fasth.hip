@@ -1326,7 +1326,9 @@ static int launch_chain(const ChainArgs& a, hipStream_t stream) {
 //   Z = Cg Ca^T (k x k);  E = sym(striu(Z)) + diag(Z)   for A = H X
 //                         E = sym(stril(Z)) + diag(Z)   for A = H^T X
 //   dV_i = -(Ca g^T + Cg a^T) + E V_i
-// grid (ceil(d / 64), nb), 256 threads; every workgroup rebuilds the small matrix E.
+// grid (ceil(d / 64), nb), 256 threads. With few columns every workgroup rebuilds the small matrix Z on its
+// way over the mini-batch (2 k^2 m FLOP each, no extra launch); with many (k >= 64 and k m >= 32768)
+// dv_z_kernel forms the Z of every block once and the workgroups read it (PREZ).
 // ------------------------------------------------------------------------------------------
 
 struct DvArgs {
@@ -1336,6 +1338,7 @@ struct DvArgs {
   const float* saveG;   // [nb][m][d]
   const float* saveCg;  // [m][n]
   float* dV;            // [n][d]
+  float* Z;             // [nb][kp][kp]: Z = Cg Ca^T per block when it is formed by dv_z_kernel
   int d, n, m, k, kp;
   int transpose;        // of the forward product
   int accumulate;       // add to dV instead of overwriting it (a factor that enters a layer twice)
@@ -1346,7 +1349,49 @@ struct DvPair {
   DvArgs a[2];
 };
 
-template <int KT, int VEC>  // kp = 16 KT; VEC = 4 when d is a multiple of 4 (16-byte loads along x), else 1
+// Z_i = Cg_i Ca_i^T for every block: one workgroup per 16 x 16 tile of Z_i, grid (kt^2, nb, products). The four
+// waves split the mini-batch columns (wave w takes columns 16 c + 4 w .. + 3) and their partial tiles meet in
+// LDS. Operands come straight from the coefficient matrices [m][n]: lane (q, li) needs Cg(16 ti + li, col + q)
+// and Ca(16 tj + li, col + q), 16 consecutive floats per q.
+__global__ void __launch_bounds__(256) dv_z_kernel(DvPair pair) {
+  __shared__ __align__(16) float part[4][256];
+  const DvArgs p = pair.a[blockIdx.z];
+  const int k = p.k, kp = p.kp, m = p.m, n = p.n, kt = kp / 16;
+  if ((int)blockIdx.y * k >= n || (int)blockIdx.x >= kt * kt) return;  // whole workgroup, before the barrier
+  const int i = blockIdx.y, ti = blockIdx.x / kt, tj = blockIdx.x % kt;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, li = lane & 15, q = lane >> 4;
+  const BufferDesc cgdesc = make_buffer(p.saveCg, (size_t)m * n * sizeof(float));
+  const BufferDesc cadesc = make_buffer(p.saveCa, (size_t)m * n * sizeof(float));
+  const bool g_ok = 16 * ti + li < k, a_ok = 16 * tj + li < k;  // rows of the padding read as zero
+  const unsigned g_row = (unsigned)(i * k + 16 * ti + li) * 4u, a_row = (unsigned)(i * k + 16 * tj + li) * 4u;
+  constexpr int UN = 8;  // column groups in flight per wave
+  f32x4 acc[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
+  for (int c0 = 4 * wave; c0 < m; c0 += 16 * UN) {
+    float a[UN], b[UN];
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+      const int col = c0 + 16 * u + q;
+      const unsigned off = (unsigned)col * (unsigned)n * 4u;
+      a[u] = buffer_load<1>(cgdesc, (col < m && g_ok) ? off + g_row : kOob, 0).e[0];
+      b[u] = buffer_load<1>(cadesc, (col < m && a_ok) ? off + a_row : kOob, 0).e[0];
+    }
+#pragma unroll
+    for (int u = 0; u < UN; ++u) acc[u & 1] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[u], b[u], acc[u & 1], 0, 0, 0);
+  }
+  const f32x4 z = acc[0] + acc[1];
+  *reinterpret_cast<float4*>(&part[wave][4 * lane]) = make_float4(z[0], z[1], z[2], z[3]);
+  __syncthreads();
+  if (wave == 0) {
+    float* Zi = p.Z + (size_t)i * kp * kp;
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) {
+      const float v = (part[0][4 * lane + jj] + part[1][4 * lane + jj]) + (part[2][4 * lane + jj] + part[3][4 * lane + jj]);
+      Zi[(16 * ti + 4 * q + jj) * kp + 16 * tj + li] = v;
+    }
+  }
+}
+
+template <int KT, int VEC, bool PREZ>  // kp = 16 KT; VEC = 4 when d is a multiple of 4 (16-byte loads along x), else 1
 __global__ void __launch_bounds__(256) dv_kernel(DvPair pair) {
   extern __shared__ __align__(16) float smem[];
   constexpr int kp = 16 * KT;
@@ -1440,12 +1485,14 @@ __global__ void __launch_bounds__(256) dv_kernel(DvPair pair) {
     to_lds(cur);
     __syncthreads();
     if (mc + kDvMChunk < m) fetch(mc + kDvMChunk, cur);  // in flight during this chunk's products
+    if constexpr (!PREZ) {
 #pragma unroll
-    for (int w = 0; w < kMaxZ; ++w) {
-      const int t = wave + 4 * w;
-      if (t < kt * kt) {
-        const int ti = t / kt, tj = t % kt;
-        z[w] = tile_mma(Cgs + ti * 16 * LDC, LDC, 1, Cas + tj * 16 * LDC, 1, LDC, kDvMChunk, z[w]);
+      for (int w = 0; w < kMaxZ; ++w) {
+        const int t = wave + 4 * w;
+        if (t < kt * kt) {
+          const int ti = t / kt, tj = t % kt;
+          z[w] = tile_mma(Cgs + ti * 16 * LDC, LDC, 1, Cas + tj * 16 * LDC, 1, LDC, kDvMChunk, z[w]);
+        }
       }
     }
 #pragma unroll
@@ -1461,20 +1508,29 @@ __global__ void __launch_bounds__(256) dv_kernel(DvPair pair) {
   // E: mirror the triangle of Z that carries the gradient of T_i^-1. The matrix-core layout gives
   // lane (q, li) the entries Z(16 ti + 4 q + jj, 16 tj + li); each is written to its own place and,
   // if it lies in the carrying triangle, to the mirrored place as well.
+  if constexpr (PREZ) {
+    const float* Zi = p.Z + (size_t)i * kp * kp;
+    for (int idx = tid; idx < kp * kp; idx += 256) {
+      const int r = idx / kp, c = idx % kp;
+      const bool own = p.transpose ? (r >= c) : (r <= c);  // the entry itself carries, else its mirror image does
+      Es[r * LDE + c] = own ? Zi[r * kp + c] : Zi[c * kp + r];
+    }
+  } else {
 #pragma unroll
-  for (int w = 0; w < kMaxZ; ++w) {
-    const int t = wave + 4 * w;
-    if (t < kt * kt) {
-      const int ti = t / kt, tj = t % kt;
+    for (int w = 0; w < kMaxZ; ++w) {
+      const int t = wave + 4 * w;
+      if (t < kt * kt) {
+        const int ti = t / kt, tj = t % kt;
 #pragma unroll
-      for (int jj = 0; jj < 4; ++jj) {
-        const int r = ti * 16 + 4 * q + jj, c = tj * 16 + li;
-        const bool carries = p.transpose ? (r > c) : (r < c);
-        if (carries) {
-          Es[r * LDE + c] = z[w][jj];
-          Es[c * LDE + r] = z[w][jj];
-        } else if (r == c) {
-          Es[r * LDE + c] = z[w][jj];
+        for (int jj = 0; jj < 4; ++jj) {
+          const int r = ti * 16 + 4 * q + jj, c = tj * 16 + li;
+          const bool carries = p.transpose ? (r > c) : (r < c);
+          if (carries) {
+            Es[r * LDE + c] = z[w][jj];
+            Es[c * LDE + r] = z[w][jj];
+          } else if (r == c) {
+            Es[r * LDE + c] = z[w][jj];
+          }
         }
       }
     }
@@ -1752,6 +1808,7 @@ static DvArgs dv_args(const Product& P, const float* V, float* dV, int transpose
   DvArgs a;
   a.accumulate = accumulate ? 1 : 0;
   a.V = V; a.saveA = P.saveA(); a.saveCa = P.saveCa(); a.saveG = P.saveG(); a.saveCg = P.saveCg(); a.dV = dV;
+  a.Z = P.Spart();  // the partial Gram matrices are dead once the factors exist; Z needs nb kp^2 of their floats
   a.d = P.d; a.n = P.n; a.m = P.m; a.k = P.k; a.kp = P.L.kp; a.transpose = transpose;
   return a;
 }
@@ -1764,18 +1821,30 @@ static int launch_dv(const DvPair& pair, int count, int kp, bool vec4, hipStream
     nb = std::max(nb, pair.a[1].n / pair.a[1].k);
   }
   const dim3 grid(xt, nb, count);
+  // Many columns and blocks of 64 rows or more: Z of every block once, by a launch of its own (measured at
+  // d = n = 1024, m = 4096: dV 374 -> 326 us at k = 64, 853 -> 545 us at k = 128, but 294 -> 309 us at k = 32, where
+  // the rebuild is a fifth of the work). Same condition for both products of a pair: they share m and k.
+  const DvArgs& a0 = pair.a[0];
+  const bool prez = a0.k >= 64 && (size_t)a0.m * a0.k >= 32768 && (size_t)a0.m * a0.n * sizeof(float) < kOob && a0.Z != nullptr &&
+                    (count == 1 || (pair.a[1].m == a0.m && pair.a[1].k == a0.k && pair.a[1].Z != nullptr));
   prof::Scope ps_(FASTH_KERNEL_DV, stream);
+  if (prez) {
+    const int kt = kp / 16;
+    hipLaunchKernelGGL(dv_z_kernel, dim3(kt * kt, nb, count), dim3(256), 0, stream, pair);
+    FASTH_HIP(hipGetLastError());
+  }
+#define FASTH_LAUNCH_DV_(KT, VV, PZ)                                                      \
+  do {                                                                                    \
+    int rc_ = allow_lds(dv_kernel<KT, VV, PZ>, lds);                                      \
+    if (rc_ != FASTH_OK) return rc_;                                                      \
+    hipLaunchKernelGGL((dv_kernel<KT, VV, PZ>), grid, dim3(256), lds, stream, pair);      \
+  } while (0)
 #define FASTH_LAUNCH_DV(KT)                                                               \
   do {                                                                                    \
-    if (vec4) {                                                                           \
-      int rc_ = allow_lds(dv_kernel<KT, 4>, lds);                                         \
-      if (rc_ != FASTH_OK) return rc_;                                                    \
-      hipLaunchKernelGGL((dv_kernel<KT, 4>), grid, dim3(256), lds, stream, pair);         \
-    } else {                                                                              \
-      int rc_ = allow_lds(dv_kernel<KT, 1>, lds);                                         \
-      if (rc_ != FASTH_OK) return rc_;                                                    \
-      hipLaunchKernelGGL((dv_kernel<KT, 1>), grid, dim3(256), lds, stream, pair);         \
-    }                                                                                     \
+    if (vec4 && prez) FASTH_LAUNCH_DV_(KT, 4, true);                                      \
+    else if (vec4) FASTH_LAUNCH_DV_(KT, 4, false);                                        \
+    else if (prez) FASTH_LAUNCH_DV_(KT, 1, true);                                         \
+    else FASTH_LAUNCH_DV_(KT, 1, false);                                                  \
   } while (0)
   switch (kp) {
     case 16: FASTH_LAUNCH_DV(1); break;
@@ -1784,6 +1853,7 @@ static int launch_dv(const DvPair& pair, int count, int kp, bool vec4, hipStream
     default: FASTH_LAUNCH_DV(8); break;
   }
 #undef FASTH_LAUNCH_DV
+#undef FASTH_LAUNCH_DV_
   FASTH_HIP(hipGetLastError());
   return FASTH_OK;
 }

@@ -116,7 +116,7 @@ def test_layers_wide_minibatch():
     """The layers on the matrix-core chain kernel: the diagonal factor fused into its input fetch (every mode),
     a rectangular Sigma (rows of the chain's input that do not exist), and the gradient of sigma from a launch of
     its own."""
-    d, n, m, k = 256, 64, 800, 32
+    d, n, m, k = 256, 128, 800, 64  # k >= 64, k m >= 32768: the dV kernel reads Z formed by a launch of its own
     p = synthetic.svd_layer_problem(d, n, m, seed=5100)
     for inverse in (False, True):
         _say(f"svd layer wide inverse={inverse}")
@@ -136,7 +136,7 @@ def test_layers_wide_minibatch():
     for rows, cols in ((256, 192), (192, 256)):
         _say(f"svd rect wide rows={rows} cols={cols}")
         q = synthetic.rect_layer_problem(rows, cols, 32, 32, 800, seed=5300 + rows)
-        got = gpu_svd_rect(q["Uv"], q["sigma"], q["Vv"], q["X"], q["G"], 16)
+        got = gpu_svd_rect(q["Uv"], q["sigma"], q["Vv"], q["X"], q["G"], 16)  # k m < 32768: Z rebuilt per workgroup
         ref = orc.rectangular_gradients(q["Uv"], q["sigma"], q["Vv"], q["X"], q["G"])
         for name, g, r in zip(("Y", "dUv", "dsigma", "dVv", "dX"), got, ref):
             assert g.shape == r.shape, name
