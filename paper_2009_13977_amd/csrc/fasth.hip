@@ -1475,11 +1475,21 @@ __global__ void __launch_bounds__(256) dv_kernel(DvPair pair) {
   // One pass over the mini-batch accumulates both Z = Cg Ca^T and Ca g^T + Cg a^T.
   constexpr int kMaxZ = (KT * KT + 3) / 4;  // Z tiles per wave
   constexpr int kMaxAcc = KT;               // KT x 4 output tiles over 4 waves
-  f32x4 z[kMaxZ], acc[kMaxAcc];
+  // The contraction over a chunk's 32 columns may run in any order: lane (q, li) takes columns 8 q .. 8 q + 7, so
+  // an operand that is contiguous along the columns (the coefficient tiles) comes as two 16-byte LDS reads per
+  // 8 matrix instructions. A wave's output tiles all lie in x tile `wave` (t = wave + 4 w), so its g^T / a^T
+  // operands are fetched once per chunk and serve all KT row tiles. The two terms of a tile accumulate
+  // separately (two independent chains of matrix instructions) and are added at the end.
+  static_assert(kDvMChunk == 32, "column order of the contraction");
+  auto row8 = [&](const float* base, float (&v)[8]) {
+    const float4 lo = *reinterpret_cast<const float4*>(base), hi = *reinterpret_cast<const float4*>(base + 4);
+    v[0] = lo.x; v[1] = lo.y; v[2] = lo.z; v[3] = lo.w; v[4] = hi.x; v[5] = hi.y; v[6] = hi.z; v[7] = hi.w;
+  };
+  f32x4 z[kMaxZ], acc[kMaxAcc], acc2[kMaxAcc];
 #pragma unroll
   for (int w = 0; w < kMaxZ; ++w) z[w] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-  for (int w = 0; w < kMaxAcc; ++w) acc[w] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int w = 0; w < kMaxAcc; ++w) acc[w] = acc2[w] = f32x4{0.f, 0.f, 0.f, 0.f};
   for (int mc = 0; mc < m; mc += kDvMChunk) {
     if (mc) __syncthreads();
     to_lds(cur);
@@ -1491,20 +1501,34 @@ __global__ void __launch_bounds__(256) dv_kernel(DvPair pair) {
         const int t = wave + 4 * w;
         if (t < kt * kt) {
           const int ti = t / kt, tj = t % kt;
-          z[w] = tile_mma(Cgs + ti * 16 * LDC, LDC, 1, Cas + tj * 16 * LDC, 1, LDC, kDvMChunk, z[w]);
+          float cg[8], ca[8];
+          row8(Cgs + (ti * 16 + li) * LDC + 8 * q, cg);
+          row8(Cas + (tj * 16 + li) * LDC + 8 * q, ca);
+#pragma unroll
+          for (int kk = 0; kk < 8; ++kk) z[w] = __builtin_amdgcn_mfma_f32_16x16x4f32(cg[kk], ca[kk], z[w], 0, 0, 0);
         }
       }
     }
+    float bg[8], ba[8];
 #pragma unroll
-    for (int w = 0; w < kMaxAcc; ++w) {
-      const int t = wave + 4 * w;
-      if (t < kt * 4) {
-        const int ti = t / 4, tx = t % 4;
-        acc[w] = tile_mma(Cas + ti * 16 * LDC, LDC, 1, gT + tx * 16, LDX, 1, kDvMChunk, acc[w]);
-        acc[w] = tile_mma(Cgs + ti * 16 * LDC, LDC, 1, aT + tx * 16, LDX, 1, kDvMChunk, acc[w]);
+    for (int kk = 0; kk < 8; ++kk) {
+      bg[kk] = gT[(8 * q + kk) * LDX + wave * 16 + li];
+      ba[kk] = aT[(8 * q + kk) * LDX + wave * 16 + li];
+    }
+#pragma unroll
+    for (int w = 0; w < kMaxAcc; ++w) {  // row tile ti = w, x tile = wave
+      float ca[8], cg[8];
+      row8(Cas + (w * 16 + li) * LDC + 8 * q, ca);
+      row8(Cgs + (w * 16 + li) * LDC + 8 * q, cg);
+#pragma unroll
+      for (int kk = 0; kk < 8; ++kk) {
+        acc[w] = __builtin_amdgcn_mfma_f32_16x16x4f32(ca[kk], bg[kk], acc[w], 0, 0, 0);
+        acc2[w] = __builtin_amdgcn_mfma_f32_16x16x4f32(cg[kk], ba[kk], acc2[w], 0, 0, 0);
       }
     }
   }
+#pragma unroll
+  for (int w = 0; w < kMaxAcc; ++w) acc[w] += acc2[w];
   // E: mirror the triangle of Z that carries the gradient of T_i^-1. The matrix-core layout gives
   // lane (q, li) the entries Z(16 ti + 4 q + jj, 16 tj + li); each is written to its own place and,
   // if it lies in the carrying triangle, to the mirrored place as well.
