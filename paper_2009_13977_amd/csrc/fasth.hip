@@ -648,11 +648,15 @@ struct PipeRegs {
 // so nothing downstream sees the difference; p.nb counts the steps. SUB is the number of steps per block
 // (0: taken from p.sub at run time). PAD: k is not a multiple of K, so a block's last step has fewer than K
 // rows; the missing rows repeat the last one and their inner products and coefficients are forced to zero.
-template <int K, int VW, int NT, int RL = 0, int SUB = 1, bool PAD = false>  // RL: rows of the next block fetched during the reduction
+// RL: rows of the next block fetched during the reduction; P1: during the first product (0: half of the rest).
+template <int K, int VW, int NT, int RL = 0, int SUB = 1, bool PAD = false, int P1 = 0>
 __global__ void __launch_bounds__(NT) chain_pipe_kernel(ChainArgs p) {
   typedef PipeRegs<K, VW, NT> Regs;
   constexpr int NW = NT / 64, G = Regs::G, LPT = Regs::LPT;
-  constexpr int PR = (K - RL) / 2;  // rows of the next block fetched during each of the two products
+  constexpr int PR = P1 > 0 ? P1 : (K - RL) / 2;  // rows of the next block fetched during the first product
+  constexpr int PR2 = K - RL - PR;                  // ... and during the second
+  constexpr int S1 = K / PR, S2 = K / PR2;          // one fetch every S1 (S2) rows of the product
+  static_assert(PR >= 1 && PR2 >= 1 && S1 >= 1 && S2 >= 1, "prefetch split");
   static_assert(K % 4 == 0 && K * G <= NT && LPT >= 1, "shape");
   static_assert(RL % 2 == 0 && RL <= K / 4 && (RL == 0 || K >= 8), "prefetch split");
   static_assert(!PAD || SUB == 0, "ragged steps take the step count at run time");
@@ -718,8 +722,8 @@ __global__ void __launch_bounds__(NT) chain_pipe_kernel(ChainArgs p) {
     float pj[K];
 #pragma unroll
     for (int j = 0; j < K; ++j) {
-      if (j % 2 == 0 && j / 2 < PR) {
-        nxt.v[j / 2] = load_chunk<VW>(row_ptr(inext, j / 2));
+      if (j % S1 == 0 && j / S1 < PR) {
+        nxt.v[j / S1] = load_chunk<VW>(row_ptr(inext, j / S1));
         __builtin_amdgcn_sched_barrier(0);
       }
       float acc = 0.f;
@@ -773,8 +777,8 @@ __global__ void __launch_bounds__(NT) chain_pipe_kernel(ChainArgs p) {
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int j = 0; j < K; ++j) {
-      if (j % 2 == 0 && j / 2 < PR) {
-        nxt.v[PR + RL + j / 2] = load_chunk<VW>(row_ptr(inext, PR + RL + j / 2));
+      if (j % S2 == 0 && j / S2 < PR2) {
+        nxt.v[PR + RL + j / S2] = load_chunk<VW>(row_ptr(inext, PR + RL + j / S2));
         __builtin_amdgcn_sched_barrier(0);
       }
 #pragma unroll
@@ -802,7 +806,7 @@ __global__ void __launch_bounds__(NT) chain_pipe_kernel(ChainArgs p) {
   }
 }
 
-template <int K, int VW, int NT, int RL = 0, int SUB = 1, bool PAD = false>
+template <int K, int VW, int NT, int RL = 0, int SUB = 1, bool PAD = false, int P1 = 0>
 static int launch_chain_pipe(const ChainArgs& args, hipStream_t stream) {
   ChainArgs a = args;
   a.sub = SUB > 0 ? SUB : (args.k + K - 1) / K;
@@ -810,7 +814,7 @@ static int launch_chain_pipe(const ChainArgs& args, hipStream_t stream) {
   if ((size_t)VW * NT < (size_t)a.d || (PAD ? a.sub * K > a.kp : a.sub * K != a.k)) return FASTH_EINVAL;
   const int side = a.ds_out ? (a.ds_rows + NT / 64 - 1) / (NT / 64) : 0;
   prof::Scope ps_(FASTH_KERNEL_CHAIN, stream);
-  hipLaunchKernelGGL((chain_pipe_kernel<K, VW, NT, RL, SUB, PAD>), dim3(a.m + side), dim3(NT), 0, stream, a);
+  hipLaunchKernelGGL((chain_pipe_kernel<K, VW, NT, RL, SUB, PAD, P1>), dim3(a.m + side), dim3(NT), 0, stream, a);
   FASTH_HIP(hipGetLastError());
   return FASTH_OK;
 }
@@ -1254,7 +1258,10 @@ static int launch_chain_kernel(const ChainArgs& a, hipStream_t stream) {
     if (k == 16 && d <= 2048) return launch_chain_pipe<16, 4, 512, 4>(a, stream);
     if (k == 32 && d <= 256) return launch_chain_pipe<32, 1, 256, 8>(a, stream);
     if (k == 32 && d <= 512) return launch_chain_pipe<32, 2, 256, 8>(a, stream);
-    if (k == 32 && d <= 1024) return launch_chain_pipe<32, 4, 256, 8>(a, stream);
+    // (10 of the 32 rows of the next block fetched during the first product, 8 during the reduction, 14 during
+    // the update: with 12 / 8 / 12 more of the second register copy spills to the accumulator file; 117.2 -> 115.8 us
+    // per forward + backward at d = n = 1024, m = 32)
+    if (k == 32 && d <= 1024) return launch_chain_pipe<32, 4, 256, 8, 1, false, 10>(a, stream);
     if (k == 64 && d <= 256) return launch_chain_pipe<64, 1, 256, 16>(a, stream);
     if (k == 64 && d <= 512) return launch_chain_pipe<64, 2, 256, 16>(a, stream);
     // Larger blocks and longer vectors: two register copies of the whole block do not fit, but the block can be
@@ -1262,17 +1269,17 @@ static int launch_chain_kernel(const ChainArgs& a, hipStream_t stream) {
     // one copy refilled in place or rows streamed twice (d = n = 2048: 178 us for k = 32, 64 and 128 alike,
     // against 222, 359 and 406 us)
     if (d <= 1024) {
-      if (k == 64) return launch_chain_pipe<32, 4, 256, 8, 2>(a, stream);
-      if (k == 128) return launch_chain_pipe<32, 4, 256, 8, 4>(a, stream);
+      if (k == 64) return launch_chain_pipe<32, 4, 256, 8, 2, false, 10>(a, stream);
+      if (k == 128) return launch_chain_pipe<32, 4, 256, 8, 4, false, 10>(a, stream);
       if (k == 8) return launch_chain_pipe<8, 4, 256, 2>(a, stream);
       // any other block size: steps of 8, 16 or 32 rows, the last one of a block short
       if (k < 8) return launch_chain_pipe<8, 4, 256, 2, 0, true>(a, stream);
       if (k < 16) return launch_chain_pipe<16, 4, 256, 4, 0, true>(a, stream);
       return launch_chain_pipe<32, 4, 256, 8, 0, true>(a, stream);
     } else if (d <= 2048) {
-      if (k == 32) return launch_chain_pipe<16, 4, 512, 4, 2>(a, stream);
-      if (k == 64) return launch_chain_pipe<16, 4, 512, 4, 4>(a, stream);
-      if (k == 128) return launch_chain_pipe<16, 4, 512, 4, 8>(a, stream);
+      if (k == 32) return launch_chain_pipe<16, 4, 512, 4, 2, false, 5>(a, stream);  // fetch split 5 / 4 / 7
+      if (k == 64) return launch_chain_pipe<16, 4, 512, 4, 4, false, 5>(a, stream);
+      if (k == 128) return launch_chain_pipe<16, 4, 512, 4, 8, false, 5>(a, stream);
       if (k == 8) return launch_chain_pipe<8, 4, 512, 2>(a, stream);
       if (k < 8) return launch_chain_pipe<8, 4, 512, 2, 0, true>(a, stream);
       return launch_chain_pipe<16, 4, 512, 4, 0, true>(a, stream);
