@@ -660,7 +660,7 @@ __global__ void __launch_bounds__(NT) chain_pipe_kernel(ChainArgs p) {
   static_assert(K % 4 == 0 && K * G <= NT && LPT >= 1, "shape");
   static_assert(RL % 2 == 0 && RL <= K / 4 && (RL == 0 || K >= 8), "prefetch split");
   static_assert(!PAD || SUB == 0, "ragged steps take the step count at run time");
-  __shared__ float Bpart[NW][K];
+  __shared__ __align__(16) float Bpart[NW][K];
   __shared__ __align__(16) float Cv[K];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -709,7 +709,7 @@ __global__ void __launch_bounds__(NT) chain_pipe_kernel(ChainArgs p) {
     const int row = t_active ? trow : 0;
 #pragma unroll
     for (int e = 0; e < LPT; ++e) {
-      const int l = tg + G * e;
+      const int l = tg * LPT + e;  // a thread's columns are consecutive: its partial sums come as 16-byte LDS reads
       r.t[e] = p.transpose ? Ti[l * LDT + row] : Ti[row * LDT + l];
     }
   };
@@ -748,13 +748,29 @@ __global__ void __launch_bounds__(NT) chain_pipe_kernel(ChainArgs p) {
     lds_barrier();
     if (t_active) {
       float c = 0.f;
+      if constexpr (LPT % 4 == 0) {
 #pragma unroll
-      for (int e = 0; e < LPT; ++e) {
-        const int l = tg + G * e;
-        float b = 0.f;
+        for (int e4 = 0; e4 < LPT / 4; ++e4) {
+          float4 b = *reinterpret_cast<const float4*>(&Bpart[0][tg * LPT + 4 * e4]);
 #pragma unroll
-        for (int w = 0; w < NW; ++w) b += Bpart[w][l];
-        c = fmaf(cur.t[e], b, c);
+          for (int w = 1; w < NW; ++w) {
+            const float4 t4 = *reinterpret_cast<const float4*>(&Bpart[w][tg * LPT + 4 * e4]);
+            b.x += t4.x; b.y += t4.y; b.z += t4.z; b.w += t4.w;
+          }
+          c = fmaf(cur.t[4 * e4], b.x, c);
+          c = fmaf(cur.t[4 * e4 + 1], b.y, c);
+          c = fmaf(cur.t[4 * e4 + 2], b.z, c);
+          c = fmaf(cur.t[4 * e4 + 3], b.w, c);
+        }
+      } else {
+#pragma unroll
+        for (int e = 0; e < LPT; ++e) {
+          const int l = tg * LPT + e;
+          float b = Bpart[0][l];
+#pragma unroll
+          for (int w = 1; w < NW; ++w) b += Bpart[w][l];
+          c = fmaf(cur.t[e], b, c);
+        }
       }
       c = group_sum<G>(c);
       if (PAD && trow >= kv) c = 0.f;
