@@ -116,7 +116,7 @@ def main() -> int:
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (the path shards over mini-batch columns; "
-              "see DESIGN.md). Re-run with --gpus 1.", file=sys.stderr)
+              "each GPU would take a share of them and the only exchange would be one sum of dV). Re-run with --gpus 1.", file=sys.stderr)
         return 2
 
     import numpy as np
