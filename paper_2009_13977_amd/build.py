@@ -15,7 +15,9 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG_DIR)
 LIB_PATH = os.path.join(PKG_DIR, "libfasth.so")
 SOURCES = [os.path.join(PKG_DIR, "csrc", "fasth.hip")]
-HEADERS = [os.path.join(PKG_DIR, "csrc", "fasth_device.h"), os.path.join(ROOT, "include", "fasth.h")]
+HEADERS = [os.path.join(PKG_DIR, "csrc", h) for h in ("fasth_device.h", "fasth_common.h", "fasth_factor.h",
+                                                      "fasth_chain.h", "fasth_dv.h", "fasth_sequential.h")]
+HEADERS.append(os.path.join(ROOT, "include", "fasth.h"))
 
 
 def hipcc_path() -> str:

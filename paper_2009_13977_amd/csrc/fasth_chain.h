@@ -1,0 +1,944 @@
+// Algorithm 1 Step 2 and Algorithm 2 Step 1: the sequential block chain (chain_pipe_kernel, chain_tile_kernel,
+// chain_stream_kernel, chain_kernel) and its launcher.
+// Included by fasth.hip, the library's single translation unit.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include "fasth_common.h"
+
+namespace fasth {
+
+// ------------------------------------------------------------------------------------------
+// The sequential block chain (Algorithm 1 Step 2; Algorithm 2 Step 1, Eq. 3).
+// One workgroup per column of the d x m input: columns never interact, so no workgroup waits for
+// another. Per block i:  B = V_i a,  C = op(T_i) B,  a <- a - V_i^T C,
+// op(T) = T for P_i (blocks nb..1), T^T for P_i^T (blocks 1..nb).
+// Thread t owns elements x = t + u * blockDim.x of the column. The k inner products of a block are
+// independent, which is the parallelism FastH adds over the one-at-a-time algorithm.
+// Saved for the backward pass: the input column of every block and the coefficient vector C.
+// ------------------------------------------------------------------------------------------
+
+// Diagonal factor applied to row x of a chain's input (Section 2.2 and Table 1):
+// 1: sigma, 2: 1/sigma (inverse), 3: e^sigma (matrix exponential), 4: (1 - sigma)/(1 + sigma) (Cayley map).
+__device__ __forceinline__ float diag_factor(int mode, float sigma) {
+  switch (mode) {
+    case 1: return sigma;
+    case 2: return 1.f / sigma;
+    case 3: return expf(sigma);
+    case 4: return (1.f - sigma) / (1.f + sigma);
+    default: return 1.f;
+  }
+}
+
+struct ChainArgs {
+  const float* V;         // [n][d]
+  const float* T;         // [nb][kp][kp]
+  const float* in;        // [d][m]
+  float* out;             // [d][m]
+  float* save_in;         // [nb][m][d] or null
+  float* save_c;          // [m][n] or null
+  const float* in_scale;  // [d] or null: input row x is multiplied by diag_factor(in_scale_mode, in_scale[x])
+  int in_scale_mode;
+  int in_rows;            // rows of `in` that exist; rows in_rows..d-1 of the chain's input are zero
+  int d, n, m, k, kp, nb;
+  int transpose;
+  int sub;                // chain_pipe_kernel: steps per block (set by its launcher)
+  // Optional side product of the SVD layers' backward pass, which has the chain's input as one operand:
+  // ds_out[r] = s'(in_scale[r]) sum_l in[r][l] ds_z1[r][l] for r < ds_rows (s = diag_factor(in_scale_mode, .)).
+  // Null ds_out: not wanted. Kernels that cannot take it along leave it to a launch of dsigma_kernel.
+  const float* ds_z1;     // [ds_rows][m]
+  float* ds_out;          // [ds_rows]
+  int ds_rows;
+};
+
+// Gradient of the diagonal step of the SVD layer (Section 2.2), one wave per row: with Z2 = s * Z1 row-wise
+// (s = sigma, 1/sigma or a function of sigma),
+//   ds_r = sum_l dZ2[r][l] Z1[r][l];  dsigma_r = ds_r * s'(sigma_r)  (e.g. -ds_r / sigma_r^2 for s = 1/sigma).
+__device__ __forceinline__ void dsigma_row(const float* __restrict__ dZ2, const float* __restrict__ Z1,
+                                           const float* __restrict__ sigma, float* __restrict__ dsigma, int row,
+                                           int m, int mode) {
+  const int lane = threadIdx.x & 63;
+  float r[1] = {0.f};
+  for (int l = lane; l < m; l += 64) r[0] += dZ2[(size_t)row * m + l] * Z1[(size_t)row * m + l];
+  wave_reduce_multi<1>(r);
+  if (lane == 0) {
+    // chain rule from the diagonal factor s(sigma) to sigma: mode = diag_factor mode
+    float v = r[0];
+    const float sg = sigma[row];
+    if (mode == 2) v = -v / (sg * sg);
+    else if (mode == 3) v *= expf(sg);
+    else if (mode == 4) v *= -2.f / ((1.f + sg) * (1.f + sg));
+    dsigma[row] = v;
+  }
+}
+
+__global__ void __launch_bounds__(256) dsigma_kernel(const float* __restrict__ dZ2, const float* __restrict__ Z1,
+                                                     const float* __restrict__ sigma, float* __restrict__ dsigma,
+                                                     int d, int m, int mode) {
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row < d) dsigma_row(dZ2, Z1, sigma, dsigma, row, m, mode);
+}
+
+template <int U>
+__global__ void __launch_bounds__(1024) chain_kernel(ChainArgs p) {
+  extern __shared__ float smem[];
+  const int nthreads = blockDim.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nw = nthreads >> 6;
+  const int col = blockIdx.x;
+  const int d = p.d, k = p.k, kp = p.kp, m = p.m;
+  const int LDT = kp + 1;
+  float* Ts = smem;               // [kp][LDT]
+  float* Bpart = Ts + kp * LDT;   // [nw][kp]
+  float* Bv = Bpart + nw * kp;    // [kp]
+  float* Cv = Bv + kp;            // [kp]
+  float a[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const int x = tid + u * nthreads;
+    float v = 0.f;
+    if (x < d && x < p.in_rows) {
+      v = p.in[(size_t)x * m + col];
+      if (p.in_scale_mode) v *= diag_factor(p.in_scale_mode, p.in_scale[x]);
+    }
+    a[u] = v;
+  }
+  const int sel = reduce_sel<8>(lane);
+  for (int s = 0; s < p.nb; ++s) {
+    const int i = p.transpose ? s : p.nb - 1 - s;
+    const float* Vi = p.V + (size_t)i * k * d;
+    const float* Ti = p.T + (size_t)i * kp * kp;
+    for (int idx = tid; idx < kp * kp; idx += nthreads) Ts[(idx / kp) * LDT + idx % kp] = Ti[idx];
+    if (p.save_in) {
+      float* dst = p.save_in + ((size_t)i * m + col) * d;
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int x = tid + u * nthreads;
+        if (x < d) dst[x] = a[u];
+      }
+    }
+    for (int j0 = 0; j0 < k; j0 += 8) {
+      float pj[8];
+#pragma unroll
+      for (int jj = 0; jj < 8; ++jj) {
+        pj[jj] = 0.f;
+        if (j0 + jj < k) {
+          const float* vr = Vi + (size_t)(j0 + jj) * d;
+#pragma unroll
+          for (int u = 0; u < U; ++u) {
+            const int x = tid + u * nthreads;
+            if (x < d) pj[jj] += vr[x] * a[u];
+          }
+        }
+      }
+      wave_reduce_multi<8>(pj);
+      if ((lane & reduce_writer_mask<8>()) == 0) Bpart[wave * kp + j0 + sel] = pj[0];
+    }
+    __syncthreads();
+    if (tid < kp) {
+      float b = 0.f;
+      if (tid < k)
+        for (int w = 0; w < nw; ++w) b += Bpart[w * kp + tid];
+      Bv[tid] = b;
+    }
+    __syncthreads();
+    if (tid < kp) {
+      float c = 0.f;
+      if (p.transpose) {
+        for (int l = 0; l < kp; ++l) c += Ts[l * LDT + tid] * Bv[l];
+      } else {
+        for (int l = 0; l < kp; ++l) c += Ts[tid * LDT + l] * Bv[l];
+      }
+      Cv[tid] = c;
+      if (p.save_c && tid < k) p.save_c[(size_t)col * p.n + i * k + tid] = c;
+    }
+    __syncthreads();
+    for (int j = 0; j < k; ++j) {
+      const float c = Cv[j];
+      const float* vr = Vi + (size_t)j * d;
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int x = tid + u * nthreads;
+        if (x < d) a[u] -= c * vr[x];
+      }
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const int x = tid + u * nthreads;
+    if (x < d) p.out[(size_t)x * m + col] = a[u];
+  }
+}
+
+// ---- Register-resident chain kernels -------------------------------------------------------
+// Thread t owns one VW-wide chunk of the column (x = VW t .. VW t + VW - 1), so a wave load of one
+// row of V covers 64 VW contiguous floats and the whole k x d block V_i is K * VW registers per
+// thread. V_i is read from memory once per block and used for both products.
+//
+// Two register copies: the rows of block i+1 are loaded a couple at a time between the multiply-adds
+// of block i (during B = V_i a, during the reduction and during a -= V_i^T C), which feeds the CU's
+// address unit (64 B per clock) evenly instead of in one burst that stalls the wave behind it.
+// Blocks too large for two copies are applied as steps of fewer rows (SUB below).
+// The barriers order LDS traffic only, so global loads stay in flight across them.
+template <int VW> struct VecOf;
+template <> struct VecOf<1> { typedef float type; };
+template <> struct VecOf<2> { typedef float2 type; };
+template <> struct VecOf<4> { typedef float4 type; };
+
+template <int VW>
+struct Chunk {
+  float e[VW];
+};
+
+template <int VW>
+__device__ __forceinline__ Chunk<VW> load_chunk(const float* ptr) {
+  Chunk<VW> c;
+  const typename VecOf<VW>::type v = *reinterpret_cast<const typename VecOf<VW>::type*>(ptr);
+  if constexpr (VW == 1) { c.e[0] = v; }
+  else if constexpr (VW == 2) { c.e[0] = v.x; c.e[1] = v.y; }
+  else { c.e[0] = v.x; c.e[1] = v.y; c.e[2] = v.z; c.e[3] = v.w; }
+  return c;
+}
+
+template <int VW>
+__device__ __forceinline__ void store_chunk(float* ptr, const Chunk<VW>& c) {
+  typename VecOf<VW>::type v;
+  if constexpr (VW == 1) { v = c.e[0]; }
+  else if constexpr (VW == 2) { v.x = c.e[0]; v.y = c.e[1]; }
+  else { v.x = c.e[0]; v.y = c.e[1]; v.z = c.e[2]; v.w = c.e[3]; }
+  *reinterpret_cast<typename VecOf<VW>::type*>(ptr) = v;
+}
+
+// Loads this thread's part of column `col` of a [d][m] matrix, with the optional row scaling.
+template <int VW>
+__device__ __forceinline__ Chunk<VW> load_column_chunk(const ChainArgs& p, int col, unsigned x0, bool ok) {
+  Chunk<VW> a;
+#pragma unroll
+  for (int r = 0; r < VW; ++r) {
+    float v = 0.f;
+    if (ok && x0 + r < (unsigned)p.in_rows) {
+      v = p.in[(size_t)(x0 + r) * p.m + col];
+      if (p.in_scale_mode) v *= diag_factor(p.in_scale_mode, p.in_scale[x0 + r]);
+    }
+    a.e[r] = v;
+  }
+  return a;
+}
+
+template <int K, int VW, int NT>
+struct PipeRegs {
+  static constexpr int G0 = (NT / K) < 16 ? (NT / K) : 16;
+  static constexpr int G = G0 < K ? G0 : K;  // threads sharing one row of T
+  static constexpr int LPT = K / G;
+  Chunk<VW> v[K];
+  float t[LPT];
+};
+
+// A block of more than K rows is applied as several steps of K rows. The diagonal K x K blocks of its factor T_i
+// are the factors of the row groups (T_i is triangular and the groups are consecutive reflections), the
+// coefficients of the steps put together are T_i V_i a, and the block's input is saved at its first step,
+// so nothing downstream sees the difference; p.nb counts the steps. SUB is the number of steps per block
+// (0: taken from p.sub at run time). PAD: k is not a multiple of K, so a block's last step has fewer than K
+// rows; the missing rows repeat the last one and their inner products and coefficients are forced to zero.
+// RL: rows of the next block fetched during the reduction; P1: during the first product (0: half of the rest).
+template <int K, int VW, int NT, int RL = 0, int SUB = 1, bool PAD = false, int P1 = 0>
+__global__ void __launch_bounds__(NT) chain_pipe_kernel(ChainArgs p) {
+  typedef PipeRegs<K, VW, NT> Regs;
+  constexpr int NW = NT / 64, G = Regs::G, LPT = Regs::LPT;
+  constexpr int PR = P1 > 0 ? P1 : (K - RL) / 2;  // rows of the next block fetched during the first product
+  constexpr int PR2 = K - RL - PR;                  // ... and during the second
+  constexpr int S1 = K / PR, S2 = K / PR2;          // one fetch every S1 (S2) rows of the product
+  static_assert(PR >= 1 && PR2 >= 1 && S1 >= 1 && S2 >= 1, "prefetch split");
+  static_assert(K % 4 == 0 && K * G <= NT && LPT >= 1, "shape");
+  static_assert(RL % 2 == 0 && RL <= K / 4 && (RL == 0 || K >= 8), "prefetch split");
+  static_assert(!PAD || SUB == 0, "ragged steps take the step count at run time");
+  __shared__ __align__(16) float Bpart[NW][K];
+  __shared__ __align__(16) float Cv[K];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int col = blockIdx.x, m = p.m, d = p.d;
+  if (col >= m) {  // workgroups beyond the columns: the side product, on compute units the chain leaves idle
+    const int row = (col - m) * NW + wave;
+    if (row < p.ds_rows) dsigma_row(p.in, p.ds_z1, p.in_scale, p.ds_out, row, m, p.in_scale_mode);
+    return;
+  }
+  const int trow = tid / G, tg = tid % G;
+  const bool t_active = tid < K * G;
+  const int nb = p.nb;
+  // A wave whose chunks all lie beyond d and that has no row of T to multiply only keeps the barrier count:
+  // it issues no loads, which would cost the compute unit's address unit as much as useful ones.
+  if (wave * 64 * VW >= d && wave * 64 >= K * G) {
+    if (lane < K) Bpart[wave][lane] = 0.f;
+    for (int s = 0; s < nb; ++s) {
+      lds_barrier();
+      lds_barrier();
+    }
+    return;
+  }
+  // Threads whose chunk lies beyond d read chunk 0 (always valid memory) and keep their part of
+  // the column at zero, so they contribute nothing and need no branch per load.
+  const bool ok = VW * tid < d;
+  const unsigned x0 = ok ? VW * tid : 0;
+  Chunk<VW> a = load_column_chunk<VW>(p, col, x0, ok);
+  const int sel = reduce_sel<K>(lane);
+  auto block_of = [&](int s) { return p.transpose ? s : nb - 1 - s; };
+  const int sub = SUB > 0 ? SUB : p.sub;
+  auto step_block = [&](int i) { return SUB == 1 ? i : i / sub; };
+  auto step_part = [&](int i) { return SUB == 1 ? 0 : i % sub; };
+  auto rows_valid = [&](int i) { return PAD ? min(K, p.k - step_part(i) * K) : K; };
+  // uniform row base (scalar registers) + 32-bit per-lane offset
+  auto row_ptr = [&](int i, int j) {
+    if constexpr (PAD) {
+      const int row = step_block(i) * p.k + step_part(i) * K + min(j, rows_valid(i) - 1);
+      return p.V + (size_t)row * (size_t)d + x0;
+    } else {
+      return p.V + ((size_t)i * K + j) * (size_t)d + x0;
+    }
+  };
+  auto load_t = [&](int i, Regs& r) {
+    const int LDT = (SUB > 0 && K * SUB >= 16) ? K * SUB : p.kp;  // row stride of the stored factor
+    const float* Ti = p.T + (size_t)step_block(i) * LDT * LDT + (size_t)step_part(i) * (K * LDT + K);
+    const int row = t_active ? trow : 0;
+#pragma unroll
+    for (int e = 0; e < LPT; ++e) {
+      const int l = tg * LPT + e;  // a thread's columns are consecutive: its partial sums come as 16-byte LDS reads
+      r.t[e] = p.transpose ? Ti[l * LDT + row] : Ti[row * LDT + l];
+    }
+  };
+
+  // Applies block i held in `cur` while fetching block inext into `nxt`.
+  auto apply_block = [&](int i, Regs& cur, int inext, Regs& nxt) {
+    if (p.save_in && ok && (SUB == 1 || step_part(i) == (p.transpose ? 0 : sub - 1)))
+      store_chunk<VW>(p.save_in + ((size_t)step_block(i) * m + col) * d + x0, a);
+    const int kv = rows_valid(i);
+    float pj[K];
+#pragma unroll
+    for (int j = 0; j < K; ++j) {
+      if (j % S1 == 0 && j / S1 < PR) {
+        nxt.v[j / S1] = load_chunk<VW>(row_ptr(inext, j / S1));
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      float acc = 0.f;
+#pragma unroll
+      for (int r = 0; r < VW; ++r) acc = fmaf(cur.v[j].e[r], a.e[r], acc);
+      pj[j] = (PAD && j >= kv) ? 0.f : acc;
+    }
+    load_t(inext, nxt);
+    if constexpr (RL > 0) {
+      auto prefetch = [&](int t) {
+        if (t % 4 == 0 && t / 4 < RL) {
+          __builtin_amdgcn_sched_barrier(0);
+          nxt.v[PR + t / 4] = load_chunk<VW>(row_ptr(inext, PR + t / 4));
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      };
+      wave_reduce_multi_reg<K>(pj, prefetch);
+    } else {
+      wave_reduce_multi_reg<K>(pj);
+    }
+    if ((lane & reduce_writer_mask<K>()) == 0) Bpart[wave][sel] = pj[0];
+    lds_barrier();
+    if (t_active) {
+      float c = 0.f;
+      if constexpr (LPT % 4 == 0) {
+#pragma unroll
+        for (int e4 = 0; e4 < LPT / 4; ++e4) {
+          float4 b = *reinterpret_cast<const float4*>(&Bpart[0][tg * LPT + 4 * e4]);
+#pragma unroll
+          for (int w = 1; w < NW; ++w) {
+            const float4 t4 = *reinterpret_cast<const float4*>(&Bpart[w][tg * LPT + 4 * e4]);
+            b.x += t4.x; b.y += t4.y; b.z += t4.z; b.w += t4.w;
+          }
+          c = fmaf(cur.t[4 * e4], b.x, c);
+          c = fmaf(cur.t[4 * e4 + 1], b.y, c);
+          c = fmaf(cur.t[4 * e4 + 2], b.z, c);
+          c = fmaf(cur.t[4 * e4 + 3], b.w, c);
+        }
+      } else {
+#pragma unroll
+        for (int e = 0; e < LPT; ++e) {
+          const int l = tg * LPT + e;
+          float b = Bpart[0][l];
+#pragma unroll
+          for (int w = 1; w < NW; ++w) b += Bpart[w][l];
+          c = fmaf(cur.t[e], b, c);
+        }
+      }
+      c = group_sum<G>(c);
+      if (PAD && trow >= kv) c = 0.f;
+      if (tg == 0) {
+        Cv[trow] = c;
+        if constexpr (PAD) {
+          if (p.save_c && trow < kv) p.save_c[(size_t)col * p.n + (size_t)step_block(i) * p.k + step_part(i) * K + trow] = c;
+        } else {
+          if (p.save_c) p.save_c[(size_t)col * p.n + (size_t)i * K + trow] = c;
+        }
+      }
+    }
+    lds_barrier();
+    // The coefficient vector comes from LDS eight values at a time, one group ahead of its use: holding all K
+    // would push more of the second register copy into the accumulator file (115.7 -> 114.3 us at the headline).
+    constexpr int CG = K >= 16 ? 8 : K;
+    float cc[2][CG];
+    auto read_cc = [&](int grp, float (&dst)[CG]) {
+#pragma unroll
+      for (int j4 = 0; j4 < CG / 4; ++j4) {
+        const float4 c4 = reinterpret_cast<const float4*>(Cv)[grp * (CG / 4) + j4];
+        dst[4 * j4] = c4.x; dst[4 * j4 + 1] = c4.y; dst[4 * j4 + 2] = c4.z; dst[4 * j4 + 3] = c4.w;
+      }
+    };
+    read_cc(0, cc[0]);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int j = 0; j < K; ++j) {
+      if (j % CG == 0 && j + CG < K) {
+        read_cc(j / CG + 1, cc[(j / CG + 1) & 1]);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      if (j % S2 == 0 && j / S2 < PR2) {
+        nxt.v[PR + RL + j / S2] = load_chunk<VW>(row_ptr(inext, PR + RL + j / S2));
+        __builtin_amdgcn_sched_barrier(0);
+      }
+#pragma unroll
+      for (int r = 0; r < VW; ++r) a.e[r] = fmaf(-cc[(j / CG) & 1][j % CG], cur.v[j].e[r], a.e[r]);
+    }
+    if (!ok) {
+#pragma unroll
+      for (int r = 0; r < VW; ++r) a.e[r] = 0.f;
+    }
+  };
+
+  Regs ra, rb;
+#pragma unroll
+  for (int j = 0; j < K; ++j) ra.v[j] = load_chunk<VW>(row_ptr(block_of(0), j));
+  load_t(block_of(0), ra);
+  int s = 0;
+  for (; s + 1 < nb; s += 2) {
+    apply_block(block_of(s), ra, block_of(s + 1), rb);
+    apply_block(block_of(s + 1), rb, block_of(s + 2 < nb ? s + 2 : s + 1), ra);
+  }
+  if (s < nb) apply_block(block_of(s), ra, block_of(s), rb);
+  if (ok) {
+#pragma unroll
+    for (int r = 0; r < VW; ++r) p.out[(size_t)(x0 + r) * m + col] = a.e[r];
+  }
+}
+
+template <int K, int VW, int NT, int RL = 0, int SUB = 1, bool PAD = false, int P1 = 0>
+static int launch_chain_pipe(const ChainArgs& args, hipStream_t stream) {
+  ChainArgs a = args;
+  a.sub = SUB > 0 ? SUB : (args.k + K - 1) / K;
+  a.nb = args.nb * a.sub;
+  if ((size_t)VW * NT < (size_t)a.d || (PAD ? a.sub * K > a.kp : a.sub * K != a.k)) return FASTH_EINVAL;
+  const int side = a.ds_out ? (a.ds_rows + NT / 64 - 1) / (NT / 64) : 0;
+  prof::Scope ps_(FASTH_KERNEL_CHAIN, stream);
+  hipLaunchKernelGGL((chain_pipe_kernel<K, VW, NT, RL, SUB, PAD, P1>), dim3(a.m + side), dim3(NT), 0, stream, a);
+  FASTH_HIP(hipGetLastError());
+  return FASTH_OK;
+}
+
+// ---- Matrix-core chain kernel for wide mini-batches ------------------------------------------
+// With many columns the two products of a block step, B = V_i A and A -= V_i^T C, are dense contractions with a
+// real N dimension, so they go to the fp32 matrix cores: one workgroup of 4 (d <= 1024) or 8 waves per tile of 16 columns.
+//  * The d x 16 tile of A lives in the accumulator registers for the whole chain. The x axis is cut into groups
+//    of 64; wave w of NW owns groups w, w + NW, ... Within a group, accumulator tile r (0..3), register j of lane
+//    (q, i) = (lane / 16, lane % 16) holds A(x = 64 g + 16 q + 4 j + r, column i): the order in which a
+//    contraction runs over x is free, and this one lets the same registers serve as the product's output tile
+//    (A -= V^T C) and as the B operand of the next step's first product without any shuffle, while every fetch
+//    of V from LDS is 16 bytes wide.
+//  * Rows are taken 16 at a time (a block of more rows in several steps with the diagonal 16 x 16 blocks of its
+//    factor, as in chain_pipe_kernel). Each wave stages only its own groups of the 16 rows in LDS (fetched
+//    from memory into registers a step ahead with row-contiguous 16-byte loads, written to LDS when the step's
+//    second product has read the old rows); both products read them. 75 KiB of LDS and under 256 registers per
+//    workgroup let two workgroups share a compute unit and fill each other's waits.
+//  * One barrier per step: the waves' partial B (16 x 16 each) meet in LDS, then every wave forms
+//    C = op(T) B itself (4 matrix instructions), which is already laid out as the B operand of the update.
+constexpr int kTileCols = 16;           // columns per workgroup
+constexpr int kTileRows = 16;           // rows of V per step
+constexpr int kTileMaxGroups = 4;       // groups of 64 x per wave
+constexpr int kTileMaxD = 8 * kTileMaxGroups * 64;  // with 8 waves
+static constexpr size_t tile_lds_bytes(int waves, int groups) {
+  return sizeof(float) * (size_t)(waves * kTileRows * (64 * groups + 4) + 2 * waves * 256);
+}
+
+// kTileGroups: groups per wave, the same for all four waves (a group that lies beyond d is all zeros: its
+// fetches are out of the buffers' range, so it costs matrix instructions but no branch).
+// NW: waves per workgroup, 4 for d <= 1024, 8 (two per SIMD) for d <= 2048.
+template <int NW, int kTileGroups>
+__global__ void __launch_bounds__(64 * NW) chain_tile_kernel(ChainArgs p) {
+  constexpr int kTileLd = 64 * kTileGroups + 4;  // row stride of a wave's slice in LDS (floats)
+  extern __shared__ float smem[];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int q = lane >> 4, i = lane & 15;
+  const int d = p.d, m = p.m, n = p.n, k = p.k, kp = p.kp;
+  const int col = blockIdx.x * kTileCols + i;
+  const bool col_ok = col < m;
+  float* Vw = smem + (size_t)wave * kTileRows * kTileLd;         // this wave's slice of the step's rows: [16][kTileLd]
+  float* Bp = smem + (size_t)NW * kTileRows * kTileLd;           // partial products: [2][NW][256]
+  auto group_x = [&](int g) { return 64 * (wave + NW * g); };
+
+  // Input tile through a buffer bounded by the rows that exist: rows beyond them, columns beyond m and groups
+  // this wave does not own read as zero without a branch, so all fetches are in flight together.
+  f32x4 A[4 * kTileGroups];
+  const BufferDesc xdesc = make_buffer(p.in, (size_t)p.in_rows * m * sizeof(float));
+#pragma unroll
+  for (int g = 0; g < kTileGroups; ++g) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int x = group_x(g) + 16 * q + 4 * j + r;
+        const unsigned off = col_ok ? ((unsigned)x * (unsigned)m + (unsigned)col) * 4u : kOob;
+        A[4 * g + r][j] = buffer_load<1>(xdesc, off, 0).e[0];
+      }
+    }
+  }
+  if (p.in_scale_mode) {
+    const BufferDesc sdesc = make_buffer(p.in_scale, (size_t)p.in_rows * sizeof(float));
+    f32x4 sg[4 * kTileGroups];
+#pragma unroll
+    for (int g = 0; g < kTileGroups; ++g) {
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int x = group_x(g) + 16 * q + 4 * j + r;
+          sg[4 * g + r][j] = buffer_load<1>(sdesc, (unsigned)x * 4u, 0).e[0];
+        }
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    // The mode as a compile-time constant, and no branch per element: rows that do not exist hold zero in A
+    // already; their sigma is replaced by 1 so that the factor stays finite.
+    auto scale_rows = [&](auto mode) {
+#pragma unroll
+      for (int g = 0; g < kTileGroups; ++g) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const int x = group_x(g) + 16 * q + 4 * j + r;
+            const float sv = x < p.in_rows ? sg[4 * g + r][j] : 1.f;
+            A[4 * g + r][j] *= diag_factor(decltype(mode)::value, sv);
+          }
+        }
+      }
+    };
+    switch (p.in_scale_mode) {
+      case 1: scale_rows(std::integral_constant<int, 1>()); break;
+      case 2: scale_rows(std::integral_constant<int, 2>()); break;
+      case 3: scale_rows(std::integral_constant<int, 3>()); break;
+      default: scale_rows(std::integral_constant<int, 4>()); break;
+    }
+  }
+
+  // staging of a step's 16 rows: lane l fetches 16 bytes at x = group_x(l / 16) + 4 (l % 16) of every row
+  const BufferDesc vdesc = make_buffer(p.V, (size_t)n * d * sizeof(float));
+  const int stage_x = group_x(lane >> 4) + 4 * (lane & 15);
+  const unsigned stage_off = ((lane >> 4) < kTileGroups && stage_x < d) ? (unsigned)stage_x * 4u : kOob;
+  BufVec<4> stage[kTileRows];
+  auto fetch_rows = [&](int row0) {
+#pragma unroll
+    for (int rr = 0; rr < kTileRows; ++rr)
+      stage[rr] = buffer_load<4>(vdesc, stage_off, (unsigned)(row0 + rr) * (unsigned)d * 4u);
+  };
+  auto stash_rows = [&]() {
+    float* dst = Vw + 4 * lane;
+#pragma unroll
+    for (int rr = 0; rr < kTileRows; ++rr) {
+      if (kTileGroups == 4 || (lane >> 4) < kTileGroups) lds_store<4>(dst + rr * kTileLd, stage[rr]);  // a row holds 64 kTileGroups floats
+    }
+  };
+  // op(T) of the step that starts at row0, as the A operand of C = op(T) B: lane (q, i) holds op(T)(i, 4 kk + q)
+  auto fetch_t = [&](int blk, int part, float (&t)[4]) {
+    const float* Tb = p.T + (size_t)blk * kp * kp + (size_t)part * kTileRows * (kp + 1);
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) t[kk] = p.transpose ? Tb[(4 * kk + q) * kp + i] : Tb[i * kp + 4 * kk + q];
+  };
+
+  const int ns = n / kTileRows;
+  auto row_of = [&](int s) { return p.transpose ? kTileRows * s : n - kTileRows * (s + 1); };
+  // The rows of step s + 1 are fetched into registers during step s and replace those of step s in LDS once its
+  // second product has read them; the factor of step s + 1 is fetched at the start of step s.
+  // (blk, part): block and 16-row part of the current step, (blkn, partn) of the next; counters, no division.
+  const int sub = k / kTileRows;
+  int blk = p.transpose ? 0 : p.nb - 1, part = p.transpose ? 0 : sub - 1;
+  float tcur[4], tnxt[4];
+  fetch_rows(row_of(0));
+  fetch_t(blk, part, tcur);
+  stash_rows();
+  fetch_rows(row_of(ns > 1 ? 1 : 0));
+  for (int s = 0; s < ns; ++s) {
+    const int row0 = row_of(s), cur = s & 1;
+    int blkn = blk, partn = part;
+    if (s + 1 < ns) {
+      if (p.transpose) {
+        if (++partn == sub) { partn = 0; ++blkn; }
+      } else {
+        if (--partn < 0) { partn = sub - 1; --blkn; }
+      }
+    }
+    fetch_t(blkn, partn, tnxt);
+    if (p.save_in && part == (p.transpose ? 0 : sub - 1)) {
+      const BufferDesc adesc = make_buffer(p.save_in + (size_t)blk * m * d, (size_t)m * d * sizeof(float));
+#pragma unroll
+      for (int g = 0; g < kTileGroups; ++g) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int x = group_x(g) + 16 * q + 4 * j;
+          const unsigned off = (col_ok && x < d) ? ((unsigned)col * (unsigned)d + (unsigned)x) * 4u : kOob;
+          BufVec<4> v;
+          v.e[0] = A[4 * g][j]; v.e[1] = A[4 * g + 1][j]; v.e[2] = A[4 * g + 2][j]; v.e[3] = A[4 * g + 3][j];
+          buffer_store<4>(adesc, off, 0, v);
+        }
+      }
+    }
+    const float* Vc = Vw;
+    // B (partial over this wave's x) = V_rows A: four independent accumulation chains
+    f32x4 acc[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) acc[r] = f32x4{0.f, 0.f, 0.f, 0.f};
+    // operand fetches run two ahead of the matrix instructions that use them
+    auto v1_at = [&](int t) {  // t = 4 g + j
+      return *reinterpret_cast<const float4*>(Vc + i * kTileLd + 64 * (t >> 2) + 16 * q + 4 * (t & 3));
+    };
+    {
+      float4 va = v1_at(0), vb = v1_at(1);
+      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+#pragma unroll
+      for (int t = 0; t < 4 * kTileGroups; ++t) {
+        const int g = t >> 2, j = t & 3;
+        const float4 v4 = va;
+        va = vb;
+        if (t + 2 < 4 * kTileGroups) vb = v1_at(t + 2);
+        acc[0] = __builtin_amdgcn_mfma_f32_16x16x4f32(v4.x, A[4 * g][j], acc[0], 0, 0, 0);
+        acc[1] = __builtin_amdgcn_mfma_f32_16x16x4f32(v4.y, A[4 * g + 1][j], acc[1], 0, 0, 0);
+        acc[2] = __builtin_amdgcn_mfma_f32_16x16x4f32(v4.z, A[4 * g + 2][j], acc[2], 0, 0, 0);
+        acc[3] = __builtin_amdgcn_mfma_f32_16x16x4f32(v4.w, A[4 * g + 3][j], acc[3], 0, 0, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // one LDS read ...
+        __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);  // ... then four matrix instructions
+      }
+    }
+    const f32x4 bpart = (acc[0] + acc[1]) + (acc[2] + acc[3]);
+    // element (row 4 kk + qq, column i) of a wave's partial sits at ((qq * 16 + i) * 4 + kk): the writes of a
+    // wave hit 64 different banks and the operand fetch below is one 16-byte read per wave summed over
+    float* bw = Bp + (size_t)(cur * NW + wave) * 256;
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) bw[(jj * 16 + i) * 4 + q] = bpart[jj];
+    lds_barrier();
+    const float* br = Bp + (size_t)cur * NW * 256 + (q * 16 + i) * 4;
+    float4 b = *reinterpret_cast<const float4*>(br);
+#pragma unroll
+    for (int w = 1; w < NW; ++w) {
+      const float4 t4 = *reinterpret_cast<const float4*>(br + w * 256);
+      b.x += t4.x; b.y += t4.y; b.z += t4.z; b.w += t4.w;
+    }
+    f32x4 C = f32x4{0.f, 0.f, 0.f, 0.f};
+    C = __builtin_amdgcn_mfma_f32_16x16x4f32(tcur[0], b.x, C, 0, 0, 0);
+    C = __builtin_amdgcn_mfma_f32_16x16x4f32(tcur[1], b.y, C, 0, 0, 0);
+    C = __builtin_amdgcn_mfma_f32_16x16x4f32(tcur[2], b.z, C, 0, 0, 0);
+    C = __builtin_amdgcn_mfma_f32_16x16x4f32(tcur[3], b.w, C, 0, 0, 0);
+    if (p.save_c && wave == 0 && col_ok)
+      *reinterpret_cast<float4*>(p.save_c + (size_t)col * n + row0 + 4 * q) = make_float4(C[0], C[1], C[2], C[3]);
+    // A -= V_rows^T C: contraction slice s2 pairs K index q with row 4 q + s2, which is where lane (q, i) holds C
+    auto v2_at = [&](int t) {  // t = 4 g + s2
+      return *reinterpret_cast<const float4*>(Vc + (4 * q + (t & 3)) * kTileLd + 64 * (t >> 2) + 4 * i);
+    };
+    {
+      const float cn[4] = {-C[0], -C[1], -C[2], -C[3]};
+      float4 va = v2_at(0), vb = v2_at(1);
+      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+#pragma unroll
+      for (int t = 0; t < 4 * kTileGroups; ++t) {
+        const int g = t >> 2, s2 = t & 3;
+        const float4 v4 = va;
+        va = vb;
+        if (t + 2 < 4 * kTileGroups) vb = v2_at(t + 2);
+        A[4 * g] = __builtin_amdgcn_mfma_f32_16x16x4f32(v4.x, cn[s2], A[4 * g], 0, 0, 0);
+        A[4 * g + 1] = __builtin_amdgcn_mfma_f32_16x16x4f32(v4.y, cn[s2], A[4 * g + 1], 0, 0, 0);
+        A[4 * g + 2] = __builtin_amdgcn_mfma_f32_16x16x4f32(v4.z, cn[s2], A[4 * g + 2], 0, 0, 0);
+        A[4 * g + 3] = __builtin_amdgcn_mfma_f32_16x16x4f32(v4.w, cn[s2], A[4 * g + 3], 0, 0, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+      }
+    }
+    stash_rows();
+    fetch_rows(row_of(s + 2 < ns ? s + 2 : s));
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) tcur[kk] = tnxt[kk];
+    blk = blkn; part = partn;
+  }
+  const BufferDesc odesc = make_buffer(p.out, (size_t)d * m * sizeof(float));
+#pragma unroll
+  for (int g = 0; g < kTileGroups; ++g) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int x = group_x(g) + 16 * q + 4 * j + r;
+        const unsigned off = col_ok ? ((unsigned)x * (unsigned)m + (unsigned)col) * 4u : kOob;
+        BufVec<1> v;
+        v.e[0] = A[4 * g + r][j];
+        buffer_store<1>(odesc, off, 0, v);
+      }
+    }
+  }
+}
+
+// Shapes the matrix-core chain serves, and from how many columns on it is the faster one.
+#ifndef FASTH_TILE_MIN_COLS
+#define FASTH_TILE_MIN_COLS 769  // the per-column kernel needs a fourth round of 256 workgroups from here on
+#endif
+static bool chain_uses_tile(const ChainArgs& a) {
+  return a.m >= FASTH_TILE_MIN_COLS && a.d % 4 == 0 && a.d <= kTileMaxD && a.k % kTileRows == 0 &&
+         (size_t)a.d * a.m * sizeof(float) < kOob;  // its buffers take 32-bit byte offsets
+}
+
+static int launch_chain_tile(const ChainArgs& a, hipStream_t stream) {
+  if (a.d > kTileMaxD || a.d % 4 != 0 || a.k % kTileRows != 0 || a.n % a.k != 0 ||
+      (size_t)a.d * a.m * sizeof(float) >= kOob || (size_t)a.n * a.d * sizeof(float) >= kOob)
+    return FASTH_EINVAL;
+  const dim3 grid((a.m + kTileCols - 1) / kTileCols);
+#define FASTH_LAUNCH_TILE(WW, GG)                                                                           \
+  do {                                                                                                      \
+    int rc_ = allow_lds(chain_tile_kernel<WW, GG>, tile_lds_bytes(WW, GG));                                 \
+    if (rc_ != FASTH_OK) return rc_;                                                                        \
+    prof::Scope ps_(FASTH_KERNEL_CHAIN, stream);                                                            \
+    hipLaunchKernelGGL((chain_tile_kernel<WW, GG>), grid, dim3(64 * WW), tile_lds_bytes(WW, GG), stream, a); \
+  } while (0)
+  if (a.d <= 1024) {
+    const int groups = (a.d + 255) / 256;  // per wave
+    if (groups <= 1) FASTH_LAUNCH_TILE(4, 1);
+    else if (groups == 2) FASTH_LAUNCH_TILE(4, 2);
+    else if (groups == 3) FASTH_LAUNCH_TILE(4, 3);
+    else FASTH_LAUNCH_TILE(4, 4);
+  } else {
+    const int groups = (a.d + 511) / 512;
+    if (groups <= 3) FASTH_LAUNCH_TILE(8, 3);
+    else FASTH_LAUNCH_TILE(8, 4);
+  }
+#undef FASTH_LAUNCH_TILE
+  FASTH_HIP(hipGetLastError());
+  return FASTH_OK;
+}
+
+// ---- Streaming chain kernel ----------------------------------------------------------------
+// Any k <= 128 and any d <= VW * NT. The block is too large for registers, so its rows pass
+// through them eight at a time, twice per block (once per product); the second read comes from
+// the L2. The next group of rows is fetched while the current one is used.
+template <int VW, int NT>
+__global__ void __launch_bounds__(NT) chain_stream_kernel(ChainArgs p) {
+  extern __shared__ float smem[];
+  constexpr int NW = NT / 64, R = 8;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int col = blockIdx.x, m = p.m, d = p.d, k = p.k, kp = p.kp;
+  const int LDT = kp + 4;
+  float* Ts = smem;               // [kp][LDT]: op(T_i), row-contiguous
+  float* Bpart = Ts + kp * LDT;   // [NW][kp]
+  float* Bv = Bpart + NW * kp;    // [kp]
+  float* Cpart = Bv + kp;         // [8][kp]
+  float* Cv = Cpart + 8 * kp;     // [kp]
+  const bool ok = VW * tid < d;
+  const unsigned x0 = ok ? VW * tid : 0;
+  Chunk<VW> a = load_column_chunk<VW>(p, col, x0, ok);
+  const int sel = reduce_sel<R>(lane);
+  const int ngroups = (k + R - 1) / R;
+  // matvec work split: mg threads per row of T, each over kp / mg columns
+  int mg = NT / kp < 8 ? NT / kp : 8;
+  if (mg > kp / 4) mg = kp / 4;
+  const int mrow = tid / mg, mpart = tid % mg, mlen = kp / mg;
+  for (int s = 0; s < p.nb; ++s) {
+    const int i = p.transpose ? s : p.nb - 1 - s;
+    const float* Vi = p.V + (size_t)i * k * d + x0;
+    const float* Ti = p.T + (size_t)i * kp * kp;
+    for (int idx = tid; idx < kp * kp; idx += NT) {
+      const int r = idx / kp, c = idx % kp;
+      if (p.transpose) Ts[c * LDT + r] = Ti[idx];
+      else Ts[r * LDT + c] = Ti[idx];
+    }
+    if (p.save_in && ok) store_chunk<VW>(p.save_in + ((size_t)i * m + col) * d + x0, a);
+    auto load_group = [&](int g, Chunk<VW> (&rows)[R]) {
+#pragma unroll
+      for (int jj = 0; jj < R; ++jj) {
+        const int j = min(g * R + jj, k - 1);  // rows past the block repeat its last row; their results are ignored
+        rows[jj] = load_chunk<VW>(Vi + (size_t)j * d);
+      }
+    };
+    auto dots = [&](int g, const Chunk<VW> (&rows)[R]) {
+      float pj[R];
+#pragma unroll
+      for (int jj = 0; jj < R; ++jj) {
+        float acc = 0.f;
+#pragma unroll
+        for (int r = 0; r < VW; ++r) acc = fmaf(rows[jj].e[r], a.e[r], acc);
+        pj[jj] = acc;
+      }
+      wave_reduce_multi_reg<R>(pj);
+      if ((lane & reduce_writer_mask<R>()) == 0) Bpart[wave * kp + g * R + sel] = pj[0];
+    };
+    Chunk<VW> ga[R], gb[R];
+    load_group(0, ga);
+    for (int g = 0; g < ngroups; g += 2) {
+      if (g + 1 < ngroups) load_group(g + 1, gb);
+      dots(g, ga);
+      if (g + 1 < ngroups) {
+        if (g + 2 < ngroups) load_group(g + 2, ga);
+        dots(g + 1, gb);
+      }
+    }
+    load_group(0, ga);  // first group of the second pass, in flight during the small products
+    lds_barrier();
+    if (tid < kp) {
+      float b = 0.f;
+      if (tid < k)
+        for (int w = 0; w < NW; ++w) b += Bpart[w * kp + tid];
+      Bv[tid] = b;
+    }
+    lds_barrier();
+    if (mrow < kp) {
+      const float* trow_ptr = Ts + mrow * LDT + mpart * mlen;
+      const float* bptr = Bv + mpart * mlen;
+      float c = 0.f;
+      for (int l = 0; l < mlen; l += 4) {
+        const float4 t4 = *reinterpret_cast<const float4*>(trow_ptr + l);
+        const float4 b4 = *reinterpret_cast<const float4*>(bptr + l);
+        c = fmaf(t4.x, b4.x, c); c = fmaf(t4.y, b4.y, c); c = fmaf(t4.z, b4.z, c); c = fmaf(t4.w, b4.w, c);
+      }
+      Cpart[mpart * kp + mrow] = c;
+    }
+    lds_barrier();
+    if (tid < kp) {
+      float c = 0.f;
+      for (int g = 0; g < mg; ++g) c += Cpart[g * kp + tid];
+      if (tid >= k) c = 0.f;
+      Cv[tid] = c;
+      if (p.save_c && tid < k) p.save_c[(size_t)col * p.n + (size_t)i * k + tid] = c;
+    }
+    lds_barrier();
+    auto update = [&](int g, const Chunk<VW> (&rows)[R]) {
+#pragma unroll
+      for (int jj = 0; jj < R; ++jj) {
+        const float c = Cv[g * R + jj];  // zero for rows past the block
+#pragma unroll
+        for (int r = 0; r < VW; ++r) a.e[r] = fmaf(-c, rows[jj].e[r], a.e[r]);
+      }
+    };
+    for (int g = 0; g < ngroups; g += 2) {
+      if (g + 1 < ngroups) load_group(g + 1, gb);
+      update(g, ga);
+      if (g + 1 < ngroups) {
+        if (g + 2 < ngroups) load_group(g + 2, ga);
+        update(g + 1, gb);
+      }
+    }
+    if (!ok) {
+#pragma unroll
+      for (int r = 0; r < VW; ++r) a.e[r] = 0.f;
+    }
+    lds_barrier();  // Ts, Bpart and Cv are rewritten by the next block
+  }
+  if (ok) {
+#pragma unroll
+    for (int r = 0; r < VW; ++r) p.out[(size_t)(x0 + r) * m + col] = a.e[r];
+  }
+}
+
+template <int VW, int NT>
+static int launch_chain_stream(const ChainArgs& a, hipStream_t stream) {
+  const size_t lds = sizeof(float) * ((size_t)a.kp * (a.kp + 4) + (size_t)(NT / 64) * a.kp + 10 * (size_t)a.kp);
+  int rc = allow_lds(chain_stream_kernel<VW, NT>, lds);
+  if (rc != FASTH_OK) return rc;
+  prof::Scope ps_(FASTH_KERNEL_CHAIN, stream);
+  hipLaunchKernelGGL((chain_stream_kernel<VW, NT>), dim3(a.m), dim3(NT), lds, stream, a);
+  FASTH_HIP(hipGetLastError());
+  return FASTH_OK;
+}
+
+template <int VW>
+static int launch_chain_stream_vw(const ChainArgs& a, hipStream_t stream) {
+  const int chunks = a.d / VW;
+  if (chunks <= 256) return launch_chain_stream<VW, 256>(a, stream);
+  if (chunks <= 512) return launch_chain_stream<VW, 512>(a, stream);
+  return launch_chain_stream<VW, 1024>(a, stream);
+}
+
+static bool chain_takes_side_product(const ChainArgs& a) {
+  return !chain_uses_tile(a) && a.d % 4 == 0 && a.d <= 4096;
+}
+
+static int launch_chain_kernel(const ChainArgs& a, hipStream_t stream) {
+  const int d = a.d, k = a.k;
+  if (chain_uses_tile(a)) return launch_chain_tile(a, stream);
+  if (chain_takes_side_product(a)) {  // every launch in this branch is a chain_pipe_kernel
+    // whole block in registers, two copies; a quarter of the next block is fetched during the reduction
+    if (k == 16 && d <= 1024) return launch_chain_pipe<16, 4, 256, 4>(a, stream);
+    if (k == 16 && d <= 2048) return launch_chain_pipe<16, 4, 512, 4>(a, stream);
+    if (k == 32 && d <= 256) return launch_chain_pipe<32, 1, 256, 8>(a, stream);
+    if (k == 32 && d <= 512) return launch_chain_pipe<32, 2, 256, 8>(a, stream);
+    // (10 of the 32 rows of the next block fetched during the first product, 8 during the reduction, 14 during
+    // the update: with 12 / 8 / 12 more of the second register copy spills to the accumulator file; 117.2 -> 115.8 us
+    // per forward + backward at d = n = 1024, m = 32)
+    if (k == 32 && d <= 1024) return launch_chain_pipe<32, 4, 256, 8, 1, false, 10>(a, stream);
+    if (k == 64 && d <= 256) return launch_chain_pipe<64, 1, 256, 16>(a, stream);
+    if (k == 64 && d <= 512) return launch_chain_pipe<64, 2, 256, 16>(a, stream);
+    // Larger blocks and longer vectors: two register copies of the whole block do not fit, but the block can be
+    // applied as steps of 32 rows (d <= 1024) or 16 rows (d <= 2048, two waves per SIMD), which is faster than
+    // one copy refilled in place or rows streamed twice (d = n = 2048: 178 us for k = 32, 64 and 128 alike,
+    // against 222, 359 and 406 us)
+    if (d <= 1024) {
+      if (k == 64) return launch_chain_pipe<32, 4, 256, 8, 2, false, 10>(a, stream);
+      if (k == 128) return launch_chain_pipe<32, 4, 256, 8, 4, false, 10>(a, stream);
+      if (k == 8) return launch_chain_pipe<8, 4, 256, 2>(a, stream);
+      // any other block size: steps of 8, 16 or 32 rows, the last one of a block short
+      if (k < 8) return launch_chain_pipe<8, 4, 256, 2, 0, true>(a, stream);
+      if (k < 16) return launch_chain_pipe<16, 4, 256, 4, 0, true>(a, stream);
+      return launch_chain_pipe<32, 4, 256, 8, 0, true>(a, stream);
+    } else if (d <= 2048) {
+      if (k == 32) return launch_chain_pipe<16, 4, 512, 4, 2, false, 5>(a, stream);  // fetch split 5 / 4 / 7
+      if (k == 64) return launch_chain_pipe<16, 4, 512, 4, 4, false, 5>(a, stream);
+      if (k == 128) return launch_chain_pipe<16, 4, 512, 4, 8, false, 5>(a, stream);
+      if (k == 8) return launch_chain_pipe<8, 4, 512, 2>(a, stream);
+      if (k < 8) return launch_chain_pipe<8, 4, 512, 2, 0, true>(a, stream);
+      return launch_chain_pipe<16, 4, 512, 4, 0, true>(a, stream);
+    } else {
+      // 16 waves share 512 registers per lane: two copies of 8 rows
+      if (k % 8 == 0) return launch_chain_pipe<8, 4, 1024, 2, 0>(a, stream);
+      return launch_chain_pipe<8, 4, 1024, 2, 0, true>(a, stream);
+    }
+  }
+  if (d % 2 == 0 && d <= 2048) return launch_chain_stream_vw<2>(a, stream);
+  if (d <= 1024) return launch_chain_stream_vw<1>(a, stream);
+  int threads = 256;
+  if (d > 256 * 8) threads = 512;
+  if (d > 512 * 8) threads = 1024;
+  const int per = (d + threads - 1) / threads;
+  const int nw = threads / 64;
+  const size_t lds = sizeof(float) * ((size_t)a.kp * (a.kp + 1) + (size_t)nw * a.kp + 2 * a.kp);
+  dim3 grid(a.m), block(threads);
+#define FASTH_LAUNCH_CHAIN(UU)                                                   \
+  do {                                                                           \
+    int rc_ = allow_lds(chain_kernel<UU>, lds);                                  \
+    if (rc_ != FASTH_OK) return rc_;                                             \
+    prof::Scope ps_(FASTH_KERNEL_CHAIN, stream);                                 \
+    hipLaunchKernelGGL(chain_kernel<UU>, grid, block, lds, stream, a);           \
+  } while (0)
+  if (per <= 1) FASTH_LAUNCH_CHAIN(1);
+  else if (per <= 2) FASTH_LAUNCH_CHAIN(2);
+  else if (per <= 4) FASTH_LAUNCH_CHAIN(4);
+  else if (per <= 8) FASTH_LAUNCH_CHAIN(8);
+  else FASTH_LAUNCH_CHAIN(16);
+#undef FASTH_LAUNCH_CHAIN
+  FASTH_HIP(hipGetLastError());
+  return FASTH_OK;
+}
+
+static int launch_chain(const ChainArgs& a, hipStream_t stream) {
+  const int rc = launch_chain_kernel(a, stream);
+  if (rc != FASTH_OK || !a.ds_out || chain_takes_side_product(a)) return rc;
+  prof::Scope ps_(FASTH_KERNEL_DSIGMA, stream);
+  hipLaunchKernelGGL(dsigma_kernel, dim3((a.ds_rows + 3) / 4), dim3(256), 0, stream, a.in, a.ds_z1, a.in_scale, a.ds_out,
+                     a.ds_rows, a.m, a.in_scale_mode);
+  FASTH_HIP(hipGetLastError());
+  return FASTH_OK;
+}
+
+}  // namespace fasth

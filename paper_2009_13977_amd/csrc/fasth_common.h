@@ -1,0 +1,118 @@
+// Host-side shape bookkeeping, the workspace layout, error and timing helpers shared by the FastH kernels' launchers.
+// Included by fasth.hip, the library's single translation unit.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdint>
+#include <cstdio>
+#include <cstdlib>
+#include <type_traits>
+#include <vector>
+
+#include "fasth.h"
+#include "fasth_device.h"
+
+namespace fasth {
+
+// ------------------------------------------------------------------------------------------
+// Host-side shape bookkeeping
+// ------------------------------------------------------------------------------------------
+
+constexpr int kMaxBlock = 128;     // largest k: a k x k factor must fit in LDS with scratch
+constexpr int kMaxD = 16384;       // chain kernel: 1024 threads x 16 elements
+constexpr int kGramChunk = 128;    // columns of V per LDS tile in the Gram kernel
+constexpr int kMaxGramSplit = 16;  // partial Gram matrices per block
+constexpr int kDvTile = 64;        // columns of dV per workgroup
+constexpr int kDvMChunk = 32;      // mini-batch columns per LDS tile in the dV kernel
+
+static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+static int padded_block(int k) {
+  int kp = 16;
+  while (kp < k) kp *= 2;
+  return kp;
+}
+
+struct Layout {
+  int kp, nb, gram_split;
+  size_t off_T, off_Spart, off_saveA, off_saveCa, off_saveG, off_saveCg, total;
+};
+
+static Layout make_layout(int d, int n, int m, int k) {
+  Layout L;
+  L.kp = padded_block(k);
+  L.nb = n / k;
+  int split = (d + kGramChunk - 1) / kGramChunk;
+  L.gram_split = split > kMaxGramSplit ? kMaxGramSplit : split;
+  size_t off = 256;  // header, reserved
+  auto take = [&](size_t floats) {
+    size_t o = off;
+    off = align_up(off + floats * sizeof(float), 256);
+    return o;
+  };
+  L.off_T = take((size_t)L.nb * L.kp * L.kp);
+  L.off_Spart = take((size_t)L.nb * L.gram_split * L.kp * L.kp);
+  L.off_saveA = take((size_t)L.nb * m * d);
+  L.off_saveCa = take((size_t)m * n);
+  L.off_saveG = take((size_t)L.nb * m * d);
+  L.off_saveCg = take((size_t)m * n);
+  L.total = off;
+  return L;
+}
+
+static int check_shape(const fasth_shape* s) {
+  if (!s) return FASTH_EINVAL;
+  if (s->d < 1 || s->n < 1 || s->m < 1 || s->k < 1) return FASTH_EINVAL;
+  if (s->n % s->k != 0) return FASTH_EINVAL;
+  if (s->transpose != 0 && s->transpose != 1) return FASTH_EINVAL;
+  if (s->k > kMaxBlock || s->d > kMaxD || s->m > 65535) return FASTH_EUNSUPPORTED;
+  return FASTH_OK;
+}
+
+static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+#define FASTH_HIP(call)                      \
+  do {                                       \
+    hipError_t e_ = (call);                  \
+    if (e_ != hipSuccess) return FASTH_EHIP; \
+  } while (0)
+
+// Optional per-kernel timing for benchmarks: a pair of HIP events around every launch.
+namespace prof {
+struct Rec { int id; hipEvent_t beg, end; };
+static bool enabled = false;
+static std::vector<Rec> recs;
+static std::vector<hipEvent_t> pool;
+static hipEvent_t get_event() {
+  if (!pool.empty()) { hipEvent_t e = pool.back(); pool.pop_back(); return e; }
+  hipEvent_t e = nullptr;
+  if (hipEventCreate(&e) != hipSuccess) return nullptr;
+  return e;
+}
+struct Scope {
+  Rec r{-1, nullptr, nullptr};
+  hipStream_t st;
+  Scope(int id, hipStream_t s) : st(s) {
+    if (!enabled) return;
+    r.id = id; r.beg = get_event(); r.end = get_event();
+    if (r.beg) (void)hipEventRecord(r.beg, st);
+  }
+  ~Scope() {
+    if (r.id < 0) return;
+    if (r.end) (void)hipEventRecord(r.end, st);
+    recs.push_back(r);
+  }
+};
+}  // namespace prof
+
+template <typename K>
+static int allow_lds(K kernel, size_t bytes) {
+  if (bytes > 64 * 1024) {
+    FASTH_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes));
+  }
+  return FASTH_OK;
+}
+
+}  // namespace fasth

@@ -1,0 +1,296 @@
+// Algorithm 1 Step 1: the k x k block factors T_i (gram_partial_kernel + t_build_kernel, factor_fused_kernel).
+// Included by fasth.hip, the library's single translation unit.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include "fasth_common.h"
+
+namespace fasth {
+
+// ------------------------------------------------------------------------------------------
+// Algorithm 1 Step 1a: partial Gram matrices S_i = V_i V_i^T, split over d.
+// grid (gram_split, nb), 256 threads. Only the 16x16 tiles on or above the diagonal are formed.
+// ------------------------------------------------------------------------------------------
+
+template <int VEC>  // VEC = 4 when d is a multiple of 4 (16-byte loads), else 1
+__global__ void __launch_bounds__(256) gram_partial_kernel(const float* __restrict__ V, float* __restrict__ Spart,
+                                                           int d, int k, int kp, int gram_split) {
+  extern __shared__ __align__(16) float smem[];
+  const int LD = kGramChunk + 4;
+  float* Vs = smem;  // [kp][LD]
+  const int i = blockIdx.y, s = blockIdx.x;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int chunk = ((d + gram_split - 1) / gram_split + 3) & ~3;
+  const int xbeg = s * chunk;
+  const int xend = min(d, xbeg + chunk);
+  const int kt = kp / 16;
+  const int ntiles = kt * (kt + 1) / 2;
+  constexpr int kMaxTilesPerWave = 9;  // kp = 128: 36 upper tiles over 4 waves
+  f32x4 acc[kMaxTilesPerWave];
+#pragma unroll
+  for (int w = 0; w < kMaxTilesPerWave; ++w) acc[w] = f32x4{0.f, 0.f, 0.f, 0.f};
+  // the block's k rows as one buffer: rows k .. kp - 1 of the padded block lie beyond it and read as zero
+  const BufferDesc vdesc = make_buffer(V + (size_t)i * k * d, (size_t)k * d * sizeof(float));
+  constexpr int XV = kGramChunk / VEC;             // loads per slab row
+  constexpr int kMaxPer = kMaxBlock * XV / 256;    // loads per thread and slab at the largest block
+  const int per = kp * XV / 256;
+  for (int x0 = xbeg; x0 < xend; x0 += kGramChunk) {
+    BufVec<VEC> stage[kMaxPer];
+#pragma unroll
+    for (int it = 0; it < kMaxPer; ++it) {
+      if (it < per) {  // uniform
+        const int idx = tid + it * 256, j = idx / XV, x = x0 + (idx % XV) * VEC;
+        stage[it] = buffer_load<VEC>(vdesc, x < xend ? (unsigned)(j * d + x) * 4u : kOob, 0);
+      }
+    }
+#pragma unroll
+    for (int it = 0; it < kMaxPer; ++it) {
+      if (it < per) {
+        const int idx = tid + it * 256;
+        lds_store<VEC>(Vs + (idx / XV) * LD + (idx % XV) * VEC, stage[it]);
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int w = 0; w < kMaxTilesPerWave; ++w) {
+      const int t = wave + 4 * w;
+      if (t < ntiles) {
+        int ti = 0, rem = t;
+        while (rem >= kt - ti) { rem -= kt - ti; ++ti; }
+        const int tj = ti + rem;
+        acc[w] = tile_mma(Vs + ti * 16 * LD, LD, 1, Vs + tj * 16 * LD, 1, LD, kGramChunk, acc[w]);
+      }
+    }
+    __syncthreads();
+  }
+  float* out = Spart + ((size_t)i * gram_split + s) * kp * kp;
+  const int li = lane & 15, q = lane >> 4;
+#pragma unroll
+  for (int w = 0; w < kMaxTilesPerWave; ++w) {
+    const int t = wave + 4 * w;
+    if (t < ntiles) {
+      int ti = 0, rem = t;
+      while (rem >= kt - ti) { rem -= kt - ti; ++ti; }
+      const int tj = ti + rem;
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) out[(ti * 16 + 4 * q + jj) * kp + tj * 16 + li] = acc[w][jj];
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Algorithm 1 Step 1b: T_i = (diag(S)/2 + striu(S))^-1, one workgroup per block.
+// 16x16 diagonal blocks by unrolled back substitution, then [[T11, -T11 M12 T22], [0, T22]] doubles
+// the block size each level with matrix-core products. Rows/columns >= k (padding) form an identity.
+// ------------------------------------------------------------------------------------------
+
+// In-place inverse of the upper-triangular kp x kp matrix Ms (row stride LDM) in LDS by block
+// doubling; Xs is scratch of max(kp * (kp/2 + 4) / 2 + 64, kp * 17) floats. Called by every thread of the workgroup
+// (a multiple of 64 threads); Ms must be complete (barrier) on entry and is complete on return.
+__device__ __forceinline__ void invert_upper_lds(float* Ms, float* Xs, int kp, int LDM) {
+  const int tid = threadIdx.x, nthreads = blockDim.x, wave = tid >> 6, nwaves = nthreads >> 6, lane = tid & 63;
+  // 16x16 diagonal blocks: thread c of a block solves for column c by back substitution, fully
+  // unrolled so that the reads of M (a copy in Xs) are independent of the values being computed.
+  float* Ds = Xs;  // [kp/16][16][17]
+  if (tid < kp) {
+    const int base = tid & ~15, c = tid & 15;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) Ds[(base + r) * 17 + c] = Ms[(base + r) * LDM + base + c];
+  }
+  __syncthreads();
+  if (tid < kp) {
+    const int base = tid & ~15, c = tid & 15;
+    const float* D = Ds + base * 17;
+    float x[16], rdiag[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) rdiag[r] = 1.f / D[r * 17 + r];  // all sixteen at once, off the dependent chain
+#pragma unroll
+    for (int r = 15; r >= 0; --r) {
+      float sum = r == c ? 1.f : 0.f;
+      // oldest x first: the value computed last enters last, so each row adds one multiply-add to the chain
+#pragma unroll
+      for (int l = 15; l > r; --l) sum = fmaf(-D[r * 17 + l], x[l], sum);
+      x[r] = sum * rdiag[r];  // rows below c stay exactly zero
+    }
+#pragma unroll
+    for (int r = 0; r < 16; ++r) Ms[(base + r) * LDM + base + c] = x[r];
+  }
+  __syncthreads();
+  const int li = lane & 15, q = lane >> 4;
+  for (int b = 16; b < kp; b *= 2) {
+    const int tpb = b / 16, per_pair = tpb * tpb, items = (kp / (2 * b)) * per_pair;
+    const int LDX = b + 4;
+    for (int it = wave; it < items; it += nwaves) {  // X = M12 T22
+      const int pr = it / per_pair, ti = (it % per_pair) / tpb, tj = it % tpb, r0 = pr * 2 * b;
+      f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+      acc = tile_mma(Ms + (r0 + 16 * ti) * LDM + r0 + b, LDM, 1, Ms + (r0 + b) * LDM + r0 + b + 16 * tj, LDM, 1, b, acc);
+      float* X = Xs + pr * b * LDX;
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) X[(16 * ti + 4 * q + jj) * LDX + 16 * tj + li] = acc[jj];
+    }
+    __syncthreads();
+    for (int it = wave; it < items; it += nwaves) {  // T12 = -T11 X
+      const int pr = it / per_pair, ti = (it % per_pair) / tpb, tj = it % tpb, r0 = pr * 2 * b;
+      f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+      acc = tile_mma(Ms + (r0 + 16 * ti) * LDM + r0, LDM, 1, Xs + pr * b * LDX + 16 * tj, LDX, 1, b, acc);
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) Ms[(r0 + 16 * ti + 4 * q + jj) * LDM + r0 + b + 16 * tj + li] = -acc[jj];
+    }
+    __syncthreads();
+  }
+}
+
+__global__ void __launch_bounds__(1024) t_build_kernel(const float* __restrict__ Spart, float* __restrict__ T,
+                                                      int k, int kp, int gram_split) {
+  extern __shared__ float smem[];
+  const int LDM = kp + 4;
+  float* Ms = smem;                 // [kp][LDM]
+  float* Xs = Ms + kp * LDM;        // scratch of the inversion
+  const int i = blockIdx.x;
+  const int tid = threadIdx.x, nthreads = blockDim.x;
+  const float* Sp = Spart + (size_t)i * gram_split * kp * kp;
+  // Four neighbouring entries of a row at a time (kp is a multiple of 16, so they share a 16 x 16 tile); tiles
+  // below the diagonal hold nothing and are not read. All partial sums of an entry are in flight at once.
+  for (int idx4 = tid; idx4 < kp * kp / 4; idx4 += nthreads) {
+    const int j = idx4 / (kp / 4), l0 = (idx4 % (kp / 4)) * 4;
+    float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (j / 16 <= l0 / 16 && j < k) {
+      float4 part[kMaxGramSplit];
+#pragma unroll
+      for (int s = 0; s < kMaxGramSplit; ++s)
+        part[s] = s < gram_split ? *reinterpret_cast<const float4*>(Sp + (size_t)s * kp * kp + 4 * (size_t)idx4)
+                                 : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+      for (int s = 0; s < kMaxGramSplit; ++s) {
+        sum.x += part[s].x; sum.y += part[s].y; sum.z += part[s].z; sum.w += part[s].w;
+      }
+    }
+    const float e[4] = {sum.x, sum.y, sum.z, sum.w};
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int l = l0 + u;
+      float v = 0.f;
+      if (j < k && l < k && j <= l) v = j == l ? 0.5f * e[u] : e[u];
+      else if (j == l) v = 1.f;
+      Ms[j * LDM + l] = v;
+    }
+  }
+  __syncthreads();
+  invert_upper_lds(Ms, Xs, kp, LDM);
+  float* Ti = T + (size_t)i * kp * kp;
+  for (int idx = tid; idx < kp * kp; idx += nthreads) Ti[idx] = Ms[(idx / kp) * LDM + idx % kp];
+}
+
+// Algorithm 1 Step 1 in one kernel for small blocks (kp = 16 KT <= 32): one workgroup of 8 waves per
+// block streams the block's rows through LDS in 128-column slabs; wave w multiplies columns
+// [16 w, 16 w + 16) of each slab, the 8 partial Gram matrices are added through LDS, and the same
+// workgroup inverts. Saves a launch and the round trip of the partial sums through memory.
+// Up to two products (the two orthogonal factors of an SVD layer) are factored by one launch:
+// blockIdx.y picks the product, blockIdx.x its block.
+struct FactorPair {
+  const float* V[2];  // [n][d]
+  float* T[2];        // [nb][kp][kp]
+  int d[2], k[2], nb[2];
+};
+
+template <int KT, int VEC>  // VEC = 4 when d is a multiple of 4 (16-byte loads), else 1
+__global__ void __launch_bounds__(512) factor_fused_kernel(FactorPair fp) {
+  const int which = blockIdx.y;
+  if ((int)blockIdx.x >= fp.nb[which]) return;  // whole workgroup, before any barrier
+  const float* __restrict__ V = fp.V[which];
+  float* __restrict__ T = fp.T[which];
+  const int d = fp.d[which], k = fp.k[which];
+  constexpr int kp = 16 * KT, LD = kGramChunk + 4, NTILE = KT * (KT + 1) / 2, NW = 8, LDM = kp + 4;
+  constexpr int PER = kp * kGramChunk / 512 / VEC;  // loads per thread and slab
+  constexpr int XV = kGramChunk / VEC;              // loads per slab row
+  __shared__ __align__(16) float Vs[kp * LD];
+  __shared__ float Red[NW * NTILE * 256];
+  __shared__ float Ms[kp * LDM];
+  __shared__ float Xs[(kp * (kp / 2 + 4) / 2 + 64) > kp * 17 ? (kp * (kp / 2 + 4) / 2 + 64) : kp * 17];
+  const int i = blockIdx.x;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, li = lane & 15, q = lane >> 4;
+  // the block's k rows as one buffer: rows k .. kp - 1 of the padded block lie beyond it and read as zero
+  const BufferDesc vdesc = make_buffer(V + (size_t)i * k * d, (size_t)k * d * sizeof(float));
+  f32x4 acc[NTILE];
+#pragma unroll
+  for (int t = 0; t < NTILE; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+  // Eight slabs (1024 columns) are fetched at once, so the trip to memory is paid once per 1024
+  // columns of V instead of once per slab.
+  constexpr int NS = 8;
+  BufVec<VEC> stage[NS][PER];
+  for (int xs = 0; xs < d; xs += NS * kGramChunk) {
+#pragma unroll
+    for (int sl = 0; sl < NS; ++sl) {
+#pragma unroll
+      for (int it = 0; it < PER; ++it) {
+        const int idx = tid + it * 512, j = idx / XV, x = xs + sl * kGramChunk + (idx % XV) * VEC;
+        stage[sl][it] = buffer_load<VEC>(vdesc, x < d ? (unsigned)(j * d + x) * 4u : kOob, 0);
+      }
+    }
+#pragma unroll
+    for (int sl = 0; sl < NS; ++sl) {
+      if (xs + sl * kGramChunk < d) {  // uniform across the workgroup
+#pragma unroll
+        for (int it = 0; it < PER; ++it) {
+          const int idx = tid + it * 512;
+          lds_store<VEC>(Vs + (idx / XV) * LD + (idx % XV) * VEC, stage[sl][it]);
+        }
+        __syncthreads();
+        // This wave's 16 columns of the slab, one 16-byte read per 16-row group: lane (i, q) holds
+        // columns 4 q .. 4 q + 3 of row i, which serves as the A fragment of row group ti and as the
+        // B fragment of row group tj alike (the matrix cores sum over q; product u takes element u).
+        float4 frag[KT];
+#pragma unroll
+        for (int tt = 0; tt < KT; ++tt)
+          frag[tt] = *reinterpret_cast<const float4*>(Vs + (16 * tt + li) * LD + 16 * wave + 4 * q);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          int t = 0;
+#pragma unroll
+          for (int ti = 0; ti < KT; ++ti) {
+            const float av = u == 0 ? frag[ti].x : u == 1 ? frag[ti].y : u == 2 ? frag[ti].z : frag[ti].w;
+#pragma unroll
+            for (int tj = ti; tj < KT; ++tj) {
+              const float bv = u == 0 ? frag[tj].x : u == 1 ? frag[tj].y : u == 2 ? frag[tj].z : frag[tj].w;
+              acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, bv, acc[t], 0, 0, 0);
+              ++t;
+            }
+          }
+        }
+        __syncthreads();
+      }
+    }
+  }
+#pragma unroll
+  for (int t = 0; t < NTILE; ++t) {
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) Red[(wave * NTILE + t) * 256 + (4 * q + jj) * 16 + li] = acc[t][jj];
+  }
+  __syncthreads();
+  for (int idx = tid; idx < kp * kp; idx += 512) {
+    const int j = idx / kp, l = idx % kp;
+    float v = 0.f;
+    if (j < k && l < k && j <= l) {
+      const int ti = j / 16, tj = l / 16;
+      const int t = ti * KT - ti * (ti - 1) / 2 + (tj - ti);  // index of tile (ti, tj) in the upper-triangle order
+#pragma unroll
+      for (int w = 0; w < NW; ++w) v += Red[(w * NTILE + t) * 256 + (j % 16) * 16 + l % 16];
+      if (j == l) v *= 0.5f;
+    } else if (j == l) {
+      v = 1.f;
+    }
+    Ms[j * LDM + l] = v;
+  }
+  __syncthreads();
+  invert_upper_lds(Ms, Xs, kp, LDM);
+  float* Ti = T + (size_t)i * kp * kp;
+  for (int idx = tid; idx < kp * kp; idx += 512) Ti[idx] = Ms[(idx / kp) * LDM + idx % kp];
+}
+
+static size_t t_build_lds(int kp) {
+  size_t scratch = (size_t)kp * (kp / 2 + 4) / 2 + 64;
+  if (scratch < (size_t)kp * 17) scratch = (size_t)kp * 17;
+  return sizeof(float) * ((size_t)kp * (kp + 4) + scratch);
+}
+
+}  // namespace fasth
