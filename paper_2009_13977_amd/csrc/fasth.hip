@@ -18,7 +18,7 @@
 //   dv_kernel            Algorithm 2 Step 2 as dense products per block (MFMA)
 //   seq_*                the one-reflection-at-a-time comparison
 //   dsigma_kernel        the diagonal step of the SVD layer
-// The kernels live in fasth_factor.h, fasth_chain.h, fasth_dv.h and fasth_sequential.h (helpers in
+// The kernels live in fasth_factor.h, fasth_chain.h (+ fasth_chain_tile.h), fasth_dv.h and fasth_sequential.h (helpers in
 // fasth_common.h and fasth_device.h); this file holds the host drivers and the C entry points.
 #include <hip/hip_runtime.h>
 
