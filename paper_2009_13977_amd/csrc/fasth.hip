@@ -64,15 +64,25 @@ static Product bind(int d, int n, int m, int k, void* ws) {
   return P;
 }
 
+// Blocks of up to 32 rows are factored by one kernel; blocks of 64 rows only while d is short, because one
+// workgroup per block then streams 64 d floats alone (measured: d = 256 18.0 -> 13.6 us, d = 1024 19.5 -> 21.5 us,
+// d = 2048 23 -> 34 us against the two kernels that split the Gram product over d).
+#ifndef FASTH_FUSED64_MAX_D
+#define FASTH_FUSED64_MAX_D 512
+#endif
+static bool factor_is_fused(int kp, int d) { return kp <= 32 || (kp == 64 && d <= FASTH_FUSED64_MAX_D); }
+
 static int launch_factor_fused(const FactorPair& fp, int count, int kp, bool vec4, hipStream_t stream) {
   prof::Scope ps_(FASTH_KERNEL_FACTOR, stream);
   const dim3 grid(count == 2 && fp.nb[1] > fp.nb[0] ? fp.nb[1] : fp.nb[0], count), block(512);
   if (vec4) {
     if (kp == 16) hipLaunchKernelGGL((factor_fused_kernel<1, 4>), grid, block, 0, stream, fp);
-    else hipLaunchKernelGGL((factor_fused_kernel<2, 4>), grid, block, 0, stream, fp);
+    else if (kp == 32) hipLaunchKernelGGL((factor_fused_kernel<2, 4>), grid, block, 0, stream, fp);
+    else hipLaunchKernelGGL((factor_fused_kernel<4, 4>), grid, block, 0, stream, fp);
   } else {
     if (kp == 16) hipLaunchKernelGGL((factor_fused_kernel<1, 1>), grid, block, 0, stream, fp);
-    else hipLaunchKernelGGL((factor_fused_kernel<2, 1>), grid, block, 0, stream, fp);
+    else if (kp == 32) hipLaunchKernelGGL((factor_fused_kernel<2, 1>), grid, block, 0, stream, fp);
+    else hipLaunchKernelGGL((factor_fused_kernel<4, 1>), grid, block, 0, stream, fp);
   }
   FASTH_HIP(hipGetLastError());
   return FASTH_OK;
@@ -84,7 +94,7 @@ static void set_factor_slot(FactorPair& fp, int slot, const Product& P, const fl
 
 static int build_factors(const Product& P, const float* V, hipStream_t stream) {
   const int kp = P.L.kp;
-  if (kp <= 32) {
+  if (factor_is_fused(kp, P.d)) {
     FactorPair fp;
     set_factor_slot(fp, 0, P, V);
     set_factor_slot(fp, 1, P, V);  // unused
@@ -118,7 +128,8 @@ static int build_factors(const Product& P, const float* V, hipStream_t stream) {
 // kernel with the same template arguments; otherwise one after the other.
 static int build_factors_pair(const Product& P0, const float* V0, const Product& P1, const float* V1,
                               hipStream_t stream) {
-  if (P0.L.kp <= 32 && P0.L.kp == P1.L.kp && (P0.d % 4 == 0) == (P1.d % 4 == 0)) {
+  if (factor_is_fused(P0.L.kp, P0.d) && factor_is_fused(P1.L.kp, P1.d) && P0.L.kp == P1.L.kp &&
+      (P0.d % 4 == 0) == (P1.d % 4 == 0)) {
     FactorPair fp;
     set_factor_slot(fp, 0, P0, V0);
     set_factor_slot(fp, 1, P1, V1);

@@ -598,8 +598,11 @@ static int launch_chain_kernel(const ChainArgs& a, hipStream_t stream) {
     // the update: with 12 / 8 / 12 more of the second register copy spills to the accumulator file; 117.2 -> 115.8 us
     // per forward + backward at d = n = 1024, m = 32)
     if (k == 32 && d <= 1024) return launch_chain_pipe<32, 4, 256, 8, 1, false, 10>(a, stream);
-    if (k == 64 && d <= 256) return launch_chain_pipe<64, 1, 256, 16>(a, stream);
-    if (k == 64 && d <= 512) return launch_chain_pipe<64, 2, 256, 16>(a, stream);
+    // blocks of 64 and 128 rows as steps of 32, at the lane width that keeps all four waves busy
+    if (k == 64 && d <= 256) return launch_chain_pipe<32, 1, 256, 8, 2>(a, stream);
+    if (k == 64 && d <= 512) return launch_chain_pipe<32, 2, 256, 8, 2>(a, stream);
+    if (k == 128 && d <= 256) return launch_chain_pipe<32, 1, 256, 8, 4>(a, stream);
+    if (k == 128 && d <= 512) return launch_chain_pipe<32, 2, 256, 8, 4>(a, stream);
     // Larger blocks and longer vectors: two register copies of the whole block do not fit, but the block can be
     // applied as steps of 32 rows (d <= 1024) or 16 rows (d <= 2048, two waves per SIMD), which is faster than
     // one copy refilled in place or rows streamed twice (d = n = 2048: 178 us for k = 32, 64 and 128 alike,

@@ -181,7 +181,7 @@ __global__ void __launch_bounds__(1024) t_build_kernel(const float* __restrict__
   for (int idx = tid; idx < kp * kp; idx += nthreads) Ti[idx] = Ms[(idx / kp) * LDM + idx % kp];
 }
 
-// Algorithm 1 Step 1 in one kernel for small blocks (kp = 16 KT <= 32): one workgroup of 8 waves per
+// Algorithm 1 Step 1 in one kernel for blocks of up to 64 rows (kp = 16 KT): one workgroup of 8 waves per
 // block streams the block's rows through LDS in 128-column slabs; wave w multiplies columns
 // [16 w, 16 w + 16) of each slab, the 8 partial Gram matrices are added through LDS, and the same
 // workgroup inverts. Saves a launch and the round trip of the partial sums through memory.
@@ -203,8 +203,11 @@ __global__ void __launch_bounds__(512) factor_fused_kernel(FactorPair fp) {
   constexpr int kp = 16 * KT, LD = kGramChunk + 4, NTILE = KT * (KT + 1) / 2, NW = 8, LDM = kp + 4;
   constexpr int PER = kp * kGramChunk / 512 / VEC;  // loads per thread and slab
   constexpr int XV = kGramChunk / VEC;              // loads per slab row
+  // Partial Gram matrices meet in LDS. Up to 32 rows all eight waves' tiles fit side by side; for 64 rows
+  // (10 tiles a wave) the upper four waves hand theirs to the lower four first, which halves the space.
+  constexpr int RW = KT <= 2 ? NW : NW / 2;  // waves whose partial tiles are held at once
   __shared__ __align__(16) float Vs[kp * LD];
-  __shared__ float Red[NW * NTILE * 256];
+  __shared__ float Red[RW * NTILE * 256];
   __shared__ float Ms[kp * LDM];
   __shared__ float Xs[(kp * (kp / 2 + 4) / 2 + 64) > kp * 17 ? (kp * (kp / 2 + 4) / 2 + 64) : kp * 17];
   const int i = blockIdx.x;
@@ -261,10 +264,36 @@ __global__ void __launch_bounds__(512) factor_fused_kernel(FactorPair fp) {
       }
     }
   }
+  if constexpr (RW == NW) {
 #pragma unroll
-  for (int t = 0; t < NTILE; ++t) {
+    for (int t = 0; t < NTILE; ++t) {
 #pragma unroll
-    for (int jj = 0; jj < 4; ++jj) Red[(wave * NTILE + t) * 256 + (4 * q + jj) * 16 + li] = acc[t][jj];
+      for (int jj = 0; jj < 4; ++jj) Red[(wave * NTILE + t) * 256 + (4 * q + jj) * 16 + li] = acc[t][jj];
+    }
+  } else {
+    if (wave >= RW) {
+#pragma unroll
+      for (int t = 0; t < NTILE; ++t) {
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) Red[((wave - RW) * NTILE + t) * 256 + (4 * q + jj) * 16 + li] = acc[t][jj];
+      }
+    }
+    __syncthreads();
+    if (wave < RW) {
+#pragma unroll
+      for (int t = 0; t < NTILE; ++t) {
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) acc[t][jj] += Red[(wave * NTILE + t) * 256 + (4 * q + jj) * 16 + li];
+      }
+    }
+    __syncthreads();
+    if (wave < RW) {
+#pragma unroll
+      for (int t = 0; t < NTILE; ++t) {
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) Red[(wave * NTILE + t) * 256 + (4 * q + jj) * 16 + li] = acc[t][jj];
+      }
+    }
   }
   __syncthreads();
   for (int idx = tid; idx < kp * kp; idx += 512) {
@@ -274,7 +303,7 @@ __global__ void __launch_bounds__(512) factor_fused_kernel(FactorPair fp) {
       const int ti = j / 16, tj = l / 16;
       const int t = ti * KT - ti * (ti - 1) / 2 + (tj - ti);  // index of tile (ti, tj) in the upper-triangle order
 #pragma unroll
-      for (int w = 0; w < NW; ++w) v += Red[(w * NTILE + t) * 256 + (j % 16) * 16 + l % 16];
+      for (int w = 0; w < RW; ++w) v += Red[(w * NTILE + t) * 256 + (j % 16) * 16 + l % 16];
       if (j == l) v *= 0.5f;
     } else if (j == l) {
       v = 1.f;
