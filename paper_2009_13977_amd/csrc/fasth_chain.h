@@ -590,6 +590,10 @@ static int launch_chain_kernel(const ChainArgs& a, hipStream_t stream) {
   if (chain_uses_tile(a)) return launch_chain_tile(a, stream);
   if (chain_takes_side_product(a)) {  // every launch in this branch is a chain_pipe_kernel
     // whole block in registers, two copies; a quarter of the next block is fetched during the reduction
+    if (k == 16 && d <= 256) return launch_chain_pipe<16, 1, 256, 4>(a, stream);  // narrower lanes keep all four waves busy
+    if (k == 16 && d <= 512) return launch_chain_pipe<16, 2, 256, 4>(a, stream);
+    if (k == 8 && d <= 256) return launch_chain_pipe<8, 1, 256, 2>(a, stream);
+    if (k == 8 && d <= 512) return launch_chain_pipe<8, 2, 256, 2>(a, stream);
     if (k == 16 && d <= 1024) return launch_chain_pipe<16, 4, 256, 4>(a, stream);
     if (k == 16 && d <= 2048) return launch_chain_pipe<16, 4, 512, 4>(a, stream);
     if (k == 32 && d <= 256) return launch_chain_pipe<32, 1, 256, 8>(a, stream);

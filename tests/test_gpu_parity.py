@@ -61,7 +61,7 @@ DISPATCH = [
     (3072, 64, 3, 32), (2304, 48, 2, 24), (4096, 56, 2, 28), (4096, 256, 1, 128), (2052, 10, 2, 5),
     (1024, 56, 3, 28), (784, 112, 2, 56), (1024, 36, 2, 12), (1024, 15, 2, 5), (1024, 40, 2, 8),
     (2048, 40, 2, 8), (2048, 20, 2, 5), (1536, 72, 2, 24), (1280, 200, 2, 100),
-    (512, 256, 3, 128), (256, 256, 2, 128),
+    (512, 256, 3, 128), (256, 256, 2, 128), (256, 48, 3, 16), (512, 48, 3, 16), (200, 40, 3, 8), (400, 40, 3, 8),
 ]
 
 
