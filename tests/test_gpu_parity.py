@@ -144,6 +144,35 @@ def test_layers_wide_minibatch():
             assert rel_err(g, r) <= REL_TOL, (name, rel_err(g, r))
 
 
+def _random_shapes(count, seed):
+    """Seeded shapes over the whole supported range: any d (multiples of 4 and not), block sizes that do and do not
+    divide into 8/16/32-row steps, narrow and wide mini-batches, n != d. Few reflections keep the checker fast."""
+    rng = np.random.default_rng(seed)
+    shapes = []
+    for _ in range(count):
+        d = int(rng.choice([rng.integers(1, 64), rng.integers(64, 600), rng.integers(600, 2100), rng.integers(2100, 4200)]))
+        if rng.random() < 0.7:
+            d = max(4, d // 4 * 4)
+        k = int(rng.choice([1, 2, 3, 5, 7, 8, 12, 16, 20, 24, 28, 32, 40, 48, 56, 64, 96, 100, 128]))
+        nb = int(rng.integers(1, 4))
+        m = int(rng.choice([1, 2, 5, 16, 31, 32, 33, 64, 100, 770, 900])) if d <= 2100 else int(rng.choice([1, 3, 32, 40]))
+        if m > 700 and d > 1100:
+            nb = 1
+        shapes.append((d, nb * k, m, k, bool(rng.integers(0, 2))))
+    return shapes
+
+
+@pytest.mark.parametrize("d,n,m,k,transpose", _random_shapes(48, seed=20260927))
+def test_fasth_random_shapes(d, n, m, k, transpose):
+    _say(f"fasth random d={d} n={n} m={m} k={k} transpose={transpose}")
+    p = synthetic.householder_problem(d, n, m, seed=12000 + d + n + m + k)
+    A, dV, dX = gpu_fasth(p["V"], p["X"], p["G"], k, transpose)
+    A0, dV0, dX0 = orc.product_gradients(p["V"], p["X"], p["G"], transpose=transpose)
+    assert rel_err(A, A0) <= REL_TOL
+    assert rel_err(dX, dX0) <= REL_TOL
+    assert rel_err(dV, dV0) <= REL_TOL
+
+
 @pytest.mark.parametrize("name", ["d64_m32_k32", "d256_m32_k32", "d1024_m32_k32",
                                   "d2048_m64_k32", "d2048_m64_k64", "d2048_m64_k128"])
 def test_fasth_benchmark_configs(name):
