@@ -329,6 +329,33 @@ def test_svd_layer_benchmark_config(inverse):
     assert max(errs.values()) <= REL_TOL
 
 
+def _random_layer_shapes(count, seed):
+    rng = np.random.default_rng(seed)
+    shapes = []
+    for _ in range(count):
+        d = int(rng.choice([rng.integers(4, 64), rng.integers(64, 600), rng.integers(600, 1500)]))
+        if rng.random() < 0.7:
+            d = max(4, d // 4 * 4)
+        k = int(rng.choice([1, 3, 8, 12, 16, 24, 32, 48, 64]))
+        nb = int(rng.integers(1, 3))
+        m = int(rng.choice([1, 5, 32, 33, 100, 800]))
+        shapes.append((d, nb * k, m, k, bool(rng.integers(0, 2))))
+    return shapes
+
+
+@pytest.mark.parametrize("d,n,m,k,inverse", _random_layer_shapes(16, seed=20260928))
+def test_svd_layer_random_shapes(d, n, m, k, inverse):
+    """Every chain-kernel family under the layer: fused diagonal factor, gradient of sigma riding along or launched
+    on its own, both factors' launches shared or separate."""
+    _say(f"svd layer random d={d} n={n} m={m} k={k} inverse={inverse}")
+    p = synthetic.svd_layer_problem(d, n, m, seed=13000 + d + n + m + k)
+    got = gpu_svd_layer(p["Uv"], p["sigma"], p["Vv"], p["X"], p["G"], k, inverse)
+    fn = orc.svd_layer_inverse_gradients if inverse else orc.svd_layer_gradients
+    ref = fn(p["Uv"], p["sigma"], p["Vv"], p["X"], p["G"])
+    for name, g, r in zip(("Y", "dUv", "dsigma", "dVv", "dX"), got, ref):
+        assert rel_err(g, r) <= REL_TOL, (name, rel_err(g, r))
+
+
 def test_svd_layer_inverse_round_trip():
     """Table 1: W^-1 (W X) = X."""
     import torch
