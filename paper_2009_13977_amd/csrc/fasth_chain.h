@@ -1,5 +1,5 @@
 // Algorithm 1 Step 2 and Algorithm 2 Step 1: the sequential block chain (chain_pipe_kernel, chain_tile_kernel,
-// chain_stream_kernel, chain_kernel) and its launcher.
+// chain_kernel) and its launcher.
 // Included by fasth.hip, the library's single translation unit.
 #pragma once
 #include <hip/hip_runtime.h>
@@ -239,7 +239,11 @@ struct PipeRegs {
 // (0: taken from p.sub at run time). PAD: k is not a multiple of K, so a block's last step has fewer than K
 // rows; the missing rows repeat the last one and their inner products and coefficients are forced to zero.
 // RL: rows of the next block fetched during the reduction; P1: during the first product (0: half of the rest).
-template <int K, int VW, int NT, int RL = 0, int SUB = 1, bool PAD = false, int P1 = 0>
+// UNAL: d is not a multiple of VW, so rows are not 16-byte aligned and the last chunk of a row hangs over its end.
+// Rows are then fetched through a buffer that spans V (4-byte alignment is enough for it, and what lies beyond V
+// reads as zero); the overhanging elements see the next row's values, so they are put back to zero after every
+// update and never stored.
+template <int K, int VW, int NT, int RL = 0, int SUB = 1, bool PAD = false, int P1 = 0, bool UNAL = false>
 __global__ void __launch_bounds__(NT) chain_pipe_kernel(ChainArgs p) {
   typedef PipeRegs<K, VW, NT> Regs;
   constexpr int NW = NT / 64, G = Regs::G, LPT = Regs::LPT;
@@ -278,6 +282,9 @@ __global__ void __launch_bounds__(NT) chain_pipe_kernel(ChainArgs p) {
   const bool ok = VW * tid < d;
   const unsigned x0 = ok ? VW * tid : 0;
   Chunk<VW> a = load_column_chunk<VW>(p, col, x0, ok);
+  bool keep[VW];  // elements of this thread's chunk that exist
+#pragma unroll
+  for (int r = 0; r < VW; ++r) keep[r] = ok && (!UNAL || x0 + r < (unsigned)d);
   const int sel = reduce_sel<K>(lane);
   auto block_of = [&](int s) { return p.transpose ? s : nb - 1 - s; };
   const int sub = SUB > 0 ? SUB : p.sub;
@@ -293,6 +300,19 @@ __global__ void __launch_bounds__(NT) chain_pipe_kernel(ChainArgs p) {
       return p.V + ((size_t)i * K + j) * (size_t)d + x0;
     }
   };
+  const BufferDesc vdesc = make_buffer(p.V, UNAL ? (size_t)p.n * d * sizeof(float) : 0);
+  auto load_row = [&](int i, int j) {
+    if constexpr (UNAL) {
+      const unsigned row = (unsigned)(step_block(i) * p.k + step_part(i) * K + (PAD ? min(j, rows_valid(i) - 1) : j));
+      const BufVec<VW> v = buffer_load<VW>(vdesc, x0 * 4u, row * (unsigned)d * 4u);
+      Chunk<VW> c;
+#pragma unroll
+      for (int r = 0; r < VW; ++r) c.e[r] = v.e[r];
+      return c;
+    } else {
+      return load_chunk<VW>(row_ptr(i, j));
+    }
+  };
   auto load_t = [&](int i, Regs& r) {
     const int LDT = (SUB > 0 && K * SUB >= 16) ? K * SUB : p.kp;  // row stride of the stored factor
     const float* Ti = p.T + (size_t)step_block(i) * LDT * LDT + (size_t)step_part(i) * (K * LDT + K);
@@ -306,14 +326,22 @@ __global__ void __launch_bounds__(NT) chain_pipe_kernel(ChainArgs p) {
 
   // Applies block i held in `cur` while fetching block inext into `nxt`.
   auto apply_block = [&](int i, Regs& cur, int inext, Regs& nxt) {
-    if (p.save_in && ok && (SUB == 1 || step_part(i) == (p.transpose ? 0 : sub - 1)))
-      store_chunk<VW>(p.save_in + ((size_t)step_block(i) * m + col) * d + x0, a);
+    if (p.save_in && ok && (SUB == 1 || step_part(i) == (p.transpose ? 0 : sub - 1))) {
+      float* dst = p.save_in + ((size_t)step_block(i) * m + col) * d + x0;
+      if constexpr (UNAL) {
+#pragma unroll
+        for (int r = 0; r < VW; ++r)
+          if (keep[r]) dst[r] = a.e[r];
+      } else {
+        store_chunk<VW>(dst, a);
+      }
+    }
     const int kv = rows_valid(i);
     float pj[K];
 #pragma unroll
     for (int j = 0; j < K; ++j) {
       if (j % S1 == 0 && j / S1 < PR) {
-        nxt.v[j / S1] = load_chunk<VW>(row_ptr(inext, j / S1));
+        nxt.v[j / S1] = load_row(inext, j / S1);
         __builtin_amdgcn_sched_barrier(0);
       }
       float acc = 0.f;
@@ -326,7 +354,7 @@ __global__ void __launch_bounds__(NT) chain_pipe_kernel(ChainArgs p) {
       auto prefetch = [&](int t) {
         if (t % 4 == 0 && t / 4 < RL) {
           __builtin_amdgcn_sched_barrier(0);
-          nxt.v[PR + t / 4] = load_chunk<VW>(row_ptr(inext, PR + t / 4));
+          nxt.v[PR + t / 4] = load_row(inext, PR + t / 4);
           __builtin_amdgcn_sched_barrier(0);
         }
       };
@@ -394,21 +422,20 @@ __global__ void __launch_bounds__(NT) chain_pipe_kernel(ChainArgs p) {
         __builtin_amdgcn_sched_barrier(0);
       }
       if (j % S2 == 0 && j / S2 < PR2) {
-        nxt.v[PR + RL + j / S2] = load_chunk<VW>(row_ptr(inext, PR + RL + j / S2));
+        nxt.v[PR + RL + j / S2] = load_row(inext, PR + RL + j / S2);
         __builtin_amdgcn_sched_barrier(0);
       }
 #pragma unroll
       for (int r = 0; r < VW; ++r) a.e[r] = fmaf(-cc[(j / CG) & 1][j % CG], cur.v[j].e[r], a.e[r]);
     }
-    if (!ok) {
 #pragma unroll
-      for (int r = 0; r < VW; ++r) a.e[r] = 0.f;
-    }
+    for (int r = 0; r < VW; ++r)
+      if (!keep[r]) a.e[r] = 0.f;
   };
 
   Regs ra, rb;
 #pragma unroll
-  for (int j = 0; j < K; ++j) ra.v[j] = load_chunk<VW>(row_ptr(block_of(0), j));
+  for (int j = 0; j < K; ++j) ra.v[j] = load_row(block_of(0), j);
   load_t(block_of(0), ra);
   int s = 0;
   for (; s + 1 < nb; s += 2) {
@@ -416,21 +443,22 @@ __global__ void __launch_bounds__(NT) chain_pipe_kernel(ChainArgs p) {
     apply_block(block_of(s + 1), rb, block_of(s + 2 < nb ? s + 2 : s + 1), ra);
   }
   if (s < nb) apply_block(block_of(s), ra, block_of(s), rb);
-  if (ok) {
 #pragma unroll
-    for (int r = 0; r < VW; ++r) p.out[(size_t)(x0 + r) * m + col] = a.e[r];
-  }
+  for (int r = 0; r < VW; ++r)
+    if (keep[r]) p.out[(size_t)(x0 + r) * m + col] = a.e[r];
 }
 
-template <int K, int VW, int NT, int RL = 0, int SUB = 1, bool PAD = false, int P1 = 0>
+template <int K, int VW, int NT, int RL = 0, int SUB = 1, bool PAD = false, int P1 = 0, bool UNAL = false>
 static int launch_chain_pipe(const ChainArgs& args, hipStream_t stream) {
   ChainArgs a = args;
   a.sub = SUB > 0 ? SUB : (args.k + K - 1) / K;
   a.nb = args.nb * a.sub;
-  if ((size_t)VW * NT < (size_t)a.d || (PAD ? a.sub * K > a.kp : a.sub * K != a.k)) return FASTH_EINVAL;
+  if ((size_t)VW * NT < (size_t)a.d || (PAD ? a.sub * K > a.kp : a.sub * K != a.k) ||
+      (UNAL ? (size_t)a.n * a.d * sizeof(float) >= kOob : a.d % VW != 0))
+    return FASTH_EINVAL;
   const int side = a.ds_out ? (a.ds_rows + NT / 64 - 1) / (NT / 64) : 0;
   prof::Scope ps_(FASTH_KERNEL_CHAIN, stream);
-  hipLaunchKernelGGL((chain_pipe_kernel<K, VW, NT, RL, SUB, PAD, P1>), dim3(a.m + side), dim3(NT), 0, stream, a);
+  hipLaunchKernelGGL((chain_pipe_kernel<K, VW, NT, RL, SUB, PAD, P1, UNAL>), dim3(a.m + side), dim3(NT), 0, stream, a);
   FASTH_HIP(hipGetLastError());
   return FASTH_OK;
 }
@@ -441,154 +469,29 @@ static int launch_chain_pipe(const ChainArgs& args, hipStream_t stream) {
 
 namespace fasth {
 
-// ---- Streaming chain kernel ----------------------------------------------------------------
-// Any k <= 128 and any d <= VW * NT. The block is too large for registers, so its rows pass
-// through them eight at a time, twice per block (once per product); the second read comes from
-// the L2. The next group of rows is fetched while the current one is used.
-template <int VW, int NT>
-__global__ void __launch_bounds__(NT) chain_stream_kernel(ChainArgs p) {
-  extern __shared__ float smem[];
-  constexpr int NW = NT / 64, R = 8;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int col = blockIdx.x, m = p.m, d = p.d, k = p.k, kp = p.kp;
-  const int LDT = kp + 4;
-  float* Ts = smem;               // [kp][LDT]: op(T_i), row-contiguous
-  float* Bpart = Ts + kp * LDT;   // [NW][kp]
-  float* Bv = Bpart + NW * kp;    // [kp]
-  float* Cpart = Bv + kp;         // [8][kp]
-  float* Cv = Cpart + 8 * kp;     // [kp]
-  const bool ok = VW * tid < d;
-  const unsigned x0 = ok ? VW * tid : 0;
-  Chunk<VW> a = load_column_chunk<VW>(p, col, x0, ok);
-  const int sel = reduce_sel<R>(lane);
-  const int ngroups = (k + R - 1) / R;
-  // matvec work split: mg threads per row of T, each over kp / mg columns
-  int mg = NT / kp < 8 ? NT / kp : 8;
-  if (mg > kp / 4) mg = kp / 4;
-  const int mrow = tid / mg, mpart = tid % mg, mlen = kp / mg;
-  for (int s = 0; s < p.nb; ++s) {
-    const int i = p.transpose ? s : p.nb - 1 - s;
-    const float* Vi = p.V + (size_t)i * k * d + x0;
-    const float* Ti = p.T + (size_t)i * kp * kp;
-    for (int idx = tid; idx < kp * kp; idx += NT) {
-      const int r = idx / kp, c = idx % kp;
-      if (p.transpose) Ts[c * LDT + r] = Ti[idx];
-      else Ts[r * LDT + c] = Ti[idx];
-    }
-    if (p.save_in && ok) store_chunk<VW>(p.save_in + ((size_t)i * m + col) * d + x0, a);
-    auto load_group = [&](int g, Chunk<VW> (&rows)[R]) {
-#pragma unroll
-      for (int jj = 0; jj < R; ++jj) {
-        const int j = min(g * R + jj, k - 1);  // rows past the block repeat its last row; their results are ignored
-        rows[jj] = load_chunk<VW>(Vi + (size_t)j * d);
-      }
-    };
-    auto dots = [&](int g, const Chunk<VW> (&rows)[R]) {
-      float pj[R];
-#pragma unroll
-      for (int jj = 0; jj < R; ++jj) {
-        float acc = 0.f;
-#pragma unroll
-        for (int r = 0; r < VW; ++r) acc = fmaf(rows[jj].e[r], a.e[r], acc);
-        pj[jj] = acc;
-      }
-      wave_reduce_multi_reg<R>(pj);
-      if ((lane & reduce_writer_mask<R>()) == 0) Bpart[wave * kp + g * R + sel] = pj[0];
-    };
-    Chunk<VW> ga[R], gb[R];
-    load_group(0, ga);
-    for (int g = 0; g < ngroups; g += 2) {
-      if (g + 1 < ngroups) load_group(g + 1, gb);
-      dots(g, ga);
-      if (g + 1 < ngroups) {
-        if (g + 2 < ngroups) load_group(g + 2, ga);
-        dots(g + 1, gb);
-      }
-    }
-    load_group(0, ga);  // first group of the second pass, in flight during the small products
-    lds_barrier();
-    if (tid < kp) {
-      float b = 0.f;
-      if (tid < k)
-        for (int w = 0; w < NW; ++w) b += Bpart[w * kp + tid];
-      Bv[tid] = b;
-    }
-    lds_barrier();
-    if (mrow < kp) {
-      const float* trow_ptr = Ts + mrow * LDT + mpart * mlen;
-      const float* bptr = Bv + mpart * mlen;
-      float c = 0.f;
-      for (int l = 0; l < mlen; l += 4) {
-        const float4 t4 = *reinterpret_cast<const float4*>(trow_ptr + l);
-        const float4 b4 = *reinterpret_cast<const float4*>(bptr + l);
-        c = fmaf(t4.x, b4.x, c); c = fmaf(t4.y, b4.y, c); c = fmaf(t4.z, b4.z, c); c = fmaf(t4.w, b4.w, c);
-      }
-      Cpart[mpart * kp + mrow] = c;
-    }
-    lds_barrier();
-    if (tid < kp) {
-      float c = 0.f;
-      for (int g = 0; g < mg; ++g) c += Cpart[g * kp + tid];
-      if (tid >= k) c = 0.f;
-      Cv[tid] = c;
-      if (p.save_c && tid < k) p.save_c[(size_t)col * p.n + (size_t)i * k + tid] = c;
-    }
-    lds_barrier();
-    auto update = [&](int g, const Chunk<VW> (&rows)[R]) {
-#pragma unroll
-      for (int jj = 0; jj < R; ++jj) {
-        const float c = Cv[g * R + jj];  // zero for rows past the block
-#pragma unroll
-        for (int r = 0; r < VW; ++r) a.e[r] = fmaf(-c, rows[jj].e[r], a.e[r]);
-      }
-    };
-    for (int g = 0; g < ngroups; g += 2) {
-      if (g + 1 < ngroups) load_group(g + 1, gb);
-      update(g, ga);
-      if (g + 1 < ngroups) {
-        if (g + 2 < ngroups) load_group(g + 2, ga);
-        update(g + 1, gb);
-      }
-    }
-    if (!ok) {
-#pragma unroll
-      for (int r = 0; r < VW; ++r) a.e[r] = 0.f;
-    }
-    lds_barrier();  // Ts, Bpart and Cv are rewritten by the next block
-  }
-  if (ok) {
-#pragma unroll
-    for (int r = 0; r < VW; ++r) p.out[(size_t)(x0 + r) * m + col] = a.e[r];
-  }
+// chain_pipe_kernel serves every d up to 4096 (rows that are not 16-byte aligned go through a buffer, whose offsets
+// are 32 bits wide); it also takes the side product along.
+static bool chain_uses_pipe(const ChainArgs& a) {
+  return !chain_uses_tile(a) && a.d <= 4096 && (a.d % 4 == 0 || (size_t)a.n * a.d * sizeof(float) < kOob);
 }
-
-template <int VW, int NT>
-static int launch_chain_stream(const ChainArgs& a, hipStream_t stream) {
-  const size_t lds = sizeof(float) * ((size_t)a.kp * (a.kp + 4) + (size_t)(NT / 64) * a.kp + 10 * (size_t)a.kp);
-  int rc = allow_lds(chain_stream_kernel<VW, NT>, lds);
-  if (rc != FASTH_OK) return rc;
-  prof::Scope ps_(FASTH_KERNEL_CHAIN, stream);
-  hipLaunchKernelGGL((chain_stream_kernel<VW, NT>), dim3(a.m), dim3(NT), lds, stream, a);
-  FASTH_HIP(hipGetLastError());
-  return FASTH_OK;
-}
-
-template <int VW>
-static int launch_chain_stream_vw(const ChainArgs& a, hipStream_t stream) {
-  const int chunks = a.d / VW;
-  if (chunks <= 256) return launch_chain_stream<VW, 256>(a, stream);
-  if (chunks <= 512) return launch_chain_stream<VW, 512>(a, stream);
-  return launch_chain_stream<VW, 1024>(a, stream);
-}
-
-static bool chain_takes_side_product(const ChainArgs& a) {
-  return !chain_uses_tile(a) && a.d % 4 == 0 && a.d <= 4096;
-}
+static bool chain_takes_side_product(const ChainArgs& a) { return chain_uses_pipe(a); }
 
 static int launch_chain_kernel(const ChainArgs& a, hipStream_t stream) {
   const int d = a.d, k = a.k;
   if (chain_uses_tile(a)) return launch_chain_tile(a, stream);
-  if (chain_takes_side_product(a)) {  // every launch in this branch is a chain_pipe_kernel
+  if (chain_uses_pipe(a) && d % 4 != 0) {
+    // rows not 16-byte aligned: the general form of the kernel (any block size, short last step)
+    if (d <= 1024) {
+      if (k <= 8) return launch_chain_pipe<8, 4, 256, 2, 0, true, 0, true>(a, stream);
+      if (k <= 16) return launch_chain_pipe<16, 4, 256, 4, 0, true, 0, true>(a, stream);
+      return launch_chain_pipe<32, 4, 256, 8, 0, true, 0, true>(a, stream);
+    } else if (d <= 2048) {
+      if (k <= 8) return launch_chain_pipe<8, 4, 512, 2, 0, true, 0, true>(a, stream);
+      return launch_chain_pipe<16, 4, 512, 4, 0, true, 0, true>(a, stream);
+    }
+    return launch_chain_pipe<8, 4, 1024, 2, 0, true, 0, true>(a, stream);
+  }
+  if (chain_uses_pipe(a)) {
     // whole block in registers, two copies; a quarter of the next block is fetched during the reduction
     if (k == 16 && d <= 256) return launch_chain_pipe<16, 1, 256, 4>(a, stream);  // narrower lanes keep all four waves busy
     if (k == 16 && d <= 512) return launch_chain_pipe<16, 2, 256, 4>(a, stream);
@@ -632,8 +535,7 @@ static int launch_chain_kernel(const ChainArgs& a, hipStream_t stream) {
       return launch_chain_pipe<8, 4, 1024, 2, 0, true>(a, stream);
     }
   }
-  if (d % 2 == 0 && d <= 2048) return launch_chain_stream_vw<2>(a, stream);
-  if (d <= 1024) return launch_chain_stream_vw<1>(a, stream);
+  // longer vectors (or a V of 2 GiB and more with unaligned rows): the general kernel
   int threads = 256;
   if (d > 256 * 8) threads = 512;
   if (d > 512 * 8) threads = 1024;

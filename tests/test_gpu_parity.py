@@ -48,9 +48,9 @@ def test_fasth_small_cases(d, n, m, k, transpose):
 
 # One case per chain-kernel variant the launcher can pick: blocks held in registers and applied whole or
 # as steps of 8, 16 or 32 rows (with a short last step when k is not a multiple of the step), at every
-# workgroup size including shapes that leave whole waves without work, the streaming kernel at the
-# narrower vector widths, and the generic kernel for very long vectors. Few reflections and columns
-# keep the checker fast.
+# workgroup size including shapes that leave whole waves without work, vector lengths that are not a
+# multiple of 4 (rows not 16-byte aligned, last chunk hanging over the row's end), and the general
+# kernel for very long vectors. Few reflections and columns keep the checker fast.
 DISPATCH = [
     (1024, 32, 3, 16), (2048, 32, 3, 16),
     (256, 64, 3, 32), (512, 64, 3, 32), (1024, 96, 3, 32), (2048, 64, 3, 32), (1500, 64, 3, 32),
