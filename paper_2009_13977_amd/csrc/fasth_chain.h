@@ -13,8 +13,8 @@ namespace fasth {
 // One workgroup per column of the d x m input: columns never interact, so no workgroup waits for
 // another. Per block i:  B = V_i a,  C = op(T_i) B,  a <- a - V_i^T C,
 // op(T) = T for P_i (blocks nb..1), T^T for P_i^T (blocks 1..nb).
-// Thread t owns elements x = t + u * blockDim.x of the column. The k inner products of a block are
-// independent, which is the parallelism FastH adds over the one-at-a-time algorithm.
+// The k inner products of a block are independent, which is the parallelism FastH adds over the
+// one-at-a-time algorithm.
 // Saved for the backward pass: the input column of every block and the coefficient vector C.
 // ------------------------------------------------------------------------------------------
 
@@ -79,40 +79,55 @@ __global__ void __launch_bounds__(256) dsigma_kernel(const float* __restrict__ d
   if (row < d) dsigma_row(dZ2, Z1, sigma, dsigma, row, m, mode);
 }
 
+// General form for vectors too long for the register-resident kernels: 1024 threads, thread t owns the chunks of
+// four consecutive elements x = 4 (t + 1024 u) .. + 3, u < U, so a wave fetches 1 KiB of a row at a time. A block's
+// rows pass through the registers twice, once per product (the second time from the cache). Rows are fetched
+// through a buffer descriptor spanning the block, so any d works: 4-byte alignment is enough for it, what lies
+// beyond the block reads as zero, and elements of a row's last chunk that hang over the row's end are masked.
 template <int U>
 __global__ void __launch_bounds__(1024) chain_kernel(ChainArgs p) {
   extern __shared__ float smem[];
-  const int nthreads = blockDim.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nw = nthreads >> 6;
+  constexpr int NT = 1024, NW = NT / 64;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int col = blockIdx.x;
   const int d = p.d, k = p.k, kp = p.kp, m = p.m;
   const int LDT = kp + 1;
   float* Ts = smem;               // [kp][LDT]
-  float* Bpart = Ts + kp * LDT;   // [nw][kp]
-  float* Bv = Bpart + nw * kp;    // [kp]
+  float* Bpart = Ts + kp * LDT;   // [NW][kp]
+  float* Bv = Bpart + NW * kp;    // [kp]
   float* Cv = Bv + kp;            // [kp]
-  float a[U];
+  float a[U][4];
+  unsigned off[U];  // byte offset of chunk u within a row, or beyond every buffer if the chunk does not exist
 #pragma unroll
   for (int u = 0; u < U; ++u) {
-    const int x = tid + u * nthreads;
-    float v = 0.f;
-    if (x < d && x < p.in_rows) {
-      v = p.in[(size_t)x * m + col];
-      if (p.in_scale_mode) v *= diag_factor(p.in_scale_mode, p.in_scale[x]);
+    const int x0 = 4 * (tid + u * NT);
+    off[u] = x0 < d ? (unsigned)x0 * 4u : kOob;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int x = x0 + r;
+      float v = 0.f;
+      if (x < d && x < p.in_rows) {
+        v = p.in[(size_t)x * m + col];
+        if (p.in_scale_mode) v *= diag_factor(p.in_scale_mode, p.in_scale[x]);
+      }
+      a[u][r] = v;
     }
-    a[u] = v;
   }
   const int sel = reduce_sel<8>(lane);
   for (int s = 0; s < p.nb; ++s) {
     const int i = p.transpose ? s : p.nb - 1 - s;
-    const float* Vi = p.V + (size_t)i * k * d;
+    const BufferDesc vdesc = make_buffer(p.V + (size_t)i * k * d, (size_t)k * d * sizeof(float));
     const float* Ti = p.T + (size_t)i * kp * kp;
-    for (int idx = tid; idx < kp * kp; idx += nthreads) Ts[(idx / kp) * LDT + idx % kp] = Ti[idx];
+    for (int idx = tid; idx < kp * kp; idx += NT) Ts[(idx / kp) * LDT + idx % kp] = Ti[idx];
     if (p.save_in) {
       float* dst = p.save_in + ((size_t)i * m + col) * d;
 #pragma unroll
       for (int u = 0; u < U; ++u) {
-        const int x = tid + u * nthreads;
-        if (x < d) dst[x] = a[u];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int x = 4 * (tid + u * NT) + r;
+          if (x < d) dst[x] = a[u][r];
+        }
       }
     }
     for (int j0 = 0; j0 < k; j0 += 8) {
@@ -120,23 +135,23 @@ __global__ void __launch_bounds__(1024) chain_kernel(ChainArgs p) {
 #pragma unroll
       for (int jj = 0; jj < 8; ++jj) {
         pj[jj] = 0.f;
-        if (j0 + jj < k) {
-          const float* vr = Vi + (size_t)(j0 + jj) * d;
+        // rows past the block lie beyond the buffer and read as zero
+        const unsigned row_off = (unsigned)(j0 + jj) * (unsigned)d * 4u;
 #pragma unroll
-          for (int u = 0; u < U; ++u) {
-            const int x = tid + u * nthreads;
-            if (x < d) pj[jj] += vr[x] * a[u];
-          }
+        for (int u = 0; u < U; ++u) {
+          const BufVec<4> v = buffer_load<4>(vdesc, off[u], row_off);
+#pragma unroll
+          for (int r = 0; r < 4; ++r) pj[jj] = fmaf(v.e[r], a[u][r], pj[jj]);  // a is zero where the chunk hangs over
         }
       }
       wave_reduce_multi<8>(pj);
-      if ((lane & reduce_writer_mask<8>()) == 0) Bpart[wave * kp + j0 + sel] = pj[0];
+      if ((lane & reduce_writer_mask<8>()) == 0 && j0 + sel < kp) Bpart[wave * kp + j0 + sel] = pj[0];
     }
     __syncthreads();
     if (tid < kp) {
       float b = 0.f;
       if (tid < k)
-        for (int w = 0; w < nw; ++w) b += Bpart[w * kp + tid];
+        for (int w = 0; w < NW; ++w) b += Bpart[w * kp + tid];
       Bv[tid] = b;
     }
     __syncthreads();
@@ -153,18 +168,29 @@ __global__ void __launch_bounds__(1024) chain_kernel(ChainArgs p) {
     __syncthreads();
     for (int j = 0; j < k; ++j) {
       const float c = Cv[j];
-      const float* vr = Vi + (size_t)j * d;
+      const unsigned row_off = (unsigned)j * (unsigned)d * 4u;
 #pragma unroll
       for (int u = 0; u < U; ++u) {
-        const int x = tid + u * nthreads;
-        if (x < d) a[u] -= c * vr[x];
+        const BufVec<4> v = buffer_load<4>(vdesc, off[u], row_off);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) a[u][r] = fmaf(-c, v.e[r], a[u][r]);
       }
+    }
+    // elements beyond d have just seen the next row's values: back to zero
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+        if (4 * (tid + u * NT) + r >= d) a[u][r] = 0.f;
     }
   }
 #pragma unroll
   for (int u = 0; u < U; ++u) {
-    const int x = tid + u * nthreads;
-    if (x < d) p.out[(size_t)x * m + col] = a[u];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int x = 4 * (tid + u * NT) + r;
+      if (x < d) p.out[(size_t)x * m + col] = a[u][r];
+    }
   }
 }
 
@@ -536,11 +562,8 @@ static int launch_chain_kernel(const ChainArgs& a, hipStream_t stream) {
     }
   }
   // longer vectors (or a V of 2 GiB and more with unaligned rows): the general kernel
-  int threads = 256;
-  if (d > 256 * 8) threads = 512;
-  if (d > 512 * 8) threads = 1024;
-  const int per = (d + threads - 1) / threads;
-  const int nw = threads / 64;
+  const int threads = 1024, nw = threads / 64;
+  const int per = (d + 4 * threads - 1) / (4 * threads);  // chunks of four elements per thread
   const size_t lds = sizeof(float) * ((size_t)a.kp * (a.kp + 1) + (size_t)nw * a.kp + 2 * a.kp);
   dim3 grid(a.m), block(threads);
 #define FASTH_LAUNCH_CHAIN(UU)                                                   \
@@ -550,11 +573,11 @@ static int launch_chain_kernel(const ChainArgs& a, hipStream_t stream) {
     prof::Scope ps_(FASTH_KERNEL_CHAIN, stream);                                 \
     hipLaunchKernelGGL(chain_kernel<UU>, grid, block, lds, stream, a);           \
   } while (0)
+  if (per > 4) return FASTH_EUNSUPPORTED;  // d > 16384: check_shape refuses it before
   if (per <= 1) FASTH_LAUNCH_CHAIN(1);
   else if (per <= 2) FASTH_LAUNCH_CHAIN(2);
-  else if (per <= 4) FASTH_LAUNCH_CHAIN(4);
-  else if (per <= 8) FASTH_LAUNCH_CHAIN(8);
-  else FASTH_LAUNCH_CHAIN(16);
+  else if (per == 3) FASTH_LAUNCH_CHAIN(3);
+  else FASTH_LAUNCH_CHAIN(4);
 #undef FASTH_LAUNCH_CHAIN
   FASTH_HIP(hipGetLastError());
   return FASTH_OK;

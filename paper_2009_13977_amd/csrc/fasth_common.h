@@ -20,7 +20,7 @@ namespace fasth {
 // ------------------------------------------------------------------------------------------
 
 constexpr int kMaxBlock = 128;     // largest k: a k x k factor must fit in LDS with scratch
-constexpr int kMaxD = 16384;       // chain kernel: 1024 threads x 16 elements
+constexpr int kMaxD = 16384;       // general chain kernel: 1024 threads x 4 chunks of 4 elements
 constexpr int kGramChunk = 128;    // columns of V per LDS tile in the Gram kernel
 constexpr int kMaxGramSplit = 16;  // partial Gram matrices per block
 constexpr int kDvTile = 64;        // columns of dV per workgroup
