@@ -163,6 +163,8 @@ static DvArgs dv_args(const Product& P, const float* V, float* dV, int transpose
   a.accumulate = accumulate ? 1 : 0;
   a.V = V; a.saveA = P.saveA(); a.saveCa = P.saveCa(); a.saveG = P.saveG(); a.saveCg = P.saveCg(); a.dV = dV;
   a.Z = P.Spart();  // the partial Gram matrices are dead once the factors exist; Z needs nb kp^2 of their floats
+  a.msplit = P.L.dv_split;
+  a.dVpart = reinterpret_cast<float*>(P.ws + P.L.off_dVpart);
   a.d = P.d; a.n = P.n; a.m = P.m; a.k = P.k; a.kp = P.L.kp; a.transpose = transpose;
   return a;
 }
@@ -174,13 +176,17 @@ static int launch_dv(const DvPair& pair, int count, int kp, bool vec4, hipStream
     xt = std::max(xt, (pair.a[1].d + kDvTile - 1) / kDvTile);
     nb = std::max(nb, pair.a[1].n / pair.a[1].k);
   }
-  const dim3 grid(xt, nb, count);
+  const DvArgs& a0 = pair.a[0];
+  const int msplit = a0.msplit;  // the same for both products of a launch (run_dv_pair checks)
+  const dim3 grid(xt, nb, count * msplit);
   // Many columns and blocks of 64 rows or more: Z of every block once, by a launch of its own (measured at
   // d = n = 1024, m = 4096: dV 374 -> 326 us at k = 64, 853 -> 545 us at k = 128, but 294 -> 309 us at k = 32, where
   // the rebuild is a fifth of the work). Same condition for both products of a pair: they share m and k.
-  const DvArgs& a0 = pair.a[0];
-  const bool prez = a0.k >= 64 && (size_t)a0.m * a0.k >= 32768 && (size_t)a0.m * a0.n * sizeof(float) < kOob && a0.Z != nullptr &&
-                    (count == 1 || (pair.a[1].m == a0.m && pair.a[1].k == a0.k && pair.a[1].Z != nullptr));
+  // A split mini-batch needs it too: no workgroup sees all columns.
+  const bool z_fits = (size_t)a0.m * a0.n * sizeof(float) < kOob && a0.Z != nullptr &&
+                      (count == 1 || (pair.a[1].m == a0.m && pair.a[1].k == a0.k && pair.a[1].Z != nullptr));
+  if (msplit > 1 && !z_fits) return FASTH_EINVAL;  // cannot happen: a split is only chosen for small n d
+  const bool prez = z_fits && (msplit > 1 || (a0.k >= 64 && (size_t)a0.m * a0.k >= 32768));
   prof::Scope ps_(FASTH_KERNEL_DV, stream);
   if (prez) {
     const int kt = kp / 16;
@@ -209,6 +215,12 @@ static int launch_dv(const DvPair& pair, int count, int kp, bool vec4, hipStream
 #undef FASTH_LAUNCH_DV
 #undef FASTH_LAUNCH_DV_
   FASTH_HIP(hipGetLastError());
+  if (msplit > 1) {
+    size_t nd = (size_t)a0.n * a0.d;
+    if (count == 2) nd = std::max(nd, (size_t)pair.a[1].n * pair.a[1].d);
+    hipLaunchKernelGGL(dv_sum_kernel, dim3((unsigned)((nd + 255) / 256), count), dim3(256), 0, stream, pair);
+    FASTH_HIP(hipGetLastError());
+  }
   return FASTH_OK;
 }
 
@@ -223,7 +235,7 @@ static int run_dv(const Product& P, const float* V, float* dV, int transpose, hi
 // arguments; otherwise one after the other.
 static int run_dv_pair(const Product& P0, const float* V0, float* dV0, int transpose0, const Product& P1,
                        const float* V1, float* dV1, int transpose1, hipStream_t stream) {
-  if (P0.L.kp == P1.L.kp && (P0.d % 4 == 0) == (P1.d % 4 == 0)) {
+  if (P0.L.kp == P1.L.kp && (P0.d % 4 == 0) == (P1.d % 4 == 0) && P0.L.dv_split == P1.L.dv_split) {
     DvPair pair;
     pair.a[0] = dv_args(P0, V0, dV0, transpose0, false);
     pair.a[1] = dv_args(P1, V1, dV1, transpose1, false);

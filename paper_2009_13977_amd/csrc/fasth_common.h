@@ -35,9 +35,21 @@ static int padded_block(int k) {
 }
 
 struct Layout {
-  int kp, nb, gram_split;
-  size_t off_T, off_Spart, off_saveA, off_saveCa, off_saveG, off_saveCg, total;
+  int kp, nb, gram_split, dv_split;
+  size_t off_T, off_Spart, off_saveA, off_saveCa, off_saveG, off_saveCg, off_dVpart, total;
 };
+
+// The dV kernel has one workgroup per (64-column tile of dV, block). When that is too few to fill the chip and the
+// mini-batch is wide (a short, narrow V against many columns: a 1 x 1 convolution with few channels), the
+// mini-batch is split over up to 32 workgroups whose partial sums meet in a buffer of the workspace.
+static int dv_minibatch_split(int d, int n, int m, int k) {
+  const int wgs = ((d + kDvTile - 1) / kDvTile) * (n / k);
+  if (wgs >= 128 || m < 256) return 1;
+  int split = 256 / wgs;
+  if (split > m / 128) split = m / 128;
+  if (split > 32) split = 32;
+  return split < 1 ? 1 : split;
+}
 
 static Layout make_layout(int d, int n, int m, int k) {
   Layout L;
@@ -57,6 +69,8 @@ static Layout make_layout(int d, int n, int m, int k) {
   L.off_saveCa = take((size_t)m * n);
   L.off_saveG = take((size_t)L.nb * m * d);
   L.off_saveCg = take((size_t)m * n);
+  L.dv_split = dv_minibatch_split(d, n, m, k);
+  L.off_dVpart = take(L.dv_split > 1 ? (size_t)L.dv_split * n * d : 0);
   L.total = off;
   return L;
 }

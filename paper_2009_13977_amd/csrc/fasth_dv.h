@@ -28,6 +28,8 @@ struct DvArgs {
   const float* saveCg;  // [m][n]
   float* dV;            // [n][d]
   float* Z;             // [nb][kp][kp]: Z = Cg Ca^T per block when it is formed by dv_z_kernel
+  float* dVpart;        // [msplit][n][d]: partial sums when the mini-batch is split over workgroups
+  int msplit;           // workgroups per (tile, block) along the mini-batch; 1: no split
   int d, n, m, k, kp;
   int transpose;        // of the forward product
   int accumulate;       // add to dV instead of overwriting it (a factor that enters a layer twice)
@@ -84,9 +86,14 @@ template <int KT, int VEC, bool PREZ>  // kp = 16 KT; VEC = 4 when d is a multip
 __global__ void __launch_bounds__(256) dv_kernel(DvPair pair) {
   extern __shared__ __align__(16) float smem[];
   constexpr int kp = 16 * KT;
-  const DvArgs p = pair.a[blockIdx.z];
+  // blockIdx.z = product * msplit + part of the mini-batch (msplit is the same for both products of a launch)
+  const int msplit = pair.a[0].msplit, part = (int)blockIdx.z % msplit;
+  const DvArgs p = pair.a[blockIdx.z / msplit];
   const int k = p.k, d = p.d, m = p.m, n = p.n;
   if ((int)blockIdx.y * k >= n || (int)blockIdx.x * kDvTile >= d) return;  // whole workgroup, before any barrier
+  // this workgroup's columns: whole chunks of kDvMChunk
+  const int cols_per_part = ((m + msplit - 1) / msplit + kDvMChunk - 1) / kDvMChunk * kDvMChunk;
+  const int m_begin = part * cols_per_part, m_end = min(m, m_begin + cols_per_part);
   constexpr int LDE = kp + 4, LDC = kDvMChunk + 4, LDX = kDvTile + 4;
   float* Es = smem;                   // [kp][LDE]
   float* Cas = Es + kp * LDE;         // [kp][LDC]
@@ -154,7 +161,7 @@ __global__ void __launch_bounds__(256) dv_kernel(DvPair pair) {
     }
   };
   Chunk cur;
-  fetch(0, cur);
+  fetch(m_begin < m ? m_begin : 0, cur);
 #pragma unroll
   for (int it = 0; it < V_PER; ++it) {
     const int idx = tid + it * 256;
@@ -179,11 +186,11 @@ __global__ void __launch_bounds__(256) dv_kernel(DvPair pair) {
   for (int w = 0; w < kMaxZ; ++w) z[w] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int w = 0; w < kMaxAcc; ++w) acc[w] = acc2[w] = f32x4{0.f, 0.f, 0.f, 0.f};
-  for (int mc = 0; mc < m; mc += kDvMChunk) {
-    if (mc) __syncthreads();
+  for (int mc = m_begin; mc < m_end; mc += kDvMChunk) {
+    if (mc > m_begin) __syncthreads();
     to_lds(cur);
     __syncthreads();
-    if (mc + kDvMChunk < m) fetch(mc + kDvMChunk, cur);  // in flight during this chunk's products
+    if (mc + kDvMChunk < m_end) fetch(mc + kDvMChunk, cur);  // in flight during this chunk's products
     if constexpr (!PREZ) {
 #pragma unroll
       for (int w = 0; w < kMaxZ; ++w) {
@@ -256,18 +263,32 @@ __global__ void __launch_bounds__(256) dv_kernel(DvPair pair) {
     if (t < kt * 4) {
       const int ti = t / 4, tx = t % 4;
       f32x4 ev = {0.f, 0.f, 0.f, 0.f};
-      ev = tile_mma(Es + ti * 16 * LDE, LDE, 1, Vs + tx * 16, LDX, 1, kp, ev);
+      if (part == 0) ev = tile_mma(Es + ti * 16 * LDE, LDE, 1, Vs + tx * 16, LDX, 1, kp, ev);  // E V_i enters once
 #pragma unroll
       for (int jj = 0; jj < 4; ++jj) {
         const int j = ti * 16 + 4 * q + jj, x = x0 + tx * 16 + li;
         if (j < k && x < d) {
-          float* dst = p.dV + ((size_t)i * k + j) * d + x;
           const float val = ev[jj] - acc[w][jj];
-          *dst = p.accumulate ? *dst + val : val;
+          if (msplit > 1) {
+            p.dVpart[((size_t)part * n + (size_t)i * k + j) * d + x] = val;  // summed by dv_sum_kernel
+          } else {
+            float* dst = p.dV + ((size_t)i * k + j) * d + x;
+            *dst = p.accumulate ? *dst + val : val;
+          }
         }
       }
     }
   }
+}
+
+// dV = sum of the mini-batch parts (fixed order), for up to two products: blockIdx.y picks the product.
+__global__ void __launch_bounds__(256) dv_sum_kernel(DvPair pair) {
+  const DvArgs p = pair.a[blockIdx.y];
+  const size_t nd = (size_t)p.n * p.d, idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= nd) return;
+  float sum = p.dVpart[idx];
+  for (int part = 1; part < p.msplit; ++part) sum += p.dVpart[(size_t)part * nd + idx];
+  p.dV[idx] = p.accumulate ? p.dV[idx] + sum : sum;
 }
 
 static size_t dv_lds(int kp) {
