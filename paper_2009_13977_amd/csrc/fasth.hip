@@ -164,6 +164,7 @@ static DvArgs dv_args(const Product& P, const float* V, float* dV, int transpose
   a.V = V; a.saveA = P.saveA(); a.saveCa = P.saveCa(); a.saveG = P.saveG(); a.saveCg = P.saveCg(); a.dV = dV;
   a.Z = P.Spart();  // the partial Gram matrices are dead once the factors exist; Z needs nb kp^2 of their floats
   a.msplit = P.L.dv_split;
+  a.cols_per_part = ((P.m + a.msplit - 1) / a.msplit + kDvMChunk - 1) / kDvMChunk * kDvMChunk;
   a.dVpart = reinterpret_cast<float*>(P.ws + P.L.off_dVpart);
   a.d = P.d; a.n = P.n; a.m = P.m; a.k = P.k; a.kp = P.L.kp; a.transpose = transpose;
   return a;

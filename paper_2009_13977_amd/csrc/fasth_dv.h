@@ -30,6 +30,7 @@ struct DvArgs {
   float* Z;             // [nb][kp][kp]: Z = Cg Ca^T per block when it is formed by dv_z_kernel
   float* dVpart;        // [msplit][n][d]: partial sums when the mini-batch is split over workgroups
   int msplit;           // workgroups per (tile, block) along the mini-batch; 1: no split
+  int cols_per_part;    // columns per such workgroup, a multiple of the chunk of 32 (m rounded up if msplit = 1)
   int d, n, m, k, kp;
   int transpose;        // of the forward product
   int accumulate;       // add to dV instead of overwriting it (a factor that enters a layer twice)
@@ -87,13 +88,13 @@ __global__ void __launch_bounds__(256) dv_kernel(DvPair pair) {
   extern __shared__ __align__(16) float smem[];
   constexpr int kp = 16 * KT;
   // blockIdx.z = product * msplit + part of the mini-batch (msplit is the same for both products of a launch)
-  const int msplit = pair.a[0].msplit, part = (int)blockIdx.z % msplit;
-  const DvArgs p = pair.a[blockIdx.z / msplit];
+  // (a launch has at most two products, so the product index needs no division)
+  const int msplit = pair.a[0].msplit, which = (int)blockIdx.z >= msplit ? 1 : 0, part = (int)blockIdx.z - which * msplit;
+  const DvArgs p = pair.a[which];
   const int k = p.k, d = p.d, m = p.m, n = p.n;
   if ((int)blockIdx.y * k >= n || (int)blockIdx.x * kDvTile >= d) return;  // whole workgroup, before any barrier
-  // this workgroup's columns: whole chunks of kDvMChunk
-  const int cols_per_part = ((m + msplit - 1) / msplit + kDvMChunk - 1) / kDvMChunk * kDvMChunk;
-  const int m_begin = part * cols_per_part, m_end = min(m, m_begin + cols_per_part);
+  // this workgroup's columns: whole chunks of kDvMChunk (cols_per_part comes from the host)
+  const int m_begin = part * p.cols_per_part, m_end = min(m, m_begin + p.cols_per_part);
   constexpr int LDE = kp + 4, LDC = kDvMChunk + 4, LDX = kDvTile + 4;
   float* Es = smem;                   // [kp][LDE]
   float* Cas = Es + kp * LDE;         // [kp][LDC]
