@@ -62,9 +62,10 @@ const char* fasth_strerror(int code);
 
 /* Bytes of device workspace fasth_forward / fasth_backward need for `shape`
  * (block factors T_i, partial Gram matrices, the saved block inputs A_{i+1}
- * of Algorithm 1's Remark, the saved gradients dL/dA_i of Algorithm 2 Step 1
- * and the small per-block coefficient vectors). Returns 0 if the shape is
- * invalid or unsupported. */
+ * of Algorithm 1's Remark, the saved gradients dL/dA_i of Algorithm 2 Step 1,
+ * the small per-block coefficient vectors and, for a small V against a wide
+ * mini-batch, partial sums of dV). Returns 0 if the shape is invalid or
+ * unsupported. */
 size_t fasth_workspace_bytes(const fasth_shape* shape);
 
 /* Algorithm 1. A = H X (or H^T X). Step 1 builds, for every block i, the
