@@ -283,12 +283,33 @@ def test_block_size_independence():
             assert rel_err(g, r) <= REL_TOL
 
 
-def test_bitwise_repeatable():
-    p = synthetic.householder_problem(256, 256, 32, seed=5)
-    a = gpu_fasth(p["V"], p["X"], p["G"], 32)
-    b = gpu_fasth(p["V"], p["X"], p["G"], 32)
+@pytest.mark.parametrize("d,n,m,k", [(256, 256, 32, 32), (128, 64, 1024, 32), (1024, 64, 800, 64), (1001, 48, 5, 24)])
+def test_bitwise_repeatable(d, n, m, k):
+    """Every sum runs in a fixed order (no atomics), also where the mini-batch is split over workgroups and on the
+    matrix-core chain kernel: two runs give the same bits."""
+    p = synthetic.householder_problem(d, n, m, seed=5)
+    a = gpu_fasth(p["V"], p["X"], p["G"], k)
+    b = gpu_fasth(p["V"], p["X"], p["G"], k)
     for x, y in zip(a, b):
         assert np.array_equal(x, y)
+
+
+def test_prepare_once_apply_many_wide():
+    """The same on the matrix-core chain kernel (4096 columns): factors once, H then H^T gives X back."""
+    import torch
+    from paper_2009_13977_amd import binding as B
+    from helpers import to_gpu
+    d, n, m, k = 512, 64, 4096, 32
+    p = synthetic.householder_problem(d, n, m, seed=22)
+    Vd, Xd = to_gpu(p["V"]), to_gpu(p["X"])
+    Y1 = torch.empty_like(Xd); Y2 = torch.empty_like(Xd)
+    ws = B.new_workspace(B.fasth_workspace_bytes(d, n, m, k))
+    B.fasth_prepare(Vd, m, ws, k)
+    B.fasth_apply(Vd, Xd, Y1, ws, k)
+    B.fasth_apply(Vd, Y1, Y2, ws, k, transpose=True)
+    torch.cuda.synchronize()
+    assert rel_err(Y1.cpu().numpy(), orc.product_apply(p["V"], p["X"])) <= REL_TOL
+    assert rel_err(Y2.cpu().numpy(), p["X"]) <= REL_TOL
 
 
 @pytest.mark.parametrize("transpose", [False, True])
