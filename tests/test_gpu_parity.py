@@ -134,9 +134,10 @@ def test_layers_wide_minibatch():
         ref = orc.symmetric_gradients(p["Uv"], sigma, p["X"], p["G"], function)
         for name, g, r in zip(("Y", "dUv", "dsigma", "dX"), got, ref):
             assert rel_err(g, r) <= REL_TOL, (name, rel_err(g, r))
-    for rows, cols in ((256, 192), (192, 256)):
+    # (2048, 64): the two factors differ in how the dV mini-batch is split, so their dV launches stay separate
+    for rows, cols in ((256, 192), (192, 256), (2048, 64)):
         _say(f"svd rect wide rows={rows} cols={cols}")
-        q = synthetic.rect_layer_problem(rows, cols, 32, 32, 800, seed=5300 + rows)
+        q = synthetic.rect_layer_problem(rows, cols, 32 if rows < 2048 else 128, 32, 800, seed=5300 + rows)
         got = gpu_svd_rect(q["Uv"], q["sigma"], q["Vv"], q["X"], q["G"], 16)  # k m < 32768: Z rebuilt per workgroup
         ref = orc.rectangular_gradients(q["Uv"], q["sigma"], q["Vv"], q["X"], q["G"])
         for name, g, r in zip(("Y", "dUv", "dsigma", "dVv", "dX"), got, ref):
