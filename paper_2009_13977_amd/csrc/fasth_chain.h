@@ -279,7 +279,6 @@ __global__ void __launch_bounds__(NT) chain_pipe_kernel(ChainArgs p) {
   static_assert(PR >= 1 && PR2 >= 1 && S1 >= 1 && S2 >= 1, "prefetch split");
   static_assert(K % 4 == 0 && K * G <= NT && LPT >= 1, "shape");
   static_assert(RL % 2 == 0 && RL <= K / 4 && (RL == 0 || K >= 8), "prefetch split");
-  static_assert(!PAD || SUB == 0, "ragged steps take the step count at run time");
   __shared__ __align__(16) float Bpart[NW][K];
   __shared__ __align__(16) float Cv[K];
   const int tid = threadIdx.x, lane = tid & 63;
@@ -340,7 +339,7 @@ __global__ void __launch_bounds__(NT) chain_pipe_kernel(ChainArgs p) {
     }
   };
   auto load_t = [&](int i, Regs& r) {
-    const int LDT = (SUB > 0 && K * SUB >= 16) ? K * SUB : p.kp;  // row stride of the stored factor
+    const int LDT = (SUB > 0 && !PAD && K * SUB >= 16) ? K * SUB : p.kp;  // row stride of the stored factor
     const float* Ti = p.T + (size_t)step_block(i) * LDT * LDT + (size_t)step_part(i) * (K * LDT + K);
     const int row = t_active ? trow : 0;
 #pragma unroll
@@ -479,7 +478,7 @@ static int launch_chain_pipe(const ChainArgs& args, hipStream_t stream) {
   ChainArgs a = args;
   a.sub = SUB > 0 ? SUB : (args.k + K - 1) / K;
   a.nb = args.nb * a.sub;
-  if ((size_t)VW * NT < (size_t)a.d || (PAD ? a.sub * K > a.kp : a.sub * K != a.k) ||
+  if ((size_t)VW * NT < (size_t)a.d || (PAD ? (a.sub * K > a.kp || a.sub != (a.k + K - 1) / K) : a.sub * K != a.k) ||
       (UNAL ? (size_t)a.n * a.d * sizeof(float) >= kOob : a.d % VW != 0))
     return FASTH_EINVAL;
   const int side = a.ds_out ? (a.ds_rows + NT / 64 - 1) / (NT / 64) : 0;
@@ -545,8 +544,11 @@ static int launch_chain_kernel(const ChainArgs& a, hipStream_t stream) {
       if (k == 128) return launch_chain_pipe<32, 4, 256, 8, 4, false, 10>(a, stream);
       if (k == 8) return launch_chain_pipe<8, 4, 256, 2>(a, stream);
       // any other block size: steps of 8, 16 or 32 rows, the last one of a block short
-      if (k < 8) return launch_chain_pipe<8, 4, 256, 2, 0, true>(a, stream);
-      if (k < 16) return launch_chain_pipe<16, 4, 256, 4, 0, true>(a, stream);
+      if (k < 8) return launch_chain_pipe<8, 4, 256, 2, 1, true>(a, stream);
+      if (k < 16) return launch_chain_pipe<16, 4, 256, 4, 1, true>(a, stream);
+      if (k < 32) return launch_chain_pipe<32, 4, 256, 8, 1, true, 10>(a, stream);  // one short step per block
+      if (k < 64) return launch_chain_pipe<32, 4, 256, 8, 2, true, 10>(a, stream);  // a full step and a short one
+      if (k > 96) return launch_chain_pipe<32, 4, 256, 8, 4, true, 10>(a, stream);
       return launch_chain_pipe<32, 4, 256, 8, 0, true>(a, stream);
     } else if (d <= 2048) {
       if (k == 32) return launch_chain_pipe<16, 4, 512, 4, 2, false, 5>(a, stream);  // fetch split 5 / 4 / 7
