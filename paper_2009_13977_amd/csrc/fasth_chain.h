@@ -266,9 +266,9 @@ struct PipeRegs {
 // rows; the missing rows repeat the last one and their inner products and coefficients are forced to zero.
 // RL: rows of the next block fetched during the reduction; P1: during the first product (0: half of the rest).
 // UNAL: d is not a multiple of VW, so rows are not 16-byte aligned and the last chunk of a row hangs over its end.
-// Rows are then fetched through a buffer that spans V (4-byte alignment is enough for it, and what lies beyond V
-// reads as zero); the overhanging elements see the next row's values, so they are put back to zero after every
-// update and never stored.
+// Rows are then fetched through a buffer that spans the block (4-byte alignment is enough for it, and what lies
+// beyond the block reads as zero); the overhanging elements see the next row's values, so they are put back to
+// zero after every update and never stored.
 template <int K, int VW, int NT, int RL = 0, int SUB = 1, bool PAD = false, int P1 = 0, bool UNAL = false>
 __global__ void __launch_bounds__(NT) chain_pipe_kernel(ChainArgs p) {
   typedef PipeRegs<K, VW, NT> Regs;
@@ -325,10 +325,11 @@ __global__ void __launch_bounds__(NT) chain_pipe_kernel(ChainArgs p) {
       return p.V + ((size_t)i * K + j) * (size_t)d + x0;
     }
   };
-  const BufferDesc vdesc = make_buffer(p.V, UNAL ? (size_t)p.n * d * sizeof(float) : 0);
   auto load_row = [&](int i, int j) {
     if constexpr (UNAL) {
-      const unsigned row = (unsigned)(step_block(i) * p.k + step_part(i) * K + (PAD ? min(j, rows_valid(i) - 1) : j));
+      // the buffer spans the step's block of k rows (at most 2 MiB), so V itself may be of any size
+      const BufferDesc vdesc = make_buffer(p.V + (size_t)step_block(i) * p.k * d, (size_t)p.k * d * sizeof(float));
+      const unsigned row = (unsigned)(step_part(i) * K + (PAD ? min(j, rows_valid(i) - 1) : j));
       const BufVec<VW> v = buffer_load<VW>(vdesc, x0 * 4u, row * (unsigned)d * 4u);
       Chunk<VW> c;
 #pragma unroll
@@ -479,7 +480,7 @@ static int launch_chain_pipe(const ChainArgs& args, hipStream_t stream) {
   a.sub = SUB > 0 ? SUB : (args.k + K - 1) / K;
   a.nb = args.nb * a.sub;
   if ((size_t)VW * NT < (size_t)a.d || (PAD ? (a.sub * K > a.kp || a.sub != (a.k + K - 1) / K) : a.sub * K != a.k) ||
-      (UNAL ? (size_t)a.n * a.d * sizeof(float) >= kOob : a.d % VW != 0))
+      (!UNAL && a.d % VW != 0))
     return FASTH_EINVAL;
   const int side = a.ds_out ? (a.ds_rows + NT / 64 - 1) / (NT / 64) : 0;
   prof::Scope ps_(FASTH_KERNEL_CHAIN, stream);
@@ -494,11 +495,8 @@ static int launch_chain_pipe(const ChainArgs& args, hipStream_t stream) {
 
 namespace fasth {
 
-// chain_pipe_kernel serves every d up to 4096 (rows that are not 16-byte aligned go through a buffer, whose offsets
-// are 32 bits wide); it also takes the side product along.
-static bool chain_uses_pipe(const ChainArgs& a) {
-  return !chain_uses_tile(a) && a.d <= 4096 && (a.d % 4 == 0 || (size_t)a.n * a.d * sizeof(float) < kOob);
-}
+// chain_pipe_kernel serves every d up to 4096; it also takes the side product along.
+static bool chain_uses_pipe(const ChainArgs& a) { return !chain_uses_tile(a) && a.d <= 4096; }
 static bool chain_takes_side_product(const ChainArgs& a) { return chain_uses_pipe(a); }
 
 static int launch_chain_kernel(const ChainArgs& a, hipStream_t stream) {
@@ -563,7 +561,7 @@ static int launch_chain_kernel(const ChainArgs& a, hipStream_t stream) {
       return launch_chain_pipe<8, 4, 1024, 2, 0, true>(a, stream);
     }
   }
-  // longer vectors (or a V of 2 GiB and more with unaligned rows): the general kernel
+  // longer vectors: the general kernel
   const int threads = 1024, nw = threads / 64;
   const int per = (d + 4 * threads - 1) / (4 * threads);  // chunks of four elements per thread
   const size_t lds = sizeof(float) * ((size_t)a.kp * (a.kp + 1) + (size_t)nw * a.kp + 2 * a.kp);
@@ -576,8 +574,7 @@ static int launch_chain_kernel(const ChainArgs& a, hipStream_t stream) {
     hipLaunchKernelGGL(chain_kernel<UU>, grid, block, lds, stream, a);           \
   } while (0)
   if (per > 4) return FASTH_EUNSUPPORTED;  // d > 16384: check_shape refuses it before
-  if (per <= 1) FASTH_LAUNCH_CHAIN(1);
-  else if (per <= 2) FASTH_LAUNCH_CHAIN(2);
+  if (per <= 2) FASTH_LAUNCH_CHAIN(2);
   else if (per == 3) FASTH_LAUNCH_CHAIN(3);
   else FASTH_LAUNCH_CHAIN(4);
 #undef FASTH_LAUNCH_CHAIN

@@ -62,6 +62,7 @@ DISPATCH = [
     (1024, 56, 3, 28), (784, 112, 2, 56), (1024, 36, 2, 12), (1024, 15, 2, 5), (1024, 40, 2, 8),
     (2048, 40, 2, 8), (2048, 20, 2, 5), (1536, 72, 2, 24), (1280, 200, 2, 100),
     (512, 256, 3, 128), (256, 256, 2, 128), (256, 48, 3, 16), (512, 48, 3, 16), (200, 40, 3, 8), (400, 40, 3, 8),
+    (2046, 14, 2, 7), (9000, 16, 2, 8), (12290, 8, 1, 8),
 ]
 
 
@@ -84,6 +85,7 @@ WIDE = [
     (256, 64, 800, 32), (512, 32, 1030, 16), (768, 96, 770, 48), (1024, 64, 780, 32), (1000, 128, 1100, 64),
     (100, 32, 769, 16), (320, 256, 900, 128),
     (2048, 32, 780, 16), (1500, 48, 770, 48), (1280, 64, 800, 64),  # 8 waves per workgroup
+    (125, 128, 800, 64), (125, 256, 800, 128),  # odd d: per-column chain in rounds, dV with 4-byte fetches reading Z
 ]
 
 
@@ -314,7 +316,7 @@ def test_prepare_once_apply_many_wide():
 
 
 @pytest.mark.parametrize("transpose", [False, True])
-@pytest.mark.parametrize("d,n,m", [(64, 64, 32), (100, 60, 5), (300, 300, 3), (1024, 256, 4)])
+@pytest.mark.parametrize("d,n,m", [(64, 64, 32), (100, 60, 5), (300, 300, 3), (1024, 256, 4), (5000, 12, 2), (9000, 8, 2)])
 def test_sequential_kernels(d, n, m, transpose):
     _say(f"sequential d={d} n={n} m={m} transpose={transpose}")
     p = synthetic.householder_problem(d, n, m, seed=2000 + d + n + m)
