@@ -275,6 +275,36 @@ def test_prepare_once_apply_many():
     assert rel_err(dV.cpu().numpy(), dV0) <= REL_TOL and rel_err(dX.cpu().numpy(), dX0) <= REL_TOL
 
 
+@pytest.mark.parametrize("d,n,m,k,spread", [(256, 256, 32, 32, 3), (1024, 128, 8, 64, 4), (512, 64, 800, 32, 3), (96, 96, 8, 48, 5)])
+def test_row_scales_over_many_orders_of_magnitude(d, n, m, k, spread):
+    """H_j does not depend on the length of v_j (Eq. 1), but the block factors are built from unnormalised vectors:
+    rows scaled by 10^U(-spread, spread) must not cost accuracy. dV rows scale like 1/|v_j|, so they are compared
+    after scaling back, which makes the short rows count."""
+    _say(f"row scales d={d} n={n} m={m} k={k} spread=1e+-{spread}")
+    p = synthetic.householder_problem(d, n, m, seed=99)
+    scale = (10.0 ** np.random.default_rng(7).uniform(-spread, spread, n)).astype(np.float32)
+    V = (p["V"] * scale[:, None]).astype(np.float32)
+    A, dV, dX = gpu_fasth(V, p["X"], p["G"], k)
+    A0, dV0, dX0 = orc.product_gradients(V, p["X"], p["G"])
+    assert rel_err(A, A0) <= REL_TOL and rel_err(dX, dX0) <= REL_TOL
+    assert rel_err(dV * scale[:, None], dV0 * scale[:, None]) <= REL_TOL
+
+
+def test_nearly_parallel_vectors_within_a_block():
+    """Three of every four vectors differ from their predecessor by a thousandth: the block's Gram matrix is close
+    to singular while every reflection stays well defined."""
+    d, n, m, k = 256, 64, 8, 32
+    p = synthetic.householder_problem(d, n, m, seed=98)
+    V = p["V"].copy()
+    for j in range(1, n):
+        if j % 4:
+            V[j] = V[j - 1] + 1e-3 * V[j]
+    got = gpu_fasth(V, p["X"], p["G"], k)
+    ref = orc.product_gradients(V, p["X"], p["G"])
+    for g, r in zip(got, ref):
+        assert rel_err(g, r) <= REL_TOL
+
+
 def test_block_size_independence():
     """Theorem 1 correctness: the result does not depend on how reflections are grouped."""
     p = synthetic.householder_problem(96, 96, 8, seed=77)
