@@ -26,7 +26,9 @@ if ROOT not in sys.path:
 
 FP32_MATRIX_PEAK_TFLOPS = 157.3  # MI355X published dense fp32 matrix (MFMA) and packed-vector peak
 HBM_PEAK_GBS = 8000.0
-CHAIN_TRAFFIC_BYTES = {"d1024_m32_k32": 17514.0 * 1024 * 2.0 + 4340.0 * 1024}
+CHAIN_TRAFFIC_BYTES = {"d1024_m32_k32": 17514.0 * 1024 * 2.0 + 4340.0 * 1024,
+                       # chain_tile_kernel with the block inputs saved (profiles/kernel_trace_and_mfma_d1024_m4096_k32.txt)
+                       "d1024_m4096_k32": 33414.0 * 1024 * 2.0 + 575000.0 * 1024}
 
 
 def f_paper(d, n, m, k):
@@ -227,8 +229,8 @@ def main() -> int:
             "unit": "TFLOP/s",
             "frac": chain_tflops / FP32_MATRIX_PEAK_TFLOPS,
             # HBM bytes per launch from rocprofv3 FETCH_SIZE (x2.0) + WRITE_SIZE (x1.0), scaled by a 256 MiB
-            # copy in the same run; measured for the headline workload only
-            # (profiles/hbm_traffic_d1024_m32_k32.txt).
+            # copy in the same run; measured for the headline and the 4096-column workloads
+            # (profiles/hbm_traffic_d1024_m32_k32.txt, profiles/kernel_trace_and_mfma_d1024_m4096_k32.txt).
             "traffic": CHAIN_TRAFFIC_BYTES.get(name),
         },
     }
