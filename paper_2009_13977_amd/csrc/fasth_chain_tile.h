@@ -31,7 +31,7 @@ static constexpr size_t tile_lds_bytes(int waves, int groups) {
   return sizeof(float) * (size_t)(waves * kTileRows * (64 * groups + 4) + 2 * waves * 256);
 }
 
-// kTileGroups: groups per wave, the same for all four waves (a group that lies beyond d is all zeros: its
+// kTileGroups: groups per wave, the same for all waves (a group that lies beyond d is all zeros: its
 // fetches are out of the buffers' range, so it costs matrix instructions but no branch).
 // NW: waves per workgroup, 4 for d <= 1024, 8 (two per SIMD) for d <= 2048.
 template <int NW, int kTileGroups>
