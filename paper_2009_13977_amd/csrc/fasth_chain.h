@@ -264,17 +264,22 @@ struct PipeRegs {
 // so nothing downstream sees the difference; p.nb counts the steps. SUB is the number of steps per block
 // (0: taken from p.sub at run time). PAD: k is not a multiple of K, so a block's last step has fewer than K
 // rows; the missing rows repeat the last one and their inner products and coefficients are forced to zero.
-// RL: rows of the next block fetched during the reduction; P1: during the first product (0: half of the rest).
+// RL: rows of the next block fetched during the reduction; P1: during the first product (0: half of the rest);
+// XB: at each of four points next to the two barriers (before and after each), where a wave waits anyway: for the
+// other waves, or for the LDS reads it has just issued. A fetch keeps the issuing wave from its arithmetic for ~35
+// clocks, so the fewer of them sit between the multiply-adds the better (d = 4096: 1.61 -> 1.40 ms per forward +
+// backward with XB = 1, d = 2048: 396 -> 372 us, d = 1024: 113.7 -> 112.2 us).
 // UNAL: d is not a multiple of VW, so rows are not 16-byte aligned and the last chunk of a row hangs over its end.
 // Rows are then fetched through a buffer that spans the block (4-byte alignment is enough for it, and what lies
 // beyond the block reads as zero); the overhanging elements see the next row's values, so they are put back to
 // zero after every update and never stored.
-template <int K, int VW, int NT, int RL = 0, int SUB = 1, bool PAD = false, int P1 = 0, bool UNAL = false>
+template <int K, int VW, int NT, int RL = 0, int SUB = 1, bool PAD = false, int P1 = 0, bool UNAL = false, int XB = 0>
 __global__ void __launch_bounds__(NT) chain_pipe_kernel(ChainArgs p) {
   typedef PipeRegs<K, VW, NT> Regs;
   constexpr int NW = NT / 64, G = Regs::G, LPT = Regs::LPT;
   constexpr int PR = P1 > 0 ? P1 : (K - RL) / 2;  // rows of the next block fetched during the first product
-  constexpr int PR2 = K - RL - PR;                  // ... and during the second
+  constexpr int PR2 = K - RL - PR - 4 * XB;         // ... and during the second
+  constexpr int X0 = PR + RL;                       // first of the 4 XB rows fetched on either side of the two barriers
   constexpr int S1 = K / PR, S2 = K / PR2;          // one fetch every S1 (S2) rows of the product
   static_assert(PR >= 1 && PR2 >= 1 && S1 >= 1 && S2 >= 1, "prefetch split");
   static_assert(K % 4 == 0 && K * G <= NT && LPT >= 1, "shape");
@@ -389,7 +394,14 @@ __global__ void __launch_bounds__(NT) chain_pipe_kernel(ChainArgs p) {
       wave_reduce_multi_reg<K>(pj);
     }
     if ((lane & reduce_writer_mask<K>()) == 0) Bpart[wave][sel] = pj[0];
+    auto fetch_at_barrier = [&](int q) {
+#pragma unroll
+      for (int e = 0; e < XB; ++e) nxt.v[X0 + q * XB + e] = load_row(inext, X0 + q * XB + e);
+      if constexpr (XB > 0) __builtin_amdgcn_sched_barrier(0);
+    };
+    fetch_at_barrier(0);
     lds_barrier();
+    fetch_at_barrier(1);
     if (t_active) {
       float c = 0.f;
       if constexpr (LPT % 4 == 0) {
@@ -427,7 +439,9 @@ __global__ void __launch_bounds__(NT) chain_pipe_kernel(ChainArgs p) {
         }
       }
     }
+    fetch_at_barrier(2);
     lds_barrier();
+    fetch_at_barrier(3);
     // The coefficient vector comes from LDS eight values at a time, one group ahead of its use: holding all K
     // would push more of the second register copy into the accumulator file (115.7 -> 114.3 us at the headline).
     constexpr int CG = K >= 16 ? 8 : K;
@@ -448,7 +462,7 @@ __global__ void __launch_bounds__(NT) chain_pipe_kernel(ChainArgs p) {
         __builtin_amdgcn_sched_barrier(0);
       }
       if (j % S2 == 0 && j / S2 < PR2) {
-        nxt.v[PR + RL + j / S2] = load_row(inext, PR + RL + j / S2);
+        nxt.v[X0 + 4 * XB + j / S2] = load_row(inext, X0 + 4 * XB + j / S2);
         __builtin_amdgcn_sched_barrier(0);
       }
 #pragma unroll
@@ -474,7 +488,7 @@ __global__ void __launch_bounds__(NT) chain_pipe_kernel(ChainArgs p) {
     if (keep[r]) p.out[(size_t)(x0 + r) * m + col] = a.e[r];
 }
 
-template <int K, int VW, int NT, int RL = 0, int SUB = 1, bool PAD = false, int P1 = 0, bool UNAL = false>
+template <int K, int VW, int NT, int RL = 0, int SUB = 1, bool PAD = false, int P1 = 0, bool UNAL = false, int XB = 0>
 static int launch_chain_pipe(const ChainArgs& args, hipStream_t stream) {
   ChainArgs a = args;
   a.sub = SUB > 0 ? SUB : (args.k + K - 1) / K;
@@ -484,7 +498,7 @@ static int launch_chain_pipe(const ChainArgs& args, hipStream_t stream) {
     return FASTH_EINVAL;
   const int side = a.ds_out ? (a.ds_rows + NT / 64 - 1) / (NT / 64) : 0;
   prof::Scope ps_(FASTH_KERNEL_CHAIN, stream);
-  hipLaunchKernelGGL((chain_pipe_kernel<K, VW, NT, RL, SUB, PAD, P1, UNAL>), dim3(a.m + side), dim3(NT), 0, stream, a);
+  hipLaunchKernelGGL((chain_pipe_kernel<K, VW, NT, RL, SUB, PAD, P1, UNAL, XB>), dim3(a.m + side), dim3(NT), 0, stream, a);
   FASTH_HIP(hipGetLastError());
   return FASTH_OK;
 }
@@ -507,58 +521,57 @@ static int launch_chain_kernel(const ChainArgs& a, hipStream_t stream) {
     if (d <= 1024) {
       if (k <= 8) return launch_chain_pipe<8, 4, 256, 2, 0, true, 0, true>(a, stream);
       if (k <= 16) return launch_chain_pipe<16, 4, 256, 4, 0, true, 0, true>(a, stream);
-      return launch_chain_pipe<32, 4, 256, 8, 0, true, 0, true>(a, stream);
+      return launch_chain_pipe<32, 4, 256, 8, 0, true, 7, true, 1>(a, stream);
     } else if (d <= 2048) {
-      if (k <= 8) return launch_chain_pipe<8, 4, 512, 2, 0, true, 0, true>(a, stream);
-      return launch_chain_pipe<16, 4, 512, 4, 0, true, 0, true>(a, stream);
+      if (k <= 8) return launch_chain_pipe<8, 4, 512, 2, 0, true, 1, true, 1>(a, stream);
+      return launch_chain_pipe<16, 4, 512, 4, 0, true, 4, true, 1>(a, stream);
     }
-    return launch_chain_pipe<8, 4, 1024, 2, 0, true, 0, true>(a, stream);
+    return launch_chain_pipe<8, 4, 1024, 2, 0, true, 1, true, 1>(a, stream);
   }
   if (chain_uses_pipe(a)) {
     // whole block in registers, two copies; a quarter of the next block is fetched during the reduction
-    if (k == 16 && d <= 256) return launch_chain_pipe<16, 1, 256, 4>(a, stream);  // narrower lanes keep all four waves busy
-    if (k == 16 && d <= 512) return launch_chain_pipe<16, 2, 256, 4>(a, stream);
+    if (k == 16 && d <= 256) return launch_chain_pipe<16, 1, 256, 4, 1, false, 4, false, 1>(a, stream);  // narrower lanes keep all four waves busy
+    if (k == 16 && d <= 512) return launch_chain_pipe<16, 2, 256, 4, 1, false, 4, false, 1>(a, stream);
     if (k == 8 && d <= 256) return launch_chain_pipe<8, 1, 256, 2>(a, stream);
     if (k == 8 && d <= 512) return launch_chain_pipe<8, 2, 256, 2>(a, stream);
-    if (k == 16 && d <= 1024) return launch_chain_pipe<16, 4, 256, 4>(a, stream);
-    if (k == 16 && d <= 2048) return launch_chain_pipe<16, 4, 512, 4>(a, stream);
-    if (k == 32 && d <= 256) return launch_chain_pipe<32, 1, 256, 8>(a, stream);
-    if (k == 32 && d <= 512) return launch_chain_pipe<32, 2, 256, 8>(a, stream);
-    // (10 of the 32 rows of the next block fetched during the first product, 8 during the reduction, 14 during
-    // the update: with 12 / 8 / 12 more of the second register copy spills to the accumulator file; 117.2 -> 115.8 us
-    // per forward + backward at d = n = 1024, m = 32)
-    if (k == 32 && d <= 1024) return launch_chain_pipe<32, 4, 256, 8, 1, false, 10>(a, stream);
+    if (k == 16 && d <= 1024) return launch_chain_pipe<16, 4, 256, 4, 1, false, 4, false, 1>(a, stream);
+    if (k == 16 && d <= 2048) return launch_chain_pipe<16, 4, 512, 4, 1, false, 4, false, 1>(a, stream);
+    if (k == 32 && d <= 256) return launch_chain_pipe<32, 1, 256, 8, 1, false, 7, false, 1>(a, stream);
+    if (k == 32 && d <= 512) return launch_chain_pipe<32, 2, 256, 8, 1, false, 7, false, 1>(a, stream);
+    // (7 of the 32 rows of the next block fetched during the first product, 8 during the reduction, 4 next to the
+    // barriers, 13 during the update)
+    if (k == 32 && d <= 1024) return launch_chain_pipe<32, 4, 256, 8, 1, false, 7, false, 1>(a, stream);
     // blocks of 64 and 128 rows as steps of 32, at the lane width that keeps all four waves busy
-    if (k == 64 && d <= 256) return launch_chain_pipe<32, 1, 256, 8, 2>(a, stream);
-    if (k == 64 && d <= 512) return launch_chain_pipe<32, 2, 256, 8, 2>(a, stream);
-    if (k == 128 && d <= 256) return launch_chain_pipe<32, 1, 256, 8, 4>(a, stream);
-    if (k == 128 && d <= 512) return launch_chain_pipe<32, 2, 256, 8, 4>(a, stream);
+    if (k == 64 && d <= 256) return launch_chain_pipe<32, 1, 256, 8, 2, false, 7, false, 1>(a, stream);
+    if (k == 64 && d <= 512) return launch_chain_pipe<32, 2, 256, 8, 2, false, 7, false, 1>(a, stream);
+    if (k == 128 && d <= 256) return launch_chain_pipe<32, 1, 256, 8, 4, false, 7, false, 1>(a, stream);
+    if (k == 128 && d <= 512) return launch_chain_pipe<32, 2, 256, 8, 4, false, 7, false, 1>(a, stream);
     // Larger blocks and longer vectors: two register copies of the whole block do not fit, but the block can be
     // applied as steps of 32 rows (d <= 1024) or 16 rows (d <= 2048, two waves per SIMD), which is faster than
     // one copy refilled in place or rows streamed twice (d = n = 2048: 178 us for k = 32, 64 and 128 alike,
     // against 222, 359 and 406 us)
     if (d <= 1024) {
-      if (k == 64) return launch_chain_pipe<32, 4, 256, 8, 2, false, 10>(a, stream);
-      if (k == 128) return launch_chain_pipe<32, 4, 256, 8, 4, false, 10>(a, stream);
-      if (k == 8) return launch_chain_pipe<8, 4, 256, 2>(a, stream);
+      if (k == 64) return launch_chain_pipe<32, 4, 256, 8, 2, false, 7, false, 1>(a, stream);
+      if (k == 128) return launch_chain_pipe<32, 4, 256, 8, 4, false, 7, false, 1>(a, stream);
+      if (k == 8) return launch_chain_pipe<8, 4, 256, 2, 1, false, 1, false, 1>(a, stream);
       // any other block size: steps of 8, 16 or 32 rows, the last one of a block short
-      if (k < 8) return launch_chain_pipe<8, 4, 256, 2, 1, true>(a, stream);
-      if (k < 16) return launch_chain_pipe<16, 4, 256, 4, 1, true>(a, stream);
-      if (k < 32) return launch_chain_pipe<32, 4, 256, 8, 1, true, 10>(a, stream);  // one short step per block
-      if (k < 64) return launch_chain_pipe<32, 4, 256, 8, 2, true, 10>(a, stream);  // a full step and a short one
-      if (k > 96) return launch_chain_pipe<32, 4, 256, 8, 4, true, 10>(a, stream);
-      return launch_chain_pipe<32, 4, 256, 8, 0, true>(a, stream);
+      if (k < 8) return launch_chain_pipe<8, 4, 256, 2, 1, true, 1, false, 1>(a, stream);
+      if (k < 16) return launch_chain_pipe<16, 4, 256, 4, 1, true, 4, false, 1>(a, stream);
+      if (k < 32) return launch_chain_pipe<32, 4, 256, 8, 1, true, 7, false, 1>(a, stream);  // one short step per block
+      if (k < 64) return launch_chain_pipe<32, 4, 256, 8, 2, true, 7, false, 1>(a, stream);  // a full step and a short one
+      if (k > 96) return launch_chain_pipe<32, 4, 256, 8, 4, true, 7, false, 1>(a, stream);
+      return launch_chain_pipe<32, 4, 256, 8, 0, true, 7, false, 1>(a, stream);
     } else if (d <= 2048) {
-      if (k == 32) return launch_chain_pipe<16, 4, 512, 4, 2, false, 5>(a, stream);  // fetch split 5 / 4 / 7
-      if (k == 64) return launch_chain_pipe<16, 4, 512, 4, 4, false, 5>(a, stream);
-      if (k == 128) return launch_chain_pipe<16, 4, 512, 4, 8, false, 5>(a, stream);
-      if (k == 8) return launch_chain_pipe<8, 4, 512, 2>(a, stream);
-      if (k < 8) return launch_chain_pipe<8, 4, 512, 2, 0, true>(a, stream);
-      return launch_chain_pipe<16, 4, 512, 4, 0, true>(a, stream);
+      if (k == 32) return launch_chain_pipe<16, 4, 512, 4, 2, false, 4, false, 1>(a, stream);  // fetch split 4 / 4 / 4 / 4
+      if (k == 64) return launch_chain_pipe<16, 4, 512, 4, 4, false, 4, false, 1>(a, stream);
+      if (k == 128) return launch_chain_pipe<16, 4, 512, 4, 8, false, 4, false, 1>(a, stream);
+      if (k == 8) return launch_chain_pipe<8, 4, 512, 2, 1, false, 1, false, 1>(a, stream);
+      if (k < 8) return launch_chain_pipe<8, 4, 512, 2, 0, true, 1, false, 1>(a, stream);
+      return launch_chain_pipe<16, 4, 512, 4, 0, true, 4, false, 1>(a, stream);
     } else {
       // 16 waves share 512 registers per lane: two copies of 8 rows
-      if (k % 8 == 0) return launch_chain_pipe<8, 4, 1024, 2, 0>(a, stream);
-      return launch_chain_pipe<8, 4, 1024, 2, 0, true>(a, stream);
+      if (k % 8 == 0) return launch_chain_pipe<8, 4, 1024, 2, 0, false, 1, false, 1>(a, stream);
+      return launch_chain_pipe<8, 4, 1024, 2, 0, true, 1, false, 1>(a, stream);
     }
   }
   // longer vectors: the general kernel
