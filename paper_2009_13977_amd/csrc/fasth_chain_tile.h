@@ -151,15 +151,47 @@ __global__ void __launch_bounds__(64 * NW) chain_tile_kernel(ChainArgs p) {
     }
     fetch_t(blkn, partn, tnxt);
     if (p.save_in && part == (p.transpose ? 0 : sub - 1)) {
+      // A lane holds 64 contiguous bytes of its column per group, as four 16-byte pieces j (x = .. + 4 j). Stored as
+      // they lie, the 64 lanes of a store would touch 64 different cache lines (adjacent lanes are adjacent COLUMNS,
+      // d floats apart), which costs the address unit four times a coalesced store. So the four lanes of a quad
+      // (columns 4a .. 4a + 3) first transpose their 4 x 4 pieces: in store t, lane 4a + b then writes piece b of
+      // column 4a + t, and each quad covers 64 contiguous bytes. Two exchange stages (lane ^ 1, lane ^ 2), one DPP
+      // move and three selects per pair of registers.
       const BufferDesc adesc = make_buffer(p.save_in + (size_t)blk * m * d, (size_t)m * d * sizeof(float));
+      const int b = i & 3;
+      const bool odd = (b & 1) != 0, upper = (b & 2) != 0;
+      const int colq = blockIdx.x * kTileCols + (i & ~3);  // first column of the quad
 #pragma unroll
       for (int g = 0; g < kTileGroups; ++g) {
+        float pc[4][4];  // [piece][element]
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const int x = group_x(g) + 16 * q + 4 * j;
-          const unsigned off = (col_ok && x < d) ? ((unsigned)col * (unsigned)d + (unsigned)x) * 4u : kOob;
+        for (int pp = 0; pp < 2; ++pp) {
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const float a0 = A[4 * g + r][2 * pp], a1 = A[4 * g + r][2 * pp + 1];
+            // one exchange: odd lanes hand over their piece 2pp and get the partner's piece 2pp + 1 (the move itself
+            // is unconditional: inside a divergent branch it would read lanes that are switched off)
+            const float got = dpp_move<kDppQuadXor1>(odd ? a0 : a1);
+            pc[2 * pp][r] = odd ? got : a0;
+            pc[2 * pp + 1][r] = odd ? a1 : got;
+          }
+        }
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const float x0 = pc[c][r], x1 = pc[c + 2][r];
+            const float got = dpp_move<kDppQuadXor2>(upper ? x0 : x1);  // lanes 2, 3 hand over piece c, get piece c + 2
+            pc[c][r] = upper ? got : x0;
+            pc[c + 2][r] = upper ? x1 : got;
+          }
+        }
+        const int x = group_x(g) + 16 * q + 4 * b;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          const unsigned off = (colq + t < m && x < d) ? ((unsigned)(colq + t) * (unsigned)d + (unsigned)x) * 4u : kOob;
           BufVec<4> v;
-          v.e[0] = A[4 * g][j]; v.e[1] = A[4 * g + 1][j]; v.e[2] = A[4 * g + 2][j]; v.e[3] = A[4 * g + 3][j];
+          v.e[0] = pc[t][0]; v.e[1] = pc[t][1]; v.e[2] = pc[t][2]; v.e[3] = pc[t][3];
           buffer_store<4>(adesc, off, 0, v);
         }
       }
