@@ -193,9 +193,9 @@ def main() -> int:
     kernels = {kn: {"ms_avg": t / c, "launches_per_step": c / args.steps} for kn, (t, c) in prof.items() if c}
     chain_ms = kernels["chain_kernel"]["ms_avg"]
     chain_tflops = chain_flops(d, n, m) / (chain_ms * 1e-3) / 1e12
-    # More than 768 columns (d <= 1024) run the chain on the matrix cores; below that it is one workgroup per
+    # More than 1024 columns (d <= 1024) run the chain on the matrix cores; below that it is one workgroup per
     # column on the vector units.
-    chain_on_matrix_cores = m > 768 and d <= 1024 and d % 4 == 0 and k % 16 == 0
+    chain_on_matrix_cores = m > 1024 and d <= 1024 and d % 4 == 0 and k % 16 == 0
 
     out = {
         "metric": "fasth_fwd_bwd_gflops_paper_count",

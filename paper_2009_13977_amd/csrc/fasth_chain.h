@@ -536,6 +536,15 @@ static int launch_chain_kernel(const ChainArgs& a, hipStream_t stream) {
     if (k == 8 && d <= 512) return launch_chain_pipe<8, 2, 256, 2>(a, stream);
     if (k == 16 && d <= 1024) return launch_chain_pipe<16, 4, 256, 4, 1, false, 4, false, 1>(a, stream);
     if (k == 16 && d <= 2048) return launch_chain_pipe<16, 4, 512, 4, 1, false, 4, false, 1>(a, stream);
+    // More columns than compute units (and too few for the matrix-core kernel): steps of 16 rows take 166 registers
+    // against the 291 of 32-row steps, so three workgroups share a compute unit and fill each other's waits
+    // (d = 1024, k = 32, per forward + backward: m = 384: 233 -> 194 us, m = 512: 244 -> 222, m = 768: 356 -> 321;
+    // up to 256 columns the 32-row steps are the faster ones: 137 against 149 us at m = 256).
+    if (a.m > kComputeUnits && d > 512 && d <= 1024) {
+      if (k == 32) return launch_chain_pipe<16, 4, 256, 4, 2, false, 4, false, 1>(a, stream);
+      if (k == 64) return launch_chain_pipe<16, 4, 256, 4, 4, false, 4, false, 1>(a, stream);
+      if (k == 128) return launch_chain_pipe<16, 4, 256, 4, 8, false, 4, false, 1>(a, stream);
+    }
     if (k == 32 && d <= 256) return launch_chain_pipe<32, 1, 256, 8, 1, false, 7, false, 1>(a, stream);
     if (k == 32 && d <= 512) return launch_chain_pipe<32, 2, 256, 8, 1, false, 7, false, 1>(a, stream);
     // (7 of the 32 rows of the next block fetched during the first product, 8 during the reduction, 4 next to the

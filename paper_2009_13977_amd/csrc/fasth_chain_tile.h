@@ -290,7 +290,7 @@ __global__ void __launch_bounds__(64 * NW) chain_tile_kernel(ChainArgs p) {
 
 // Shapes the matrix-core chain serves, and from how many columns on it is the faster one.
 #ifndef FASTH_TILE_MIN_COLS
-#define FASTH_TILE_MIN_COLS 769  // the per-column kernel needs a fourth round of 256 workgroups from here on
+#define FASTH_TILE_MIN_COLS 1025  // up to 1024 columns the per-column kernel is faster (three workgroups per compute unit)
 #endif
 static bool chain_uses_tile(const ChainArgs& a) {
   return a.m >= FASTH_TILE_MIN_COLS && a.d % 4 == 0 && a.d <= kTileMaxD && a.k % kTileRows == 0 &&

@@ -23,6 +23,7 @@ constexpr int kMaxBlock = 128;     // largest k: a k x k factor must fit in LDS 
 constexpr int kMaxD = 16384;       // general chain kernel: 1024 threads x 4 chunks of 4 elements
 constexpr int kGramChunk = 128;    // columns of V per LDS tile in the Gram kernel
 constexpr int kMaxGramSplit = 16;  // partial Gram matrices per block
+constexpr int kComputeUnits = 256; // of the MI355X: launches of more workgroups than this run in rounds or share units
 constexpr int kDvTile = 64;        // columns of dV per workgroup
 constexpr int kDvMChunk = 32;      // mini-batch columns per LDS tile in the dV kernel
 

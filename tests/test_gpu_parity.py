@@ -78,14 +78,16 @@ def test_fasth_every_chain_kernel(d, n, m, k, transpose):
     assert rel_err(dV, dV0) <= REL_TOL
 
 
-# Wide mini-batches (more than 768 columns) take the matrix-core chain kernel: 16 columns per workgroup, rows in
+# Wide mini-batches (more than 1024 columns) take the matrix-core chain kernel: 16 columns per workgroup, rows in
 # steps of 16. Cases: every groups-per-wave variant (d <= 256, 512, 768, 1024; 1536, 2048), d and m with ragged tails, blocks
 # of one and of several steps, n != d; few reflections keep the checker fast.
 WIDE = [
-    (256, 64, 800, 32), (512, 32, 1030, 16), (768, 96, 770, 48), (1024, 64, 780, 32), (1000, 128, 1100, 64),
-    (100, 32, 769, 16), (320, 256, 900, 128),
-    (2048, 32, 780, 16), (1500, 48, 770, 48), (1280, 64, 800, 64),  # 8 waves per workgroup
+    (256, 64, 1040, 32), (512, 32, 1030, 16), (768, 96, 1026, 48), (1024, 64, 1036, 32), (1000, 128, 1100, 64),
+    (100, 32, 1025, 16), (320, 256, 1056, 128),
+    (2048, 32, 1036, 16), (1500, 48, 1026, 48), (1280, 64, 1040, 64),  # 8 waves per workgroup
     (125, 128, 800, 64), (125, 256, 800, 128),  # odd d: per-column chain in rounds, dV with 4-byte fetches reading Z
+    # more columns than compute units, fewer than the matrix-core kernel takes: 16-row steps, several workgroups per unit
+    (1024, 64, 300, 32), (768, 128, 260, 64), (1024, 128, 780, 128), (1024, 32, 1024, 32), (516, 96, 770, 32),
 ]
 
 
@@ -119,7 +121,7 @@ def test_layers_wide_minibatch():
     """The layers on the matrix-core chain kernel: the diagonal factor fused into its input fetch (every mode),
     a rectangular Sigma (rows of the chain's input that do not exist), and the gradient of sigma from a launch of
     its own."""
-    d, n, m, k = 256, 128, 800, 64  # k >= 64, k m >= 32768: the dV kernel reads Z formed by a launch of its own
+    d, n, m, k = 256, 128, 1040, 64  # k >= 64, k m >= 32768: the dV kernel reads Z formed by a launch of its own
     p = synthetic.svd_layer_problem(d, n, m, seed=5100)
     for inverse in (False, True):
         _say(f"svd layer wide inverse={inverse}")
@@ -139,7 +141,7 @@ def test_layers_wide_minibatch():
     # (2048, 64): the two factors differ in how the dV mini-batch is split, so their dV launches stay separate
     for rows, cols in ((256, 192), (192, 256), (2048, 64)):
         _say(f"svd rect wide rows={rows} cols={cols}")
-        q = synthetic.rect_layer_problem(rows, cols, 32 if rows < 2048 else 128, 32, 800, seed=5300 + rows)
+        q = synthetic.rect_layer_problem(rows, cols, 32 if rows < 2048 else 128, 32, 1040, seed=5300 + rows)
         got = gpu_svd_rect(q["Uv"], q["sigma"], q["Vv"], q["X"], q["G"], 16)  # k m < 32768: Z rebuilt per workgroup
         ref = orc.rectangular_gradients(q["Uv"], q["sigma"], q["Vv"], q["X"], q["G"])
         for name, g, r in zip(("Y", "dUv", "dsigma", "dVv", "dX"), got, ref):
@@ -158,7 +160,7 @@ def _random_shapes(count, seed):
             d = max(4, d // 4 * 4)
         k = int(rng.choice([1, 2, 3, 5, 7, 8, 12, 16, 20, 24, 28, 32, 40, 48, 56, 64, 96, 100, 128]))
         nb = int(rng.integers(1, 4))
-        m = int(rng.choice([1, 2, 5, 16, 31, 32, 33, 64, 100, 770, 900])) if d <= 2100 else int(rng.choice([1, 3, 32, 40]))
+        m = int(rng.choice([1, 2, 5, 16, 31, 32, 33, 64, 100, 1030, 1100])) if d <= 2100 else int(rng.choice([1, 3, 32, 40]))
         if m > 700 and d > 1100:
             nb = 1
         shapes.append((d, nb * k, m, k, bool(rng.integers(0, 2))))
@@ -275,7 +277,7 @@ def test_prepare_once_apply_many():
     assert rel_err(dV.cpu().numpy(), dV0) <= REL_TOL and rel_err(dX.cpu().numpy(), dX0) <= REL_TOL
 
 
-@pytest.mark.parametrize("d,n,m,k,spread", [(256, 256, 32, 32, 3), (1024, 128, 8, 64, 4), (512, 64, 800, 32, 3), (96, 96, 8, 48, 5)])
+@pytest.mark.parametrize("d,n,m,k,spread", [(256, 256, 32, 32, 3), (1024, 128, 8, 64, 4), (512, 64, 1040, 32, 3), (96, 96, 8, 48, 5)])
 def test_row_scales_over_many_orders_of_magnitude(d, n, m, k, spread):
     """H_j does not depend on the length of v_j (Eq. 1), but the block factors are built from unnormalised vectors:
     rows scaled by 10^U(-spread, spread) must not cost accuracy. dV rows scale like 1/|v_j|, so they are compared
@@ -316,7 +318,7 @@ def test_block_size_independence():
             assert rel_err(g, r) <= REL_TOL
 
 
-@pytest.mark.parametrize("d,n,m,k", [(256, 256, 32, 32), (128, 64, 1024, 32), (1024, 64, 800, 64), (1001, 48, 5, 24)])
+@pytest.mark.parametrize("d,n,m,k", [(256, 256, 32, 32), (128, 64, 1040, 32), (1024, 64, 1040, 64), (1001, 48, 5, 24)])
 def test_bitwise_repeatable(d, n, m, k):
     """Every sum runs in a fixed order (no atomics), also where the mini-batch is split over workgroups and on the
     matrix-core chain kernel: two runs give the same bits."""
@@ -392,7 +394,7 @@ def _random_layer_shapes(count, seed):
             d = max(4, d // 4 * 4)
         k = int(rng.choice([1, 3, 8, 12, 16, 24, 32, 48, 64]))
         nb = int(rng.integers(1, 3))
-        m = int(rng.choice([1, 5, 32, 33, 100, 800]))
+        m = int(rng.choice([1, 5, 32, 33, 100, 1040]))
         shapes.append((d, nb * k, m, k, bool(rng.integers(0, 2))))
     return shapes
 
