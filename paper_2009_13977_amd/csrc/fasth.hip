@@ -147,6 +147,7 @@ static int run_chain(const Product& P, const float* V, const float* in, float* o
                      float* ds_out = nullptr, int ds_rows = 0) {
   ChainArgs a;
   a.V = V; a.T = factors ? factors : P.T(); a.in = in; a.out = out;
+  a.Tt = a.T + (size_t)P.L.nb * P.L.kp * P.L.kp;
   a.save_in = !save ? nullptr : activation ? P.saveA() : P.saveG();
   a.save_c = !save ? nullptr : activation ? P.saveCa() : P.saveCg();
   a.in_scale = in_scale; a.in_scale_mode = in_scale_mode;

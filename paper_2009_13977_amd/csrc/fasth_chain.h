@@ -33,6 +33,7 @@ __device__ __forceinline__ float diag_factor(int mode, float sigma) {
 struct ChainArgs {
   const float* V;         // [n][d]
   const float* T;         // [nb][kp][kp]
+  const float* Tt;        // [nb][kp][kp]: the transposed factors
   const float* in;        // [d][m]
   float* out;             // [d][m]
   float* save_in;         // [nb][m][d] or null
@@ -346,12 +347,19 @@ __global__ void __launch_bounds__(NT) chain_pipe_kernel(ChainArgs p) {
   };
   auto load_t = [&](int i, Regs& r) {
     const int LDT = (SUB > 0 && !PAD && K * SUB >= 16) ? K * SUB : p.kp;  // row stride of the stored factor
-    const float* Ti = p.T + (size_t)step_block(i) * LDT * LDT + (size_t)step_part(i) * (K * LDT + K);
-    const int row = t_active ? trow : 0;
+    // rows of op(T): of the factor itself or of its stored transpose, so a thread's LPT entries are consecutive in
+    // memory either way (one 16-byte fetch for every four) as its partial sums are in LDS
+    const float* Ti = (p.transpose ? p.Tt : p.T) + (size_t)step_block(i) * LDT * LDT + (size_t)step_part(i) * (K * LDT + K);
+    const float* src = Ti + (t_active ? trow : 0) * LDT + tg * LPT;
+    if constexpr (LPT % 4 == 0) {
 #pragma unroll
-    for (int e = 0; e < LPT; ++e) {
-      const int l = tg * LPT + e;  // a thread's columns are consecutive: its partial sums come as 16-byte LDS reads
-      r.t[e] = p.transpose ? Ti[l * LDT + row] : Ti[row * LDT + l];
+      for (int e4 = 0; e4 < LPT / 4; ++e4) {
+        const float4 t4 = reinterpret_cast<const float4*>(src)[e4];
+        r.t[4 * e4] = t4.x; r.t[4 * e4 + 1] = t4.y; r.t[4 * e4 + 2] = t4.z; r.t[4 * e4 + 3] = t4.w;
+      }
+    } else {
+#pragma unroll
+      for (int e = 0; e < LPT; ++e) r.t[e] = src[e];
     }
   };
 

@@ -64,7 +64,7 @@ static Layout make_layout(int d, int n, int m, int k) {
     off = align_up(off + floats * sizeof(float), 256);
     return o;
   };
-  L.off_T = take((size_t)L.nb * L.kp * L.kp);
+  L.off_T = take(2 * (size_t)L.nb * L.kp * L.kp);  // the factors and, behind them, their transposes
   L.off_Spart = take((size_t)L.nb * L.gram_split * L.kp * L.kp);
   L.off_saveA = take((size_t)L.nb * m * d);
   L.off_saveCa = take((size_t)m * n);

@@ -177,8 +177,13 @@ __global__ void __launch_bounds__(1024) t_build_kernel(const float* __restrict__
   }
   __syncthreads();
   invert_upper_lds(Ms, Xs, kp, LDM);
+  // T_i and, nb factors further on, its transpose: a chain kernel then reads rows of op(T_i) in either direction
   float* Ti = T + (size_t)i * kp * kp;
-  for (int idx = tid; idx < kp * kp; idx += nthreads) Ti[idx] = Ms[(idx / kp) * LDM + idx % kp];
+  float* Tti = Ti + (size_t)gridDim.x * kp * kp;
+  for (int idx = tid; idx < kp * kp; idx += nthreads) {
+    Ti[idx] = Ms[(idx / kp) * LDM + idx % kp];
+    Tti[idx] = Ms[(idx % kp) * LDM + idx / kp];
+  }
 }
 
 // Algorithm 1 Step 1 in one kernel for blocks of up to 64 rows (kp = 16 KT): one workgroup of 8 waves per
@@ -189,7 +194,7 @@ __global__ void __launch_bounds__(1024) t_build_kernel(const float* __restrict__
 // blockIdx.y picks the product, blockIdx.x its block.
 struct FactorPair {
   const float* V[2];  // [n][d]
-  float* T[2];        // [nb][kp][kp]
+  float* T[2];        // [2][nb][kp][kp]: the factors, then their transposes
   int d[2], k[2], nb[2];
 };
 
@@ -312,8 +317,13 @@ __global__ void __launch_bounds__(512) factor_fused_kernel(FactorPair fp) {
   }
   __syncthreads();
   invert_upper_lds(Ms, Xs, kp, LDM);
+  // T_i and, nb factors further on, its transpose: a chain kernel then reads rows of op(T_i) in either direction
   float* Ti = T + (size_t)i * kp * kp;
-  for (int idx = tid; idx < kp * kp; idx += 512) Ti[idx] = Ms[(idx / kp) * LDM + idx % kp];
+  float* Tti = Ti + (size_t)fp.nb[which] * kp * kp;
+  for (int idx = tid; idx < kp * kp; idx += 512) {
+    Ti[idx] = Ms[(idx / kp) * LDM + idx % kp];
+    Tti[idx] = Ms[(idx % kp) * LDM + idx / kp];
+  }
 }
 
 static size_t t_build_lds(int kp) {
