@@ -514,6 +514,7 @@ static int launch_chain_pipe(const ChainArgs& args, hipStream_t stream) {
 }  // namespace fasth
 
 #include "fasth_chain_tile.h"  // chain_tile_kernel: the same steps on the matrix cores, for wide mini-batches
+#include "fasth_chain_pair.h"  // chain_pair_kernel: the per-column chain with two waves per SIMD
 
 namespace fasth {
 
@@ -544,6 +545,13 @@ static int launch_chain_kernel(const ChainArgs& a, hipStream_t stream) {
     if (k == 8 && d <= 512) return launch_chain_pipe<8, 2, 256, 2>(a, stream);
     if (k == 16 && d <= 1024) return launch_chain_pipe<16, 4, 256, 4, 1, false, 4, false, 1>(a, stream);
     if (k == 16 && d <= 2048) return launch_chain_pipe<16, 4, 512, 4, 1, false, 4, false, 1>(a, stream);
+    // 512 < d <= 1024, at most one column per compute unit: eight waves per column, pairs of lanes sharing a chunk
+    // (d = n = 1024, m = 32, k = 32: 108.6 -> 102.3 us per forward + backward against the 4-wave kernel below)
+    if (chain_pair_serves(a) && a.m <= kComputeUnits) {
+      if (k == 32) return launch_chain_pair<1, 4, 4, 3, 2>(a, stream);
+      if (k == 64) return launch_chain_pair<2, 4, 4, 3, 2>(a, stream);
+      return launch_chain_pair<4, 4, 4, 3, 2>(a, stream);
+    }
     // More columns than compute units (and too few for the matrix-core kernel): steps of 16 rows take 166 registers
     // against the 291 of 32-row steps, so three workgroups share a compute unit and fill each other's waits
     // (d = 1024, k = 32, per forward + backward: m = 384: 233 -> 194 us, m = 512: 244 -> 222, m = 768: 356 -> 321;

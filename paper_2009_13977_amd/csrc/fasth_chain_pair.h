@@ -1,0 +1,225 @@
+// Algorithm 1 Step 2 and Algorithm 2 Step 1 for 512 < d <= 1024 and blocks of 32, 64 or 128 rows: chain_pair_kernel,
+// the per-column chain with two waves per SIMD.
+// Included by fasth_chain.h.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include "fasth_common.h"
+
+namespace fasth {
+
+// A fetch keeps the wave that issues it from its arithmetic for ~35 clocks, and with one wave per SIMD (the 4-wave
+// kernel) nothing else can use the SIMD meanwhile. Eight waves, two per SIMD, can fill each other's stalls; but a
+// wave-wide fetch costs the compute unit's address unit the same 16 clocks whether its lanes take 16 or 8 bytes, so
+// the eight waves together must not issue more fetches than the four did. Here two lanes share one 16-byte chunk of
+// the column (x = 4J .. 4J + 3, both hold the same four elements of `a`) and split the ROWS of a step between them:
+// the lane of parity h holds rows 2jj + h of the 32-row step, 16 fetches of 16 bytes per lane and step instead of 32.
+//   B = V a:      each lane forms the partial inner products of its 16 rows; they are summed over the 32 lanes of
+//                 equal parity (register butterfly that skips the parity bit) and over the waves through LDS.
+//   a -= V^T C:   the lane of parity 0 starts from a, the other from 0, each subtracts its 16 rows' terms, and
+//                 the two exchange their sums with one DPP move per element: x + y = y + x exactly, so both lanes
+//                 keep bit-identical copies of a.
+// The parity is lane bit 3 and the partner of lane i is lane i ^ 15 of its row of 16 (DPP row_mirror): lanes 0..7 of a
+// row take chunks c .. c + 7 of one row of V, lanes 8..15 the same chunks of the next row in reverse order, so 8
+// adjacent lanes fetch 128 contiguous bytes, which costs the address unit no more than 1 KiB contiguous per wave
+// (lane pairs (2j, 2j + 1) on alternate rows cost twice as much). The butterfly's remaining stages use lane bits
+// 5, 4 (permlane swaps) and 2, 1, 0 (DPP half-mirror and quad permutes, none of which changes bit 3).
+struct PairLanes {
+  static constexpr int M0 = 4, M1 = 2, M2 = 1;  // lane bits below 8 for the last two halving stages and the last sum
+  __device__ static __forceinline__ int parity(int lane) { return (lane >> 3) & 1; }
+  // chunk of the wave's 32 that the lane works on
+  __device__ static __forceinline__ int chunk(int lane) { return 8 * (lane >> 4) + ((lane & 8) ? 7 - (lane & 7) : (lane & 7)); }
+  __device__ static __forceinline__ float partner(float x) { return dpp_move<kDppRowMirror>(x); }
+};
+
+struct PairRegs {
+  Chunk<4> v[16];  // this lane's 16 rows of the step, its pair's chunk
+  float t[2];      // two entries of this thread's row of op(T) of the step
+};
+
+// SUB: steps of 32 rows per block (k = 32 SUB; the diagonal 32 x 32 blocks of T_i are the steps' factors).
+// Three register copies of a step's rows (64 registers each): while step s is applied, the rows of step s + 2 are
+// fetched, so every fetch has more than a whole step to arrive and may be issued wherever it costs least.
+// Of a lane's 16 fetches per step, P1 are issued during the first product, RL during the reduction, XA after the
+// first barrier and XC after the second (while the LDS reads issued there are on their way), the rest during the update.
+template <int SUB, int P1, int RL, int XA, int XC>
+__global__ void __launch_bounds__(512) chain_pair_kernel(ChainArgs p) {
+  typedef PairLanes Lanes;
+  constexpr int K = 32, KH = 16, NW = 8, G = 16;
+  constexpr int PR2 = KH - RL - P1 - XA - XC;
+  constexpr int S1 = KH / P1, S2 = KH / PR2;
+  constexpr int RS = RL > 4 ? 2 : 4;  // one fetch every RS exchanges of the reduction
+  constexpr int XA0 = P1 + RL, XC0 = XA0 + XA, U0 = XC0 + XC;
+  static_assert(P1 >= 1 && PR2 >= 1 && RL >= 0 && RL <= 8 && XA >= 0 && XC >= 0, "prefetch split");
+  __shared__ __align__(16) float Bpart[NW][K];
+  __shared__ __align__(16) float Cv[2][KH];  // [parity][jj] = coefficient of row 2 jj + parity
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int col = blockIdx.x, m = p.m, d = p.d;
+  if (col >= m) {  // workgroups beyond the columns: the side product, on compute units the chain leaves idle
+    const int row = (col - m) * NW + wave;
+    if (row < p.ds_rows) dsigma_row(p.in, p.ds_z1, p.in_scale, p.ds_out, row, m, p.in_scale_mode);
+    return;
+  }
+  const int h = Lanes::parity(lane);
+  const unsigned x0w = 4u * (unsigned)(wave * 32 + Lanes::chunk(lane));
+  const bool ok = x0w < (unsigned)d;
+  const unsigned x0 = ok ? x0w : 0u;  // lanes beyond d fetch chunk 0 (valid memory) and keep their elements at zero
+  const unsigned lane_off = (unsigned)h * (unsigned)d + x0;
+  Chunk<4> a = load_column_chunk<4>(p, col, x0, ok);
+  const int trow = tid / G, tg = tid % G;
+  const int nb = p.nb;
+  const int sel = ((lane & 32) ? 8 : 0) + ((lane & 16) ? 4 : 0) + ((lane & Lanes::M0) ? 2 : 0) + ((lane & Lanes::M1) ? 1 : 0);
+  const bool writer = (lane & Lanes::M2) == 0;
+  auto block_of = [&](int s) { return p.transpose ? s : nb - 1 - s; };  // step index of the s-th step applied
+  auto step_block = [&](int i) { return SUB == 1 ? i : i / SUB; };
+  auto step_part = [&](int i) { return SUB == 1 ? 0 : i % SUB; };
+  auto load_row = [&](int i, int jj, Chunk<4>& dst) {
+    dst = load_chunk<4>(p.V + ((size_t)i * K + 2 * jj) * (size_t)d + lane_off);
+  };
+  auto load_t = [&](int i, PairRegs& r) {
+    constexpr int LDT = K * SUB;
+    const float* Ti = (p.transpose ? p.Tt : p.T) + (size_t)step_block(i) * LDT * LDT + (size_t)step_part(i) * (K * LDT + K);
+    const float2 t2 = *reinterpret_cast<const float2*>(Ti + trow * LDT + 2 * tg);
+    r.t[0] = t2.x; r.t[1] = t2.y;
+  };
+
+  // Applies step i held in `cur` while fetching step ifetch (two steps on) into `dst`.
+  auto apply_step = [&](int i, PairRegs& cur, int ifetch, PairRegs& dst) {
+    if (p.save_in && ok && h == 0 && (SUB == 1 || step_part(i) == (p.transpose ? 0 : SUB - 1)))
+      store_chunk<4>(p.save_in + ((size_t)step_block(i) * m + col) * d + x0, a);
+    float pj[KH];
+#pragma unroll
+    for (int jj = 0; jj < KH; ++jj) {
+      if (jj % S1 == 0 && jj / S1 < P1) {
+        load_row(ifetch, jj / S1, dst.v[jj / S1]);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      float acc = 0.f;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) acc = fmaf(cur.v[jj].e[r], a.e[r], acc);
+      pj[jj] = acc;
+    }
+    load_t(ifetch, dst);
+    auto prefetch = [&](int t) {
+      if (t % RS == 0 && t / RS < RL) {
+        __builtin_amdgcn_sched_barrier(0);
+        load_row(ifetch, P1 + t / RS, dst.v[P1 + t / RS]);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    };
+    // sum over the 32 lanes of this parity: 16 values, five lane bits
+    reduce_stage<KH, 16, 32, 0>(pj, lane, prefetch);
+    reduce_stage<KH, 8, 16, 8>(pj, lane, prefetch);
+    reduce_stage<KH, 4, Lanes::M0, 12>(pj, lane, prefetch);
+    reduce_stage<KH, 2, Lanes::M1, 14>(pj, lane, prefetch);
+    reduce_stage<KH, 1, Lanes::M2, 15>(pj, lane, prefetch);
+    if (writer) Bpart[wave][2 * sel + h] = pj[0];
+    lds_barrier();
+    {
+      float2 bw[NW];
+#pragma unroll
+      for (int w = 0; w < NW; ++w) bw[w] = *reinterpret_cast<const float2*>(&Bpart[w][2 * tg]);
+      if constexpr (XA > 0) {  // fetches while the partial sums are on their way from LDS
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int e = 0; e < XA; ++e) load_row(ifetch, XA0 + e, dst.v[XA0 + e]);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      float2 b = bw[0];
+#pragma unroll
+      for (int w = 1; w < NW; ++w) {
+        b.x += bw[w].x;
+        b.y += bw[w].y;
+      }
+      float c = fmaf(cur.t[1], b.y, cur.t[0] * b.x);
+      c = group_sum<G>(c);
+      if (tg == 0) {
+        Cv[trow & 1][trow >> 1] = c;
+        if (p.save_c) p.save_c[(size_t)col * p.n + (size_t)i * K + trow] = c;
+      }
+    }
+    lds_barrier();
+    float cc[2][8];
+    auto read_cc = [&](int grp, float (&out)[8]) {
+#pragma unroll
+      for (int j4 = 0; j4 < 2; ++j4) {
+        const float4 c4 = reinterpret_cast<const float4*>(Cv[h])[grp * 2 + j4];
+        out[4 * j4] = c4.x; out[4 * j4 + 1] = c4.y; out[4 * j4 + 2] = c4.z; out[4 * j4 + 3] = c4.w;
+      }
+    };
+    read_cc(0, cc[0]);
+    read_cc(1, cc[1]);
+    if constexpr (XC > 0) {  // fetches while the coefficients are on their way from LDS
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int e = 0; e < XC; ++e) load_row(ifetch, XC0 + e, dst.v[XC0 + e]);
+    }
+    float acc[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) acc[r] = h == 0 ? a.e[r] : 0.f;
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int jj = 0; jj < KH; ++jj) {
+      if (jj % S2 == 0 && jj / S2 < PR2) {
+        // the multiply-adds so far stay ahead of this fetch (instruction selection would otherwise issue the
+        // step's fetches in one burst while the coefficients are still on their way from LDS)
+        if (jj > 0) asm volatile("" : "+v"(acc[0]), "+v"(acc[1]), "+v"(acc[2]), "+v"(acc[3]));
+        __builtin_amdgcn_sched_barrier(0);
+        load_row(ifetch, U0 + jj / S2, dst.v[U0 + jj / S2]);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+#pragma unroll
+      for (int r = 0; r < 4; ++r) acc[r] = fmaf(-cc[jj / 8][jj % 8], cur.v[jj].e[r], acc[r]);
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const float sum = acc[r] + Lanes::partner(acc[r]);
+      a.e[r] = ok ? sum : 0.f;
+    }
+  };
+
+  auto step_at = [&](int s) { return block_of(s < nb ? s : nb - 1); };  // fetches past the end repeat the last step
+  PairRegs ra, rb, rc;
+#pragma unroll
+  for (int jj = 0; jj < KH; ++jj) load_row(step_at(0), jj, ra.v[jj]);
+  load_t(step_at(0), ra);
+#pragma unroll
+  for (int jj = 0; jj < KH; ++jj) load_row(step_at(1), jj, rb.v[jj]);
+  load_t(step_at(1), rb);
+  int s = 0;
+  for (; s + 2 < nb; s += 3) {
+    apply_step(block_of(s), ra, step_at(s + 2), rc);
+    apply_step(block_of(s + 1), rb, step_at(s + 3), ra);
+    apply_step(block_of(s + 2), rc, step_at(s + 4), rb);
+  }
+  if (s < nb) {
+    apply_step(block_of(s), ra, step_at(s + 2), rc);
+    if (s + 1 < nb) apply_step(block_of(s + 1), rb, step_at(s + 3), ra);
+  }
+  if (ok) {
+    // each lane of a pair stores two of the chunk's four elements
+    const float o0 = h ? a.e[2] : a.e[0], o1 = h ? a.e[3] : a.e[1];
+    p.out[(size_t)(x0 + 2 * h) * m + col] = o0;
+    p.out[(size_t)(x0 + 2 * h + 1) * m + col] = o1;
+  }
+}
+
+static bool chain_pair_serves(const ChainArgs& a) {
+  return a.d > 512 && a.d <= 1024 && a.d % 4 == 0 && (a.k == 32 || a.k == 64 || a.k == 128);
+}
+
+template <int SUB, int P1, int RL, int XA, int XC>
+static int launch_chain_pair(const ChainArgs& args, hipStream_t stream) {
+  ChainArgs a = args;
+  a.sub = SUB;
+  a.nb = args.nb * SUB;
+  if (!chain_pair_serves(a) || a.k != 32 * SUB || a.kp != a.k) return FASTH_EINVAL;
+  const int side = a.ds_out ? (a.ds_rows + 7) / 8 : 0;
+  prof::Scope ps_(FASTH_KERNEL_CHAIN, stream);
+  hipLaunchKernelGGL((chain_pair_kernel<SUB, P1, RL, XA, XC>), dim3(a.m + side), dim3(512), 0, stream, a);
+  FASTH_HIP(hipGetLastError());
+  return FASTH_OK;
+}
+
+}  // namespace fasth
