@@ -545,12 +545,20 @@ static int launch_chain_kernel(const ChainArgs& a, hipStream_t stream) {
     if (k == 8 && d <= 512) return launch_chain_pipe<8, 2, 256, 2>(a, stream);
     if (k == 16 && d <= 1024) return launch_chain_pipe<16, 4, 256, 4, 1, false, 4, false, 1>(a, stream);
     if (k == 16 && d <= 2048) return launch_chain_pipe<16, 4, 512, 4, 1, false, 4, false, 1>(a, stream);
-    // 512 < d <= 1024, at most one column per compute unit: eight waves per column, pairs of lanes sharing a chunk
-    // (d = n = 1024, m = 32, k = 32: 108.6 -> 102.3 us per forward + backward against the 4-wave kernel below)
+    // Blocks of 32, 64 or 128 rows, at most one column per compute unit: one wave per 128 elements of the column,
+    // pairs of lanes sharing a chunk (d = n = 1024, m = 32, k = 32: 108.6 -> 102.3 us per forward + backward against
+    // the kernels below; d = 512: 54.2 -> 44.8 us; d = 256: 30.4 -> 29.1 us)
     if (chain_pair_serves(a) && a.m <= kComputeUnits) {
-      if (k == 32) return launch_chain_pair<1, 4, 4, 3, 2>(a, stream);
-      if (k == 64) return launch_chain_pair<2, 4, 4, 3, 2>(a, stream);
-      return launch_chain_pair<4, 4, 4, 3, 2>(a, stream);
+#define FASTH_LAUNCH_PAIR(NW)                                                    \
+  do {                                                                           \
+    if (k == 32) return launch_chain_pair<NW, 1, 4, 4, 3, 2>(a, stream);         \
+    if (k == 64) return launch_chain_pair<NW, 2, 4, 4, 3, 2>(a, stream);         \
+    return launch_chain_pair<NW, 4, 4, 4, 3, 2>(a, stream);                      \
+  } while (0)
+      if (d <= 256) FASTH_LAUNCH_PAIR(2);
+      if (d <= 512) FASTH_LAUNCH_PAIR(4);
+      FASTH_LAUNCH_PAIR(8);
+#undef FASTH_LAUNCH_PAIR
     }
     // More columns than compute units (and too few for the matrix-core kernel): steps of 16 rows take 166 registers
     // against the 291 of 32-row steps, so three workgroups share a compute unit and fill each other's waits

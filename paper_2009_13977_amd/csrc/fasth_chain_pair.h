@@ -1,5 +1,5 @@
-// Algorithm 1 Step 2 and Algorithm 2 Step 1 for 512 < d <= 1024 and blocks of 32, 64 or 128 rows: chain_pair_kernel,
-// the per-column chain with two waves per SIMD.
+// Algorithm 1 Step 2 and Algorithm 2 Step 1 for d <= 1024 (a multiple of 4) and blocks of 32, 64 or 128 rows:
+// chain_pair_kernel, the per-column chain in which pairs of lanes share a chunk of the column.
 // Included by fasth_chain.h.
 #pragma once
 #include <hip/hip_runtime.h>
@@ -32,9 +32,10 @@ struct PairLanes {
   __device__ static __forceinline__ float partner(float x) { return dpp_move<kDppRowMirror>(x); }
 };
 
+template <int LPT>
 struct PairRegs {
   Chunk<4> v[16];  // this lane's 16 rows of the step, its pair's chunk
-  float t[2];      // two entries of this thread's row of op(T) of the step
+  float t[LPT];    // this thread's entries of its row of op(T) of the step
 };
 
 // SUB: steps of 32 rows per block (k = 32 SUB; the diagonal 32 x 32 blocks of T_i are the steps' factors).
@@ -42,10 +43,13 @@ struct PairRegs {
 // fetched, so every fetch has more than a whole step to arrive and may be issued wherever it costs least.
 // Of a lane's 16 fetches per step, P1 are issued during the first product, RL during the reduction, XA after the
 // first barrier and XC after the second (while the LDS reads issued there are on their way), the rest during the update.
-template <int SUB, int P1, int RL, int XA, int XC>
-__global__ void __launch_bounds__(512) chain_pair_kernel(ChainArgs p) {
+// NW: waves per workgroup, 128 elements of the column each (8 for d <= 1024, 4 for d <= 512, 2 for d <= 256).
+template <int NW, int SUB, int P1, int RL, int XA, int XC>
+__global__ void __launch_bounds__(64 * NW) chain_pair_kernel(ChainArgs p) {
   typedef PairLanes Lanes;
-  constexpr int K = 32, KH = 16, NW = 8, G = 16;
+  constexpr int K = 32, KH = 16, G = 2 * NW, LPT = K / G;  // G threads share a row of op(T), LPT entries each
+  typedef PairRegs<LPT> Regs;
+  static_assert(NW == 2 || NW == 4 || NW == 8, "waves");
   constexpr int PR2 = KH - RL - P1 - XA - XC;
   constexpr int S1 = KH / P1, S2 = KH / PR2;
   constexpr int RS = RL > 4 ? 2 : 4;  // one fetch every RS exchanges of the reduction
@@ -77,15 +81,24 @@ __global__ void __launch_bounds__(512) chain_pair_kernel(ChainArgs p) {
   auto load_row = [&](int i, int jj, Chunk<4>& dst) {
     dst = load_chunk<4>(p.V + ((size_t)i * K + 2 * jj) * (size_t)d + lane_off);
   };
-  auto load_t = [&](int i, PairRegs& r) {
+  auto load_t = [&](int i, Regs& r) {
     constexpr int LDT = K * SUB;
     const float* Ti = (p.transpose ? p.Tt : p.T) + (size_t)step_block(i) * LDT * LDT + (size_t)step_part(i) * (K * LDT + K);
-    const float2 t2 = *reinterpret_cast<const float2*>(Ti + trow * LDT + 2 * tg);
-    r.t[0] = t2.x; r.t[1] = t2.y;
+    const float* src = Ti + trow * LDT + LPT * tg;
+    if constexpr (LPT == 2) {
+      const float2 t2 = *reinterpret_cast<const float2*>(src);
+      r.t[0] = t2.x; r.t[1] = t2.y;
+    } else {
+#pragma unroll
+      for (int e4 = 0; e4 < LPT / 4; ++e4) {
+        const float4 t4 = reinterpret_cast<const float4*>(src)[e4];
+        r.t[4 * e4] = t4.x; r.t[4 * e4 + 1] = t4.y; r.t[4 * e4 + 2] = t4.z; r.t[4 * e4 + 3] = t4.w;
+      }
+    }
   };
 
   // Applies step i held in `cur` while fetching step ifetch (two steps on) into `dst`.
-  auto apply_step = [&](int i, PairRegs& cur, int ifetch, PairRegs& dst) {
+  auto apply_step = [&](int i, Regs& cur, int ifetch, Regs& dst) {
     if (p.save_in && ok && h == 0 && (SUB == 1 || step_part(i) == (p.transpose ? 0 : SUB - 1)))
       store_chunk<4>(p.save_in + ((size_t)step_block(i) * m + col) * d + x0, a);
     float pj[KH];
@@ -117,22 +130,34 @@ __global__ void __launch_bounds__(512) chain_pair_kernel(ChainArgs p) {
     if (writer) Bpart[wave][2 * sel + h] = pj[0];
     lds_barrier();
     {
-      float2 bw[NW];
+      float bw[NW][LPT];
 #pragma unroll
-      for (int w = 0; w < NW; ++w) bw[w] = *reinterpret_cast<const float2*>(&Bpart[w][2 * tg]);
+      for (int w = 0; w < NW; ++w) {
+        if constexpr (LPT == 2) {
+          const float2 t2 = *reinterpret_cast<const float2*>(&Bpart[w][LPT * tg]);
+          bw[w][0] = t2.x; bw[w][1] = t2.y;
+        } else {
+#pragma unroll
+          for (int e4 = 0; e4 < LPT / 4; ++e4) {
+            const float4 t4 = *reinterpret_cast<const float4*>(&Bpart[w][LPT * tg + 4 * e4]);
+            bw[w][4 * e4] = t4.x; bw[w][4 * e4 + 1] = t4.y; bw[w][4 * e4 + 2] = t4.z; bw[w][4 * e4 + 3] = t4.w;
+          }
+        }
+      }
       if constexpr (XA > 0) {  // fetches while the partial sums are on their way from LDS
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int e = 0; e < XA; ++e) load_row(ifetch, XA0 + e, dst.v[XA0 + e]);
         __builtin_amdgcn_sched_barrier(0);
       }
-      float2 b = bw[0];
+      float c = 0.f;
 #pragma unroll
-      for (int w = 1; w < NW; ++w) {
-        b.x += bw[w].x;
-        b.y += bw[w].y;
+      for (int e = 0; e < LPT; ++e) {
+        float b = bw[0][e];
+#pragma unroll
+        for (int w = 1; w < NW; ++w) b += bw[w][e];
+        c = fmaf(cur.t[e], b, c);
       }
-      float c = fmaf(cur.t[1], b.y, cur.t[0] * b.x);
       c = group_sum<G>(c);
       if (tg == 0) {
         Cv[trow & 1][trow >> 1] = c;
@@ -180,7 +205,7 @@ __global__ void __launch_bounds__(512) chain_pair_kernel(ChainArgs p) {
   };
 
   auto step_at = [&](int s) { return block_of(s < nb ? s : nb - 1); };  // fetches past the end repeat the last step
-  PairRegs ra, rb, rc;
+  Regs ra, rb, rc;
 #pragma unroll
   for (int jj = 0; jj < KH; ++jj) load_row(step_at(0), jj, ra.v[jj]);
   load_t(step_at(0), ra);
@@ -206,18 +231,18 @@ __global__ void __launch_bounds__(512) chain_pair_kernel(ChainArgs p) {
 }
 
 static bool chain_pair_serves(const ChainArgs& a) {
-  return a.d > 512 && a.d <= 1024 && a.d % 4 == 0 && (a.k == 32 || a.k == 64 || a.k == 128);
+  return a.d <= 1024 && a.d % 4 == 0 && (a.k == 32 || a.k == 64 || a.k == 128);
 }
 
-template <int SUB, int P1, int RL, int XA, int XC>
+template <int NW, int SUB, int P1, int RL, int XA, int XC>
 static int launch_chain_pair(const ChainArgs& args, hipStream_t stream) {
   ChainArgs a = args;
   a.sub = SUB;
   a.nb = args.nb * SUB;
-  if (!chain_pair_serves(a) || a.k != 32 * SUB || a.kp != a.k) return FASTH_EINVAL;
-  const int side = a.ds_out ? (a.ds_rows + 7) / 8 : 0;
+  if (!chain_pair_serves(a) || a.d > 128 * NW || a.k != 32 * SUB || a.kp != a.k) return FASTH_EINVAL;
+  const int side = a.ds_out ? (a.ds_rows + NW - 1) / NW : 0;
   prof::Scope ps_(FASTH_KERNEL_CHAIN, stream);
-  hipLaunchKernelGGL((chain_pair_kernel<SUB, P1, RL, XA, XC>), dim3(a.m + side), dim3(512), 0, stream, a);
+  hipLaunchKernelGGL((chain_pair_kernel<NW, SUB, P1, RL, XA, XC>), dim3(a.m + side), dim3(64 * NW), 0, stream, a);
   FASTH_HIP(hipGetLastError());
   return FASTH_OK;
 }

@@ -63,9 +63,9 @@ DISPATCH = [
     (2048, 40, 2, 8), (2048, 20, 2, 5), (1536, 72, 2, 24), (1280, 200, 2, 100),
     (512, 256, 3, 128), (256, 256, 2, 128), (256, 48, 3, 16), (512, 48, 3, 16), (200, 40, 3, 8), (400, 40, 3, 8),
     (2046, 14, 2, 7), (9000, 16, 2, 8), (12290, 8, 1, 8),
-    # 512 < d <= 1024, blocks of 32 / 64 / 128 rows: eight waves per column, lane pairs; chains of one to five steps
+    # blocks of 32 / 64 / 128 rows, d a multiple of 4 up to 1024: 2, 4 or 8 waves per column, lane pairs; chains of one to five steps
     (1024, 32, 4, 32), (1024, 64, 3, 32), (516, 96, 2, 32), (1000, 160, 33, 32), (768, 128, 5, 64), (1024, 256, 3, 128),
-    (640, 128, 200, 128),
+    (640, 128, 200, 128), (512, 128, 9, 64), (260, 64, 7, 32), (384, 96, 2, 32), (8, 32, 3, 32), (132, 256, 40, 128),
 ]
 
 
