@@ -548,7 +548,13 @@ static int launch_chain_kernel(const ChainArgs& a, hipStream_t stream) {
     // Blocks of 32, 64 or 128 rows, at most one column per compute unit: one wave per 128 elements of the column,
     // pairs of lanes sharing a chunk (d = n = 1024, m = 32, k = 32: 108.6 -> 102.3 us per forward + backward against
     // the kernels below; d = 512: 54.2 -> 44.8 us; d = 256: 30.4 -> 29.1 us)
-    if (chain_pair_serves(a) && a.m <= kComputeUnits) {
+    // (with more columns than compute units it stays the faster one up to d = 512, where two or four of its workgroups
+    // share a unit: d = 512, m = 512: 108 -> 86 us, m = 1024: 194 -> 148 us; beyond, the 16-row steps further down win)
+    // (at d = 1024 the 4-wave kernel is the faster one again from about 180 columns on, when most compute units of
+    // an XCD stream V from its L2 at once: m = 160: 120.5 -> 118.4 us, m = 192: 121.8 -> 122.6, m = 256: 127.7 -> 133.4;
+    // at d = 768 the pairs win up to 256 columns, 101.2 -> 92.7 us)
+    const int pair_max_cols = d > 896 ? 176 : kComputeUnits;
+    if (chain_pair_serves(a) && (a.m <= pair_max_cols || d <= 512)) {
 #define FASTH_LAUNCH_PAIR(NW)                                                    \
   do {                                                                           \
     if (k == 32) return launch_chain_pair<NW, 1, 4, 4, 3, 2>(a, stream);         \
