@@ -575,16 +575,9 @@ static int launch_chain_kernel(const ChainArgs& a, hipStream_t stream) {
       if (k == 64) return launch_chain_pipe<16, 4, 256, 4, 4, false, 4, false, 1>(a, stream);
       if (k == 128) return launch_chain_pipe<16, 4, 256, 4, 8, false, 4, false, 1>(a, stream);
     }
-    if (k == 32 && d <= 256) return launch_chain_pipe<32, 1, 256, 8, 1, false, 7, false, 1>(a, stream);
-    if (k == 32 && d <= 512) return launch_chain_pipe<32, 2, 256, 8, 1, false, 7, false, 1>(a, stream);
     // (7 of the 32 rows of the next block fetched during the first product, 8 during the reduction, 4 next to the
     // barriers, 13 during the update)
     if (k == 32 && d <= 1024) return launch_chain_pipe<32, 4, 256, 8, 1, false, 7, false, 1>(a, stream);
-    // blocks of 64 and 128 rows as steps of 32, at the lane width that keeps all four waves busy
-    if (k == 64 && d <= 256) return launch_chain_pipe<32, 1, 256, 8, 2, false, 7, false, 1>(a, stream);
-    if (k == 64 && d <= 512) return launch_chain_pipe<32, 2, 256, 8, 2, false, 7, false, 1>(a, stream);
-    if (k == 128 && d <= 256) return launch_chain_pipe<32, 1, 256, 8, 4, false, 7, false, 1>(a, stream);
-    if (k == 128 && d <= 512) return launch_chain_pipe<32, 2, 256, 8, 4, false, 7, false, 1>(a, stream);
     // Larger blocks and longer vectors: two register copies of the whole block do not fit, but the block can be
     // applied as steps of 32 rows (d <= 1024) or 16 rows (d <= 2048, two waves per SIMD), which is faster than
     // one copy refilled in place or rows streamed twice (d = n = 2048: 178 us for k = 32, 64 and 128 alike,

@@ -67,6 +67,7 @@ DISPATCH = [
     (1024, 32, 4, 32), (1024, 64, 3, 32), (516, 96, 2, 32), (1000, 160, 33, 32), (768, 128, 5, 64), (1024, 256, 3, 128),
     (640, 128, 200, 128), (512, 128, 9, 64), (260, 64, 7, 32), (384, 96, 2, 32), (8, 32, 3, 32), (132, 256, 40, 128),
     (512, 64, 300, 32), (256, 128, 700, 64), (384, 128, 1024, 128),  # the same with several workgroups per compute unit
+    (1024, 64, 200, 32), (1000, 128, 180, 64), (1024, 128, 256, 128),  # d > 896, 177 .. 256 columns: four waves, 32-row steps
 ]
 
 
