@@ -26,7 +26,7 @@ if ROOT not in sys.path:
 
 FP32_MATRIX_PEAK_TFLOPS = 157.3  # MI355X published dense fp32 matrix (MFMA) and packed-vector peak
 HBM_PEAK_GBS = 8000.0
-CHAIN_TRAFFIC_BYTES = {"d1024_m32_k32": 17512.0 * 1024 * 2.0 + 4340.0 * 1024,
+CHAIN_TRAFFIC_BYTES = {"d1024_m32_k32": 17522.0 * 1024 * 2.0 + 4340.0 * 1024,
                        # chain_tile_kernel with the block inputs saved (profiles/kernel_trace_and_mfma_d1024_m4096_k32.txt)
                        "d1024_m4096_k32": 33445.0 * 1024 * 2.0 + 557000.0 * 1024}
 
