@@ -555,11 +555,15 @@ static int launch_chain_kernel(const ChainArgs& a, hipStream_t stream) {
     // at d = 768 the pairs win up to 256 columns, 101.2 -> 92.7 us)
     const int pair_max_cols = d > 896 ? 176 : kComputeUnits;
     if (chain_pair_serves(a) && (a.m <= pair_max_cols || d <= 512)) {
-#define FASTH_LAUNCH_PAIR(NW)                                                    \
-  do {                                                                           \
-    if (k == 32) return launch_chain_pair<NW, 1, 4, 4, 3, 2>(a, stream);         \
-    if (k == 64) return launch_chain_pair<NW, 2, 4, 4, 3, 2>(a, stream);         \
-    return launch_chain_pair<NW, 4, 4, 4, 3, 2>(a, stream);                      \
+#define FASTH_LAUNCH_PAIR(NW)                                                             \
+  do {                                                                                    \
+    if (k == 32) return launch_chain_pair<NW, 1, 4, 4, 3, 2>(a, stream);                  \
+    if (k == 64) return launch_chain_pair<NW, 2, 4, 4, 3, 2>(a, stream);                  \
+    if (k == 128) return launch_chain_pair<NW, 4, 4, 4, 3, 2>(a, stream);                 \
+    if (k < 32) return launch_chain_pair<NW, 1, 4, 4, 3, 2, true>(a, stream);             \
+    if (k < 64) return launch_chain_pair<NW, 2, 4, 4, 3, 2, true>(a, stream);             \
+    if (k <= 96) return launch_chain_pair<NW, 3, 4, 4, 3, 2, true>(a, stream);            \
+    return launch_chain_pair<NW, 4, 4, 4, 3, 2, true>(a, stream);                         \
   } while (0)
       if (d <= 256) FASTH_LAUNCH_PAIR(2);
       if (d <= 512) FASTH_LAUNCH_PAIR(4);

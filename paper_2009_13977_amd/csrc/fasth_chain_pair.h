@@ -39,12 +39,14 @@ struct PairRegs {
 };
 
 // SUB: steps of 32 rows per block (k = 32 SUB; the diagonal 32 x 32 blocks of T_i are the steps' factors).
+// PAD: k is not a multiple of 32 and SUB = ceil(k / 32): the last step of a block has fewer than 32 rows; its missing
+// rows repeat the last valid one and their inner products and coefficients are forced to zero.
 // Three register copies of a step's rows (64 registers each): while step s is applied, the rows of step s + 2 are
 // fetched, so every fetch has more than a whole step to arrive and may be issued wherever it costs least.
 // Of a lane's 16 fetches per step, P1 are issued during the first product, RL during the reduction, XA after the
 // first barrier and XC after the second (while the LDS reads issued there are on their way), the rest during the update.
 // NW: waves per workgroup, 128 elements of the column each (8 for d <= 1024, 4 for d <= 512, 2 for d <= 256).
-template <int NW, int SUB, int P1, int RL, int XA, int XC>
+template <int NW, int SUB, int P1, int RL, int XA, int XC, bool PAD = false>
 __global__ void __launch_bounds__(64 * NW) chain_pair_kernel(ChainArgs p) {
   typedef PairLanes Lanes;
   constexpr int K = 32, KH = 16, G = 2 * NW, LPT = K / G;  // G threads share a row of op(T), LPT entries each
@@ -78,11 +80,20 @@ __global__ void __launch_bounds__(64 * NW) chain_pair_kernel(ChainArgs p) {
   auto block_of = [&](int s) { return p.transpose ? s : nb - 1 - s; };  // step index of the s-th step applied
   auto step_block = [&](int i) { return SUB == 1 ? i : i / SUB; };
   auto step_part = [&](int i) { return SUB == 1 ? 0 : i % SUB; };
+  auto rows_valid = [&](int i) { return PAD ? min(K, p.k - step_part(i) * K) : K; };
   auto load_row = [&](int i, int jj, Chunk<4>& dst) {
-    dst = load_chunk<4>(p.V + ((size_t)i * K + 2 * jj) * (size_t)d + lane_off);
+    if constexpr (PAD) {
+      // rows 2jj and 2jj + 1 of the step, clamped to its last valid row (scalar arithmetic but for one select)
+      const int kv = rows_valid(i);
+      const int row0 = step_block(i) * p.k + step_part(i) * K + min(2 * jj, kv - 1);
+      const unsigned off = 2 * jj + 1 < kv ? lane_off : x0;
+      dst = load_chunk<4>(p.V + (size_t)row0 * (size_t)d + off);
+    } else {
+      dst = load_chunk<4>(p.V + ((size_t)i * K + 2 * jj) * (size_t)d + lane_off);
+    }
   };
   auto load_t = [&](int i, Regs& r) {
-    constexpr int LDT = K * SUB;
+    const int LDT = PAD ? p.kp : K * SUB;  // row stride of the stored factor
     const float* Ti = (p.transpose ? p.Tt : p.T) + (size_t)step_block(i) * LDT * LDT + (size_t)step_part(i) * (K * LDT + K);
     const float* src = Ti + trow * LDT + LPT * tg;
     if constexpr (LPT == 2) {
@@ -101,6 +112,7 @@ __global__ void __launch_bounds__(64 * NW) chain_pair_kernel(ChainArgs p) {
   auto apply_step = [&](int i, Regs& cur, int ifetch, Regs& dst) {
     if (p.save_in && ok && h == 0 && (SUB == 1 || step_part(i) == (p.transpose ? 0 : SUB - 1)))
       store_chunk<4>(p.save_in + ((size_t)step_block(i) * m + col) * d + x0, a);
+    const int kv = rows_valid(i);
     float pj[KH];
 #pragma unroll
     for (int jj = 0; jj < KH; ++jj) {
@@ -111,7 +123,7 @@ __global__ void __launch_bounds__(64 * NW) chain_pair_kernel(ChainArgs p) {
       float acc = 0.f;
 #pragma unroll
       for (int r = 0; r < 4; ++r) acc = fmaf(cur.v[jj].e[r], a.e[r], acc);
-      pj[jj] = acc;
+      pj[jj] = (PAD && 2 * jj + h >= kv) ? 0.f : acc;
     }
     load_t(ifetch, dst);
     auto prefetch = [&](int t) {
@@ -159,9 +171,14 @@ __global__ void __launch_bounds__(64 * NW) chain_pair_kernel(ChainArgs p) {
         c = fmaf(cur.t[e], b, c);
       }
       c = group_sum<G>(c);
+      if (PAD && trow >= kv) c = 0.f;
       if (tg == 0) {
         Cv[trow & 1][trow >> 1] = c;
-        if (p.save_c) p.save_c[(size_t)col * p.n + (size_t)i * K + trow] = c;
+        if constexpr (PAD) {
+          if (p.save_c && trow < kv) p.save_c[(size_t)col * p.n + (size_t)step_block(i) * p.k + step_part(i) * K + trow] = c;
+        } else {
+          if (p.save_c) p.save_c[(size_t)col * p.n + (size_t)i * K + trow] = c;
+        }
       }
     }
     lds_barrier();
@@ -230,19 +247,19 @@ __global__ void __launch_bounds__(64 * NW) chain_pair_kernel(ChainArgs p) {
   }
 }
 
-static bool chain_pair_serves(const ChainArgs& a) {
-  return a.d <= 1024 && a.d % 4 == 0 && (a.k == 32 || a.k == 64 || a.k == 128);
-}
+// Blocks of more than 16 rows (smaller ones would mostly fetch repeated rows in a 32-row step).
+static bool chain_pair_serves(const ChainArgs& a) { return a.d <= 1024 && a.d % 4 == 0 && a.k > 16; }
 
-template <int NW, int SUB, int P1, int RL, int XA, int XC>
+template <int NW, int SUB, int P1, int RL, int XA, int XC, bool PAD = false>
 static int launch_chain_pair(const ChainArgs& args, hipStream_t stream) {
   ChainArgs a = args;
   a.sub = SUB;
   a.nb = args.nb * SUB;
-  if (!chain_pair_serves(a) || a.d > 128 * NW || a.k != 32 * SUB || a.kp != a.k) return FASTH_EINVAL;
+  if (!chain_pair_serves(a) || a.d > 128 * NW || SUB != (a.k + 31) / 32 || (!PAD && (a.k % 32 != 0 || a.kp != a.k)) || 32 * SUB > a.kp)
+    return FASTH_EINVAL;
   const int side = a.ds_out ? (a.ds_rows + NW - 1) / NW : 0;
   prof::Scope ps_(FASTH_KERNEL_CHAIN, stream);
-  hipLaunchKernelGGL((chain_pair_kernel<NW, SUB, P1, RL, XA, XC>), dim3(a.m + side), dim3(64 * NW), 0, stream, a);
+  hipLaunchKernelGGL((chain_pair_kernel<NW, SUB, P1, RL, XA, XC, PAD>), dim3(a.m + side), dim3(64 * NW), 0, stream, a);
   FASTH_HIP(hipGetLastError());
   return FASTH_OK;
 }

@@ -68,6 +68,9 @@ DISPATCH = [
     (640, 128, 200, 128), (512, 128, 9, 64), (260, 64, 7, 32), (384, 96, 2, 32), (8, 32, 3, 32), (132, 256, 40, 128),
     (512, 64, 300, 32), (256, 128, 700, 64), (384, 128, 1024, 128),  # the same with several workgroups per compute unit
     (1024, 64, 200, 32), (1000, 128, 180, 64), (1024, 128, 256, 128),  # d > 896, 177 .. 256 columns: four waves, 32-row steps
+    # the lane-pair kernel with a short last step per block (17 <= k <= 127, not 32 or 64)
+    (784, 56, 4, 28), (1000, 200, 3, 100), (512, 192, 5, 96), (300, 40, 3, 20), (1024, 66, 2, 33), (640, 126, 2, 63),
+    (256, 34, 300, 17), (1024, 127, 2, 127),
 ]
 
 
