@@ -70,7 +70,9 @@ DISPATCH = [
     (1024, 64, 200, 32), (1000, 128, 180, 64), (1024, 128, 256, 128),  # d > 896, 177 .. 256 columns: four waves, 32-row steps
     # the lane-pair kernel with a short last step per block (17 <= k <= 127, not 32 or 64)
     (784, 56, 4, 28), (1000, 200, 3, 100), (512, 192, 5, 96), (300, 40, 3, 20), (1024, 66, 2, 33), (640, 126, 2, 63),
-    (256, 34, 300, 17), (1024, 127, 2, 127),
+    (256, 34, 300, 17), (1024, 127, 2, 127), (512, 80, 3, 40), (768, 160, 2, 80),
+    # the same block sizes where the 4-wave kernel serves (d > 896 from 177 columns, d > 512 from 257)
+    (1024, 160, 200, 80), (1024, 56, 200, 28), (640, 80, 300, 40), (1000, 200, 180, 100),
 ]
 
 
