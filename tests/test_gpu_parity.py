@@ -188,6 +188,33 @@ def test_fasth_random_shapes(d, n, m, k, transpose):
     assert rel_err(dV, dV0) <= REL_TOL
 
 
+def _random_pair_shapes(count, seed):
+    """Seeded shapes in the range of the lane-pair chain kernel: d a multiple of 4 up to 1024, 17 <= k <= 128
+    (multiples of 32 and not), one to six blocks, narrow and crowded mini-batches."""
+    rng = np.random.default_rng(seed)
+    shapes = []
+    for _ in range(count):
+        d = int(rng.integers(1, 257)) * 4
+        k = int(rng.integers(17, 129))
+        nb = int(rng.integers(1, 7))
+        m = int(rng.choice([1, 2, 7, 32, 33, 100, 177, 256, 300]))
+        if d * nb * k * m > 2e8:
+            m = 7
+        shapes.append((d, nb * k, m, k, bool(rng.integers(0, 2))))
+    return shapes
+
+
+@pytest.mark.parametrize("d,n,m,k,transpose", _random_pair_shapes(24, seed=20261128))
+def test_fasth_random_shapes_lane_pairs(d, n, m, k, transpose):
+    _say(f"fasth random (lane pairs) d={d} n={n} m={m} k={k} transpose={transpose}")
+    p = synthetic.householder_problem(d, n, m, seed=13000 + d + n + m + k)
+    A, dV, dX = gpu_fasth(p["V"], p["X"], p["G"], k, transpose)
+    A0, dV0, dX0 = orc.product_gradients(p["V"], p["X"], p["G"], transpose=transpose)
+    assert rel_err(A, A0) <= REL_TOL
+    assert rel_err(dX, dX0) <= REL_TOL
+    assert rel_err(dV, dV0) <= REL_TOL
+
+
 @pytest.mark.parametrize("name", ["d64_m32_k32", "d256_m32_k32", "d1024_m32_k32",
                                   "d2048_m64_k32", "d2048_m64_k64", "d2048_m64_k128"])
 def test_fasth_benchmark_configs(name):
