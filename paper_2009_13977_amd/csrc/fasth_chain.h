@@ -526,7 +526,12 @@ static int launch_chain_kernel(const ChainArgs& a, hipStream_t stream) {
   const int d = a.d, k = a.k;
   if (chain_uses_tile(a)) return launch_chain_tile(a, stream);
   if (chain_uses_pipe(a) && d % 4 != 0) {
-    // rows not 16-byte aligned: the general form of the kernel (any block size, short last step)
+    // rows not 16-byte aligned: the general form of the kernels (any block size, short last step)
+    if (chain_pair_serves(a) && (a.m <= (d > 896 ? 176 : kComputeUnits) || d <= 512)) {  // as for aligned rows below
+      if (d <= 256) return launch_chain_pair<2, 0, 4, 4, 3, 2, true, true>(a, stream);
+      if (d <= 512) return launch_chain_pair<4, 0, 4, 4, 3, 2, true, true>(a, stream);
+      return launch_chain_pair<8, 0, 4, 4, 3, 2, true, true>(a, stream);
+    }
     if (d <= 1024) {
       if (k <= 8) return launch_chain_pipe<8, 4, 256, 2, 0, true, 0, true>(a, stream);
       if (k <= 16) return launch_chain_pipe<16, 4, 256, 4, 0, true, 0, true>(a, stream);

@@ -41,13 +41,19 @@ struct PairRegs {
 // SUB: steps of 32 rows per block (k = 32 SUB; the diagonal 32 x 32 blocks of T_i are the steps' factors).
 // PAD: k is not a multiple of 32 and SUB = ceil(k / 32): the last step of a block has fewer than 32 rows; its missing
 // rows repeat the last valid one and their inner products and coefficients are forced to zero.
+// UNAL (with PAD, and SUB = 0: the steps per block come from p.sub): d is not a multiple of 4, so rows are not
+// 16-byte aligned and a row's last chunk hangs over its end. Rows are then fetched through a buffer that spans the
+// step's block (4-byte alignment is enough for it, what lies beyond the block reads as zero); the overhanging
+// elements of `a` see the next row's values, so they are put back to zero after every update and never stored.
 // Three register copies of a step's rows (64 registers each): while step s is applied, the rows of step s + 2 are
 // fetched, so every fetch has more than a whole step to arrive and may be issued wherever it costs least.
 // Of a lane's 16 fetches per step, P1 are issued during the first product, RL during the reduction, XA after the
 // first barrier and XC after the second (while the LDS reads issued there are on their way), the rest during the update.
 // NW: waves per workgroup, 128 elements of the column each (8 for d <= 1024, 4 for d <= 512, 2 for d <= 256).
-template <int NW, int SUB, int P1, int RL, int XA, int XC, bool PAD = false>
+template <int NW, int SUB, int P1, int RL, int XA, int XC, bool PAD = false, bool UNAL = false>
 __global__ void __launch_bounds__(64 * NW) chain_pair_kernel(ChainArgs p) {
+  static_assert(!UNAL || (PAD && SUB == 0), "the unaligned form is the general one");
+  static_assert(SUB > 0 || PAD, "steps per block");
   typedef PairLanes Lanes;
   constexpr int K = 32, KH = 16, G = 2 * NW, LPT = K / G;  // G threads share a row of op(T), LPT entries each
   typedef PairRegs<LPT> Regs;
@@ -78,8 +84,12 @@ __global__ void __launch_bounds__(64 * NW) chain_pair_kernel(ChainArgs p) {
   const int sel = ((lane & 32) ? 8 : 0) + ((lane & 16) ? 4 : 0) + ((lane & Lanes::M0) ? 2 : 0) + ((lane & Lanes::M1) ? 1 : 0);
   const bool writer = (lane & Lanes::M2) == 0;
   auto block_of = [&](int s) { return p.transpose ? s : nb - 1 - s; };  // step index of the s-th step applied
-  auto step_block = [&](int i) { return SUB == 1 ? i : i / SUB; };
-  auto step_part = [&](int i) { return SUB == 1 ? 0 : i % SUB; };
+  const int sub = SUB > 0 ? SUB : p.sub;
+  auto step_block = [&](int i) { return SUB == 1 ? i : i / sub; };
+  auto step_part = [&](int i) { return SUB == 1 ? 0 : i % sub; };
+  bool keep[4];  // elements of this lane's chunk that exist
+#pragma unroll
+  for (int r = 0; r < 4; ++r) keep[r] = ok && (!UNAL || x0 + r < (unsigned)d);
   auto rows_valid = [&](int i) { return PAD ? min(K, p.k - step_part(i) * K) : K; };
   auto load_row = [&](int i, int jj, Chunk<4>& dst) {
     if constexpr (PAD) {
@@ -87,7 +97,16 @@ __global__ void __launch_bounds__(64 * NW) chain_pair_kernel(ChainArgs p) {
       const int kv = rows_valid(i);
       const int row0 = step_block(i) * p.k + step_part(i) * K + min(2 * jj, kv - 1);
       const unsigned off = 2 * jj + 1 < kv ? lane_off : x0;
-      dst = load_chunk<4>(p.V + (size_t)row0 * (size_t)d + off);
+      if constexpr (UNAL) {
+        // the buffer spans the step's block of k rows (at most 512 KiB), so V itself may be of any size
+        const BufferDesc vdesc = make_buffer(p.V + (size_t)step_block(i) * p.k * d, (size_t)p.k * d * sizeof(float));
+        const unsigned row = (unsigned)(step_part(i) * K + min(2 * jj, kv - 1));
+        const BufVec<4> v = buffer_load<4>(vdesc, off * 4u, row * (unsigned)d * 4u);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) dst.e[r] = v.e[r];
+      } else {
+        dst = load_chunk<4>(p.V + (size_t)row0 * (size_t)d + off);
+      }
     } else {
       dst = load_chunk<4>(p.V + ((size_t)i * K + 2 * jj) * (size_t)d + lane_off);
     }
@@ -110,8 +129,16 @@ __global__ void __launch_bounds__(64 * NW) chain_pair_kernel(ChainArgs p) {
 
   // Applies step i held in `cur` while fetching step ifetch (two steps on) into `dst`.
   auto apply_step = [&](int i, Regs& cur, int ifetch, Regs& dst) {
-    if (p.save_in && ok && h == 0 && (SUB == 1 || step_part(i) == (p.transpose ? 0 : SUB - 1)))
-      store_chunk<4>(p.save_in + ((size_t)step_block(i) * m + col) * d + x0, a);
+    if (p.save_in && ok && h == 0 && (SUB == 1 || step_part(i) == (p.transpose ? 0 : sub - 1))) {
+      float* dst_in = p.save_in + ((size_t)step_block(i) * m + col) * d + x0;
+      if constexpr (UNAL) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          if (keep[r]) dst_in[r] = a.e[r];
+      } else {
+        store_chunk<4>(dst_in, a);
+      }
+    }
     const int kv = rows_valid(i);
     float pj[KH];
 #pragma unroll
@@ -217,7 +244,7 @@ __global__ void __launch_bounds__(64 * NW) chain_pair_kernel(ChainArgs p) {
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
       const float sum = acc[r] + Lanes::partner(acc[r]);
-      a.e[r] = ok ? sum : 0.f;
+      a.e[r] = keep[r] ? sum : 0.f;
     }
   };
 
@@ -242,24 +269,25 @@ __global__ void __launch_bounds__(64 * NW) chain_pair_kernel(ChainArgs p) {
   if (ok) {
     // each lane of a pair stores two of the chunk's four elements
     const float o0 = h ? a.e[2] : a.e[0], o1 = h ? a.e[3] : a.e[1];
-    p.out[(size_t)(x0 + 2 * h) * m + col] = o0;
-    p.out[(size_t)(x0 + 2 * h + 1) * m + col] = o1;
+    if (!UNAL || x0 + 2 * h < (unsigned)d) p.out[(size_t)(x0 + 2 * h) * m + col] = o0;
+    if (!UNAL || x0 + 2 * h + 1 < (unsigned)d) p.out[(size_t)(x0 + 2 * h + 1) * m + col] = o1;
   }
 }
 
 // Blocks of more than 16 rows (smaller ones would mostly fetch repeated rows in a 32-row step).
-static bool chain_pair_serves(const ChainArgs& a) { return a.d <= 1024 && a.d % 4 == 0 && a.k > 16; }
+static bool chain_pair_serves(const ChainArgs& a) { return a.d <= 1024 && a.k > 16; }
 
-template <int NW, int SUB, int P1, int RL, int XA, int XC, bool PAD = false>
+template <int NW, int SUB, int P1, int RL, int XA, int XC, bool PAD = false, bool UNAL = false>
 static int launch_chain_pair(const ChainArgs& args, hipStream_t stream) {
   ChainArgs a = args;
-  a.sub = SUB;
-  a.nb = args.nb * SUB;
-  if (!chain_pair_serves(a) || a.d > 128 * NW || SUB != (a.k + 31) / 32 || (!PAD && (a.k % 32 != 0 || a.kp != a.k)) || 32 * SUB > a.kp)
+  a.sub = (args.k + 31) / 32;
+  a.nb = args.nb * a.sub;
+  if (!chain_pair_serves(a) || a.d > 128 * NW || (SUB > 0 && SUB != a.sub) || (!PAD && (a.k % 32 != 0 || a.kp != a.k)) ||
+      32 * a.sub > a.kp || (!UNAL && a.d % 4 != 0))
     return FASTH_EINVAL;
   const int side = a.ds_out ? (a.ds_rows + NW - 1) / NW : 0;
   prof::Scope ps_(FASTH_KERNEL_CHAIN, stream);
-  hipLaunchKernelGGL((chain_pair_kernel<NW, SUB, P1, RL, XA, XC, PAD>), dim3(a.m + side), dim3(64 * NW), 0, stream, a);
+  hipLaunchKernelGGL((chain_pair_kernel<NW, SUB, P1, RL, XA, XC, PAD, UNAL>), dim3(a.m + side), dim3(64 * NW), 0, stream, a);
   FASTH_HIP(hipGetLastError());
   return FASTH_OK;
 }

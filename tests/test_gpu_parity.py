@@ -73,6 +73,9 @@ DISPATCH = [
     (256, 34, 300, 17), (1024, 127, 2, 127), (512, 80, 3, 40), (768, 160, 2, 80),
     # the same block sizes where the 4-wave kernel serves (d > 896 from 177 columns, d > 512 from 257)
     (1024, 160, 200, 80), (1024, 56, 200, 28), (640, 80, 300, 40), (1000, 200, 180, 100),
+    # the lane-pair kernel with rows that are not 16-byte aligned (d not a multiple of 4)
+    (1023, 64, 3, 32), (1021, 100, 2, 50), (515, 96, 5, 32), (510, 128, 33, 128), (255, 60, 2, 20), (131, 64, 300, 64),
+    (1022, 192, 2, 96), (769, 34, 7, 17),
 ]
 
 
