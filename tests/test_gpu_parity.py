@@ -76,6 +76,7 @@ DISPATCH = [
     # the lane-pair kernel with rows that are not 16-byte aligned (d not a multiple of 4)
     (1023, 64, 3, 32), (1021, 100, 2, 50), (515, 96, 5, 32), (510, 128, 33, 128), (255, 60, 2, 20), (131, 64, 300, 64),
     (1022, 192, 2, 96), (769, 34, 7, 17),
+    (1023, 64, 200, 32), (701, 40, 300, 20),  # ... where the 4-wave kernel serves such rows
 ]
 
 
