@@ -84,40 +84,124 @@ __global__ void __launch_bounds__(256) gram_partial_kernel(const float* __restri
 // the block size each level with matrix-core products. Rows/columns >= k (padding) form an identity.
 // ------------------------------------------------------------------------------------------
 
-// In-place inverse of the upper-triangular kp x kp matrix Ms (row stride LDM) in LDS by block
-// doubling; Xs is scratch of max(kp * (kp/2 + 4) / 2 + 64, kp * 17) floats. Called by every thread of the workgroup
-// (a multiple of 64 threads); Ms must be complete (barrier) on entry and is complete on return.
-__device__ __forceinline__ void invert_upper_lds(float* Ms, float* Xs, int kp, int LDM) {
-  const int tid = threadIdx.x, nthreads = blockDim.x, wave = tid >> 6, nwaves = nthreads >> 6, lane = tid & 63;
-  // 16x16 diagonal blocks: thread c of a block solves for column c by back substitution, fully
-  // unrolled so that the reads of M (a copy in Xs) are independent of the values being computed.
-  float* Ds = Xs;  // [kp/16][16][17]
-  if (tid < kp) {
-    const int base = tid & ~15, c = tid & 15;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) Ds[(base + r) * 17 + c] = Ms[(base + r) * LDM + base + c];
+// Floats of LDS scratch that invert_upper_lds needs beside the matrix.
+__host__ __device__ constexpr int invert_scratch_floats(int kp) {
+  return kp * (kp / 2 + 4) / 2 + 64 > kp * 21 ? kp * (kp / 2 + 4) / 2 + 64 : kp * 21;
+}
+
+// The inversion reads the 16 x 16 diagonal blocks from a copy in the scratch: rows of kDiagLd floats, which a
+// solving thread reads four entries at a time, followed by the reciprocals of the diagonal (one division per
+// entry, by whoever stores it, off the dependent chain of the solve).
+constexpr int kDiagLd = 20;
+__device__ __forceinline__ void diag_scratch_store(float* Xs, int kp, int j, int l, float v) {
+  if ((j ^ l) < 16) {  // same diagonal block
+    Xs[j * kDiagLd + (l & 15)] = v;
+    if (j == l) Xs[kp * kDiagLd + j] = 1.f / v;
+  }
+}
+
+// Fills that copy from a complete Ms; ends with a barrier.
+__device__ __forceinline__ void diag_scratch_fill(const float* Ms, float* Xs, int kp, int LDM) {
+  for (int idx = threadIdx.x; idx < kp * 16; idx += blockDim.x) {
+    const int r = idx >> 4, c = idx & 15;
+    diag_scratch_store(Xs, kp, r, (r & ~15) + c, Ms[r * LDM + (r & ~15) + c]);
   }
   __syncthreads();
+}
+
+// In-place inverse of the upper-triangular kp x kp matrix Ms (row stride LDM, a multiple of 4; Ms 16-byte
+// aligned) in LDS by block doubling; Xs is 16-byte aligned scratch of invert_scratch_floats(kp) floats that
+// holds the copy of the diagonal blocks on entry (diag_scratch_fill, or diag_scratch_store by whoever builds
+// Ms). Called by every thread of the workgroup (a multiple of 64 threads); Ms and the copy must be complete
+// (barrier) on entry and Ms is complete on return.
+// PRELOAD: a solving thread fetches all it reads of its diagonal block (144 registers) before the first row
+// instead of row by row, and works column by column; for kernels whose register budget allows it. Both orders
+// give the same bits.
+template <bool PRELOAD>
+__device__ __forceinline__ void invert_upper_lds(float* Ms, float* Xs, int kp, int LDM) {
+  const int tid = threadIdx.x, nthreads = blockDim.x, wave = tid >> 6, nwaves = nthreads >> 6, lane = tid & 63;
+  const int li = lane & 15, q = lane >> 4;
+  // 16x16 diagonal blocks: thread c of a block solves for column c by back substitution, fully unrolled so
+  // that the reads of M are independent of the values being computed (every thread of a block reads the same
+  // addresses).
   if (tid < kp) {
     const int base = tid & ~15, c = tid & 15;
-    const float* D = Ds + base * 17;
+    const float4* D4 = reinterpret_cast<const float4*>(Xs + base * kDiagLd);
+    const float4* R4 = reinterpret_cast<const float4*>(Xs + kp * kDiagLd + base);
     float x[16], rdiag[16];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) rdiag[r] = 1.f / D[r * 17 + r];  // all sixteen at once, off the dependent chain
+    for (int g = 0; g < 4; ++g) {
+      const float4 v = R4[g];
+      rdiag[4 * g] = v.x; rdiag[4 * g + 1] = v.y; rdiag[4 * g + 2] = v.z; rdiag[4 * g + 3] = v.w;
+    }
+    if constexpr (PRELOAD) {
+      // column by column: once x[l] is known it leaves every row's sum above it, products that do not depend
+      // on one another; only one multiply-add and one multiply per row lie on the dependent chain. Each sum
+      // still takes its terms oldest x first, as below.
+      float row[16][16], sum[16];
 #pragma unroll
-    for (int r = 15; r >= 0; --r) {
-      float sum = r == c ? 1.f : 0.f;
-      // oldest x first: the value computed last enters last, so each row adds one multiply-add to the chain
+      for (int r = 15; r >= 0; --r) {
 #pragma unroll
-      for (int l = 15; l > r; --l) sum = fmaf(-D[r * 17 + l], x[l], sum);
-      x[r] = sum * rdiag[r];  // rows below c stay exactly zero
+        for (int g = (r + 1) / 4; g < 4; ++g) {
+          const float4 v = D4[r * (kDiagLd / 4) + g];
+          row[r][4 * g] = v.x; row[r][4 * g + 1] = v.y; row[r][4 * g + 2] = v.z; row[r][4 * g + 3] = v.w;
+        }
+        sum[r] = r == c ? 1.f : 0.f;
+      }
+#pragma unroll
+      for (int l = 15; l >= 0; --l) {
+        x[l] = sum[l] * rdiag[l];  // rows below c stay exactly zero
+#pragma unroll
+        for (int r = l - 1; r >= 0; --r) sum[r] = fmaf(-row[r][l], x[l], sum[r]);
+      }
+    } else {
+#pragma unroll
+      for (int r = 15; r >= 0; --r) {
+        float row[16];
+#pragma unroll
+        for (int g = (r + 1) / 4; g < 4; ++g) {
+          const float4 v = D4[r * (kDiagLd / 4) + g];
+          row[4 * g] = v.x; row[4 * g + 1] = v.y; row[4 * g + 2] = v.z; row[4 * g + 3] = v.w;
+        }
+        float sum = r == c ? 1.f : 0.f;
+        // oldest x first: the value computed last enters last, so each row adds one multiply-add to the chain
+#pragma unroll
+        for (int l = 15; l > r; --l) sum = fmaf(-row[l], x[l], sum);
+        x[r] = sum * rdiag[r];  // rows below c stay exactly zero
+      }
     }
 #pragma unroll
     for (int r = 0; r < 16; ++r) Ms[(base + r) * LDM + base + c] = x[r];
   }
   __syncthreads();
-  const int li = lane & 15, q = lane >> 4;
-  for (int b = 16; b < kp; b *= 2) {
+  // [[T11, -T11 M12 T22], [0, T22]] for pairs of 16 x 16 blocks, one wave per pair and both products in
+  // registers: product j of X = M12 T22 sums over the inner indices 4 q + j, for which lane (i, q) supplies
+  // M12(i, 4 q + j) and T22(4 q + j, i); the lane then owns X(4 q + j, i), which is exactly the operand that
+  // product j of T11 X wants from it.
+  if (kp >= 32) {
+    for (int pr = wave; pr < kp / 32; pr += nwaves) {
+      const int r0 = pr * 32;
+      const float4 m12 = *reinterpret_cast<const float4*>(Ms + (r0 + li) * LDM + r0 + 16 + 4 * q);
+      const float4 t11 = *reinterpret_cast<const float4*>(Ms + (r0 + li) * LDM + r0 + 4 * q);
+      float t22[4];
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) t22[jj] = Ms[(r0 + 16 + 4 * q + jj) * LDM + r0 + 16 + li];
+      f32x4 X = {0.f, 0.f, 0.f, 0.f};
+      X = __builtin_amdgcn_mfma_f32_16x16x4f32(m12.x, t22[0], X, 0, 0, 0);
+      X = __builtin_amdgcn_mfma_f32_16x16x4f32(m12.y, t22[1], X, 0, 0, 0);
+      X = __builtin_amdgcn_mfma_f32_16x16x4f32(m12.z, t22[2], X, 0, 0, 0);
+      X = __builtin_amdgcn_mfma_f32_16x16x4f32(m12.w, t22[3], X, 0, 0, 0);
+      f32x4 R = {0.f, 0.f, 0.f, 0.f};
+      R = __builtin_amdgcn_mfma_f32_16x16x4f32(t11.x, X[0], R, 0, 0, 0);
+      R = __builtin_amdgcn_mfma_f32_16x16x4f32(t11.y, X[1], R, 0, 0, 0);
+      R = __builtin_amdgcn_mfma_f32_16x16x4f32(t11.z, X[2], R, 0, 0, 0);
+      R = __builtin_amdgcn_mfma_f32_16x16x4f32(t11.w, X[3], R, 0, 0, 0);
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) Ms[(r0 + 4 * q + jj) * LDM + r0 + 16 + li] = -R[jj];
+    }
+    __syncthreads();
+  }
+  for (int b = 32; b < kp; b *= 2) {
     const int tpb = b / 16, per_pair = tpb * tpb, items = (kp / (2 * b)) * per_pair;
     const int LDX = b + 4;
     for (int it = wave; it < items; it += nwaves) {  // X = M12 T22
@@ -142,7 +226,7 @@ __device__ __forceinline__ void invert_upper_lds(float* Ms, float* Xs, int kp, i
 
 __global__ void __launch_bounds__(1024) t_build_kernel(const float* __restrict__ Spart, float* __restrict__ T,
                                                       int k, int kp, int gram_split) {
-  extern __shared__ float smem[];
+  extern __shared__ __align__(16) float smem[];
   const int LDM = kp + 4;
   float* Ms = smem;                 // [kp][LDM]
   float* Xs = Ms + kp * LDM;        // scratch of the inversion
@@ -176,7 +260,8 @@ __global__ void __launch_bounds__(1024) t_build_kernel(const float* __restrict__
     }
   }
   __syncthreads();
-  invert_upper_lds(Ms, Xs, kp, LDM);
+  diag_scratch_fill(Ms, Xs, kp, LDM);
+  invert_upper_lds<false>(Ms, Xs, kp, LDM);
   // T_i and, nb factors further on, its transpose: a chain kernel then reads rows of op(T_i) in either direction
   float* Ti = T + (size_t)i * kp * kp;
   float* Tti = Ti + (size_t)gridDim.x * kp * kp;
@@ -211,10 +296,10 @@ __global__ void __launch_bounds__(512) factor_fused_kernel(FactorPair fp) {
   // Partial Gram matrices meet in LDS. Up to 32 rows all eight waves' tiles fit side by side; for 64 rows
   // (10 tiles a wave) the upper four waves hand theirs to the lower four first, which halves the space.
   constexpr int RW = KT <= 2 ? NW : NW / 2;  // waves whose partial tiles are held at once
-  __shared__ __align__(16) float Vs[kp * LD];
+  __shared__ __align__(16) float Vs2[2][kp * LD];  // slabs alternate between the two: one barrier per slab
   __shared__ float Red[RW * NTILE * 256];
-  __shared__ float Ms[kp * LDM];
-  __shared__ float Xs[(kp * (kp / 2 + 4) / 2 + 64) > kp * 17 ? (kp * (kp / 2 + 4) / 2 + 64) : kp * 17];
+  __shared__ __align__(16) float Ms[kp * LDM];
+  __shared__ __align__(16) float Xs[invert_scratch_floats(kp)];
   const int i = blockIdx.x;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, li = lane & 15, q = lane >> 4;
   // the block's k rows as one buffer: rows k .. kp - 1 of the padded block lie beyond it and read as zero
@@ -238,6 +323,9 @@ __global__ void __launch_bounds__(512) factor_fused_kernel(FactorPair fp) {
 #pragma unroll
     for (int sl = 0; sl < NS; ++sl) {
       if (xs + sl * kGramChunk < d) {  // uniform across the workgroup
+        // A wave that writes this buffer has passed the barrier of the slab before, which every wave reaches
+        // only after its reads of the slab before that one, the buffer's last user.
+        float* Vs = Vs2[sl & 1];
 #pragma unroll
         for (int it = 0; it < PER; ++it) {
           const int idx = tid + it * 512;
@@ -265,7 +353,6 @@ __global__ void __launch_bounds__(512) factor_fused_kernel(FactorPair fp) {
             }
           }
         }
-        __syncthreads();
       }
     }
   }
@@ -314,9 +401,10 @@ __global__ void __launch_bounds__(512) factor_fused_kernel(FactorPair fp) {
       v = 1.f;
     }
     Ms[j * LDM + l] = v;
+    diag_scratch_store(Xs, kp, j, l, v);
   }
   __syncthreads();
-  invert_upper_lds(Ms, Xs, kp, LDM);
+  invert_upper_lds<true>(Ms, Xs, kp, LDM);
   // T_i and, nb factors further on, its transpose: a chain kernel then reads rows of op(T_i) in either direction
   float* Ti = T + (size_t)i * kp * kp;
   float* Tti = Ti + (size_t)fp.nb[which] * kp * kp;
@@ -327,9 +415,7 @@ __global__ void __launch_bounds__(512) factor_fused_kernel(FactorPair fp) {
 }
 
 static size_t t_build_lds(int kp) {
-  size_t scratch = (size_t)kp * (kp / 2 + 4) / 2 + 64;
-  if (scratch < (size_t)kp * 17) scratch = (size_t)kp * 17;
-  return sizeof(float) * ((size_t)kp * (kp + 4) + scratch);
+  return sizeof(float) * ((size_t)kp * (kp + 4) + (size_t)invert_scratch_floats(kp));
 }
 
 }  // namespace fasth
