@@ -74,6 +74,29 @@ __device__ __forceinline__ f32x4 tile_mma(const float* As, int sai, int sak, con
   return acc;
 }
 
+// The same product for a compile-time depth K (a multiple of 16) with A contiguous along the inner index
+// (16-byte aligned rows) and B contiguous along c: the sum may run in any order, so lane (i, q) takes the inner
+// indices q K/4 .. (q + 1) K/4 - 1, its A operands come as 16-byte reads, and every read is issued before the
+// first matrix instruction instead of one trip to LDS per 4-deep slice.
+template <int K>
+__device__ __forceinline__ f32x4 tile_mma_rows(const float* As, int sai, const float* Bs, int sbk, f32x4 acc) {
+  static_assert(K % 16 == 0, "four inner indices per 16-byte read and lane group");
+  const int lane = threadIdx.x & (kWave - 1);
+  const int i = lane & 15, q = lane >> 4;
+  constexpr int PER = K / 4;
+  float a[PER], b[PER];
+#pragma unroll
+  for (int g = 0; g < PER / 4; ++g) {
+    const float4 v = *reinterpret_cast<const float4*>(As + i * sai + q * PER + 4 * g);
+    a[4 * g] = v.x; a[4 * g + 1] = v.y; a[4 * g + 2] = v.z; a[4 * g + 3] = v.w;
+  }
+#pragma unroll
+  for (int kk = 0; kk < PER; ++kk) b[kk] = Bs[(q * PER + kk) * sbk + i];
+#pragma unroll
+  for (int kk = 0; kk < PER; ++kk) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a[kk], b[kk], acc, 0, 0, 0);
+  return acc;
+}
+
 // Sum NV per-lane values over the 64 lanes of a wave. On return v[0] holds, in every lane, the
 // wave-wide sum of the input v[sel] where sel = reduce_sel<NV>(lane); the other entries are scratch.
 // Each exchange halves the number of live values, so NV values cost NV - 1 + log2(64 / NV) shuffles.

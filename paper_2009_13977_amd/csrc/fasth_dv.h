@@ -264,7 +264,7 @@ __global__ void __launch_bounds__(256) dv_kernel(DvPair pair) {
     if (t < kt * 4) {
       const int ti = t / 4, tx = t % 4;
       f32x4 ev = {0.f, 0.f, 0.f, 0.f};
-      if (part == 0) ev = tile_mma(Es + ti * 16 * LDE, LDE, 1, Vs + tx * 16, LDX, 1, kp, ev);  // E V_i enters once
+      if (part == 0) ev = tile_mma_rows<kp>(Es + ti * 16 * LDE, LDE, Vs + tx * 16, LDX, ev);  // E V_i enters once
 #pragma unroll
       for (int jj = 0; jj < 4; ++jj) {
         const int j = ti * 16 + 4 * q + jj, x = x0 + tx * 16 + li;
