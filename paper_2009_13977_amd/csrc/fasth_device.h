@@ -58,18 +58,36 @@ __device__ __forceinline__ void lds_store(float* dst, const BufVec<VEC>& v) {
 }
 
 // One 16x16 output tile of a matrix product on the fp32 matrix cores, operands in LDS.
-//   acc(r, c) += sum_{kk < K} A(r, kk) * B(kk, c),   K a multiple of 4
-//   A(r, kk) = As[r * sai + kk * sak],  B(kk, c) = Bs[kk * sbk + c * sbj]
-// v_mfma_f32_16x16x4_f32 lane layout: lane = 16 q + i supplies A(i, q) and B(q, i) of each
-// 4-deep slice and owns acc[j] = tile(4 q + j, i).
-__device__ __forceinline__ f32x4 tile_mma(const float* As, int sai, int sak, const float* Bs, int sbk,
-                                          int sbj, int K, f32x4 acc) {
+//   acc(r, c) += sum_{kk < K} A(r, kk) * B(kk, c),   K a multiple of 32
+//   A(r, kk) = As[r * sai + kk] with 16-byte aligned rows;
+//   B(kk, c) = Bs[c * sb + kk] (B_ALONG_K: contiguous along the inner index like A, 16-byte aligned) or Bs[kk * sb + c].
+// v_mfma_f32_16x16x4_f32 lane layout: lane = 16 q + i supplies A(i, .) and B(., i) for the q-th of the four inner
+// indices of an instruction and owns acc[j] = tile(4 q + j, i). The inner sum may run in any order: of each 16
+// inner indices lane (i, q) takes 4 q .. 4 q + 3, one 16-byte read per operand that is contiguous along the inner
+// index, and the reads of 32 inner indices are issued ahead of their eight instructions (one trip to LDS per
+// instruction otherwise, which is what bounds a short product).
+template <bool B_ALONG_K>
+__device__ __forceinline__ f32x4 tile_mma(const float* As, int sai, const float* Bs, int sb, int K, f32x4 acc) {
   const int lane = threadIdx.x & (kWave - 1);
   const int i = lane & 15, q = lane >> 4;
-  const float* ap = As + i * sai + q * sak;
-  const float* bp = Bs + q * sbk + i * sbj;
-  for (int kk = 0; kk < K; kk += 4) {
-    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(ap[kk * sak], bp[kk * sbk], acc, 0, 0, 0);
+  const float* ap = As + i * sai + 4 * q;
+  const float* bp = B_ALONG_K ? Bs + i * sb + 4 * q : Bs + 4 * q * sb + i;
+  for (int k0 = 0; k0 < K; k0 += 32) {
+    float a[8], b[8];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const float4 v = *reinterpret_cast<const float4*>(ap + k0 + 16 * h);
+      a[4 * h] = v.x; a[4 * h + 1] = v.y; a[4 * h + 2] = v.z; a[4 * h + 3] = v.w;
+      if constexpr (B_ALONG_K) {
+        const float4 w = *reinterpret_cast<const float4*>(bp + k0 + 16 * h);
+        b[4 * h] = w.x; b[4 * h + 1] = w.y; b[4 * h + 2] = w.z; b[4 * h + 3] = w.w;
+      } else {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) b[4 * h + u] = bp[(k0 + 16 * h + u) * sb];
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a[u], b[u], acc, 0, 0, 0);
   }
   return acc;
 }

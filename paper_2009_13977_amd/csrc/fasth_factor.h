@@ -58,7 +58,7 @@ __global__ void __launch_bounds__(256) gram_partial_kernel(const float* __restri
         int ti = 0, rem = t;
         while (rem >= kt - ti) { rem -= kt - ti; ++ti; }
         const int tj = ti + rem;
-        acc[w] = tile_mma(Vs + ti * 16 * LD, LD, 1, Vs + tj * 16 * LD, 1, LD, kGramChunk, acc[w]);
+        acc[w] = tile_mma<true>(Vs + ti * 16 * LD, LD, Vs + tj * 16 * LD, LD, kGramChunk, acc[w]);
       }
     }
     __syncthreads();
@@ -207,7 +207,7 @@ __device__ __forceinline__ void invert_upper_lds(float* Ms, float* Xs, int kp, i
     for (int it = wave; it < items; it += nwaves) {  // X = M12 T22
       const int pr = it / per_pair, ti = (it % per_pair) / tpb, tj = it % tpb, r0 = pr * 2 * b;
       f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-      acc = tile_mma(Ms + (r0 + 16 * ti) * LDM + r0 + b, LDM, 1, Ms + (r0 + b) * LDM + r0 + b + 16 * tj, LDM, 1, b, acc);
+      acc = tile_mma<false>(Ms + (r0 + 16 * ti) * LDM + r0 + b, LDM, Ms + (r0 + b) * LDM + r0 + b + 16 * tj, LDM, b, acc);
       float* X = Xs + pr * b * LDX;
 #pragma unroll
       for (int jj = 0; jj < 4; ++jj) X[(16 * ti + 4 * q + jj) * LDX + 16 * tj + li] = acc[jj];
@@ -216,7 +216,7 @@ __device__ __forceinline__ void invert_upper_lds(float* Ms, float* Xs, int kp, i
     for (int it = wave; it < items; it += nwaves) {  // T12 = -T11 X
       const int pr = it / per_pair, ti = (it % per_pair) / tpb, tj = it % tpb, r0 = pr * 2 * b;
       f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-      acc = tile_mma(Ms + (r0 + 16 * ti) * LDM + r0, LDM, 1, Xs + pr * b * LDX + 16 * tj, LDX, 1, b, acc);
+      acc = tile_mma<false>(Ms + (r0 + 16 * ti) * LDM + r0, LDM, Xs + pr * b * LDX + 16 * tj, LDX, b, acc);
 #pragma unroll
       for (int jj = 0; jj < 4; ++jj) Ms[(r0 + 16 * ti + 4 * q + jj) * LDM + r0 + b + 16 * tj + li] = -acc[jj];
     }
