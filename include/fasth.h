@@ -87,6 +87,18 @@ int fasth_prepare(const fasth_shape* shape, const float* V, void* workspace, siz
 int fasth_apply(const fasth_shape* shape, const float* V, const float* X, float* A,
                 void* workspace, size_t workspace_bytes, int save_for_backward, void* stream);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, serving loops that
+ * forbid it, harnesses without an allocator): A = H X (or H^T X) exactly as fasth_forward computes it,
+ * with the block factors in a fixed array of FASTH_STATIC_SCRATCH_BYTES that is part of the library's
+ * GPU code (one copy per GPU, held until the process ends) instead of a caller's workspace. Nothing is
+ * saved for a backward pass. The call allocates and frees nothing; its first use on a device looks up
+ * the array's address. Shapes whose factors and partial Gram matrices need more than the array holds
+ * (about 4 n kp (2 + min(16, ceil(d / 128))) bytes, kp = k rounded up to a power of two >= 16) return
+ * FASTH_EUNSUPPORTED before any GPU call. Every call on one GPU uses the same array: calls that overlap
+ * on one GPU (different streams or threads) race; calls on one stream do not. */
+#define FASTH_STATIC_SCRATCH_BYTES (8u << 20)
+int fasth_forward_static(const fasth_shape* shape, const float* V, const float* X, float* A, void* stream);
+
 /* Algorithm 2. Given G = dL/dA [d][m], writes dX = dL/dX [d][m] and
  * dV [n][d] (row j-1 = dL/dv_j, summed over the m columns, Eq. 5). The
  * workspace must be exactly as the fasth_forward call with the same shape

@@ -25,6 +25,7 @@ EXPORTED_SYMBOLS = (
     "fasth_strerror",
     "fasth_workspace_bytes",
     "fasth_forward",
+    "fasth_forward_static",
     "fasth_prepare",
     "fasth_apply",
     "fasth_backward",
@@ -90,6 +91,8 @@ def load_library() -> ctypes.CDLL:
     lib.fasth_workspace_bytes.argtypes = [shp]
     lib.fasth_forward.restype = I
     lib.fasth_forward.argtypes = [shp, P, P, P, P, S, P]
+    lib.fasth_forward_static.restype = I
+    lib.fasth_forward_static.argtypes = [shp, P, P, P, P]
     lib.fasth_backward.restype = I
     lib.fasth_backward.argtypes = [shp, P, P, P, P, P, S, P]
     lib.fasth_tune_block_size.restype = I
@@ -194,6 +197,15 @@ def fasth_forward(V, X, A, workspace, k: int, transpose: bool = False) -> None:
     rc = load_library().fasth_forward(ctypes.byref(shape), _ptr(V, "V"), _ptr(X, "X"), _ptr(A, "A"),
                                       _ptr(workspace, "workspace"), workspace.numel(), _stream())
     _check(rc, "fasth_forward")
+
+
+def fasth_forward_static(V, X, A, k: int, transpose: bool = False) -> None:
+    n, d = V.shape
+    m = X.shape[1]
+    assert X.shape == (d, m) and A.shape == (d, m)
+    shape = _shape(d, n, m, k, transpose)
+    rc = load_library().fasth_forward_static(ctypes.byref(shape), _ptr(V, "V"), _ptr(X, "X"), _ptr(A, "A"), _stream())
+    _check(rc, "fasth_forward_static")
 
 
 def fasth_prepare(V, m: int, workspace, k: int) -> None:

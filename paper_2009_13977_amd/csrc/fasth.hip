@@ -24,6 +24,7 @@
 
 #include <algorithm>
 #include <cstdint>
+#include <mutex>
 #include <type_traits>
 #include <cstdio>
 #include <cstdlib>
@@ -363,6 +364,34 @@ static RectLayout make_rect_layout(const fasth_shape& u, const fasth_shape& v) {
 }  // namespace fasth
 
 // ------------------------------------------------------------------------------------------
+// Scratch memory of fasth_forward_static: one array per GPU, part of the loaded code object, so the call
+// needs no allocation. In host code the array's name is only a handle; its device address is looked up once
+// per device and kept.
+// ------------------------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[FASTH_STATIC_SCRATCH_BYTES];
+
+namespace fasth {
+constexpr int kMaxDevices = 64;
+static void* scratch_addr[kMaxDevices] = {};
+static std::mutex scratch_mutex;
+
+static int static_scratch(void** out) {
+  int dev = -1;
+  FASTH_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return FASTH_EUNSUPPORTED;
+  std::lock_guard<std::mutex> lock(scratch_mutex);
+  if (!scratch_addr[dev]) {
+    void* p = nullptr;
+    FASTH_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return FASTH_EHIP;
+    scratch_addr[dev] = p;
+  }
+  *out = scratch_addr[dev];
+  return FASTH_OK;
+}
+}  // namespace fasth
+
+// ------------------------------------------------------------------------------------------
 // C ABI
 // ------------------------------------------------------------------------------------------
 
@@ -438,6 +467,22 @@ int fasth_forward(const fasth_shape* shape, const float* V, const float* X, floa
   hipStream_t st = static_cast<hipStream_t>(stream);
   if ((rc = build_factors(P, V, st)) != FASTH_OK) return rc;
   return run_chain(P, V, X, A, shape->transpose, true, nullptr, 0, st);
+}
+
+int fasth_forward_static(const fasth_shape* shape, const float* V, const float* X, float* A, void* stream) {
+  int rc = check_shape(shape);
+  if (rc != FASTH_OK) return rc;
+  if (!V || !X || !A) return FASTH_EINVAL;
+  if (!aligned16(V) || !aligned16(X) || !aligned16(A)) return FASTH_EALIGN;
+  // only the regions Step 1 writes and Step 2 reads: nothing is saved for a backward pass
+  const Layout L = make_layout(shape->d, shape->n, shape->m, shape->k);
+  if (L.off_saveA > FASTH_STATIC_SCRATCH_BYTES) return FASTH_EUNSUPPORTED;
+  void* ws = nullptr;
+  if ((rc = static_scratch(&ws)) != FASTH_OK) return rc;
+  const Product P = bind(shape->d, shape->n, shape->m, shape->k, ws);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if ((rc = build_factors(P, V, st)) != FASTH_OK) return rc;
+  return run_chain(P, V, X, A, shape->transpose, true, nullptr, 0, st, false);
 }
 
 int fasth_prepare(const fasth_shape* shape, const float* V, void* workspace, size_t workspace_bytes, void* stream) {

@@ -56,6 +56,17 @@ def test_forward_argument_errors_precede_any_gpu_call():
     assert B.load_library().fasth_forward(None, 256, 256, 256, 256, 1 << 40, None) == B.FASTH_EINVAL
 
 
+def test_static_forward_argument_errors_precede_any_gpu_call():
+    lib = B.load_library()
+    ok = B.fasth_shape(64, 64, 32, 32, 0)
+    assert lib.fasth_forward_static(ctypes.byref(ok), None, 256, 256, None) == B.FASTH_EINVAL
+    assert lib.fasth_forward_static(ctypes.byref(ok), 256, 260, 256, None) == B.FASTH_EALIGN
+    assert lib.fasth_forward_static(ctypes.byref(B.fasth_shape(64, 64, 32, 7, 0)), 256, 256, 256, None) == B.FASTH_EINVAL
+    # factors and partial Gram matrices of this shape need more than the fixed scratch array holds
+    big = B.fasth_shape(16384, 16384, 32, 128, 0)
+    assert lib.fasth_forward_static(ctypes.byref(big), 256, 256, 256, None) == B.FASTH_EUNSUPPORTED
+
+
 def test_backward_and_layer_argument_errors():
     lib = B.load_library()
     ok = B.fasth_shape(64, 64, 32, 32, 0)
