@@ -122,14 +122,17 @@ int fasth_tune_block_size(const fasth_shape* shape, const int* candidates, int n
                           const float* V, const float* X, const float* G, float* A, float* dV, float* dX,
                           void* workspace, size_t workspace_bytes, int* best_k, float* best_ms, void* stream);
 
-/* The comparison the paper measures against (Section 2.2, "O(d) sequential
- * inner products"): the same A, dX and dV computed one reflection at a time
- * on the GPU. shape->k is ignored. fasth_sequential_backward recomputes the
- * forward product itself (it needs X, not a forward workspace). */
+/* The comparison the paper measures against (the one-reflection-at-a-time evaluation of Section 2.2):
+ * the same A, dX and dV computed one reflection at a time on the GPU, n dependent inner products over d
+ * forward and 2 n backward. shape->k is ignored. fasth_sequential_backward takes A, the product that
+ * fasth_sequential_forward wrote for the same V and X: walking the reflections from the output side it
+ * recovers each reflection's input from its output (Eq. 4), so it needs neither X nor a second forward
+ * pass. Its workspace holds one Eq. 5 term per column and reflection (m n d floats), which a last kernel
+ * sums over the columns in a fixed order. */
 size_t fasth_sequential_workspace_bytes(const fasth_shape* shape);
 int fasth_sequential_forward(const fasth_shape* shape, const float* V, const float* X, float* A,
                              void* stream);
-int fasth_sequential_backward(const fasth_shape* shape, const float* V, const float* X, const float* G,
+int fasth_sequential_backward(const fasth_shape* shape, const float* V, const float* A, const float* G,
                               float* dV, float* dX, void* workspace, size_t workspace_bytes,
                               void* stream);
 
@@ -201,8 +204,9 @@ int svd_layer_log_abs_det(int d, const float* sigma, float* log_abs_det, float* 
  * the calling process is bracketed by a pair of HIP events on its stream; fasth_profile_collect
  * waits for them, adds the elapsed milliseconds and the launch count per kernel into the two HOST
  * arrays of FASTH_KERNEL_COUNT entries, and forgets the records. The extra events perturb
- * end-to-end timing, so keep profiling off in regions that report throughput. Process-global and
- * not thread-safe. */
+ * end-to-end timing, so keep profiling off in regions that report throughput. The profiling state is
+ * process-global and not thread-safe: it is the one exception to "no state between calls" (the only other
+ * thing the library remembers is which kernels it has already allowed more than 64 KiB of LDS, under a lock). */
 enum {
   FASTH_KERNEL_GRAM = 0,
   FASTH_KERNEL_TBUILD = 1,
@@ -218,6 +222,18 @@ enum {
 const char* fasth_kernel_name(int id);
 int fasth_profile_enable(int on);
 int fasth_profile_collect(float* ms, int* launches);
+/* The instantiation ("kernel<template arguments>") last launched in slot `id` since profiling was switched
+ * on; "" if none. At most 65536 launches are timed between two collects; later ones run untimed. */
+const char* fasth_profile_variant(int id);
+
+/* Benchmark aid: what this GPU delivers on the rooflines the kernels are priced against, from plain kernels of
+ * known work: fp32 matrix instructions issued from registers on every compute unit (TFLOP/s), a streaming read
+ * of `buffer` and a copy of its first half onto its second (GB/s; the copy counts bytes read plus bytes written).
+ * `buffer` is caller-owned device memory of at least 8 MiB, overwritten; several hundred MiB make the figures
+ * those of HBM rather than of the caches. Best of `repetitions` timed runs each, after one untimed run. The three
+ * results are HOST pointers. Waits for the stream (it reads event times). */
+int fasth_measure_peaks(void* buffer, size_t buffer_bytes, int repetitions, float* fp32_mfma_tflops,
+                        float* hbm_read_gbs, float* hbm_copy_gbs, void* stream);
 
 #ifdef __cplusplus
 }

@@ -47,6 +47,8 @@ EXPORTED_SYMBOLS = (
     "fasth_kernel_name",
     "fasth_profile_enable",
     "fasth_profile_collect",
+    "fasth_profile_variant",
+    "fasth_measure_peaks",
 )
 
 
@@ -137,6 +139,11 @@ def load_library() -> ctypes.CDLL:
     lib.fasth_profile_enable.argtypes = [I]
     lib.fasth_profile_collect.restype = I
     lib.fasth_profile_collect.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_int)]
+    lib.fasth_profile_variant.restype = ctypes.c_char_p
+    lib.fasth_profile_variant.argtypes = [I]
+    lib.fasth_measure_peaks.restype = I
+    lib.fasth_measure_peaks.argtypes = [P, S, I, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_float),
+                                        ctypes.POINTER(ctypes.c_float), P]
     _lib = lib
     return lib
 
@@ -267,11 +274,12 @@ def fasth_sequential_forward(V, X, A, transpose: bool = False) -> None:
     _check(rc, "fasth_sequential_forward")
 
 
-def fasth_sequential_backward(V, X, G, dV, dX, workspace, transpose: bool = False) -> None:
+def fasth_sequential_backward(V, A, G, dV, dX, workspace, transpose: bool = False) -> None:
+    """A is the product fasth_sequential_forward wrote for the same V and X."""
     n, d = V.shape
-    m = X.shape[1]
+    m = A.shape[1]
     shape = _shape(d, n, m, 1, transpose)
-    rc = load_library().fasth_sequential_backward(ctypes.byref(shape), _ptr(V, "V"), _ptr(X, "X"), _ptr(G, "G"),
+    rc = load_library().fasth_sequential_backward(ctypes.byref(shape), _ptr(V, "V"), _ptr(A, "A"), _ptr(G, "G"),
                                                   _ptr(dV, "dV"), _ptr(dX, "dX"), _ptr(workspace, "workspace"),
                                                   workspace.numel(), _stream())
     _check(rc, "fasth_sequential_backward")
@@ -390,3 +398,19 @@ def fasth_profile_collect() -> dict:
     cnt = (ctypes.c_int * FASTH_KERNEL_COUNT)()
     _check(lib.fasth_profile_collect(ms, cnt), "fasth_profile_collect")
     return {lib.fasth_kernel_name(i).decode(): (float(ms[i]), int(cnt[i])) for i in range(FASTH_KERNEL_COUNT)}
+
+
+def fasth_profile_variants() -> dict:
+    """{kernel name: instantiation last launched in that slot since profiling was switched on}."""
+    lib = load_library()
+    return {lib.fasth_kernel_name(i).decode(): lib.fasth_profile_variant(i).decode() for i in range(FASTH_KERNEL_COUNT)}
+
+
+def fasth_measure_peaks(buffer, repetitions: int = 3) -> dict:
+    """Measured fp32 matrix-instruction rate (TFLOP/s) and streaming read / copy rates (GB/s) of this GPU."""
+    mf, rd, cp = ctypes.c_float(0.0), ctypes.c_float(0.0), ctypes.c_float(0.0)
+    rc = load_library().fasth_measure_peaks(_ptr(buffer, "workspace"), buffer.numel() * buffer.element_size(),
+                                            int(repetitions), ctypes.byref(mf), ctypes.byref(rd), ctypes.byref(cp),
+                                            _stream())
+    _check(rc, "fasth_measure_peaks")
+    return {"fp32_mfma_tflops": mf.value, "hbm_read_gbs": rd.value, "hbm_copy_gbs": cp.value}

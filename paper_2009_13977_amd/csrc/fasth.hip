@@ -37,6 +37,7 @@
 #include "fasth_chain.h"
 #include "fasth_dv.h"
 #include "fasth_sequential.h"
+#include "fasth_peaks.h"
 
 namespace fasth {
 
@@ -74,7 +75,10 @@ static Product bind(int d, int n, int m, int k, void* ws) {
 static bool factor_is_fused(int kp, int d) { return kp <= 32 || (kp == 64 && d <= FASTH_FUSED64_MAX_D); }
 
 static int launch_factor_fused(const FactorPair& fp, int count, int kp, bool vec4, hipStream_t stream) {
-  prof::Scope ps_(FASTH_KERNEL_FACTOR, stream);
+  static const std::string names[6] = {variant_name("factor_fused_kernel", {1, 4}), variant_name("factor_fused_kernel", {2, 4}),
+                                       variant_name("factor_fused_kernel", {4, 4}), variant_name("factor_fused_kernel", {1, 1}),
+                                       variant_name("factor_fused_kernel", {2, 1}), variant_name("factor_fused_kernel", {4, 1})};
+  prof::Scope ps_(FASTH_KERNEL_FACTOR, stream, names[(vec4 ? 0 : 3) + (kp == 16 ? 0 : kp == 32 ? 1 : 2)].c_str());
   const dim3 grid(count == 2 && fp.nb[1] > fp.nb[0] ? fp.nb[1] : fp.nb[0], count), block(512);
   if (vec4) {
     if (kp == 16) hipLaunchKernelGGL((factor_fused_kernel<1, 4>), grid, block, 0, stream, fp);
@@ -106,7 +110,7 @@ static int build_factors(const Product& P, const float* V, hipStream_t stream) {
     int rc = allow_lds(gram_partial_kernel<4>, lds);
     if (rc == FASTH_OK) rc = allow_lds(gram_partial_kernel<1>, lds);
     if (rc != FASTH_OK) return rc;
-    prof::Scope ps_(FASTH_KERNEL_GRAM, stream);
+    prof::Scope ps_(FASTH_KERNEL_GRAM, stream, P.d % 4 == 0 ? "gram_partial_kernel<4>" : "gram_partial_kernel<1>");
     const dim3 grid(P.L.gram_split, P.L.nb);
     if (P.d % 4 == 0)
       hipLaunchKernelGGL(gram_partial_kernel<4>, grid, dim3(256), lds, stream, V, P.Spart(), P.d, P.k, kp, P.L.gram_split);
@@ -118,7 +122,7 @@ static int build_factors(const Product& P, const float* V, hipStream_t stream) {
     const size_t lds = t_build_lds(kp);
     int rc = allow_lds(t_build_kernel, lds);
     if (rc != FASTH_OK) return rc;
-    prof::Scope ps_(FASTH_KERNEL_TBUILD, stream);
+    prof::Scope ps_(FASTH_KERNEL_TBUILD, stream, "t_build_kernel");
     hipLaunchKernelGGL(t_build_kernel, dim3(P.L.nb), dim3(kp >= 128 ? 1024 : kp >= 64 ? 512 : 256), lds, stream, P.Spart(), P.T(), P.k, kp, P.L.gram_split);
     FASTH_HIP(hipGetLastError());
   }
@@ -188,9 +192,15 @@ static int launch_dv(const DvPair& pair, int count, int kp, bool vec4, hipStream
   // A split mini-batch needs it too: no workgroup sees all columns.
   const bool z_fits = (size_t)a0.m * a0.n * sizeof(float) < kOob && a0.Z != nullptr &&
                       (count == 1 || (pair.a[1].m == a0.m && pair.a[1].k == a0.k && pair.a[1].Z != nullptr));
-  if (msplit > 1 && !z_fits) return FASTH_EINVAL;  // cannot happen: a split is only chosen for small n d
+  if (msplit > 1 && !z_fits) return FASTH_EINVAL;  // dv_minibatch_split never chooses a split for such a shape
   const bool prez = z_fits && (msplit > 1 || (a0.k >= 64 && (size_t)a0.m * a0.k >= 32768));
-  prof::Scope ps_(FASTH_KERNEL_DV, stream);
+  static const std::string names[16] = {
+      variant_name("dv_kernel", {1, 1, 0}), variant_name("dv_kernel", {1, 1, 1}), variant_name("dv_kernel", {1, 4, 0}), variant_name("dv_kernel", {1, 4, 1}),
+      variant_name("dv_kernel", {2, 1, 0}), variant_name("dv_kernel", {2, 1, 1}), variant_name("dv_kernel", {2, 4, 0}), variant_name("dv_kernel", {2, 4, 1}),
+      variant_name("dv_kernel", {4, 1, 0}), variant_name("dv_kernel", {4, 1, 1}), variant_name("dv_kernel", {4, 4, 0}), variant_name("dv_kernel", {4, 4, 1}),
+      variant_name("dv_kernel", {8, 1, 0}), variant_name("dv_kernel", {8, 1, 1}), variant_name("dv_kernel", {8, 4, 0}), variant_name("dv_kernel", {8, 4, 1})};
+  prof::Scope ps_(FASTH_KERNEL_DV, stream,
+                  names[(kp == 16 ? 0 : kp == 32 ? 4 : kp == 64 ? 8 : 12) + (vec4 ? 2 : 0) + (prez ? 1 : 0)].c_str());
   if (prez) {
     const int kt = kp / 16;
     hipLaunchKernelGGL(dv_z_kernel, dim3(kt * kt, nb, count), dim3(256), 0, stream, pair);
@@ -405,7 +415,7 @@ const char* fasth_strerror(int code) {
     case FASTH_EINVAL: return "invalid argument (null pointer, non-positive size, or k does not divide n)";
     case FASTH_EWORKSPACE: return "workspace too small";
     case FASTH_EALIGN: return "pointer is not 16-byte aligned";
-    case FASTH_EHIP: return "HIP runtime call or kernel launch failed";
+    case FASTH_EHIP: return g_hip_error_text[0] ? g_hip_error_text : "HIP runtime call or kernel launch failed";
     case FASTH_EUNSUPPORTED: return "shape outside the supported range";
     default: return "unknown error code";
   }
@@ -426,8 +436,15 @@ const char* fasth_kernel_name(int id) {
   }
 }
 
+const char* fasth_profile_variant(int id) {
+  if (id < 0 || id >= FASTH_KERNEL_COUNT || !prof::variant[id]) return "";
+  return prof::variant[id];
+}
+
 int fasth_profile_enable(int on) {
   prof::enabled = on != 0;
+  if (on)
+    for (int i = 0; i < FASTH_KERNEL_COUNT; ++i) prof::variant[i] = nullptr;
   return FASTH_OK;
 }
 
@@ -449,6 +466,44 @@ int fasth_profile_collect(float* ms, int* launches) {
   }
   prof::recs.clear();
   return rc;
+}
+
+int fasth_measure_peaks(void* buffer, size_t buffer_bytes, int repetitions, float* fp32_mfma_tflops,
+                        float* hbm_read_gbs, float* hbm_copy_gbs, void* stream) {
+  if (!buffer || !fp32_mfma_tflops || !hbm_read_gbs || !hbm_copy_gbs || repetitions < 1) return FASTH_EINVAL;
+  if (!aligned16(buffer)) return FASTH_EALIGN;
+  if (buffer_bytes < (size_t)(8u << 20)) return FASTH_EWORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  FASTH_HIP(hipEventCreate(&e0));
+  if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return FASTH_EHIP; }
+  float* fbuf = static_cast<float*>(buffer);
+  const int wgs = 4 * kComputeUnits, iters = 4096;
+  const size_t pieces = buffer_bytes / 16, half = pieces / 2;
+  int rc = FASTH_OK;
+  float best[3] = {0.f, 0.f, 0.f};
+  for (int which = 0; which < 3 && rc == FASTH_OK; ++which) {
+    for (int rep = 0; rep <= repetitions && rc == FASTH_OK; ++rep) {  // the first pass is not timed
+      if (hipEventRecord(e0, st) != hipSuccess) { rc = FASTH_EHIP; break; }
+      if (which == 0) hipLaunchKernelGGL(peak_mfma_kernel, dim3(wgs), dim3(256), 0, st, fbuf, iters);
+      else if (which == 1) hipLaunchKernelGGL(peak_read_kernel, dim3(8 * kComputeUnits), dim3(256), 0, st, static_cast<const float4*>(buffer) + 4096, pieces - 4096, fbuf);
+      else hipLaunchKernelGGL(peak_copy_kernel, dim3(8 * kComputeUnits), dim3(256), 0, st, static_cast<const float4*>(buffer), static_cast<float4*>(buffer) + half, half);
+      float ms = 0.f;
+      if (hipGetLastError() != hipSuccess || hipEventRecord(e1, st) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
+          hipEventElapsedTime(&ms, e0, e1) != hipSuccess) { rc = FASTH_EHIP; break; }
+      if (rep == 0 || ms <= 0.f) continue;
+      float rate;
+      if (which == 0) rate = (float)((double)wgs * 4 * iters * kPeakMfmaPerIter * 2048.0 / (ms * 1e-3) / 1e12);
+      else if (which == 1) rate = (float)((double)(pieces - 4096) * 16.0 / (ms * 1e-3) / 1e9);
+      else rate = (float)((double)half * 32.0 / (ms * 1e-3) / 1e9);  // bytes read + bytes written
+      if (rate > best[which]) best[which] = rate;
+    }
+  }
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  if (rc != FASTH_OK) return rc;
+  *fp32_mfma_tflops = best[0]; *hbm_read_gbs = best[1]; *hbm_copy_gbs = best[2];
+  return FASTH_OK;
 }
 
 size_t fasth_workspace_bytes(const fasth_shape* shape) {
@@ -580,7 +635,7 @@ int fasth_tune_block_size(const fasth_shape* shape, const int* candidates, int n
 size_t fasth_sequential_workspace_bytes(const fasth_shape* shape) {
   if (!shape || shape->d < 1 || shape->n < 1 || shape->m < 1) return 0;
   if (shape->d > kMaxD || shape->m > 65535) return 0;
-  return (size_t)shape->m * shape->n * shape->d * sizeof(float) + (size_t)shape->d * shape->m * sizeof(float);
+  return (size_t)shape->m * shape->n * shape->d * sizeof(float);
 }
 
 static int check_seq_shape(const fasth_shape* s) {
@@ -608,7 +663,7 @@ int fasth_sequential_forward(const fasth_shape* shape, const float* V, const flo
   hipStream_t st = static_cast<hipStream_t>(stream);
   const int threads = seq_threads(shape->d), per = (shape->d + threads - 1) / threads;
   {
-    prof::Scope ps_(FASTH_KERNEL_SEQ_FORWARD, st);
+    prof::Scope ps_(FASTH_KERNEL_SEQ_FORWARD, st, "seq_forward_kernel");
     FASTH_SEQ_DISPATCH(seq_forward_kernel, per, dim3(shape->m), dim3(threads), st, V, X, A, shape->d, shape->n,
                        shape->m, shape->transpose);
   }
@@ -616,33 +671,27 @@ int fasth_sequential_forward(const fasth_shape* shape, const float* V, const flo
   return FASTH_OK;
 }
 
-int fasth_sequential_backward(const fasth_shape* shape, const float* V, const float* X, const float* G, float* dV,
+int fasth_sequential_backward(const fasth_shape* shape, const float* V, const float* A, const float* G, float* dV,
                               float* dX, void* workspace, size_t workspace_bytes, void* stream) {
   int rc = check_seq_shape(shape);
   if (rc != FASTH_OK) return rc;
-  if (!V || !X || !G || !dV || !dX || !workspace) return FASTH_EINVAL;
-  if (!aligned16(V) || !aligned16(X) || !aligned16(G) || !aligned16(dV) || !aligned16(dX) || !aligned16(workspace))
+  if (!V || !A || !G || !dV || !dX || !workspace) return FASTH_EINVAL;
+  if (!aligned16(V) || !aligned16(A) || !aligned16(G) || !aligned16(dV) || !aligned16(dX) || !aligned16(workspace))
     return FASTH_EALIGN;
   if (workspace_bytes < fasth_sequential_workspace_bytes(shape)) return FASTH_EWORKSPACE;
   hipStream_t st = static_cast<hipStream_t>(stream);
   const int d = shape->d, n = shape->n, m = shape->m;
   float* dVpart = static_cast<float*>(workspace);
-  float* A = dVpart + (size_t)m * n * d;
   const int threads = seq_threads(d), per = (d + threads - 1) / threads;
   {
-    prof::Scope ps_(FASTH_KERNEL_SEQ_FORWARD, st);
-    FASTH_SEQ_DISPATCH(seq_forward_kernel, per, dim3(m), dim3(threads), st, V, X, A, d, n, m, shape->transpose);
-  }
-  FASTH_HIP(hipGetLastError());
-  {
-    prof::Scope ps_(FASTH_KERNEL_SEQ_BACKWARD, st);
-    FASTH_SEQ_DISPATCH(seq_backward_kernel, per, dim3(m), dim3(threads), st, V, (const float*)A, G, dVpart, dX, d, n,
-                       m, shape->transpose);
+    prof::Scope ps_(FASTH_KERNEL_SEQ_BACKWARD, st, "seq_backward_kernel");
+    FASTH_SEQ_DISPATCH(seq_backward_kernel, per, dim3(m), dim3(threads), st, V, A, G, dVpart, dX, d, n, m,
+                       shape->transpose);
   }
   FASTH_HIP(hipGetLastError());
   const size_t nd = (size_t)n * d;
   {
-    prof::Scope ps_(FASTH_KERNEL_SEQ_REDUCE, st);
+    prof::Scope ps_(FASTH_KERNEL_SEQ_REDUCE, st, "seq_reduce_kernel");
     hipLaunchKernelGGL(seq_reduce_kernel, dim3((unsigned)((nd + 255) / 256)), dim3(256), 0, st, (const float*)dVpart,
                        dV, nd, m);
   }

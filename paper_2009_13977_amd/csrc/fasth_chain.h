@@ -505,7 +505,8 @@ static int launch_chain_pipe(const ChainArgs& args, hipStream_t stream) {
       (!UNAL && a.d % VW != 0))
     return FASTH_EINVAL;
   const int side = a.ds_out ? (a.ds_rows + NT / 64 - 1) / (NT / 64) : 0;
-  prof::Scope ps_(FASTH_KERNEL_CHAIN, stream);
+  static const std::string name = variant_name("chain_pipe_kernel", {K, VW, NT, RL, SUB, PAD, P1, UNAL, XB});
+  prof::Scope ps_(FASTH_KERNEL_CHAIN, stream, name.c_str());
   hipLaunchKernelGGL((chain_pipe_kernel<K, VW, NT, RL, SUB, PAD, P1, UNAL, XB>), dim3(a.m + side), dim3(NT), 0, stream, a);
   FASTH_HIP(hipGetLastError());
   return FASTH_OK;
@@ -624,7 +625,8 @@ static int launch_chain_kernel(const ChainArgs& a, hipStream_t stream) {
   do {                                                                           \
     int rc_ = allow_lds(chain_kernel<UU>, lds);                                  \
     if (rc_ != FASTH_OK) return rc_;                                             \
-    prof::Scope ps_(FASTH_KERNEL_CHAIN, stream);                                 \
+    static const std::string name_ = variant_name("chain_kernel", {UU});         \
+    prof::Scope ps_(FASTH_KERNEL_CHAIN, stream, name_.c_str());                  \
     hipLaunchKernelGGL(chain_kernel<UU>, grid, block, lds, stream, a);           \
   } while (0)
   if (per > 4) return FASTH_EUNSUPPORTED;  // d > 16384: check_shape refuses it before
@@ -639,7 +641,7 @@ static int launch_chain_kernel(const ChainArgs& a, hipStream_t stream) {
 static int launch_chain(const ChainArgs& a, hipStream_t stream) {
   const int rc = launch_chain_kernel(a, stream);
   if (rc != FASTH_OK || !a.ds_out || chain_takes_side_product(a)) return rc;
-  prof::Scope ps_(FASTH_KERNEL_DSIGMA, stream);
+  prof::Scope ps_(FASTH_KERNEL_DSIGMA, stream, "dsigma_kernel");
   hipLaunchKernelGGL(dsigma_kernel, dim3((a.ds_rows + 3) / 4), dim3(256), 0, stream, a.in, a.ds_z1, a.in_scale, a.ds_out,
                      a.ds_rows, a.m, a.in_scale_mode);
   FASTH_HIP(hipGetLastError());

@@ -286,7 +286,8 @@ static int launch_chain_pair(const ChainArgs& args, hipStream_t stream) {
       32 * a.sub > a.kp || (!UNAL && a.d % 4 != 0))
     return FASTH_EINVAL;
   const int side = a.ds_out ? (a.ds_rows + NW - 1) / NW : 0;
-  prof::Scope ps_(FASTH_KERNEL_CHAIN, stream);
+  static const std::string name = variant_name("chain_pair_kernel", {NW, SUB, P1, RL, XA, XC, PAD, UNAL});
+  prof::Scope ps_(FASTH_KERNEL_CHAIN, stream, name.c_str());
   hipLaunchKernelGGL((chain_pair_kernel<NW, SUB, P1, RL, XA, XC, PAD, UNAL>), dim3(a.m + side), dim3(64 * NW), 0, stream, a);
   FASTH_HIP(hipGetLastError());
   return FASTH_OK;

@@ -294,7 +294,7 @@ __global__ void __launch_bounds__(64 * NW) chain_tile_kernel(ChainArgs p) {
 #endif
 static bool chain_uses_tile(const ChainArgs& a) {
   return a.m >= FASTH_TILE_MIN_COLS && a.d % 4 == 0 && a.d <= kTileMaxD && a.k % kTileRows == 0 &&
-         (size_t)a.d * a.m * sizeof(float) < kOob;  // its buffers take 32-bit byte offsets
+         (size_t)a.d * a.m * sizeof(float) < kOob && (size_t)a.n * a.d * sizeof(float) < kOob;  // 32-bit byte offsets
 }
 
 static int launch_chain_tile(const ChainArgs& a, hipStream_t stream) {
@@ -306,7 +306,8 @@ static int launch_chain_tile(const ChainArgs& a, hipStream_t stream) {
   do {                                                                                                      \
     int rc_ = allow_lds(chain_tile_kernel<WW, GG>, tile_lds_bytes(WW, GG));                                 \
     if (rc_ != FASTH_OK) return rc_;                                                                        \
-    prof::Scope ps_(FASTH_KERNEL_CHAIN, stream);                                                            \
+    static const std::string name_ = variant_name("chain_tile_kernel", {WW, GG});                           \
+    prof::Scope ps_(FASTH_KERNEL_CHAIN, stream, name_.c_str());                                             \
     hipLaunchKernelGGL((chain_tile_kernel<WW, GG>), grid, dim3(64 * WW), tile_lds_bytes(WW, GG), stream, a); \
   } while (0)
   if (a.d <= 1024) {

@@ -7,6 +7,10 @@
 #include <cstdint>
 #include <cstdio>
 #include <cstdlib>
+#include <cstring>
+#include <initializer_list>
+#include <mutex>
+#include <string>
 #include <type_traits>
 #include <vector>
 
@@ -46,6 +50,9 @@ struct Layout {
 static int dv_minibatch_split(int d, int n, int m, int k) {
   const int wgs = ((d + kDvTile - 1) / kDvTile) * (n / k);
   if (wgs >= 128 || m < 256) return 1;
+  // a split needs every block's matrix Z formed beforehand from the coefficient matrices, which the kernel that does
+  // it addresses with 32-bit byte offsets
+  if ((size_t)m * n * sizeof(float) >= 0x80000000u) return 1;
   int split = 256 / wgs;
   if (split > m / 128) split = m / 128;
   if (split > 32) split = 32;
@@ -82,23 +89,47 @@ static int check_shape(const fasth_shape* s) {
   if (s->n % s->k != 0) return FASTH_EINVAL;
   if (s->transpose != 0 && s->transpose != 1) return FASTH_EINVAL;
   if (s->k > kMaxBlock || s->d > kMaxD || s->m > 65535) return FASTH_EUNSUPPORTED;
+  if (s->n / s->k > 65535) return FASTH_EUNSUPPORTED;  // blocks are a grid dimension of the factor and dV launches
   return FASTH_OK;
 }
 
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-#define FASTH_HIP(call)                      \
-  do {                                       \
-    hipError_t e_ = (call);                  \
-    if (e_ != hipSuccess) return FASTH_EHIP; \
+// Text of the last HIP error a call of this thread ran into, for fasth_strerror(FASTH_EHIP).
+static thread_local char g_hip_error_text[192] = "";
+static int note_hip_error(hipError_t e, const char* what) {
+  snprintf(g_hip_error_text, sizeof(g_hip_error_text), "HIP runtime call or kernel launch failed: %s (%s)",
+           hipGetErrorString(e), what);
+  return FASTH_EHIP;
+}
+
+#define FASTH_HIP(call)                                    \
+  do {                                                     \
+    hipError_t e_ = (call);                                \
+    if (e_ != hipSuccess) return note_hip_error(e_, #call); \
   } while (0)
 
 // Optional per-kernel timing for benchmarks: a pair of HIP events around every launch.
+// "kernel<a, b, c>": the instantiation a launcher picked, as a profiler prints it.
+static std::string variant_name(const char* base, std::initializer_list<int> args) {
+  std::string s(base);
+  s += "<";
+  bool first = true;
+  for (int a : args) {
+    if (!first) s += ", ";
+    s += std::to_string(a);
+    first = false;
+  }
+  return s + ">";
+}
+
 namespace prof {
 struct Rec { int id; hipEvent_t beg, end; };
+constexpr size_t kMaxRecords = 1u << 16;  // launches recorded between two collects; later ones go untimed
 static bool enabled = false;
 static std::vector<Rec> recs;
 static std::vector<hipEvent_t> pool;
+static const char* variant[FASTH_KERNEL_COUNT] = {};  // instantiation last launched per slot while enabled
 static hipEvent_t get_event() {
   if (!pool.empty()) { hipEvent_t e = pool.back(); pool.pop_back(); return e; }
   hipEvent_t e = nullptr;
@@ -108,8 +139,10 @@ static hipEvent_t get_event() {
 struct Scope {
   Rec r{-1, nullptr, nullptr};
   hipStream_t st;
-  Scope(int id, hipStream_t s) : st(s) {
+  Scope(int id, hipStream_t s, const char* name = nullptr) : st(s) {
     if (!enabled) return;
+    if (name && id >= 0 && id < FASTH_KERNEL_COUNT) variant[id] = name;
+    if (recs.size() >= kMaxRecords) return;
     r.id = id; r.beg = get_event(); r.end = get_event();
     if (r.beg) (void)hipEventRecord(r.beg, st);
   }
@@ -121,12 +154,29 @@ struct Scope {
 };
 }  // namespace prof
 
+// Kernels that ask for more than 64 KiB of dynamic LDS must be allowed to, once per kernel and device; the size
+// granted so far is remembered per kernel (a small table under a mutex) so that the timed path makes no such call.
+struct LdsGrant { const void* kernel; int device; size_t bytes; };
+static std::vector<LdsGrant> g_lds_grants;
+static std::mutex g_lds_mutex;
+
 template <typename K>
 static int allow_lds(K kernel, size_t bytes) {
-  if (bytes > 64 * 1024) {
-    FASTH_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes));
+  if (bytes <= 64 * 1024) return FASTH_OK;
+  const void* fn = reinterpret_cast<const void*>(kernel);
+  int dev = 0;
+  FASTH_HIP(hipGetDevice(&dev));
+  std::lock_guard<std::mutex> lock(g_lds_mutex);
+  for (LdsGrant& g : g_lds_grants) {
+    if (g.kernel == fn && g.device == dev) {
+      if (g.bytes >= bytes) return FASTH_OK;
+      FASTH_HIP(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes));
+      g.bytes = bytes;
+      return FASTH_OK;
+    }
   }
+  FASTH_HIP(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes));
+  g_lds_grants.push_back(LdsGrant{fn, dev, bytes});
   return FASTH_OK;
 }
 

@@ -24,17 +24,33 @@ __global__ void __launch_bounds__(1024) seq_forward_kernel(const float* __restri
     const int x = tid + u * nthreads;
     a[u] = x < d ? X[(size_t)x * m + col] : 0.f;
   }
+  // the next reflection's vector is fetched while this one is applied, so that only the inner product, not the
+  // trip to memory, lies between two reflections
+  float vn[U];
+  {
+    const float* vr = V + (size_t)(transpose ? 0 : n - 1) * d;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int x = tid + u * nthreads;
+      vn[u] = x < d ? vr[x] : 0.f;
+    }
+  }
   for (int s = 0; s < n; ++s) {
-    const int j = transpose ? s : n - 1 - s;
-    const float* vr = V + (size_t)j * d;
     float v[U];
     float r[2] = {0.f, 0.f};
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const int x = tid + u * nthreads;
-      v[u] = x < d ? vr[x] : 0.f;
+      v[u] = vn[u];
       r[0] += v[u] * a[u];
       r[1] += v[u] * v[u];
+    }
+    if (s + 1 < n) {
+      const float* vr = V + (size_t)(transpose ? s + 1 : n - 2 - s) * d;
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int x = tid + u * nthreads;
+        vn[u] = x < d ? vr[x] : 0.f;
+      }
     }
     wave_reduce_multi<2>(r);
     const int sel = reduce_sel<2>(lane);
@@ -73,18 +89,33 @@ __global__ void __launch_bounds__(1024) seq_backward_kernel(const float* __restr
     a[u] = x < d ? A[(size_t)x * m + col] : 0.f;
     g[u] = x < d ? G[(size_t)x * m + col] : 0.f;
   }
+  float vn[U];  // the next reflection's vector, fetched one reflection ahead as in the forward kernel
+  {
+    const float* vr = V + (size_t)(transpose ? n - 1 : 0) * d;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int x = tid + u * nthreads;
+      vn[u] = x < d ? vr[x] : 0.f;
+    }
+  }
   for (int s = 0; s < n; ++s) {
     const int j = transpose ? n - 1 - s : s;
-    const float* vr = V + (size_t)j * d;
     float v[U];
     float r[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const int x = tid + u * nthreads;
-      v[u] = x < d ? vr[x] : 0.f;
+      v[u] = vn[u];
       r[0] += v[u] * a[u];
       r[1] += v[u] * g[u];
       r[2] += v[u] * v[u];
+    }
+    if (s + 1 < n) {
+      const float* vr = V + (size_t)(transpose ? n - 2 - s : s + 1) * d;
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int x = tid + u * nthreads;
+        vn[u] = x < d ? vr[x] : 0.f;
+      }
     }
     wave_reduce_multi<4>(r);
     const int sel = reduce_sel<4>(lane);

@@ -7,7 +7,7 @@ import pytest
 
 from oracle import householder as orc
 from paper_2009_13977_amd import synthetic
-from helpers import REL_TOL, gpu_fasth, gpu_sequential, gpu_svd_layer, gpu_svd_rect, gpu_svd_sym, rel_err
+from helpers import REL_TOL, assert_close, gpu_fasth, gpu_sequential, gpu_svd_layer, gpu_svd_rect, gpu_svd_sym, rel_err
 
 pytestmark = pytest.mark.gpu
 
@@ -41,9 +41,9 @@ def test_fasth_small_cases(d, n, m, k, transpose):
     p = synthetic.householder_problem(d, n, m, seed=1000 + d + n + m + k)
     A, dV, dX = gpu_fasth(p["V"], p["X"], p["G"], k, transpose)
     A0, dV0, dX0 = orc.product_gradients(p["V"], p["X"], p["G"], transpose=transpose)
-    assert rel_err(A, A0) <= REL_TOL
-    assert rel_err(dX, dX0) <= REL_TOL
-    assert rel_err(dV, dV0) <= REL_TOL
+    assert_close(A, A0, "A")
+    assert_close(dX, dX0, "dX")
+    assert_close(dV, dV0, "dV", rows=True)
 
 
 # One case per chain-kernel variant the launcher can pick: blocks held in registers and applied whole or
@@ -87,9 +87,9 @@ def test_fasth_every_chain_kernel(d, n, m, k, transpose):
     p = synthetic.householder_problem(d, n, m, seed=4000 + d + n + m + k)
     A, dV, dX = gpu_fasth(p["V"], p["X"], p["G"], k, transpose)
     A0, dV0, dX0 = orc.product_gradients(p["V"], p["X"], p["G"], transpose=transpose)
-    assert rel_err(A, A0) <= REL_TOL
-    assert rel_err(dX, dX0) <= REL_TOL
-    assert rel_err(dV, dV0) <= REL_TOL
+    assert_close(A, A0, "A")
+    assert_close(dX, dX0, "dX")
+    assert_close(dV, dV0, "dV", rows=True)
 
 
 # Wide mini-batches (more than 1024 columns) take the matrix-core chain kernel: 16 columns per workgroup, rows in
@@ -112,9 +112,9 @@ def test_fasth_wide_minibatch(d, n, m, k, transpose):
     p = synthetic.householder_problem(d, n, m, seed=5000 + d + n + m + k)
     A, dV, dX = gpu_fasth(p["V"], p["X"], p["G"], k, transpose)
     A0, dV0, dX0 = orc.product_gradients(p["V"], p["X"], p["G"], transpose=transpose)
-    assert rel_err(A, A0) <= REL_TOL
-    assert rel_err(dX, dX0) <= REL_TOL
-    assert rel_err(dV, dV0) <= REL_TOL
+    assert_close(A, A0, "A")
+    assert_close(dX, dX0, "dX")
+    assert_close(dV, dV0, "dV", rows=True)
 
 
 def test_fasth_wide_benchmark_config():
@@ -128,7 +128,34 @@ def test_fasth_wide_benchmark_config():
     A0, dV0, dX0 = orc.product_gradients(p["V"], p["X"], p["G"])
     errs = (rel_err(A, A0), rel_err(dV, dV0), rel_err(dX, dX0))
     _say(f"  rel errors A/dV/dX: {errs}")
-    assert max(errs) <= REL_TOL
+    assert_close(A, A0, "A")
+    assert_close(dV, dV0, "dV", rows=True)
+    assert_close(dX, dX0, "dX")
+
+
+def test_fasth_widest_benchmark_config():
+    """The 16384-column workload at full size, in the launch configuration the benchmark times (its saved block
+    inputs come to 2 GiB per chain, the limit of the kernels' 32-bit byte offsets). The checker takes about a
+    minute on all of A, dV and dX; beside it, properties that hold at any size."""
+    name = "d1024_m16384_k32"
+    w = synthetic.WORKLOADS[name]
+    _say(f"fasth config {name}")
+    p = synthetic.workload_inputs(name)
+    A, dV, dX = gpu_fasth(p["V"], p["X"], p["G"], w.k)
+    _say("  properties")
+    nx, ng = np.linalg.norm(p["X"].astype(np.float64)), np.linalg.norm(p["G"].astype(np.float64))
+    assert abs(np.linalg.norm(A.astype(np.float64)) - nx) <= 1e-5 * nx       # H is orthogonal
+    assert abs(np.linalg.norm(dX.astype(np.float64)) - ng) <= 1e-5 * ng
+    # <G, H X> = <H^T G, X>
+    lhs = float(np.sum(p["G"].astype(np.float64) * A)); rhs = float(np.sum(dX.astype(np.float64) * p["X"]))
+    assert abs(lhs - rhs) <= 1e-5 * nx * ng
+    _say("  checker")
+    A0, dV0, dX0 = orc.product_gradients(p["V"], p["X"], p["G"])
+    errs = (rel_err(A, A0), rel_err(dV, dV0), rel_err(dX, dX0))
+    _say(f"  rel errors A/dV/dX: {errs}")
+    assert_close(A, A0, "A")
+    assert_close(dV, dV0, "dV", rows=True)
+    assert_close(dX, dX0, "dX")
 
 
 def test_layers_wide_minibatch():
@@ -143,7 +170,7 @@ def test_layers_wide_minibatch():
         fn = orc.svd_layer_inverse_gradients if inverse else orc.svd_layer_gradients
         ref = fn(p["Uv"], p["sigma"], p["Vv"], p["X"], p["G"])
         for name, g, r in zip(("Y", "dUv", "dsigma", "dVv", "dX"), got, ref):
-            assert rel_err(g, r) <= REL_TOL, (name, rel_err(g, r))
+            assert_close(g, r, name, rows=name.startswith("d") and name.endswith("v"))
     rng = np.random.default_rng(5200)
     sigma = rng.uniform(-0.8, 0.9, d).astype(np.float32)
     for function in ("exp", "cayley"):
@@ -151,7 +178,7 @@ def test_layers_wide_minibatch():
         got = gpu_svd_sym(p["Uv"], sigma, p["X"], p["G"], k, function)
         ref = orc.symmetric_gradients(p["Uv"], sigma, p["X"], p["G"], function)
         for name, g, r in zip(("Y", "dUv", "dsigma", "dX"), got, ref):
-            assert rel_err(g, r) <= REL_TOL, (name, rel_err(g, r))
+            assert_close(g, r, name, rows=name.startswith("d") and name.endswith("v"))
     # (2048, 64): the two factors differ in how the dV mini-batch is split, so their dV launches stay separate
     for rows, cols in ((256, 192), (192, 256), (2048, 64)):
         _say(f"svd rect wide rows={rows} cols={cols}")
@@ -160,7 +187,7 @@ def test_layers_wide_minibatch():
         ref = orc.rectangular_gradients(q["Uv"], q["sigma"], q["Vv"], q["X"], q["G"])
         for name, g, r in zip(("Y", "dUv", "dsigma", "dVv", "dX"), got, ref):
             assert g.shape == r.shape, name
-            assert rel_err(g, r) <= REL_TOL, (name, rel_err(g, r))
+            assert_close(g, r, name, rows=name.startswith("d") and name.endswith("v"))
 
 
 def _random_shapes(count, seed):
@@ -187,9 +214,9 @@ def test_fasth_random_shapes(d, n, m, k, transpose):
     p = synthetic.householder_problem(d, n, m, seed=12000 + d + n + m + k)
     A, dV, dX = gpu_fasth(p["V"], p["X"], p["G"], k, transpose)
     A0, dV0, dX0 = orc.product_gradients(p["V"], p["X"], p["G"], transpose=transpose)
-    assert rel_err(A, A0) <= REL_TOL
-    assert rel_err(dX, dX0) <= REL_TOL
-    assert rel_err(dV, dV0) <= REL_TOL
+    assert_close(A, A0, "A")
+    assert_close(dX, dX0, "dX")
+    assert_close(dV, dV0, "dV", rows=True)
 
 
 def _random_pair_shapes(count, seed):
@@ -214,9 +241,9 @@ def test_fasth_random_shapes_lane_pairs(d, n, m, k, transpose):
     p = synthetic.householder_problem(d, n, m, seed=13000 + d + n + m + k)
     A, dV, dX = gpu_fasth(p["V"], p["X"], p["G"], k, transpose)
     A0, dV0, dX0 = orc.product_gradients(p["V"], p["X"], p["G"], transpose=transpose)
-    assert rel_err(A, A0) <= REL_TOL
-    assert rel_err(dX, dX0) <= REL_TOL
-    assert rel_err(dV, dV0) <= REL_TOL
+    assert_close(A, A0, "A")
+    assert_close(dX, dX0, "dX")
+    assert_close(dV, dV0, "dV", rows=True)
 
 
 @pytest.mark.parametrize("name", ["d64_m32_k32", "d256_m32_k32", "d1024_m32_k32",
@@ -229,12 +256,15 @@ def test_fasth_benchmark_configs(name):
     A0, dV0, dX0 = orc.product_gradients(p["V"], p["X"], p["G"])
     errs = (rel_err(A, A0), rel_err(dV, dV0), rel_err(dX, dX0))
     _say(f"  rel errors A/dV/dX: {errs}")
-    assert max(errs) <= REL_TOL
+    assert_close(A, A0, "A")
+    assert_close(dV, dV0, "dV", rows=True)
+    assert_close(dX, dX0, "dX")
     # properties that hold at any size
-    assert abs(np.linalg.norm(A) - np.linalg.norm(p["X"])) <= 1e-4 * np.linalg.norm(p["X"])
+    assert abs(np.linalg.norm(A.astype(np.float64)) - np.linalg.norm(p["X"].astype(np.float64))) <= 1e-5 * np.linalg.norm(p["X"])
+    # H does not depend on the length of v_j, so the gradient of v_j is orthogonal to it (follows from Eq. 1)
     row = np.abs(np.sum(dV.astype(np.float64) * p["V"], axis=1))
     scale = np.linalg.norm(dV, axis=1) * np.linalg.norm(p["V"], axis=1)
-    assert np.max(row / scale) < 1e-3
+    assert np.max(row / scale) < 1e-5
 
 
 def test_limits_of_the_supported_range():
@@ -245,8 +275,8 @@ def test_limits_of_the_supported_range():
         p = synthetic.householder_problem(d, n, m, seed=6000 + d + n + m + k)
         got = gpu_fasth(p["V"], p["X"], p["G"], k)
         ref = orc.product_gradients(p["V"], p["X"], p["G"])
-        for g, r in zip(got, ref):
-            assert rel_err(g, r) <= REL_TOL
+        for name, g, r in zip(("A", "dV", "dX"), got, ref):
+            assert_close(g, r, name, rows=name == "dV")
 
 
 def test_workspace_reuse_and_repeated_backward():
@@ -266,9 +296,9 @@ def test_workspace_reuse_and_repeated_backward():
             B.fasth_backward(Vd, to_gpu(G), dV, dX, ws, k)
             torch.cuda.synchronize()
             A0, dV0, dX0 = orc.product_gradients(p["V"], p["X"], G)
-            assert rel_err(A.cpu().numpy(), A0) <= REL_TOL
-            assert rel_err(dV.cpu().numpy(), dV0) <= REL_TOL
-            assert rel_err(dX.cpu().numpy(), dX0) <= REL_TOL
+            assert_close(A.cpu().numpy(), A0, "A")
+            assert_close(dV.cpu().numpy(), dV0, "dV", rows=True)
+            assert_close(dX.cpu().numpy(), dX0, "dX")
 
 
 def test_runs_on_a_side_stream():
@@ -286,8 +316,9 @@ def test_runs_on_a_side_stream():
         B.fasth_backward(Vd, Gd, dV, dX, ws, 32)
     side.synchronize()
     A0, dV0, dX0 = orc.product_gradients(p["V"], p["X"], p["G"])
-    assert rel_err(A.cpu().numpy(), A0) <= REL_TOL and rel_err(dV.cpu().numpy(), dV0) <= REL_TOL
-    assert rel_err(dX.cpu().numpy(), dX0) <= REL_TOL
+    assert_close(A.cpu().numpy(), A0, "A")
+    assert_close(dV.cpu().numpy(), dV0, "dV", rows=True)
+    assert_close(dX.cpu().numpy(), dX0, "dX")
 
 
 def test_prepare_once_apply_many():
@@ -315,7 +346,8 @@ def test_prepare_once_apply_many():
     B.fasth_backward(Vd, Gd, dV, dX, ws, k)
     torch.cuda.synchronize()
     _, dV0, dX0 = orc.product_gradients(p["V"], p["X"], p["G"])
-    assert rel_err(dV.cpu().numpy(), dV0) <= REL_TOL and rel_err(dX.cpu().numpy(), dX0) <= REL_TOL
+    assert_close(dV.cpu().numpy(), dV0, "dV", rows=True)
+    assert_close(dX.cpu().numpy(), dX0, "dX")
 
 
 @pytest.mark.parametrize("d,n,m,k,spread", [(256, 256, 32, 32, 3), (1024, 128, 8, 64, 4), (512, 64, 1040, 32, 3), (96, 96, 8, 48, 5)])
@@ -395,9 +427,9 @@ def test_sequential_kernels(d, n, m, transpose):
     p = synthetic.householder_problem(d, n, m, seed=2000 + d + n + m)
     A, dV, dX = gpu_sequential(p["V"], p["X"], p["G"], transpose)
     A0, dV0, dX0 = orc.product_gradients(p["V"], p["X"], p["G"], transpose=transpose)
-    assert rel_err(A, A0) <= REL_TOL
-    assert rel_err(dX, dX0) <= REL_TOL
-    assert rel_err(dV, dV0) <= REL_TOL
+    assert_close(A, A0, "A")
+    assert_close(dX, dX0, "dX")
+    assert_close(dV, dV0, "dV", rows=True)
 
 
 @pytest.mark.parametrize("inverse", [False, True])
@@ -409,7 +441,7 @@ def test_svd_layer_small(d, n, m, k, inverse):
     fn = orc.svd_layer_inverse_gradients if inverse else orc.svd_layer_gradients
     ref = fn(p["Uv"], p["sigma"], p["Vv"], p["X"], p["G"])
     for name, g, r in zip(("Y", "dUv", "dsigma", "dVv", "dX"), got, ref):
-        assert rel_err(g, r) <= REL_TOL, name
+        assert_close(g, r, name, rows=name.startswith("d") and name.endswith("v"))
 
 
 @pytest.mark.parametrize("inverse", [False, True])
@@ -450,7 +482,7 @@ def test_svd_layer_random_shapes(d, n, m, k, inverse):
     fn = orc.svd_layer_inverse_gradients if inverse else orc.svd_layer_gradients
     ref = fn(p["Uv"], p["sigma"], p["Vv"], p["X"], p["G"])
     for name, g, r in zip(("Y", "dUv", "dsigma", "dVv", "dX"), got, ref):
-        assert rel_err(g, r) <= REL_TOL, (name, rel_err(g, r))
+        assert_close(g, r, name, rows=name.startswith("d") and name.endswith("v"))
 
 
 def test_svd_layer_inverse_round_trip():
@@ -481,7 +513,7 @@ def test_symmetric_forms(d, n, m, k, function):
     got = gpu_svd_sym(Uv, sigma, X, G, k, function)
     ref = orc.symmetric_gradients(Uv, sigma, X, G, function)
     for name, g, r in zip(("Y", "dUv", "dsigma", "dX"), got, ref):
-        assert rel_err(g, r) <= REL_TOL, (name, rel_err(g, r))
+        assert_close(g, r, name, rows=name.startswith("d") and name.endswith("v"))
 
 
 RECT = [  # rows, cols, n_u, n_v, m, k: both orientations, every family of chain kernel, ragged min(rows, cols)
@@ -500,7 +532,7 @@ def test_rectangular_layer(rows, cols, n_u, n_v, m, k):
     ref = orc.rectangular_gradients(p["Uv"], p["sigma"], p["Vv"], p["X"], p["G"])
     for name, g, r in zip(("Y", "dUv", "dsigma", "dVv", "dX"), got, ref):
         assert g.shape == r.shape, name
-        assert rel_err(g, r) <= REL_TOL, (name, rel_err(g, r))
+        assert_close(g, r, name, rows=name.startswith("d") and name.endswith("v"))
 
 
 def test_log_abs_det():
@@ -539,7 +571,8 @@ def test_block_size_search():
     _say(f"  block-size search at d=784: best k={k}, {ms * 1e3:.1f} us per pass, search took {elapsed:.3f} s")
     assert k in divisors and ms > 0
     A0, dV0, dX0 = orc.product_gradients(p["V"], p["X"], p["G"])
-    assert rel_err(A.cpu().numpy(), A0) <= REL_TOL and rel_err(dV.cpu().numpy(), dV0) <= REL_TOL
-    assert rel_err(dX.cpu().numpy(), dX0) <= REL_TOL
+    assert_close(A.cpu().numpy(), A0, "A")
+    assert_close(dV.cpu().numpy(), dV0, "dV", rows=True)
+    assert_close(dX.cpu().numpy(), dX0, "dX")
     k2, _ = B.fasth_tune_block_size(Vd, Xd, Gd, A, dV, dX, ws, candidates=[5, 16, 28, 300], repetitions=2)
     assert k2 in (16, 28)
