@@ -36,7 +36,9 @@ def row_err(got, ref) -> float:
     if ref.ndim != 2 or ref.size == 0:
         return rel_err(got, ref)
     norms = np.linalg.norm(ref, axis=1)
-    den = np.maximum(norms, ROW_FLOOR * max(float(norms.max()), np.finfo(np.float64).tiny))
+    if not norms.max() > 0:  # an all-zero reference (d = 1: every reflection is -1): absolute deviation
+        return float(np.max(np.linalg.norm(got - ref, axis=1)))
+    den = np.maximum(norms, ROW_FLOOR * float(norms.max()))
     return float(np.max(np.linalg.norm(got - ref, axis=1) / den))
 
 
