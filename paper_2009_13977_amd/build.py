@@ -36,19 +36,46 @@ def build_library(verbose: bool = True) -> str:
         # uses its accumulators as the next product's operand, and copies between the two register files
         # would cost more than the products' bookkeeping
         "-mllvm", "-amdgpu-mfma-vgpr-form=1",
+        # per-kernel register and scratch use, checked below
+        "-Rpass-analysis=kernel-resource-usage",
         "-I", os.path.join(ROOT, "include"), "-I", os.path.join(PKG_DIR, "csrc"),
         "-o", LIB_PATH, *SOURCES,
     ]
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)
-    noise = "is not a recognized feature for this target"
-    err = "\n".join(l for l in res.stderr.splitlines() if noise not in l)
+    noise = ("is not a recognized feature for this target", "[-Rpass-analysis=kernel-resource-usage]")
+    err = "\n".join(l for l in res.stderr.splitlines() if not any(x in l for x in noise))
     if res.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + res.stdout + "\n" + err)
     if verbose and err.strip():
         print(err, file=sys.stderr)
+    check_register_use(res.stderr, verbose)
     return LIB_PATH
+
+
+def check_register_use(remarks: str, verbose: bool = True) -> None:
+    """The matrix-core chain kernel is written for results of matrix instructions that stay in the ordinary vector
+    registers (`-amdgpu-mfma-vgpr-form=1`, an internal compiler switch): with the switch in effect it uses no
+    accumulation registers and no scratch memory. A compiler that accepts the switch but ignores it, or a change
+    that pushes the kernel over its register budget, shows here at build time instead of as a slow kernel."""
+    import re
+    blocks = re.split(r"remark: Function Name: ", remarks)[1:]
+    seen = 0
+    for b in blocks:
+        name = b.split()[0]
+        if "chain_tile_kernel" not in name:
+            continue
+        seen += 1
+        agpr = int(re.search(r"AGPRs: (\d+)", b).group(1))
+        scratch = int(re.search(r"ScratchSize \[bytes/lane\]: (\d+)", b).group(1))
+        if agpr or scratch:
+            raise RuntimeError(f"{name}: {agpr} accumulation registers, {scratch} bytes of scratch per lane: "
+                               "the matrix-instruction results are not staying in the vector registers")
+    if blocks and not seen:
+        raise RuntimeError("no chain_tile_kernel in the compiler's resource remarks")
+    if verbose and seen:
+        print(f"register check: {seen} chain_tile_kernel instantiations, 0 accumulation registers, 0 scratch")
 
 
 def library_is_stale() -> bool:
