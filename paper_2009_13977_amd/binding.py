@@ -80,11 +80,12 @@ def load_library() -> ctypes.CDLL:
     global _lib
     if _lib is not None:
         return _lib
-    if not os.path.exists(LIB_PATH):
+    path = os.environ.get("FASTH_LIBRARY_PATH", LIB_PATH)  # another build of the same library, e.g. for an A/B timing
+    if not os.path.exists(path):
         raise FileNotFoundError(
-            f"{LIB_PATH} is missing: build it with `python -m paper_2009_13977_amd.build` "
+            f"{path} is missing: build it with `python -m paper_2009_13977_amd.build` "
             "(there is no CPU fallback)")
-    lib = ctypes.CDLL(LIB_PATH)
+    lib = ctypes.CDLL(path)
     P, S, I = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
     shp, sshp = ctypes.POINTER(fasth_shape), ctypes.POINTER(fasth_svd_shape)
     lib.fasth_strerror.restype = ctypes.c_char_p

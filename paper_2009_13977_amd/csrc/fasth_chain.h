@@ -516,16 +516,18 @@ static int launch_chain_pipe(const ChainArgs& args, hipStream_t stream) {
 
 #include "fasth_chain_tile.h"  // chain_tile_kernel: the same steps on the matrix cores, for wide mini-batches
 #include "fasth_chain_pair.h"  // chain_pair_kernel: the per-column chain with two waves per SIMD
+#include "fasth_chain_quad.h"  // chain_quad_kernel: four columns per workgroup on the matrix cores, 256 < m <= 1024
 
 namespace fasth {
 
 // chain_pipe_kernel serves every d up to 4096; it also takes the side product along.
-static bool chain_uses_pipe(const ChainArgs& a) { return !chain_uses_tile(a) && a.d <= 4096; }
+static bool chain_uses_pipe(const ChainArgs& a) { return !chain_uses_tile(a) && !chain_uses_quad(a) && a.d <= 4096; }
 static bool chain_takes_side_product(const ChainArgs& a) { return chain_uses_pipe(a); }
 
 static int launch_chain_kernel(const ChainArgs& a, hipStream_t stream) {
   const int d = a.d, k = a.k;
   if (chain_uses_tile(a)) return launch_chain_tile(a, stream);
+  if (chain_uses_quad(a)) return launch_chain_quad(a, stream);
   if (chain_uses_pipe(a) && d % 4 != 0) {
     // rows not 16-byte aligned: the general form of the kernels (any block size, short last step)
     if (chain_pair_serves(a) && (a.m <= (d > 896 ? 176 : kComputeUnits) || d <= 512)) {  // as for aligned rows below

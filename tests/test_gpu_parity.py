@@ -102,6 +102,10 @@ WIDE = [
     (125, 128, 800, 64), (125, 256, 800, 128),  # odd d: per-column chain in rounds, dV with 4-byte fetches reading Z
     # more columns than compute units, fewer than the matrix-core kernel takes: 16-row steps, several workgroups per unit
     (1024, 64, 300, 32), (768, 128, 260, 64), (1024, 128, 780, 128), (1024, 32, 1024, 32), (516, 96, 770, 32),
+    # 769 .. 1024 columns at 512 < d <= 1024 (from 608 at d > 896): four columns per workgroup on the matrix cores;
+    # one and several steps per block, ragged d and m, n != d; and neighbours that stay with the per-column kernels
+    (1024, 64, 800, 32), (1000, 128, 771, 64), (640, 256, 1023, 128), (900, 64, 610, 32), (516, 64, 1024, 32),
+    (1024, 96, 900, 96), (768, 64, 768, 32), (1024, 64, 607, 32),
 ]
 
 
