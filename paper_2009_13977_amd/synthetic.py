@@ -51,6 +51,7 @@ WORKLOADS: Dict[str, Workload] = {
         # Section 3.3, convolutional and recurrent uses: one V applied to m * h * w (or m * r) columns
         Workload("d1024_m4096_k32", 1024, 1024, 4096, 32, SEED_BASE + 6),
         Workload("d1024_m16384_k32", 1024, 1024, 16384, 32, SEED_BASE + 7),
+        Workload("d1024_m1024_k32", 1024, 1024, 1024, 32, SEED_BASE + 8),
     )
 }
 
