@@ -43,7 +43,8 @@ enum {
   FASTH_EWORKSPACE = -2,   /* workspace smaller than *_workspace_bytes() */
   FASTH_EALIGN = -3,       /* a pointer is not 16-byte aligned */
   FASTH_EHIP = -4,         /* a HIP runtime call or kernel launch failed */
-  FASTH_EUNSUPPORTED = -5  /* shape outside the supported range (see fasth_shape) */
+  FASTH_EUNSUPPORTED = -5, /* shape outside the supported range (see fasth_shape) */
+  FASTH_ETIMEOUT = -6      /* fasth_wait_status: a kernel's wait for another workgroup gave up */
 };
 
 /* Problem shape. Supported range: 1 <= d <= 16384, 1 <= n, 1 <= m <= 65535,
@@ -59,6 +60,22 @@ typedef struct fasth_shape {
 
 /* Human-readable text for a return code (static storage, never NULL). */
 const char* fasth_strerror(int code);
+
+/* Algorithm 1 Step 2 is sequential over the blocks but its two products per block can be shared between compute
+ * units. For vectors of 1025 to 2048 elements and at most 128 columns two workgroups share each column and hand
+ * each other a block's partial inner products through the workspace, i.e. one workgroup waits for another inside
+ * a kernel. Every such wait is bounded: after a number of polls (about a million, a fraction of a second; the wait
+ * itself takes a fraction of a microsecond) the waiting wave gives up, raises a status word on the GPU and runs
+ * on, so a kernel always ends, but its outputs are then wrong. fasth_wait_status waits for `stream`, reads and
+ * clears that word and returns FASTH_OK, or FASTH_ETIMEOUT if any kernel of this library gave up on this GPU
+ * since the last check (by any caller: the word is one per GPU, not per workspace). A caller that never checks
+ * loses nothing but the report. fasth_set_wait_limit sets the number of polls for launches enqueued from now on
+ * (process-wide; negative restores the default; 0 makes every wait give up at its first unsuccessful poll, which
+ * is how the error path is tested without a kernel that hangs). Two calls that use the same workspace must not
+ * overlap on the GPU (this was already so for calls that save for a backward pass; for these shapes it also
+ * holds for fasth_apply without saving). */
+int fasth_wait_status(void* stream);
+int fasth_set_wait_limit(int polls);
 
 /* Bytes of device workspace fasth_forward / fasth_backward need for `shape`
  * (block factors T_i, partial Gram matrices, the saved block inputs A_{i+1}

@@ -20,6 +20,7 @@ FASTH_EWORKSPACE = -2
 FASTH_EALIGN = -3
 FASTH_EHIP = -4
 FASTH_EUNSUPPORTED = -5
+FASTH_ETIMEOUT = -6
 
 EXPORTED_SYMBOLS = (
     "fasth_strerror",
@@ -49,6 +50,8 @@ EXPORTED_SYMBOLS = (
     "fasth_profile_collect",
     "fasth_profile_variant",
     "fasth_measure_peaks",
+    "fasth_wait_status",
+    "fasth_set_wait_limit",
 )
 
 
@@ -142,6 +145,10 @@ def load_library() -> ctypes.CDLL:
     lib.fasth_profile_collect.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_int)]
     lib.fasth_profile_variant.restype = ctypes.c_char_p
     lib.fasth_profile_variant.argtypes = [I]
+    lib.fasth_wait_status.restype = I
+    lib.fasth_wait_status.argtypes = [P]
+    lib.fasth_set_wait_limit.restype = I
+    lib.fasth_set_wait_limit.argtypes = [I]
     lib.fasth_measure_peaks.restype = I
     lib.fasth_measure_peaks.argtypes = [P, S, I, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_float),
                                         ctypes.POINTER(ctypes.c_float), P]
@@ -415,3 +422,13 @@ def fasth_measure_peaks(buffer, repetitions: int = 3) -> dict:
                                             _stream())
     _check(rc, "fasth_measure_peaks")
     return {"fp32_mfma_tflops": mf.value, "hbm_read_gbs": rd.value, "hbm_copy_gbs": cp.value}
+
+
+def fasth_wait_status() -> int:
+    """Waits for the current stream; FASTH_OK, or FASTH_ETIMEOUT if a kernel's wait for another workgroup gave up
+    on this GPU since the last check."""
+    return int(load_library().fasth_wait_status(_stream()))
+
+
+def fasth_set_wait_limit(polls: int) -> None:
+    _check(load_library().fasth_set_wait_limit(int(polls)), "fasth_set_wait_limit")

@@ -23,6 +23,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
 #include <cstdint>
 #include <mutex>
 #include <type_traits>
@@ -46,12 +47,17 @@ namespace fasth {
 // Host drivers
 // ------------------------------------------------------------------------------------------
 
+// Polls after which a kernel's wait for another workgroup gives up (fasth_set_wait_limit).
+static std::atomic<int> g_wait_limit{kDefaultWaitLimit};
+static int wait_limit() { return g_wait_limit.load(std::memory_order_relaxed); }
+
 struct Product {  // one Householder product bound to its slice of a workspace
   int d, n, m, k;
   Layout L;
   char* ws;
   float* T() const { return reinterpret_cast<float*>(ws + L.off_T); }
   float* Spart() const { return reinterpret_cast<float*>(ws + L.off_Spart); }
+  unsigned* xch() const { return L.xch_words ? reinterpret_cast<unsigned*>(ws + L.off_xch) : nullptr; }
   float* saveA() const { return reinterpret_cast<float*>(ws + L.off_saveA); }
   float* saveCa() const { return reinterpret_cast<float*>(ws + L.off_saveCa); }
   float* saveG() const { return reinterpret_cast<float*>(ws + L.off_saveG); }
@@ -95,6 +101,7 @@ static int launch_factor_fused(const FactorPair& fp, int count, int kp, bool vec
 
 static void set_factor_slot(FactorPair& fp, int slot, const Product& P, const float* V) {
   fp.V[slot] = V; fp.T[slot] = P.T(); fp.d[slot] = P.d; fp.k[slot] = P.k; fp.nb[slot] = P.L.nb;
+  fp.xch[slot] = P.xch(); fp.xch_words[slot] = (unsigned)P.L.xch_words;
 }
 
 static int build_factors(const Product& P, const float* V, hipStream_t stream) {
@@ -113,9 +120,11 @@ static int build_factors(const Product& P, const float* V, hipStream_t stream) {
     prof::Scope ps_(FASTH_KERNEL_GRAM, stream, P.d % 4 == 0 ? "gram_partial_kernel<4>" : "gram_partial_kernel<1>");
     const dim3 grid(P.L.gram_split, P.L.nb);
     if (P.d % 4 == 0)
-      hipLaunchKernelGGL(gram_partial_kernel<4>, grid, dim3(256), lds, stream, V, P.Spart(), P.d, P.k, kp, P.L.gram_split);
+      hipLaunchKernelGGL(gram_partial_kernel<4>, grid, dim3(256), lds, stream, V, P.Spart(), P.d, P.k, kp, P.L.gram_split,
+                         P.xch(), (unsigned)P.L.xch_words);
     else
-      hipLaunchKernelGGL(gram_partial_kernel<1>, grid, dim3(256), lds, stream, V, P.Spart(), P.d, P.k, kp, P.L.gram_split);
+      hipLaunchKernelGGL(gram_partial_kernel<1>, grid, dim3(256), lds, stream, V, P.Spart(), P.d, P.k, kp, P.L.gram_split,
+                         P.xch(), (unsigned)P.L.xch_words);
     FASTH_HIP(hipGetLastError());
   }
   {
@@ -148,10 +157,14 @@ static int build_factors_pair(const Product& P0, const float* V0, const Product&
 // slots of the workspace, false into the gradient slots.
 static int run_chain(const Product& P, const float* V, const float* in, float* out, int transpose, bool activation,
                      const float* in_scale, int in_scale_mode, hipStream_t stream, bool save = true,
-                     const float* factors = nullptr, int in_rows = -1, const float* ds_z1 = nullptr,
+                     const Product* factors = nullptr, int in_rows = -1, const float* ds_z1 = nullptr,
                      float* ds_out = nullptr, int ds_rows = 0) {
+  // `factors`: the product of the same shape whose workspace holds the block factors (and the hand-off area that
+  // was cleared when they were built), if not P's own
+  const Product& F = factors ? *factors : P;
   ChainArgs a;
-  a.V = V; a.T = factors ? factors : P.T(); a.in = in; a.out = out;
+  a.V = V; a.T = F.T(); a.in = in; a.out = out;
+  a.xch = F.xch(); a.wait_limit = wait_limit();
   a.Tt = a.T + (size_t)P.L.nb * P.L.kp * P.L.kp;
   a.save_in = !save ? nullptr : activation ? P.saveA() : P.saveG();
   a.save_c = !save ? nullptr : activation ? P.saveCa() : P.saveCg();
@@ -417,8 +430,24 @@ const char* fasth_strerror(int code) {
     case FASTH_EALIGN: return "pointer is not 16-byte aligned";
     case FASTH_EHIP: return g_hip_error_text[0] ? g_hip_error_text : "HIP runtime call or kernel launch failed";
     case FASTH_EUNSUPPORTED: return "shape outside the supported range";
+    case FASTH_ETIMEOUT: return "a kernel's wait for another workgroup gave up: results since the last check are invalid";
     default: return "unknown error code";
   }
+}
+
+int fasth_set_wait_limit(int polls) {
+  g_wait_limit.store(polls < 0 ? kDefaultWaitLimit : polls, std::memory_order_relaxed);
+  return FASTH_OK;
+}
+
+int fasth_wait_status(void* stream) {
+  FASTH_HIP(hipStreamSynchronize(static_cast<hipStream_t>(stream)));
+  unsigned word = 0;
+  FASTH_HIP(hipMemcpyFromSymbol(&word, HIP_SYMBOL(g_wait_gave_up), sizeof(word)));
+  if (!word) return FASTH_OK;
+  const unsigned zero = 0;
+  FASTH_HIP(hipMemcpyToSymbol(HIP_SYMBOL(g_wait_gave_up), &zero, sizeof(zero)));
+  return FASTH_ETIMEOUT;
 }
 
 const char* fasth_kernel_name(int id) {
@@ -722,7 +751,7 @@ int svd_sym_apply(const fasth_svd_shape* shape, int function, const float* Uv, c
   float* Z1 = reinterpret_cast<float*>(ws + S.off_Z1);
   if ((rc = build_factors(Pin, Uv, st)) != FASTH_OK) return rc;
   if ((rc = run_chain(Pin, Uv, X, Z1, 1, true, nullptr, 0, st)) != FASTH_OK) return rc;
-  return run_chain(Pout, Uv, Z1, Y, 0, true, sigma, mode, st, true, Pin.T());
+  return run_chain(Pout, Uv, Z1, Y, 0, true, sigma, mode, st, true, &Pin);
 }
 
 int svd_sym_apply_backward(const fasth_svd_shape* shape, int function, const float* Uv, const float* sigma,
@@ -744,7 +773,7 @@ int svd_sym_apply_backward(const fasth_svd_shape* shape, int function, const flo
   const Product Pout = bind(fs.d, fs.n, fs.m, fs.k, ws + S.off_U);
   const float* Z1 = reinterpret_cast<const float*>(ws + S.off_Z1);
   float* dZ2 = reinterpret_cast<float*>(ws + S.off_dZ2);
-  if ((rc = run_chain(Pout, Uv, G, dZ2, 1, false, nullptr, 0, st, true, Pin.T())) != FASTH_OK) return rc;
+  if ((rc = run_chain(Pout, Uv, G, dZ2, 1, false, nullptr, 0, st, true, &Pin)) != FASTH_OK) return rc;
   if ((rc = run_dv(Pout, Uv, dUv, 0, st)) != FASTH_OK) return rc;
   if ((rc = run_chain(Pin, Uv, dZ2, dX, 0, false, sigma, mode, st, true, nullptr, -1, Z1, dsigma, fs.d)) != FASTH_OK)
     return rc;

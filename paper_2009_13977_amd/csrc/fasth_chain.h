@@ -50,6 +50,10 @@ struct ChainArgs {
   const float* ds_z1;     // [ds_rows][m]
   float* ds_out;          // [ds_rows]
   int ds_rows;
+  // Hand-off area of the workspace for kernels in which workgroups share a column (null: the shape has none), and
+  // the number of polls after which a wait for another workgroup gives up.
+  unsigned* xch;
+  int wait_limit;
 };
 
 // Gradient of the diagonal step of the SVD layer (Section 2.2), one wave per row: with Z2 = s * Z1 row-wise
@@ -521,13 +525,21 @@ static int launch_chain_pipe(const ChainArgs& args, hipStream_t stream) {
 namespace fasth {
 
 // chain_pipe_kernel serves every d up to 4096; it also takes the side product along.
-static bool chain_uses_pipe(const ChainArgs& a) { return !chain_uses_tile(a) && !chain_uses_quad(a) && a.d <= 4096; }
+static bool chain_uses_pipe(const ChainArgs& a) {
+  return !chain_uses_tile(a) && !chain_uses_quad(a) && !chain_uses_split_pair(a) && a.d <= 4096;
+}
 static bool chain_takes_side_product(const ChainArgs& a) { return chain_uses_pipe(a); }
 
 static int launch_chain_kernel(const ChainArgs& a, hipStream_t stream) {
   const int d = a.d, k = a.k;
   if (chain_uses_tile(a)) return launch_chain_tile(a, stream);
   if (chain_uses_quad(a)) return launch_chain_quad(a, stream);
+  if (chain_uses_split_pair(a)) {
+    // two compute units per column, 32-row steps (d = n = 2048, m = 64: see the measurements at the kernel)
+    if (k == 32) return launch_chain_split_pair<1>(a, stream);
+    if (k == 64) return launch_chain_split_pair<2>(a, stream);
+    return launch_chain_split_pair<4>(a, stream);
+  }
   if (chain_uses_pipe(a) && d % 4 != 0) {
     // rows not 16-byte aligned: the general form of the kernels (any block size, short last step)
     if (chain_pair_serves(a) && (a.m <= (d > 896 ? 176 : kComputeUnits) || d <= 512)) {  // as for aligned rows below

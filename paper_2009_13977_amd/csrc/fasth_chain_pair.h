@@ -50,9 +50,25 @@ struct PairRegs {
 // Of a lane's 16 fetches per step, P1 are issued during the first product, RL during the reduction, XA after the
 // first barrier and XC after the second (while the LDS reads issued there are on their way), the rest during the update.
 // NW: waves per workgroup, 128 elements of the column each (8 for d <= 1024, 4 for d <= 512, 2 for d <= 256).
-template <int NW, int SUB, int P1, int RL, int XA, int XC, bool PAD = false, bool UNAL = false>
+//
+// SPLIT: the column is longer than one workgroup's 128 NW elements and TWO workgroups share it, each holding one
+// half of the column and of every row of V (half 0: x < 128 NW, half 1: the rest), so that a step keeps its 32 rows
+// and each compute unit fetches and multiplies half of them. The only thing the halves owe each other is a step's
+// 32 partial inner products: after the sum over its own waves each workgroup hands them to the other through the
+// workspace and adds what it receives (x + y = y + x exactly, so both form the same coefficients bit for bit and
+// nothing else is exchanged). A hand-off is 16 words of 16 bytes {b[2 t], tag, b[2 t + 1], tag}: each value and its
+// "ready" travel in the same 8 bytes, a word is valid once both tags equal the step's, and two sets of words alternate between
+// steps (a workgroup cannot be more than one step ahead of its partner, which it waits for in every step). Tags
+// count on from launch to launch through a word per column that the factor kernels zero together with the
+// hand-off words, so no stale word ever carries a valid tag, also when a captured launch is replayed. Stores and
+// loads of the hand-off are agent-scope (correct wherever the two workgroups run); the launch puts partners on one
+// XCD (workgroups b and b + 8), where the trip is shortest. Every wait is bounded: after p.wait_limit polls a wave
+// gives up for the rest of the launch, raises the library's status word and runs on with what it has, so the
+// kernel always ends; fasth_wait_status() tells the host.
+template <int NW, int SUB, int P1, int RL, int XA, int XC, bool PAD = false, bool UNAL = false, bool SPLIT = false>
 __global__ void __launch_bounds__(64 * NW) chain_pair_kernel(ChainArgs p) {
   static_assert(!UNAL || (PAD && SUB == 0), "the unaligned form is the general one");
+  static_assert(!SPLIT || (NW == 8 && !PAD && !UNAL), "two halves of 1024 elements, whole steps, aligned rows");
   static_assert(SUB > 0 || PAD, "steps per block");
   typedef PairLanes Lanes;
   constexpr int K = 32, KH = 16, G = 2 * NW, LPT = K / G;  // G threads share a row of op(T), LPT entries each
@@ -67,20 +83,53 @@ __global__ void __launch_bounds__(64 * NW) chain_pair_kernel(ChainArgs p) {
   __shared__ __align__(16) float Cv[2][KH];  // [parity][jj] = coefficient of row 2 jj + parity
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int col = blockIdx.x, m = p.m, d = p.d;
+  const int m = p.m, d = p.d;
+  // SPLIT: workgroups b and b + 8 (same XCD) are the halves of column 8 (b / 16) + b % 8
+  const int half = SPLIT ? (int)(blockIdx.x >> 3) & 1 : 0;
+  const int col = SPLIT ? (int)(blockIdx.x >> 4) * 8 + (int)(blockIdx.x & 7) : (int)blockIdx.x;
   if (col >= m) {  // workgroups beyond the columns: the side product, on compute units the chain leaves idle
-    const int row = (col - m) * NW + wave;
-    if (row < p.ds_rows) dsigma_row(p.in, p.ds_z1, p.in_scale, p.ds_out, row, m, p.in_scale_mode);
+    if constexpr (!SPLIT) {
+      const int row = (col - m) * NW + wave;
+      if (row < p.ds_rows) dsigma_row(p.in, p.ds_z1, p.in_scale, p.ds_out, row, m, p.in_scale_mode);
+    }
     return;
   }
   const int h = Lanes::parity(lane);
-  const unsigned x0w = 4u * (unsigned)(wave * 32 + Lanes::chunk(lane));
+  const unsigned x0w = (unsigned)half * (128u * NW) + 4u * (unsigned)(wave * 32 + Lanes::chunk(lane));
   const bool ok = x0w < (unsigned)d;
   const unsigned x0 = ok ? x0w : 0u;  // lanes beyond d fetch chunk 0 (valid memory) and keep their elements at zero
   const unsigned lane_off = (unsigned)h * (unsigned)d + x0;
   Chunk<4> a = load_column_chunk<4>(p, col, x0, ok);
   const int trow = tid / G, tg = tid % G;
   const int nb = p.nb;
+  // SPLIT: per column [2 (receiving half)][2 (step parity)][16] words of 16 bytes, then the tag counter
+  BufferDesc xdesc;
+  unsigned tag0 = 0, steps_done = 0;
+  bool gave_up = false;
+  bool same_xcd = false;
+  if constexpr (SPLIT) {
+    xdesc = make_buffer(reinterpret_cast<const float*>(p.xch + (size_t)col * kSplitPairWords), kSplitPairWords * 4u);
+    tag0 = __builtin_amdgcn_raw_buffer_load_b32(xdesc, 1024u, 0, 16);
+    // Do the two halves run on one XCD, i.e. behind one L2? Each tells the other the id of its own (agent-scope,
+    // tagged like a hand-off) before the chain starts. If they do, the hand-offs use ordinary stores, which that
+    // L2 holds, and loads that skip only the compute unit's own cache: a shorter trip than through memory.
+    const unsigned my_xcc = __builtin_amdgcn_s_getreg((3 << 11) | 20) & 15u;  // XCC_ID
+    const unsigned hs_tag = tag0 + 1u;
+    if (tid == 0) {
+      const u32x2 w = {my_xcc, hs_tag};
+      __builtin_amdgcn_raw_buffer_store_b64(w, xdesc, 1024u + 32u + (unsigned)(1 - half) * 8u, 0, 16);
+    }
+    unsigned peer_xcc = ~0u;
+    int polls = 0;
+    for (;;) {
+      const u32x2 w = __builtin_amdgcn_raw_buffer_load_b64(xdesc, 1024u + 32u + (unsigned)half * 8u, 0, 16);
+      peer_xcc = w.x;
+      if (__all(w.y == hs_tag)) break;
+      if (polls++ >= p.wait_limit) { gave_up = true; break; }
+      asm volatile("" ::: "memory");
+    }
+    same_xcd = !gave_up && peer_xcc == my_xcc;
+  }
   const int sel = ((lane & 32) ? 8 : 0) + ((lane & 16) ? 4 : 0) + ((lane & Lanes::M0) ? 2 : 0) + ((lane & Lanes::M1) ? 1 : 0);
   const bool writer = (lane & Lanes::M2) == 0;
   auto block_of = [&](int s) { return p.transpose ? s : nb - 1 - s; };  // step index of the s-th step applied
@@ -183,20 +232,53 @@ __global__ void __launch_bounds__(64 * NW) chain_pair_kernel(ChainArgs p) {
           }
         }
       }
-      if constexpr (XA > 0) {  // fetches while the partial sums are on their way from LDS
+      auto fetch_xa = [&]() {
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int e = 0; e < XA; ++e) load_row(ifetch, XA0 + e, dst.v[XA0 + e]);
         __builtin_amdgcn_sched_barrier(0);
-      }
-      float c = 0.f;
+      };
+      // fetches while the partial sums are on their way from LDS (SPLIT: behind the hand-off, whose polls would
+      // otherwise queue up behind them: loads return in the order they were issued)
+      if constexpr (XA > 0 && !SPLIT) fetch_xa();
+      float bs[LPT];
 #pragma unroll
       for (int e = 0; e < LPT; ++e) {
         float b = bw[0][e];
 #pragma unroll
         for (int w = 1; w < NW; ++w) b += bw[w][e];
-        c = fmaf(cur.t[e], b, c);
+        bs[e] = b;
       }
+      if constexpr (SPLIT) {
+        static_assert(LPT == 2, "a hand-off word holds two values");
+        const unsigned tag = tag0 + 1u + steps_done, par = (steps_done & 1u) * 256u;
+        ++steps_done;
+        if (trow == 0) {  // the first 16 threads hold the 32 sums of this half
+          const u32x4 w = {__builtin_bit_cast(unsigned, bs[0]), tag, __builtin_bit_cast(unsigned, bs[1]), tag};
+          const unsigned to = (unsigned)(1 - half) * 512u + par + (unsigned)tg * 16u;
+          if (same_xcd) __builtin_amdgcn_raw_buffer_store_b128(w, xdesc, to, 0, 0);
+          else __builtin_amdgcn_raw_buffer_store_b128(w, xdesc, to, 0, 16);
+        }
+        unsigned r0 = 0u, r1 = 0u;  // the partner's two sums (zero once a wait has given up)
+        if (!gave_up) {
+          int polls = 0;
+          for (;;) {
+            const unsigned from = (unsigned)half * 512u + par + (unsigned)tg * 16u;
+            const u32x4 w = same_xcd ? __builtin_amdgcn_raw_buffer_load_b128(xdesc, from, 0, 2)
+                                     : __builtin_amdgcn_raw_buffer_load_b128(xdesc, from, 0, 16);
+            r0 = w.x; r1 = w.z;
+            if (__all(w.y == tag && w.w == tag)) break;
+            if (polls++ >= p.wait_limit) { gave_up = true; break; }
+            asm volatile("" ::: "memory");
+          }
+        }
+        bs[0] += __builtin_bit_cast(float, r0);
+        bs[1] += __builtin_bit_cast(float, r1);
+        if constexpr (XA > 0) fetch_xa();
+      }
+      float c = 0.f;
+#pragma unroll
+      for (int e = 0; e < LPT; ++e) c = fmaf(cur.t[e], bs[e], c);
       c = group_sum<G>(c);
       if (PAD && trow >= kv) c = 0.f;
       if (tg == 0) {
@@ -204,7 +286,7 @@ __global__ void __launch_bounds__(64 * NW) chain_pair_kernel(ChainArgs p) {
         if constexpr (PAD) {
           if (p.save_c && trow < kv) p.save_c[(size_t)col * p.n + (size_t)step_block(i) * p.k + step_part(i) * K + trow] = c;
         } else {
-          if (p.save_c) p.save_c[(size_t)col * p.n + (size_t)i * K + trow] = c;
+          if (p.save_c && half == 0) p.save_c[(size_t)col * p.n + (size_t)i * K + trow] = c;
         }
       }
     }
@@ -266,6 +348,12 @@ __global__ void __launch_bounds__(64 * NW) chain_pair_kernel(ChainArgs p) {
     apply_step(block_of(s), ra, step_at(s + 2), rc);
     if (s + 1 < nb) apply_step(block_of(s + 1), rb, step_at(s + 3), ra);
   }
+  if constexpr (SPLIT) {
+    // the next launch on this workspace counts on from here (the partner read the counter before its first hand-off,
+    // and this workgroup has received the partner's last one)
+    if (half == 0 && tid == 0) __builtin_amdgcn_raw_buffer_store_b32(tag0 + steps_done, xdesc, 1024u, 0, 16);
+    if (gave_up && lane == 0) __hip_atomic_store(&g_wait_gave_up, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
   if (ok) {
     // each lane of a pair stores two of the chunk's four elements
     const float o0 = h ? a.e[2] : a.e[0], o1 = h ? a.e[3] : a.e[1];
@@ -289,6 +377,25 @@ static int launch_chain_pair(const ChainArgs& args, hipStream_t stream) {
   static const std::string name = variant_name("chain_pair_kernel", {NW, SUB, P1, RL, XA, XC, PAD, UNAL});
   prof::Scope ps_(FASTH_KERNEL_CHAIN, stream, name.c_str());
   hipLaunchKernelGGL((chain_pair_kernel<NW, SUB, P1, RL, XA, XC, PAD, UNAL>), dim3(a.m + side), dim3(64 * NW), 0, stream, a);
+  FASTH_HIP(hipGetLastError());
+  return FASTH_OK;
+}
+
+// Two workgroups per column (SPLIT above): 1024 < d <= 2048, whole 32-row steps, at most split_pair_max_cols columns
+// so that every workgroup of the launch has a compute unit of its own and no half waits for a partner that has not
+// started.
+static bool chain_uses_split_pair(const ChainArgs& a) { return a.xch != nullptr && split_pair_serves(a.d, a.m, a.k); }
+
+template <int SUB>
+static int launch_chain_split_pair(const ChainArgs& args, hipStream_t stream) {
+  ChainArgs a = args;
+  a.sub = a.k / 32;
+  a.nb = args.nb * a.sub;
+  if (!chain_uses_split_pair(a) || SUB != a.sub || a.kp != a.k) return FASTH_EINVAL;
+  static const std::string name = variant_name("chain_pair_kernel", {8, SUB, 4, 4, 3, 2, 0, 0, 1});
+  prof::Scope ps_(FASTH_KERNEL_CHAIN, stream, name.c_str());
+  hipLaunchKernelGGL((chain_pair_kernel<8, SUB, 4, 4, 3, 2, false, false, true>), dim3(16 * ((a.m + 7) / 8)), dim3(512), 0,
+                     stream, a);
   FASTH_HIP(hipGetLastError());
   return FASTH_OK;
 }

@@ -41,8 +41,19 @@ static int padded_block(int k) {
 
 struct Layout {
   int kp, nb, gram_split, dv_split;
-  size_t off_T, off_Spart, off_saveA, off_saveCa, off_saveG, off_saveCg, off_dVpart, total;
+  size_t off_T, off_Spart, off_xch, off_saveA, off_saveCa, off_saveG, off_saveCg, off_dVpart, total;
+  size_t xch_words;  // 32-bit words of the hand-off area between workgroups that share a column (0: none)
 };
+
+// Columns of 1025 to 2048 elements are shared by two workgroups (chain_pair_kernel's SPLIT form) while both have a
+// compute unit of their own. Per column the workspace then holds 2 x 2 x 16 hand-off words of 16 bytes and a tag
+// counter (padded to 256 bytes).
+constexpr unsigned kSplitPairWords = (2 * 2 * 16 * 16 + 256) / 4;
+constexpr int kSplitPairMaxCols = kComputeUnits / 2;
+static bool split_pair_serves(int d, int m, int k) {
+  return d > 1024 && d <= 2048 && d % 4 == 0 && (k == 32 || k == 64 || k == 128) && m <= kSplitPairMaxCols;
+}
+constexpr int kDefaultWaitLimit = 1 << 20;  // polls of a bounded wait between workgroups (a fraction of a second)
 
 // The dV kernel has one workgroup per (64-column tile of dV, block). When that is too few to fill the chip and the
 // mini-batch is wide (a short, narrow V against many columns: a 1 x 1 convolution with few channels), the
@@ -73,6 +84,8 @@ static Layout make_layout(int d, int n, int m, int k) {
   };
   L.off_T = take(2 * (size_t)L.nb * L.kp * L.kp);  // the factors and, behind them, their transposes
   L.off_Spart = take((size_t)L.nb * L.gram_split * L.kp * L.kp);
+  L.xch_words = split_pair_serves(d, m, k) ? (size_t)m * kSplitPairWords : 0;
+  L.off_xch = take(L.xch_words);
   L.off_saveA = take((size_t)L.nb * m * d);
   L.off_saveCa = take((size_t)m * n);
   L.off_saveG = take((size_t)L.nb * m * d);

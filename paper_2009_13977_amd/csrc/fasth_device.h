@@ -5,6 +5,11 @@
 namespace fasth {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+
+// Raised (never cleared) by a kernel whose bounded wait for another workgroup ran out; fasth_wait_status() reads
+// and clears it. One word per GPU for the whole library: it says that a launch went wrong, not which.
+__device__ unsigned g_wait_gave_up;
 
 constexpr int kWave = 64;
 
@@ -40,7 +45,6 @@ __device__ __forceinline__ BufVec<VEC> buffer_load(BufferDesc desc, unsigned lan
 template <int VEC>
 __device__ __forceinline__ void buffer_store(BufferDesc desc, unsigned lane_bytes, unsigned uniform_bytes, const BufVec<VEC>& v) {
   if constexpr (VEC == 4) {
-    typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
     const u32x4 w = {__float_as_uint(v.e[0]), __float_as_uint(v.e[1]), __float_as_uint(v.e[2]), __float_as_uint(v.e[3])};
     __builtin_amdgcn_raw_buffer_store_b128(w, desc, lane_bytes, uniform_bytes, 0);
   } else {

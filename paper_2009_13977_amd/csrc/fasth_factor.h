@@ -12,14 +12,23 @@ namespace fasth {
 // grid (gram_split, nb), 256 threads. Only the 16x16 tiles on or above the diagonal are formed.
 // ------------------------------------------------------------------------------------------
 
+// The hand-off area of the workspace (words that workgroups of a later chain launch pass to each other, with the
+// counters their tags continue from) starts every product at zero: whichever kernel builds the factors clears it,
+// all its workgroups taking a share.
+__device__ __forceinline__ void clear_exchange_area(unsigned* xch, unsigned words, unsigned wg, unsigned wgs) {
+  for (unsigned w = wg * blockDim.x + threadIdx.x; w < words; w += wgs * blockDim.x) xch[w] = 0u;
+}
+
 template <int VEC>  // VEC = 4 when d is a multiple of 4 (16-byte loads), else 1
 __global__ void __launch_bounds__(256) gram_partial_kernel(const float* __restrict__ V, float* __restrict__ Spart,
-                                                           int d, int k, int kp, int gram_split) {
+                                                           int d, int k, int kp, int gram_split, unsigned* xch,
+                                                           unsigned xch_words) {
   extern __shared__ __align__(16) float smem[];
   const int LD = kGramChunk + 4;
   float* Vs = smem;  // [kp][LD]
   const int i = blockIdx.y, s = blockIdx.x;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  clear_exchange_area(xch, xch_words, blockIdx.y * gridDim.x + blockIdx.x, gridDim.x * gridDim.y);
   const int chunk = ((d + gram_split - 1) / gram_split + 3) & ~3;
   const int xbeg = s * chunk;
   const int xend = min(d, xbeg + chunk);
@@ -281,12 +290,15 @@ struct FactorPair {
   const float* V[2];  // [n][d]
   float* T[2];        // [2][nb][kp][kp]: the factors, then their transposes
   int d[2], k[2], nb[2];
+  unsigned* xch[2];   // hand-off area of the product's workspace, cleared here
+  unsigned xch_words[2];
 };
 
 template <int KT, int VEC>  // VEC = 4 when d is a multiple of 4 (16-byte loads), else 1
 __global__ void __launch_bounds__(512) factor_fused_kernel(FactorPair fp) {
   const int which = blockIdx.y;
   if ((int)blockIdx.x >= fp.nb[which]) return;  // whole workgroup, before any barrier
+  clear_exchange_area(fp.xch[which], fp.xch_words[which], blockIdx.x, fp.nb[which]);
   const float* __restrict__ V = fp.V[which];
   float* __restrict__ T = fp.T[which];
   const int d = fp.d[which], k = fp.k[which];

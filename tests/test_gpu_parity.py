@@ -121,6 +121,105 @@ def test_fasth_wide_minibatch(d, n, m, k, transpose):
     assert_close(dV, dV0, "dV", rows=True)
 
 
+# Columns of 1025 .. 2048 elements, at most 128 of them: two workgroups share a column and hand each other every
+# step's partial inner products through the workspace. Cases: both halves full and the second nearly empty, one and
+# several steps per block, one column, a number of columns that is no multiple of 8, the most columns it takes, n != d;
+# and neighbours that stay with one workgroup per column (129 columns, a block size with a short last step).
+SHARED = [
+    (2048, 128, 13, 32), (1280, 64, 5, 32), (1028, 128, 8, 64), (2048, 256, 64, 128), (2044, 96, 128, 32),
+    (1536, 64, 1, 64), (1032, 32, 33, 32), (2048, 64, 129, 32), (2048, 96, 16, 48),
+]
+
+
+@pytest.mark.parametrize("transpose", [False, True])
+@pytest.mark.parametrize("d,n,m,k", SHARED)
+def test_fasth_shared_columns(d, n, m, k, transpose):
+    from paper_2009_13977_amd import binding as B
+    _say(f"fasth shared columns d={d} n={n} m={m} k={k} transpose={transpose}")
+    p = synthetic.householder_problem(d, n, m, seed=6000 + d + n + m + k)
+    A, dV, dX = gpu_fasth(p["V"], p["X"], p["G"], k, transpose)
+    assert B.fasth_wait_status() == B.FASTH_OK
+    A0, dV0, dX0 = orc.product_gradients(p["V"], p["X"], p["G"], transpose=transpose)
+    assert_close(A, A0, "A")
+    assert_close(dX, dX0, "dX")
+    assert_close(dV, dV0, "dV", rows=True)
+
+
+def test_shared_columns_wait_gives_up_and_recovers():
+    """A wait between the two workgroups of a column that runs out of polls ends the kernel normally and raises the
+    status word; the next call with the ordinary limit is correct again. The limit is forced to zero from the host,
+    so the very first unsuccessful poll gives up: nothing on the GPU hangs or faults."""
+    import torch
+    from paper_2009_13977_amd import binding as B
+    from helpers import to_gpu
+    d, n, m, k = 2048, 64, 16, 32
+    _say("shared columns: wait limit 0")
+    p = synthetic.householder_problem(d, n, m, seed=6100)
+    Vd, Xd, Gd = (to_gpu(p[a]) for a in ("V", "X", "G"))
+    A = torch.empty_like(Xd); dX = torch.empty_like(Xd); dV = torch.empty_like(Vd)
+    ws = B.new_workspace(B.fasth_workspace_bytes(d, n, m, k))
+    assert B.fasth_wait_status() == B.FASTH_OK
+    B.fasth_set_wait_limit(0)
+    try:
+        B.fasth_forward(Vd, Xd, A, ws, k)
+        assert B.fasth_wait_status() == B.FASTH_ETIMEOUT   # some workgroup saw its partner's word late
+        assert B.fasth_wait_status() == B.FASTH_OK         # reading the status clears it
+    finally:
+        B.fasth_set_wait_limit(-1)
+    _say("shared columns: default limit again")
+    for _ in range(2):  # the second pass continues the tag counters of the first
+        B.fasth_forward(Vd, Xd, A, ws, k)
+        B.fasth_backward(Vd, Gd, dV, dX, ws, k)
+    assert B.fasth_wait_status() == B.FASTH_OK
+    A0, dV0, dX0 = orc.product_gradients(p["V"], p["X"], p["G"])
+    assert_close(A.cpu().numpy(), A0, "A")
+    assert_close(dX.cpu().numpy(), dX0, "dX")
+    assert_close(dV.cpu().numpy(), dV0, "dV", rows=True)
+
+
+def test_shared_columns_in_the_layers():
+    """The SVD layer, a symmetric form (one set of factors serving two products) and the rectangular layer at sizes
+    whose chains run two workgroups per column; prepared factors applied repeatedly."""
+    import torch
+    from paper_2009_13977_amd import binding as B
+    from helpers import to_gpu
+    _say("shared columns: svd layer d=1536")
+    p = synthetic.svd_layer_problem(1536, 64, 8, seed=6200)
+    for inverse in (False, True):
+        got = gpu_svd_layer(p["Uv"], p["sigma"], p["Vv"], p["X"], p["G"], 32, inverse)
+        fn = orc.svd_layer_inverse_gradients if inverse else orc.svd_layer_gradients
+        for name, g, r in zip(("Y", "dUv", "dsigma", "dVv", "dX"), got, fn(p["Uv"], p["sigma"], p["Vv"], p["X"], p["G"])):
+            assert_close(g, r, name, rows=name.startswith("d") and name.endswith("v"))
+    _say("shared columns: symmetric form d=1280")
+    rng = np.random.default_rng(6300)
+    Uv = rng.standard_normal((64, 1280)).astype(np.float32)
+    sigma = rng.uniform(-0.8, 0.9, 1280).astype(np.float32)
+    X = rng.standard_normal((1280, 6)).astype(np.float32)
+    G = rng.standard_normal((1280, 6)).astype(np.float32)
+    for name, g, r in zip(("Y", "dUv", "dsigma", "dX"), gpu_svd_sym(Uv, sigma, X, G, 32, "exp"),
+                          orc.symmetric_gradients(Uv, sigma, X, G, "exp")):
+        assert_close(g, r, name, rows=name == "dUv")
+    _say("shared columns: rectangular layer 2048 x 1100")
+    p = synthetic.rect_layer_problem(2048, 1100, 64, 32, 7, seed=6400)
+    got = gpu_svd_rect(p["Uv"], p["sigma"], p["Vv"], p["X"], p["G"], 32)
+    for name, g, r in zip(("Y", "dUv", "dsigma", "dVv", "dX"), got,
+                          orc.rectangular_gradients(p["Uv"], p["sigma"], p["Vv"], p["X"], p["G"])):
+        assert_close(g, r, name, rows=name.startswith("d") and name.endswith("v"))
+    _say("shared columns: prepared factors")
+    d, n, m, k = 2048, 64, 24, 32
+    p = synthetic.householder_problem(d, n, m, seed=6500)
+    Vd, Xd = to_gpu(p["V"]), to_gpu(p["X"])
+    Y1 = torch.empty_like(Xd); Y2 = torch.empty_like(Xd)
+    ws = B.new_workspace(B.fasth_workspace_bytes(d, n, m, k))
+    B.fasth_prepare(Vd, m, ws, k)
+    for _ in range(3):
+        B.fasth_apply(Vd, Xd, Y1, ws, k)
+        B.fasth_apply(Vd, Y1, Y2, ws, k, transpose=True)
+    assert B.fasth_wait_status() == B.FASTH_OK
+    assert_close(Y1.cpu().numpy(), orc.product_apply(p["V"], p["X"]), "H X")
+    assert_close(Y2.cpu().numpy(), p["X"].astype(np.float64), "H^T H X")
+
+
 def test_fasth_wide_benchmark_config():
     """The wide workload at full size (4096 columns) against the checker on every output."""
     name = "d1024_m4096_k32"
