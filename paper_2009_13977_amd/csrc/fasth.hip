@@ -100,12 +100,12 @@ static int launch_factor_fused(const FactorPair& fp, int count, int kp, bool vec
 }
 
 static void set_factor_slot(FactorPair& fp, int slot, const Product& P, const float* V) {
-  fp.V[slot] = V; fp.T[slot] = P.T(); fp.d[slot] = P.d; fp.k[slot] = P.k; fp.nb[slot] = P.L.nb;
+  fp.V[slot] = V; fp.T[slot] = P.T(); fp.d[slot] = P.d; fp.k[slot] = P.L.kf; fp.nb[slot] = P.L.nbf;
   fp.xch[slot] = P.xch(); fp.xch_words[slot] = (unsigned)P.L.xch_words;
 }
 
 static int build_factors(const Product& P, const float* V, hipStream_t stream) {
-  const int kp = P.L.kp;
+  const int kp = P.L.kpf;
   if (factor_is_fused(kp, P.d)) {
     FactorPair fp;
     set_factor_slot(fp, 0, P, V);
@@ -118,12 +118,12 @@ static int build_factors(const Product& P, const float* V, hipStream_t stream) {
     if (rc == FASTH_OK) rc = allow_lds(gram_partial_kernel<1>, lds);
     if (rc != FASTH_OK) return rc;
     prof::Scope ps_(FASTH_KERNEL_GRAM, stream, P.d % 4 == 0 ? "gram_partial_kernel<4>" : "gram_partial_kernel<1>");
-    const dim3 grid(P.L.gram_split, P.L.nb);
+    const dim3 grid(P.L.gram_split, P.L.nbf);
     if (P.d % 4 == 0)
-      hipLaunchKernelGGL(gram_partial_kernel<4>, grid, dim3(256), lds, stream, V, P.Spart(), P.d, P.k, kp, P.L.gram_split,
+      hipLaunchKernelGGL(gram_partial_kernel<4>, grid, dim3(256), lds, stream, V, P.Spart(), P.d, P.L.kf, kp, P.L.gram_split,
                          P.xch(), (unsigned)P.L.xch_words);
     else
-      hipLaunchKernelGGL(gram_partial_kernel<1>, grid, dim3(256), lds, stream, V, P.Spart(), P.d, P.k, kp, P.L.gram_split,
+      hipLaunchKernelGGL(gram_partial_kernel<1>, grid, dim3(256), lds, stream, V, P.Spart(), P.d, P.L.kf, kp, P.L.gram_split,
                          P.xch(), (unsigned)P.L.xch_words);
     FASTH_HIP(hipGetLastError());
   }
@@ -132,7 +132,7 @@ static int build_factors(const Product& P, const float* V, hipStream_t stream) {
     int rc = allow_lds(t_build_kernel, lds);
     if (rc != FASTH_OK) return rc;
     prof::Scope ps_(FASTH_KERNEL_TBUILD, stream, "t_build_kernel");
-    hipLaunchKernelGGL(t_build_kernel, dim3(P.L.nb), dim3(kp >= 128 ? 1024 : kp >= 64 ? 512 : 256), lds, stream, P.Spart(), P.T(), P.k, kp, P.L.gram_split);
+    hipLaunchKernelGGL(t_build_kernel, dim3(P.L.nbf), dim3(kp >= 128 ? 1024 : kp >= 64 ? 512 : 256), lds, stream, P.Spart(), P.T(), P.L.kf, kp, P.L.gram_split);
     FASTH_HIP(hipGetLastError());
   }
   return FASTH_OK;
@@ -142,12 +142,12 @@ static int build_factors(const Product& P, const float* V, hipStream_t stream) {
 // kernel with the same template arguments; otherwise one after the other.
 static int build_factors_pair(const Product& P0, const float* V0, const Product& P1, const float* V1,
                               hipStream_t stream) {
-  if (factor_is_fused(P0.L.kp, P0.d) && factor_is_fused(P1.L.kp, P1.d) && P0.L.kp == P1.L.kp &&
+  if (factor_is_fused(P0.L.kpf, P0.d) && factor_is_fused(P1.L.kpf, P1.d) && P0.L.kpf == P1.L.kpf &&
       (P0.d % 4 == 0) == (P1.d % 4 == 0)) {
     FactorPair fp;
     set_factor_slot(fp, 0, P0, V0);
     set_factor_slot(fp, 1, P1, V1);
-    return launch_factor_fused(fp, 2, P0.L.kp, P0.d % 4 == 0, stream);
+    return launch_factor_fused(fp, 2, P0.L.kpf, P0.d % 4 == 0, stream);
   }
   const int rc = build_factors(P0, V0, stream);
   return rc != FASTH_OK ? rc : build_factors(P1, V1, stream);
@@ -165,7 +165,7 @@ static int run_chain(const Product& P, const float* V, const float* in, float* o
   ChainArgs a;
   a.V = V; a.T = F.T(); a.in = in; a.out = out;
   a.xch = F.xch(); a.wait_limit = wait_limit();
-  a.Tt = a.T + (size_t)P.L.nb * P.L.kp * P.L.kp;
+  a.Tt = a.T + (size_t)F.L.nbf * F.L.kpf * F.L.kpf;
   a.save_in = !save ? nullptr : activation ? P.saveA() : P.saveG();
   a.save_c = !save ? nullptr : activation ? P.saveCa() : P.saveCg();
   a.in_scale = in_scale; a.in_scale_mode = in_scale_mode;

@@ -521,12 +521,13 @@ static int launch_chain_pipe(const ChainArgs& args, hipStream_t stream) {
 #include "fasth_chain_tile.h"  // chain_tile_kernel: the same steps on the matrix cores, for wide mini-batches
 #include "fasth_chain_pair.h"  // chain_pair_kernel: the per-column chain with two waves per SIMD
 #include "fasth_chain_quad.h"  // chain_quad_kernel: four columns per workgroup on the matrix cores, 256 < m <= 1024
+#include "fasth_chain_team.h"  // chain_team_kernel: two to four workgroups per column, steps of 64 rows, few columns
 
 namespace fasth {
 
 // chain_pipe_kernel serves every d up to 4096; it also takes the side product along.
 static bool chain_uses_pipe(const ChainArgs& a) {
-  return !chain_uses_tile(a) && !chain_uses_quad(a) && !chain_uses_split_pair(a) && a.d <= 4096;
+  return !chain_uses_tile(a) && !chain_uses_quad(a) && !chain_uses_team(a) && !chain_uses_split_pair(a) && a.d <= 4096;
 }
 static bool chain_takes_side_product(const ChainArgs& a) { return chain_uses_pipe(a); }
 
@@ -534,6 +535,7 @@ static int launch_chain_kernel(const ChainArgs& a, hipStream_t stream) {
   const int d = a.d, k = a.k;
   if (chain_uses_tile(a)) return launch_chain_tile(a, stream);
   if (chain_uses_quad(a)) return launch_chain_quad(a, stream);
+  if (chain_uses_team(a)) return launch_chain_team(a, stream);
   if (chain_uses_split_pair(a)) {
     // two compute units per column, 32-row steps (d = n = 2048, m = 64: see the measurements at the kernel)
     if (k == 32) return launch_chain_split_pair<1>(a, stream);

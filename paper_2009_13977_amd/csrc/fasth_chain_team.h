@@ -1,0 +1,318 @@
+// Algorithm 1 Step 2 and Algorithm 2 Step 1 for few columns of 513 to 2048 elements: chain_team_kernel, in which a
+// team of two to four workgroups shares a column and a step takes 64 rows.
+// Included by fasth_chain.h (the library has a single translation unit).
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include "fasth_common.h"
+
+namespace fasth {
+
+// ------------------------------------------------------------------------------------------
+// A per-column chain is bound by what ONE compute unit can fetch and multiply per step: 32 rows x 1024 elements fill
+// its registers, and a chain of n / 32 such steps is n / 32 times that. With few columns most units idle. Here a
+// column of d elements is shared by NP = ceil(d / 512) workgroups ("parts") on different compute units; part j keeps
+// elements [512 j, 512 j + 512) of the column for the whole chain and reads only those columns of V, so the same
+// registers hold 64 rows per step and the chain has n / 64 sequential steps. What the parts owe each other is a
+// step's 64 partial inner products, nothing else: every part forms C = op(T) B itself.
+//
+// Blocks of 64 rows. By Lemma 1 the product of two consecutive blocks of 32 reflections is a WY block of 64:
+// I - V^T T V with the 64 x 64 factor T = (diag(S)/2 + striu(S))^-1, S = V V^T, whose diagonal 32 x 32 blocks are
+// the two blocks' own factors. Because T is triangular, the coefficients C = op(T) V a of the rows applied first are
+// those of the first block alone, and the others are the second block's coefficients for ITS input; so for a
+// caller's k = 32 the update is applied in two halves, the state between them is the second block's input, and what
+// is saved for the backward pass is exactly what the other chain kernels save. For k = 128 the diagonal 64 x 64
+// blocks of the block's factor serve its two steps (as in the other kernels).
+//
+// Lanes. A wave holds 64 elements of the column, a lane one 16-byte chunk (lane & 15) and every fourth row of the
+// step (rows 4 jj + q, q = lane >> 4, jj < 16): 16 rows x 4 elements per lane and register copy, three copies as in
+// chain_pair_kernel (the rows of step s + 2 are fetched while step s is applied); 16 adjacent lanes fetch 256
+// contiguous bytes of one row. The 16 partial inner products of a lane are summed over the 16 lanes of its row of
+// lanes by a register-only butterfly, after which lane (q, c) holds the wave's sum for row 4 c + q, and over the
+// waves through LDS. In the update each lane subtracts its 16 rows' terms and the four lanes of a chunk add their
+// sums through two lane-half swaps in an order that gives all four the same bits.
+//
+// Hand-off. After the sum over its own waves, wave w of a part owns rows 8 w .. 8 w + 7 of the step: it writes their
+// sums as 8-byte words {value, tag} into every other part's inbox in the workspace (one store), polls its own
+// inbox for the other parts' words (one load per poll), adds the NP sums in the order of the parts (so that every
+// part gets the same bits) and puts the totals into LDS for all waves. A word is valid once its tag equals the
+// step's; inboxes alternate between two sets by step parity (a part cannot be more than one step ahead of the
+// others); tags count on from launch to launch through a word per column that the factor kernels zero together with
+// the inboxes, so no stale word ever carries a valid tag, also when a captured launch is replayed. Stores and loads
+// are agent-scope (correct wherever the parts run); the launch maps a team to one XCD (workgroups b, b + 8, ...),
+// the parts tell each other their XCC_ID before the chain starts, and if they agree the hand-offs use ordinary
+// stores (which the XCD's L2 holds) and loads that skip only the compute unit's own cache. Every wait is bounded:
+// after p.wait_limit polls a wave gives up for the rest of the launch, raises the library's status word and runs on
+// with what it has, so the kernel always ends; fasth_wait_status() tells the host.
+// ------------------------------------------------------------------------------------------
+
+struct TeamRegs {
+  Chunk<4> v[16];  // rows 4 jj + q of the step, this lane's chunk
+};
+
+// KMODE 0: caller's blocks of 32 rows, two per step (factors stored as 64 x 64 blocks); 1: blocks of 64; 2: blocks of
+// 128, two steps per block.
+template <int NP, int KMODE>
+__global__ void __launch_bounds__(512) chain_team_kernel(ChainArgs p) {
+  static_assert(NP >= 2 && NP <= 4, "the parts' sums are added within a quad of lanes");
+  constexpr int K = kTeamRows, KH = 16, NW = 8, LPT = 8, G = 8;
+  constexpr int LDT = KMODE == 2 ? 128 : 64;
+  // fetches of step s + 2 per lane: P1 during the first product, RL during the reduction, XA behind the hand-off,
+  // XC next to the last barrier, the rest during the update
+  constexpr int P1 = 4, RL = 4, XA = 3, XC = 2, PR2 = KH - P1 - RL - XA - XC;
+  constexpr int S1 = KH / P1, S2 = KH / PR2, XA0 = P1 + RL, XC0 = XA0 + XA, U0 = XC0 + XC;
+  __shared__ float Bpart[NW][K + 1];          // per wave: its sums for the 64 rows (padded: column reads below)
+  __shared__ __align__(16) float Btot[K];     // the step's inner products, summed over waves and parts
+  __shared__ __align__(16) float Cv[4][KH];   // [q][jj] = coefficient of row 4 jj + q
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int m = p.m, d = p.d;
+  // workgroups b, b + 8, ... (one XCD) are the parts of column 8 (b / (8 NP)) + b % 8
+  const int part = (int)(blockIdx.x >> 3) % NP;
+  const int col = (int)(blockIdx.x >> 3) / NP * 8 + (int)(blockIdx.x & 7);
+  if (col >= m) return;
+  const int q = lane >> 4;
+  const unsigned x0w = (unsigned)part * kTeamSlice + (unsigned)wave * 64u + 4u * (unsigned)(lane & 15);
+  const bool ok = x0w < (unsigned)d;
+  const unsigned x0 = ok ? x0w : 0u;  // lanes beyond d fetch chunk 0 (valid memory) and keep their elements at zero
+  const unsigned lane_off = (unsigned)q * (unsigned)d + x0;
+  Chunk<4> a = load_column_chunk<4>(p, col, x0, ok);
+  const int trow = tid / G, tg = tid % G;  // G threads share a row of op(T), LPT entries each
+  const int ns = p.n / K;                  // steps of the chain
+  auto step_of = [&](int s) { return p.transpose ? s : ns - 1 - s; };  // index of the s-th step applied
+  auto step_at = [&](int s) { return step_of(s < ns ? s : ns - 1); };  // fetches past the end repeat the last step
+
+  const BufferDesc xdesc = make_buffer(reinterpret_cast<const float*>(p.xch + (size_t)col * team_words_per_column(NP)),
+                                       team_words_per_column(NP) * 4u);
+  const unsigned tag0 = __builtin_amdgcn_raw_buffer_load_b32(xdesc, 0u, 0, 16);
+  bool gave_up = false, same_xcd = false;
+  {
+    const unsigned my_xcc = __builtin_amdgcn_s_getreg((3 << 11) | 20) & 15u;  // XCC_ID
+    const unsigned hs_tag = tag0 + 1u;
+    if (tid == 0) {
+      const u32x2 w = {my_xcc, hs_tag};
+      __builtin_amdgcn_raw_buffer_store_b64(w, xdesc, 32u + (unsigned)part * 8u, 0, 16);
+    }
+    unsigned peer_xcc = my_xcc;
+    const unsigned hs_from = 32u + (unsigned)(lane < NP ? lane : part) * 8u;  // every lane reads some part's word
+    int polls = 0;
+    for (;;) {
+      const u32x2 w = __builtin_amdgcn_raw_buffer_load_b64(xdesc, hs_from, 0, 16);
+      peer_xcc = w.x;
+      if (__all(w.y == hs_tag)) break;
+      if (polls++ >= p.wait_limit) { gave_up = true; break; }
+      asm volatile("" ::: "memory");
+    }
+    same_xcd = !gave_up && __all(peer_xcc == my_xcc);
+  }
+
+  auto load_row = [&](int st, int jj, Chunk<4>& dst) {
+    dst = load_chunk<4>(p.V + ((size_t)st * K + 4 * jj) * (size_t)d + lane_off);
+  };
+  float t[LPT];  // this thread's entries of its row of op(T) of the step being applied
+  auto load_t = [&](int st) {
+    const float* opT = p.transpose ? p.Tt : p.T;
+    const float* Ts = KMODE == 2 ? opT + (size_t)(st >> 1) * LDT * LDT + (size_t)(st & 1) * (K * LDT + K)
+                                 : opT + (size_t)st * LDT * LDT;
+    const float4* src = reinterpret_cast<const float4*>(Ts + trow * LDT + LPT * tg);
+    const float4 t0 = src[0], t1 = src[1];
+    t[0] = t0.x; t[1] = t0.y; t[2] = t0.z; t[3] = t0.w; t[4] = t1.x; t[5] = t1.y; t[6] = t1.z; t[7] = t1.w;
+  };
+  // Sum over the four lanes of a chunk (lane bits 4 and 5), the same bits in all four: (x + x') + (x'' + x''').
+  auto chunk_sum = [&](float x) {
+    x = swap16_sum(x, x);
+    return swap32_sum(x, x);
+  };
+  auto save_input = [&](int block) {
+    if (p.save_in && ok && q == 0) store_chunk<4>(p.save_in + ((size_t)block * m + col) * d + x0, a);
+  };
+
+  unsigned steps_done = 0;
+  // Applies step st held in `cur` while fetching step sf (two steps on) into `dst`.
+  auto apply_step = [&](int st, TeamRegs& cur, int sf, TeamRegs& dst) {
+    load_t(st);
+    // the input of the caller's block that this step starts with
+    if constexpr (KMODE == 0) save_input(2 * st + (p.transpose ? 0 : 1));
+    else if constexpr (KMODE == 1) save_input(st);
+    else if ((st & 1) == (p.transpose ? 0 : 1)) save_input(st >> 1);
+    float pj[KH];
+#pragma unroll
+    for (int jj = 0; jj < KH; ++jj) {
+      if (jj % S1 == 0 && jj / S1 < P1) {
+        load_row(sf, jj / S1, dst.v[jj / S1]);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      float acc = 0.f;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) acc = fmaf(cur.v[jj].e[r], a.e[r], acc);
+      pj[jj] = acc;
+    }
+    auto prefetch = [&](int tt) {
+      if (tt % 4 == 0 && tt / 4 < RL) {
+        __builtin_amdgcn_sched_barrier(0);
+        load_row(sf, P1 + tt / 4, dst.v[P1 + tt / 4]);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    };
+    // sum over the 16 lanes of this row of lanes: 16 values, four lane bits; lane (q, c) ends with row 4 c + q
+    reduce_stage<KH, 16, 8, 0>(pj, lane, prefetch);
+    reduce_stage<KH, 8, 4, 8>(pj, lane, prefetch);
+    reduce_stage<KH, 4, 2, 12>(pj, lane, prefetch);
+    reduce_stage<KH, 2, 1, 14>(pj, lane, prefetch);
+    Bpart[wave][4 * (lane & 15) + q] = pj[0];
+    lds_barrier();
+    {
+      // wave w owns rows 8 w .. 8 w + 7: lane l takes wave (l & 7)'s sum for row 8 w + (l >> 3)
+      const int row = 8 * wave + (lane >> 3), j = lane & 7;
+      float b = group_sum<8>(Bpart[j][row]);
+      const unsigned tag = tag0 + 1u + steps_done, par = steps_done & 1u;
+      ++steps_done;
+      // lane j < NP of each group stands for part j: its own sum, or what part j sends
+      const bool other = j < NP && j != part;
+      if (other) {
+        const u32x2 w = {__builtin_bit_cast(unsigned, b), tag};
+        const unsigned to = (unsigned)kTeamHeadBytes + ((((unsigned)j * 2u + par) * NP + (unsigned)part) * K + (unsigned)row) * 8u;
+        if (same_xcd) __builtin_amdgcn_raw_buffer_store_b64(w, xdesc, to, 0, 0);
+        else __builtin_amdgcn_raw_buffer_store_b64(w, xdesc, to, 0, 16);
+      }
+      unsigned got = 0u;  // zero once a wait has given up
+      if (!gave_up) {
+        // lanes that stand for no other part read the word of one that does (and ignore its value)
+        const unsigned src = other ? (unsigned)j : (part == 0 ? 1u : 0u);
+        const unsigned from = (unsigned)kTeamHeadBytes + ((((unsigned)part * 2u + par) * NP + src) * K + (unsigned)row) * 8u;
+        int polls = 0;
+        for (;;) {
+          const u32x2 w = same_xcd ? __builtin_amdgcn_raw_buffer_load_b64(xdesc, from, 0, 2)
+                                   : __builtin_amdgcn_raw_buffer_load_b64(xdesc, from, 0, 16);
+          got = w.x;
+          if (__all(w.y == tag)) break;
+          if (polls++ >= p.wait_limit) { gave_up = true; break; }
+          asm volatile("" ::: "memory");
+        }
+      }
+      const float mine = other ? __builtin_bit_cast(float, got) : (j == part ? b : 0.f);
+      // the parts' sums in the order of the parts, from lanes 0 .. NP - 1 of the quad
+      float total = dpp_move<0x00>(mine) + dpp_move<0x55>(mine);
+      if constexpr (NP >= 3) total += dpp_move<0xAA>(mine);
+      if constexpr (NP >= 4) total += dpp_move<0xFF>(mine);
+      if (j == 0) Btot[row] = total;
+    }
+    {  // fetches behind the hand-off (before it, its polls would queue up behind them: loads return in order)
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int e = 0; e < XA; ++e) load_row(sf, XA0 + e, dst.v[XA0 + e]);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    lds_barrier();
+    {
+      const float4 b0 = reinterpret_cast<const float4*>(Btot)[2 * tg], b1 = reinterpret_cast<const float4*>(Btot)[2 * tg + 1];
+      float c = t[0] * b0.x;
+      c = fmaf(t[1], b0.y, c); c = fmaf(t[2], b0.z, c); c = fmaf(t[3], b0.w, c);
+      c = fmaf(t[4], b1.x, c); c = fmaf(t[5], b1.y, c); c = fmaf(t[6], b1.z, c); c = fmaf(t[7], b1.w, c);
+      c = group_sum<G>(c);
+      if (tg == 0) {
+        Cv[trow & 3][trow >> 2] = c;
+        if (p.save_c && part == 0) p.save_c[(size_t)col * p.n + (size_t)st * K + trow] = c;
+      }
+    }
+    lds_barrier();
+    float cc[KH];
+#pragma unroll
+    for (int j4 = 0; j4 < 4; ++j4) {
+      const float4 c4 = reinterpret_cast<const float4*>(Cv[q])[j4];
+      cc[4 * j4] = c4.x; cc[4 * j4 + 1] = c4.y; cc[4 * j4 + 2] = c4.z; cc[4 * j4 + 3] = c4.w;
+    }
+    {
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int e = 0; e < XC; ++e) load_row(sf, XC0 + e, dst.v[XC0 + e]);
+    }
+    // Rows 4 jj + q with jj < 8 are the step's rows 0 .. 31, the others its rows 32 .. 63. The half applied first is
+    // the later block of the pair in the plain order, the earlier one in the transposed order.
+    float acc[2][4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) { acc[0][r] = 0.f; acc[1][r] = 0.f; }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int jj = 0; jj < KH; ++jj) {
+      if (jj % S2 == 0 && jj / S2 < PR2) {
+        if (jj > 0) asm volatile("" : "+v"(acc[0][0]), "+v"(acc[0][1]), "+v"(acc[0][2]), "+v"(acc[0][3]));
+        __builtin_amdgcn_sched_barrier(0);
+        load_row(sf, U0 + jj / S2, dst.v[U0 + jj / S2]);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      constexpr int kSplitAt = KMODE == 0 ? 8 : 16;
+      const int hsel = jj < kSplitAt ? 0 : 1;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) acc[hsel][r] = fmaf(cc[jj], cur.v[jj].e[r], acc[hsel][r]);
+    }
+    if constexpr (KMODE == 0) {
+      const int first = p.transpose ? 0 : 1;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const float s0 = chunk_sum(first ? acc[1][r] : acc[0][r]);
+        a.e[r] = ok ? a.e[r] - s0 : 0.f;
+      }
+      save_input(2 * st + (p.transpose ? 1 : 0));  // the input of the pair's other block
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const float s1 = chunk_sum(first ? acc[0][r] : acc[1][r]);
+        a.e[r] = ok ? a.e[r] - s1 : 0.f;
+      }
+    } else {
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const float s0 = chunk_sum(acc[0][r]);
+        a.e[r] = ok ? a.e[r] - s0 : 0.f;
+      }
+    }
+  };
+
+  TeamRegs ra, rb, rc;
+#pragma unroll
+  for (int jj = 0; jj < KH; ++jj) load_row(step_at(0), jj, ra.v[jj]);
+#pragma unroll
+  for (int jj = 0; jj < KH; ++jj) load_row(step_at(1), jj, rb.v[jj]);
+  int s = 0;
+  for (; s + 2 < ns; s += 3) {
+    apply_step(step_of(s), ra, step_at(s + 2), rc);
+    apply_step(step_of(s + 1), rb, step_at(s + 3), ra);
+    apply_step(step_of(s + 2), rc, step_at(s + 4), rb);
+  }
+  if (s < ns) {
+    apply_step(step_of(s), ra, step_at(s + 2), rc);
+    if (s + 1 < ns) apply_step(step_of(s + 1), rb, step_at(s + 3), ra);
+  }
+  // the next launch on this workspace counts on from here (every part read the counter before its first hand-off,
+  // and this part has received the others' last one)
+  if (part == 0 && tid == 0) __builtin_amdgcn_raw_buffer_store_b32(tag0 + steps_done, xdesc, 0u, 0, 16);
+  if (gave_up && lane == 0) __hip_atomic_store(&g_wait_gave_up, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  if (ok) {
+    // each of the four lanes of a chunk stores one of its elements
+    const float o = q == 0 ? a.e[0] : q == 1 ? a.e[1] : q == 2 ? a.e[2] : a.e[3];
+    p.out[(size_t)(x0 + q) * m + col] = o;
+  }
+}
+
+static bool chain_uses_team(const ChainArgs& a) { return a.xch != nullptr && team_parts(a.d, a.n, a.m, a.k) > 0; }
+
+static int launch_chain_team(const ChainArgs& a, hipStream_t stream) {
+  const int np = team_parts(a.d, a.n, a.m, a.k);
+  if (np == 0 || !a.xch) return FASTH_EINVAL;
+  const int kmode = a.k == 32 ? 0 : a.k == 64 ? 1 : 2;
+  static const std::string names[9] = {
+      variant_name("chain_team_kernel", {2, 0}), variant_name("chain_team_kernel", {2, 1}), variant_name("chain_team_kernel", {2, 2}),
+      variant_name("chain_team_kernel", {3, 0}), variant_name("chain_team_kernel", {3, 1}), variant_name("chain_team_kernel", {3, 2}),
+      variant_name("chain_team_kernel", {4, 0}), variant_name("chain_team_kernel", {4, 1}), variant_name("chain_team_kernel", {4, 2})};
+  prof::Scope ps_(FASTH_KERNEL_CHAIN, stream, names[(np - 2) * 3 + kmode].c_str());
+  const dim3 grid(8 * np * ((a.m + 7) / 8)), block(512);
+#define FASTH_LAUNCH_TEAM_(NP_, KM_) hipLaunchKernelGGL((chain_team_kernel<NP_, KM_>), grid, block, 0, stream, a)
+  if (np == 2) { if (kmode == 0) FASTH_LAUNCH_TEAM_(2, 0); else if (kmode == 1) FASTH_LAUNCH_TEAM_(2, 1); else FASTH_LAUNCH_TEAM_(2, 2); }
+  else if (np == 3) { if (kmode == 0) FASTH_LAUNCH_TEAM_(3, 0); else if (kmode == 1) FASTH_LAUNCH_TEAM_(3, 1); else FASTH_LAUNCH_TEAM_(3, 2); }
+  else { if (kmode == 0) FASTH_LAUNCH_TEAM_(4, 0); else if (kmode == 1) FASTH_LAUNCH_TEAM_(4, 1); else FASTH_LAUNCH_TEAM_(4, 2); }
+#undef FASTH_LAUNCH_TEAM_
+  FASTH_HIP(hipGetLastError());
+  return FASTH_OK;
+}
+
+}  // namespace fasth

@@ -41,6 +41,7 @@ static int padded_block(int k) {
 
 struct Layout {
   int kp, nb, gram_split, dv_split;
+  int kf, kpf, nbf;  // rows of a factor as stored (two of the caller's blocks when the team kernel merges them), padded; their number
   size_t off_T, off_Spart, off_xch, off_saveA, off_saveCa, off_saveG, off_saveCg, off_dVpart, total;
   size_t xch_words;  // 32-bit words of the hand-off area between workgroups that share a column (0: none)
 };
@@ -54,6 +55,21 @@ static bool split_pair_serves(int d, int m, int k) {
   return d > 1024 && d <= 2048 && d % 4 == 0 && (k == 32 || k == 64 || k == 128) && m <= kSplitPairMaxCols;
 }
 constexpr int kDefaultWaitLimit = 1 << 20;  // polls of a bounded wait between workgroups (a fraction of a second)
+
+// chain_team_kernel: a team of two to four workgroups per column, 512 elements each, steps of 64 rows. Parts per
+// column for a shape it serves, else 0: 512 < d <= 2048 in whole 16-byte chunks, blocks of 32 (an even number of
+// them: two are merged into a factor of 64 rows), 64 or 128 rows, and a compute unit for every workgroup of the
+// launch, so that no part waits for one that has not started.
+constexpr int kTeamRows = 64;        // rows of V per step
+constexpr int kTeamSlice = 512;      // elements of the column per workgroup
+constexpr int kTeamHeadBytes = 256;  // per column: [0] tag counter, [32 + 8 j] part j's XCC_ID word
+constexpr unsigned team_words_per_column(int np) { return (unsigned)(kTeamHeadBytes + np * 2 * np * kTeamRows * 8) / 4u; }
+static int team_parts(int d, int n, int m, int k) {
+  if (d <= kTeamSlice || d > 4 * kTeamSlice || d % 4 != 0) return 0;
+  if (!(k == 64 || k == 128 || (k == 32 && n % 64 == 0))) return 0;
+  const int np = (d + kTeamSlice - 1) / kTeamSlice;
+  return m * np <= kComputeUnits ? np : 0;
+}
 
 // The dV kernel has one workgroup per (64-column tile of dV, block). When that is too few to fill the chip and the
 // mini-batch is wide (a short, narrow V against many columns: a 1 x 1 convolution with few channels), the
@@ -74,6 +90,10 @@ static Layout make_layout(int d, int n, int m, int k) {
   Layout L;
   L.kp = padded_block(k);
   L.nb = n / k;
+  const int team = team_parts(d, n, m, k);
+  L.kf = team && k == 32 ? 64 : k;
+  L.kpf = padded_block(L.kf);
+  L.nbf = n / L.kf;
   int split = (d + kGramChunk - 1) / kGramChunk;
   L.gram_split = split > kMaxGramSplit ? kMaxGramSplit : split;
   size_t off = 256;  // header, reserved
@@ -82,9 +102,9 @@ static Layout make_layout(int d, int n, int m, int k) {
     off = align_up(off + floats * sizeof(float), 256);
     return o;
   };
-  L.off_T = take(2 * (size_t)L.nb * L.kp * L.kp);  // the factors and, behind them, their transposes
-  L.off_Spart = take((size_t)L.nb * L.gram_split * L.kp * L.kp);
-  L.xch_words = split_pair_serves(d, m, k) ? (size_t)m * kSplitPairWords : 0;
+  L.off_T = take(2 * (size_t)L.nbf * L.kpf * L.kpf);  // the factors and, behind them, their transposes
+  L.off_Spart = take((size_t)L.nbf * L.gram_split * L.kpf * L.kpf);
+  L.xch_words = team ? (size_t)m * team_words_per_column(team) : split_pair_serves(d, m, k) ? (size_t)m * kSplitPairWords : 0;
   L.off_xch = take(L.xch_words);
   L.off_saveA = take((size_t)L.nb * m * d);
   L.off_saveCa = take((size_t)m * n);

@@ -121,13 +121,18 @@ def test_fasth_wide_minibatch(d, n, m, k, transpose):
     assert_close(dV, dV0, "dV", rows=True)
 
 
-# Columns of 1025 .. 2048 elements, at most 128 of them: two workgroups share a column and hand each other every
-# step's partial inner products through the workspace. Cases: both halves full and the second nearly empty, one and
-# several steps per block, one column, a number of columns that is no multiple of 8, the most columns it takes, n != d;
-# and neighbours that stay with one workgroup per column (129 columns, a block size with a short last step).
+# Few columns of 513 .. 2048 elements are shared by workgroups that hand each other every step's partial inner products
+# through the workspace. A team of 2, 3 or 4 workgroups with steps of 64 rows (blocks of 32 merged in pairs, of 64, of
+# 128 as two steps) while every workgroup has a compute unit of its own: all three block sizes for every team size,
+# parts that are full, nearly empty (d = 516, 1028) and ragged, one column, the most columns a team size takes, n != d;
+# two workgroups per column with steps of 32 rows beyond that (d > 1024, up to 128 columns); and neighbours that stay
+# with one workgroup per column (an odd number of blocks of 32, a block size with a short last step, 129 columns).
 SHARED = [
-    (2048, 128, 13, 32), (1280, 64, 5, 32), (1028, 128, 8, 64), (2048, 256, 64, 128), (2044, 96, 128, 32),
-    (1536, 64, 1, 64), (1032, 32, 33, 32), (2048, 64, 129, 32), (2048, 96, 16, 48),
+    (1024, 128, 8, 32), (1024, 128, 5, 64), (1024, 256, 3, 128), (600, 64, 128, 32), (516, 64, 2, 64), (768, 128, 1, 128),
+    (1280, 64, 5, 32), (1536, 64, 1, 64), (1028, 128, 8, 64), (1540, 192, 80, 64), (1300, 128, 85, 128),
+    (2048, 128, 13, 32), (2048, 256, 64, 128), (1544, 128, 33, 64),
+    (2044, 96, 128, 32), (2048, 128, 65, 64), (1032, 256, 100, 128),
+    (1024, 96, 7, 32), (2048, 64, 129, 32), (2048, 96, 16, 48),
 ]
 
 
