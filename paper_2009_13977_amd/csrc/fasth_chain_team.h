@@ -166,7 +166,6 @@ __global__ void __launch_bounds__(512) chain_team_kernel(ChainArgs p) {
       const int row = 8 * wave + (lane >> 3), j = lane & 7;
       float b = group_sum<8>(Bpart[j][row]);
       const unsigned tag = tag0 + 1u + steps_done, par = steps_done & 1u;
-      ++steps_done;
       // lane j < NP of each group stands for part j: its own sum, or what part j sends
       const bool other = j < NP && j != part;
       if (other) {
@@ -247,17 +246,20 @@ __global__ void __launch_bounds__(512) chain_team_kernel(ChainArgs p) {
       for (int r = 0; r < 4; ++r) acc[hsel][r] = fmaf(cc[jj], cur.v[jj].e[r], acc[hsel][r]);
     }
     if constexpr (KMODE == 0) {
+      // The chain goes on from a minus both halves' terms at once; the state between the halves is only something to
+      // save (the input of the pair's other block), formed beside the next step's first product.
       const int first = p.transpose ? 0 : 1;
+      Chunk<4> mid = a;
+      const bool want_mid = p.save_in != nullptr;
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
-        const float s0 = chunk_sum(first ? acc[1][r] : acc[0][r]);
-        a.e[r] = ok ? a.e[r] - s0 : 0.f;
+        const float s01 = chunk_sum(acc[0][r] + acc[1][r]);
+        a.e[r] = ok ? a.e[r] - s01 : 0.f;
       }
-      save_input(2 * st + (p.transpose ? 1 : 0));  // the input of the pair's other block
+      if (want_mid) {
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const float s1 = chunk_sum(first ? acc[0][r] : acc[1][r]);
-        a.e[r] = ok ? a.e[r] - s1 : 0.f;
+        for (int r = 0; r < 4; ++r) mid.e[r] -= chunk_sum(first ? acc[1][r] : acc[0][r]);
+        if (ok && q == 0) store_chunk<4>(p.save_in + ((size_t)(2 * st + (p.transpose ? 1 : 0)) * m + col) * d + x0, mid);
       }
     } else {
 #pragma unroll
@@ -266,6 +268,7 @@ __global__ void __launch_bounds__(512) chain_team_kernel(ChainArgs p) {
         a.e[r] = ok ? a.e[r] - s0 : 0.f;
       }
     }
+    ++steps_done;
   };
 
   TeamRegs ra, rb, rc;

@@ -16,7 +16,9 @@ namespace fasth {
 // counters their tags continue from) starts every product at zero: whichever kernel builds the factors clears it,
 // all its workgroups taking a share.
 __device__ __forceinline__ void clear_exchange_area(unsigned* xch, unsigned words, unsigned wg, unsigned wgs) {
-  for (unsigned w = wg * blockDim.x + threadIdx.x; w < words; w += wgs * blockDim.x) xch[w] = 0u;
+  // the area is 256-byte aligned and a whole number of 16-byte pieces
+  u32x4* x4 = reinterpret_cast<u32x4*>(xch);
+  for (unsigned w = wg * blockDim.x + threadIdx.x; w < words / 4u; w += wgs * blockDim.x) x4[w] = u32x4{0u, 0u, 0u, 0u};
 }
 
 template <int VEC>  // VEC = 4 when d is a multiple of 4 (16-byte loads), else 1
