@@ -104,8 +104,36 @@ static void set_factor_slot(FactorPair& fp, int slot, const Product& P, const fl
   fp.xch[slot] = P.xch(); fp.xch_words[slot] = (unsigned)P.L.xch_words;
 }
 
+// Blocks of 32 rows stored as merged 64-row factors, built by one launch (both products of a layer at once when
+// count = 2).
+static bool factors_are_merged(const Product& P) { return P.L.kf != P.k; }
+
+static std::atomic<unsigned long long> g_launch_id{0x9e3779b97f4a7c15ull};  // never 0; a new value per launch
+
+static int launch_factor_pairs(const FactorPair& fp, int count, const Product& P0, const Product& P1, hipStream_t stream) {
+  const bool vec4 = P0.d % 4 == 0;
+  const int nbf = std::max(P0.L.nbf, count == 2 ? P1.L.nbf : 0);
+  unsigned long long id = g_launch_id.fetch_add(0x9e3779b97f4a7c15ull, std::memory_order_relaxed);
+  if (id == 0) id = 1;
+  // the blocks' "ready" words live where the other factor kernels keep partial Gram matrices
+  unsigned long long* r0 = reinterpret_cast<unsigned long long*>(P0.Spart());
+  unsigned long long* r1 = reinterpret_cast<unsigned long long*>(P1.Spart());
+  prof::Scope ps_(FASTH_KERNEL_FACTOR, stream, vec4 ? "pair_factor_kernel<4>" : "pair_factor_kernel<1>");
+  const dim3 grid(3 * nbf, count), block(512);
+  if (vec4) hipLaunchKernelGGL(pair_factor_kernel<4>, grid, block, 0, stream, fp, r0, r1, id, wait_limit());
+  else hipLaunchKernelGGL(pair_factor_kernel<1>, grid, block, 0, stream, fp, r0, r1, id, wait_limit());
+  FASTH_HIP(hipGetLastError());
+  return FASTH_OK;
+}
+
 static int build_factors(const Product& P, const float* V, hipStream_t stream) {
   const int kp = P.L.kpf;
+  if (factors_are_merged(P)) {
+    FactorPair fp;
+    set_factor_slot(fp, 0, P, V);
+    set_factor_slot(fp, 1, P, V);  // unused
+    return launch_factor_pairs(fp, 1, P, P, stream);
+  }
   if (factor_is_fused(kp, P.d)) {
     FactorPair fp;
     set_factor_slot(fp, 0, P, V);
@@ -142,7 +170,13 @@ static int build_factors(const Product& P, const float* V, hipStream_t stream) {
 // kernel with the same template arguments; otherwise one after the other.
 static int build_factors_pair(const Product& P0, const float* V0, const Product& P1, const float* V1,
                               hipStream_t stream) {
-  if (factor_is_fused(P0.L.kpf, P0.d) && factor_is_fused(P1.L.kpf, P1.d) && P0.L.kpf == P1.L.kpf &&
+  if (factors_are_merged(P0) && factors_are_merged(P1) && (P0.d % 4 == 0) == (P1.d % 4 == 0)) {
+    FactorPair fp;
+    set_factor_slot(fp, 0, P0, V0);
+    set_factor_slot(fp, 1, P1, V1);
+    return launch_factor_pairs(fp, 2, P0, P1, stream);
+  }
+  if (!factors_are_merged(P0) && !factors_are_merged(P1) && factor_is_fused(P0.L.kpf, P0.d) && factor_is_fused(P1.L.kpf, P1.d) && P0.L.kpf == P1.L.kpf &&
       (P0.d % 4 == 0) == (P1.d % 4 == 0)) {
     FactorPair fp;
     set_factor_slot(fp, 0, P0, V0);
