@@ -115,9 +115,8 @@ static int launch_factor_pairs(const FactorPair& fp, int count, const Product& P
   const int nbf = std::max(P0.L.nbf, count == 2 ? P1.L.nbf : 0);
   unsigned long long id = g_launch_id.fetch_add(0x9e3779b97f4a7c15ull, std::memory_order_relaxed);
   if (id == 0) id = 1;
-  // the blocks' "ready" words live where the other factor kernels keep partial Gram matrices
-  unsigned long long* r0 = reinterpret_cast<unsigned long long*>(P0.Spart());
-  unsigned long long* r1 = reinterpret_cast<unsigned long long*>(P1.Spart());
+  unsigned long long* r0 = reinterpret_cast<unsigned long long*>(P0.ws + P0.L.off_ready);
+  unsigned long long* r1 = reinterpret_cast<unsigned long long*>(P1.ws + P1.L.off_ready);
   prof::Scope ps_(FASTH_KERNEL_FACTOR, stream, vec4 ? "pair_factor_kernel<4>" : "pair_factor_kernel<1>");
   const dim3 grid(3 * nbf, count), block(512);
   if (vec4) hipLaunchKernelGGL(pair_factor_kernel<4>, grid, block, 0, stream, fp, r0, r1, id, wait_limit());

@@ -86,24 +86,13 @@ __global__ void __launch_bounds__(512) chain_team_kernel(ChainArgs p) {
                                        team_words_per_column(NP) * 4u);
   const unsigned tag0 = __builtin_amdgcn_raw_buffer_load_b32(xdesc, 0u, 0, 16);
   bool gave_up = false, same_xcd = false;
-  {
-    const unsigned my_xcc = __builtin_amdgcn_s_getreg((3 << 11) | 20) & 15u;  // XCC_ID
-    const unsigned hs_tag = tag0 + 1u;
-    if (tid == 0) {
-      const u32x2 w = {my_xcc, hs_tag};
-      __builtin_amdgcn_raw_buffer_store_b64(w, xdesc, 32u + (unsigned)part * 8u, 0, 16);
-    }
-    unsigned peer_xcc = my_xcc;
-    const unsigned hs_from = 32u + (unsigned)(lane < NP ? lane : part) * 8u;  // every lane reads some part's word
-    int polls = 0;
-    for (;;) {
-      const u32x2 w = __builtin_amdgcn_raw_buffer_load_b64(xdesc, hs_from, 0, 16);
-      peer_xcc = w.x;
-      if (__all(w.y == hs_tag)) break;
-      if (polls++ >= p.wait_limit) { gave_up = true; break; }
-      asm volatile("" ::: "memory");
-    }
-    same_xcd = !gave_up && __all(peer_xcc == my_xcc);
+  // Do the parts run on one XCD, i.e. behind one L2? Each publishes its XCC_ID (agent-scope, tagged like a hand-off)
+  // first thing and reads the others' once its first rows of V are on their way.
+  const unsigned my_xcc = __builtin_amdgcn_s_getreg((3 << 11) | 20) & 15u;
+  const unsigned hs_tag = tag0 + 1u;
+  if (tid == 0) {
+    const u32x2 w = {my_xcc, hs_tag};
+    __builtin_amdgcn_raw_buffer_store_b64(w, xdesc, 32u + (unsigned)part * 8u, 0, 16);
   }
 
   auto load_row = [&](int st, int jj, Chunk<4>& dst) {
@@ -276,6 +265,19 @@ __global__ void __launch_bounds__(512) chain_team_kernel(ChainArgs p) {
   for (int jj = 0; jj < KH; ++jj) load_row(step_at(0), jj, ra.v[jj]);
 #pragma unroll
   for (int jj = 0; jj < KH; ++jj) load_row(step_at(1), jj, rb.v[jj]);
+  {
+    unsigned peer_xcc = my_xcc;
+    const unsigned hs_from = 32u + (unsigned)(lane < NP ? lane : part) * 8u;  // every lane reads some part's word
+    int polls = 0;
+    for (;;) {
+      const u32x2 w = __builtin_amdgcn_raw_buffer_load_b64(xdesc, hs_from, 0, 16);
+      peer_xcc = w.x;
+      if (__all(w.y == hs_tag)) break;
+      if (polls++ >= p.wait_limit) { gave_up = true; break; }
+      asm volatile("" ::: "memory");
+    }
+    same_xcd = !gave_up && __all(peer_xcc == my_xcc);
+  }
   int s = 0;
   for (; s + 2 < ns; s += 3) {
     apply_step(step_of(s), ra, step_at(s + 2), rc);

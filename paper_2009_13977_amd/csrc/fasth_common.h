@@ -42,7 +42,7 @@ static int padded_block(int k) {
 struct Layout {
   int kp, nb, gram_split, dv_split;
   int kf, kpf, nbf;  // rows of a factor as stored (two of the caller's blocks when the team kernel merges them), padded; their number
-  size_t off_T, off_Spart, off_xch, off_saveA, off_saveCa, off_saveG, off_saveCg, off_dVpart, total;
+  size_t off_T, off_Spart, off_ready, off_xch, off_saveA, off_saveCa, off_saveG, off_saveCg, off_dVpart, total;
   size_t xch_words;  // 32-bit words of the hand-off area between workgroups that share a column (0: none)
 };
 
@@ -64,8 +64,11 @@ constexpr int kTeamRows = 64;        // rows of V per step
 constexpr int kTeamSlice = 512;      // elements of the column per workgroup
 constexpr int kTeamHeadBytes = 256;  // per column: [0] tag counter, [32 + 8 j] part j's XCC_ID word
 constexpr unsigned team_words_per_column(int np) { return (unsigned)(kTeamHeadBytes + np * 2 * np * kTeamRows * 8) / 4u; }
+#ifndef FASTH_TEAM_MIN_D
+#define FASTH_TEAM_MIN_D (kTeamSlice + 1)
+#endif
 static int team_parts(int d, int n, int m, int k) {
-  if (d <= kTeamSlice || d > 4 * kTeamSlice || d % 4 != 0) return 0;
+  if (d < FASTH_TEAM_MIN_D || d > 4 * kTeamSlice || d % 4 != 0) return 0;
   if (!(k == 64 || k == 128 || (k == 32 && n % 64 == 0))) return 0;
   const int np = (d + kTeamSlice - 1) / kTeamSlice;
   return m * np <= kComputeUnits ? np : 0;
@@ -103,7 +106,10 @@ static Layout make_layout(int d, int n, int m, int k) {
     return o;
   };
   L.off_T = take(2 * (size_t)L.nbf * L.kpf * L.kpf);  // the factors and, behind them, their transposes
-  L.off_Spart = take((size_t)L.nbf * L.gram_split * L.kpf * L.kpf);
+  // partial Gram matrices; merged factors are built without them and the region only serves the dV kernel's
+  // per-block matrices Z later (nb kp^2 floats, which the partial matrices always cover)
+  L.off_Spart = take(L.kf != k ? (size_t)L.nb * L.kp * L.kp : (size_t)L.nbf * L.gram_split * L.kpf * L.kpf);
+  L.off_ready = take(L.kf != k ? (size_t)L.nb * 2 : 0);  // merged factors: an 8-byte "ready" word per block of 32 rows
   L.xch_words = team ? (size_t)m * team_words_per_column(team) : split_pair_serves(d, m, k) ? (size_t)m * kSplitPairWords : 0;
   L.off_xch = take(L.xch_words);
   L.off_saveA = take((size_t)L.nb * m * d);
