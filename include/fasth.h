@@ -61,19 +61,23 @@ typedef struct fasth_shape {
 /* Human-readable text for a return code (static storage, never NULL). */
 const char* fasth_strerror(int code);
 
-/* Algorithm 1 Step 2 is sequential over the blocks but its two products per block can be shared between compute
- * units. For vectors of 1025 to 2048 elements and at most 128 columns two workgroups share each column and hand
- * each other a block's partial inner products through the workspace, i.e. one workgroup waits for another inside
- * a kernel. Every such wait is bounded: after a number of polls (about a million, a fraction of a second; the wait
- * itself takes a fraction of a microsecond) the waiting wave gives up, raises a status word on the GPU and runs
- * on, so a kernel always ends, but its outputs are then wrong. fasth_wait_status waits for `stream`, reads and
- * clears that word and returns FASTH_OK, or FASTH_ETIMEOUT if any kernel of this library gave up on this GPU
- * since the last check (by any caller: the word is one per GPU, not per workspace). A caller that never checks
- * loses nothing but the report. fasth_set_wait_limit sets the number of polls for launches enqueued from now on
- * (process-wide; negative restores the default; 0 makes every wait give up at its first unsuccessful poll, which
- * is how the error path is tested without a kernel that hangs). Two calls that use the same workspace must not
- * overlap on the GPU (this was already so for calls that save for a backward pass; for these shapes it also
- * holds for fasth_apply without saving). */
+/* Algorithm 1 Step 2 is sequential over the blocks, but the two products of a block can be shared between compute
+ * units. With few columns of more than 512 elements (d <= 4096, a compute unit for every workgroup of the launch:
+ * up to 128 columns at d <= 1024, 64 at d = 2048, 32 at d = 4096) two to eight workgroups share each column and hand each other
+ * every step's partial inner products through the workspace, and the workgroup that merges two blocks' factors
+ * waits for the workgroups that build them: one workgroup waits for another inside a kernel. Every such wait is
+ * bounded: after a number of polls (about a million, a fraction of a second; the wait itself takes a fraction of
+ * a microsecond) the waiting wave gives up, raises a status word on the GPU and runs on, so a kernel always ends,
+ * but its outputs are then wrong. fasth_wait_status waits for `stream`, reads and clears that word and returns
+ * FASTH_OK, or FASTH_ETIMEOUT if any kernel of this library gave up on this GPU since the last check (by any
+ * caller: the word is one per GPU, not per workspace). A caller that never checks loses nothing but the report.
+ * fasth_set_wait_limit sets the number of polls for launches enqueued from now on (process-wide; negative
+ * restores the default; 0 makes every wait give up at its first unsuccessful poll, which is how the error path is
+ * tested without a kernel that hangs). The kernels assume what HIP provides on this hardware: the workgroups of
+ * one launch are started in the order of their indices, and a launch of at most as many workgroups as the GPU
+ * has compute units runs them all at once. Two calls that use the same workspace must not overlap on the GPU
+ * (this was already so for calls that save for a backward pass; for these shapes it also holds for fasth_apply
+ * without saving). */
 int fasth_wait_status(void* stream);
 int fasth_set_wait_limit(int polls);
 
@@ -109,9 +113,10 @@ int fasth_apply(const fasth_shape* shape, const float* V, const float* X, float*
  * with the block factors in a fixed array of FASTH_STATIC_SCRATCH_BYTES that is part of the library's
  * GPU code (one copy per GPU, held until the process ends) instead of a caller's workspace. Nothing is
  * saved for a backward pass. The call allocates and frees nothing; its first use on a device looks up
- * the array's address. Shapes whose factors and partial Gram matrices need more than the array holds
- * (about 4 n kp (2 + min(16, ceil(d / 128))) bytes, kp = k rounded up to a power of two >= 16) return
- * FASTH_EUNSUPPORTED before any GPU call. Every call on one GPU uses the same array: calls that overlap
+ * the array's address. Shapes whose factors, partial Gram matrices and hand-off words need more than the array
+ * holds (about 4 n kp (2 + min(16, ceil(d / 128))) bytes, kp = k rounded up to a power of two >= 16; for the
+ * shapes of fasth_wait_status's comment up to 65 KiB more per column) return FASTH_EUNSUPPORTED before any
+ * GPU call. Every call on one GPU uses the same array: calls that overlap
  * on one GPU (different streams or threads) race; calls on one stream do not. */
 #define FASTH_STATIC_SCRATCH_BYTES (8u << 20)
 int fasth_forward_static(const fasth_shape* shape, const float* V, const float* X, float* A, void* stream);

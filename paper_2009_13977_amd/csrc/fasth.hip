@@ -197,7 +197,7 @@ static int run_chain(const Product& P, const float* V, const float* in, float* o
   const Product& F = factors ? *factors : P;
   ChainArgs a;
   a.V = V; a.T = F.T(); a.in = in; a.out = out;
-  a.xch = F.xch(); a.wait_limit = wait_limit();
+  a.xch = F.xch(); a.wait_limit = wait_limit(); a.parts = 0;
   a.Tt = a.T + (size_t)F.L.nbf * F.L.kpf * F.L.kpf;
   a.save_in = !save ? nullptr : activation ? P.saveA() : P.saveG();
   a.save_c = !save ? nullptr : activation ? P.saveCa() : P.saveCg();

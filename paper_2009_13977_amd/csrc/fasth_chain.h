@@ -54,6 +54,7 @@ struct ChainArgs {
   // the number of polls after which a wait for another workgroup gives up.
   unsigned* xch;
   int wait_limit;
+  int parts;              // chain_team_kernel: workgroups per column (set by its launcher)
 };
 
 // Gradient of the diagonal step of the SVD layer (Section 2.2), one wave per row: with Z2 = s * Z1 row-wise

@@ -1,5 +1,5 @@
-// Algorithm 1 Step 2 and Algorithm 2 Step 1 for few columns of 513 to 2048 elements: chain_team_kernel, in which a
-// team of two to four workgroups shares a column and a step takes 64 rows.
+// Algorithm 1 Step 2 and Algorithm 2 Step 1 for few columns of 513 to 4096 elements: chain_team_kernel, in which a
+// team of two to eight workgroups shares a column and a step takes 64 rows.
 // Included by fasth_chain.h (the library has a single translation unit).
 #pragma once
 #include <hip/hip_runtime.h>
@@ -11,7 +11,7 @@ namespace fasth {
 // ------------------------------------------------------------------------------------------
 // A per-column chain is bound by what ONE compute unit can fetch and multiply per step: 32 rows x 1024 elements fill
 // its registers, and a chain of n / 32 such steps is n / 32 times that. With few columns most units idle. Here a
-// column of d elements is shared by NP = ceil(d / 512) workgroups ("parts") on different compute units; part j keeps
+// column of d elements is shared by NP = ceil(d / 512) workgroups ("parts", 2 to 8) on different compute units; part j keeps
 // elements [512 j, 512 j + 512) of the column for the whole chain and reads only those columns of V, so the same
 // registers hold 64 rows per step and the chain has n / 64 sequential steps. What the parts owe each other is a
 // step's 64 partial inner products, nothing else: every part forms C = op(T) B itself.
@@ -51,10 +51,10 @@ struct TeamRegs {
 };
 
 // KMODE 0: caller's blocks of 32 rows, two per step (factors stored as 64 x 64 blocks); 1: blocks of 64; 2: blocks of
-// 128, two steps per block.
-template <int NP, int KMODE>
+// 128, two steps per block. The number of parts is p.parts.
+template <int KMODE>
 __global__ void __launch_bounds__(512) chain_team_kernel(ChainArgs p) {
-  static_assert(NP >= 2 && NP <= 4, "the parts' sums are added within a quad of lanes");
+  const int NP = p.parts;  // 2 .. 8: the parts' sums are added within a group of eight lanes
   constexpr int K = kTeamRows, KH = 16, NW = 8, LPT = 8, G = 8;
   constexpr int LDT = KMODE == 2 ? 128 : 64;
   // fetches of step s + 2 per lane: P1 during the first product, RL during the reduction, XA behind the hand-off,
@@ -178,11 +178,10 @@ __global__ void __launch_bounds__(512) chain_team_kernel(ChainArgs p) {
           asm volatile("" ::: "memory");
         }
       }
+      // Lane j < NP of a group holds part j's sum in EVERY part (its own, or what part j sent), the other lanes zero, so
+      // the same tree of additions over the group gives every part the same bits.
       const float mine = other ? __builtin_bit_cast(float, got) : (j == part ? b : 0.f);
-      // the parts' sums in the order of the parts, from lanes 0 .. NP - 1 of the quad
-      float total = dpp_move<0x00>(mine) + dpp_move<0x55>(mine);
-      if constexpr (NP >= 3) total += dpp_move<0xAA>(mine);
-      if constexpr (NP >= 4) total += dpp_move<0xFF>(mine);
+      const float total = group_sum<8>(mine);
       if (j == 0) Btot[row] = total;
     }
     {  // fetches behind the hand-off (before it, its polls would queue up behind them: loads return in order)
@@ -301,21 +300,23 @@ __global__ void __launch_bounds__(512) chain_team_kernel(ChainArgs p) {
 
 static bool chain_uses_team(const ChainArgs& a) { return a.xch != nullptr && team_parts(a.d, a.n, a.m, a.k) > 0; }
 
-static int launch_chain_team(const ChainArgs& a, hipStream_t stream) {
-  const int np = team_parts(a.d, a.n, a.m, a.k);
-  if (np == 0 || !a.xch) return FASTH_EINVAL;
+static int launch_chain_team(const ChainArgs& args, hipStream_t stream) {
+  ChainArgs a = args;
+  a.parts = team_parts(a.d, a.n, a.m, a.k);
+  if (a.parts == 0 || !a.xch) return FASTH_EINVAL;
   const int kmode = a.k == 32 ? 0 : a.k == 64 ? 1 : 2;
-  static const std::string names[9] = {
-      variant_name("chain_team_kernel", {2, 0}), variant_name("chain_team_kernel", {2, 1}), variant_name("chain_team_kernel", {2, 2}),
-      variant_name("chain_team_kernel", {3, 0}), variant_name("chain_team_kernel", {3, 1}), variant_name("chain_team_kernel", {3, 2}),
-      variant_name("chain_team_kernel", {4, 0}), variant_name("chain_team_kernel", {4, 1}), variant_name("chain_team_kernel", {4, 2})};
-  prof::Scope ps_(FASTH_KERNEL_CHAIN, stream, names[(np - 2) * 3 + kmode].c_str());
-  const dim3 grid(8 * np * ((a.m + 7) / 8)), block(512);
-#define FASTH_LAUNCH_TEAM_(NP_, KM_) hipLaunchKernelGGL((chain_team_kernel<NP_, KM_>), grid, block, 0, stream, a)
-  if (np == 2) { if (kmode == 0) FASTH_LAUNCH_TEAM_(2, 0); else if (kmode == 1) FASTH_LAUNCH_TEAM_(2, 1); else FASTH_LAUNCH_TEAM_(2, 2); }
-  else if (np == 3) { if (kmode == 0) FASTH_LAUNCH_TEAM_(3, 0); else if (kmode == 1) FASTH_LAUNCH_TEAM_(3, 1); else FASTH_LAUNCH_TEAM_(3, 2); }
-  else { if (kmode == 0) FASTH_LAUNCH_TEAM_(4, 0); else if (kmode == 1) FASTH_LAUNCH_TEAM_(4, 1); else FASTH_LAUNCH_TEAM_(4, 2); }
-#undef FASTH_LAUNCH_TEAM_
+  // "chain_team_kernel<KMODE> (NP parts)" for NP = 2 .. 8
+  static const std::vector<std::string> names = [] {
+    std::vector<std::string> v;
+    for (int np = 2; np <= 8; ++np)
+      for (int km = 0; km < 3; ++km) v.push_back(variant_name("chain_team_kernel", {km}) + " (" + std::to_string(np) + " parts)");
+    return v;
+  }();
+  prof::Scope ps_(FASTH_KERNEL_CHAIN, stream, names[(a.parts - 2) * 3 + kmode].c_str());
+  const dim3 grid(8 * a.parts * ((a.m + 7) / 8)), block(512);
+  if (kmode == 0) hipLaunchKernelGGL(chain_team_kernel<0>, grid, block, 0, stream, a);
+  else if (kmode == 1) hipLaunchKernelGGL(chain_team_kernel<1>, grid, block, 0, stream, a);
+  else hipLaunchKernelGGL(chain_team_kernel<2>, grid, block, 0, stream, a);
   FASTH_HIP(hipGetLastError());
   return FASTH_OK;
 }

@@ -56,8 +56,8 @@ static bool split_pair_serves(int d, int m, int k) {
 }
 constexpr int kDefaultWaitLimit = 1 << 20;  // polls of a bounded wait between workgroups (a fraction of a second)
 
-// chain_team_kernel: a team of two to four workgroups per column, 512 elements each, steps of 64 rows. Parts per
-// column for a shape it serves, else 0: 512 < d <= 2048 in whole 16-byte chunks, blocks of 32 (an even number of
+// chain_team_kernel: a team of two to eight workgroups per column, 512 elements each, steps of 64 rows. Parts per
+// column for a shape it serves, else 0: 512 < d <= 4096 in whole 16-byte chunks, blocks of 32 (an even number of
 // them: two are merged into a factor of 64 rows), 64 or 128 rows, and a compute unit for every workgroup of the
 // launch, so that no part waits for one that has not started.
 constexpr int kTeamRows = 64;        // rows of V per step
@@ -68,7 +68,7 @@ constexpr unsigned team_words_per_column(int np) { return (unsigned)(kTeamHeadBy
 #define FASTH_TEAM_MIN_D (kTeamSlice + 1)
 #endif
 static int team_parts(int d, int n, int m, int k) {
-  if (d < FASTH_TEAM_MIN_D || d > 4 * kTeamSlice || d % 4 != 0) return 0;
+  if (d < FASTH_TEAM_MIN_D || d > 8 * kTeamSlice || d % 4 != 0) return 0;
   if (!(k == 64 || k == 128 || (k == 32 && n % 64 == 0))) return 0;
   const int np = (d + kTeamSlice - 1) / kTeamSlice;
   return m * np <= kComputeUnits ? np : 0;

@@ -121,16 +121,17 @@ def test_fasth_wide_minibatch(d, n, m, k, transpose):
     assert_close(dV, dV0, "dV", rows=True)
 
 
-# Few columns of 513 .. 2048 elements are shared by workgroups that hand each other every step's partial inner products
-# through the workspace. A team of 2, 3 or 4 workgroups with steps of 64 rows (blocks of 32 merged in pairs, of 64, of
-# 128 as two steps) while every workgroup has a compute unit of its own: all three block sizes for every team size,
-# parts that are full, nearly empty (d = 516, 1028) and ragged, one column, the most columns a team size takes, n != d;
+# Few columns of 513 .. 4096 elements are shared by workgroups that hand each other every step's partial inner products
+# through the workspace. A team of 2 to 8 workgroups with steps of 64 rows (blocks of 32 merged in pairs, of 64, of
+# 128 as two steps) while every workgroup has a compute unit of its own: the three block sizes over the team sizes,
+# parts that are full, nearly empty (d = 516, 1028, 2052) and ragged, one column, the most columns a team size takes, n != d;
 # two workgroups per column with steps of 32 rows beyond that (d > 1024, up to 128 columns); and neighbours that stay
 # with one workgroup per column (an odd number of blocks of 32, a block size with a short last step, 129 columns).
 SHARED = [
     (1024, 128, 8, 32), (1024, 128, 5, 64), (1024, 256, 3, 128), (600, 64, 128, 32), (516, 64, 2, 64), (768, 128, 1, 128),
     (1280, 64, 5, 32), (1536, 64, 1, 64), (1028, 128, 8, 64), (1540, 192, 80, 64), (1300, 128, 85, 128),
     (2048, 128, 13, 32), (2048, 256, 64, 128), (1544, 128, 33, 64),
+    (2560, 128, 5, 32), (3072, 128, 42, 64), (4096, 256, 32, 128), (3600, 64, 3, 32), (2052, 128, 7, 64), (4096, 64, 33, 32),
     (2044, 96, 128, 32), (2048, 128, 65, 64), (1032, 256, 100, 128),
     (1024, 96, 7, 32), (2048, 64, 129, 32), (2048, 96, 16, 48),
 ]
