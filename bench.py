@@ -55,7 +55,7 @@ def kernel_flops(slot, d, n, m, k):
         return 4.0 * d * n * m                       # B = V_i a and a -= V_i^T C over all blocks
     if slot == "dv_kernel":
         return 4.0 * d * n * m + 2.0 * d * n * k     # the three products per block
-    if slot in ("factor_fused_kernel", "gram_partial_kernel"):
+    if slot in ("factor_fused_kernel", "team_factor_kernel"):
         return 2.0 * d * n * k                       # Gram products (upper tiles: about half is issued)
     return None
 
@@ -369,7 +369,7 @@ def main() -> int:
     launched = kernels[dom]["launched"] or dom
     dom_ms = kernels[dom]["ms_avg"]
     dom_tflops = head["dominant_kernel_tflops"]
-    on_matrix_cores = launched.startswith(("chain_tile_kernel", "dv_kernel", "factor_fused_kernel", "gram_partial_kernel"))
+    on_matrix_cores = launched.startswith(("chain_tile_kernel", "chain_quad_kernel", "dv_kernel", "factor_fused_kernel", "team_factor_kernel"))
     traffic, traffic_source = traffic_from_profiles(name, launched)
     alg_bytes = chain_algorithmic_bytes(d, n, m, k) if dom == "chain_kernel" else None
     roofline = {

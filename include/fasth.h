@@ -227,11 +227,12 @@ int svd_layer_log_abs_det(int d, const float* sigma, float* log_abs_det, float* 
  * waits for them, adds the elapsed milliseconds and the launch count per kernel into the two HOST
  * arrays of FASTH_KERNEL_COUNT entries, and forgets the records. The extra events perturb
  * end-to-end timing, so keep profiling off in regions that report throughput. The profiling state is
- * process-global and not thread-safe: it is the one exception to "no state between calls" (the only other
- * thing the library remembers is which kernels it has already allowed more than 64 KiB of LDS, under a lock). */
+ * process-global and not thread-safe. (What else the library remembers between calls: which kernels it has
+ * already allowed more than 64 KiB of LDS, under a lock; the wait limit and status word of fasth_wait_status;
+ * a counter from which every factor launch with a split Gram product draws its number.) */
 enum {
-  FASTH_KERNEL_GRAM = 0,
-  FASTH_KERNEL_TBUILD = 1,
+  FASTH_KERNEL_TEAM_FACTOR = 0,
+  FASTH_KERNEL_RESERVED = 1, /* no kernel: its entries stay zero */
   FASTH_KERNEL_CHAIN = 2,
   FASTH_KERNEL_DV = 3,
   FASTH_KERNEL_SEQ_FORWARD = 4,

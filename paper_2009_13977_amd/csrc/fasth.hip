@@ -10,16 +10,17 @@
 // inverse, and P_i^T = I - V_i^T T_i^T V_i needs no second factor.
 //
 // Kernels
-//   gram_partial_kernel  Algorithm 1 Step 1a: partial Gram matrices of every block (MFMA)
-//   t_build_kernel       Algorithm 1 Step 1b: T_i by blocked triangular inversion (MFMA)
-//   factor_fused_kernel  Algorithm 1 Step 1 in one kernel for block sizes up to 32
-//   chain_kernel         Algorithm 1 Step 2 / Algorithm 2 Step 1: the sequential block chain,
-//                        one workgroup per column of X (columns are independent)
+//   factor_fused_kernel  Algorithm 1 Step 1, one workgroup per block (block sizes up to 32; 64 for short vectors)
+//   team_factor_kernel   Algorithm 1 Step 1 with a block's Gram product split over workgroups (MFMA)
+//   chain_*_kernel       Algorithm 1 Step 2 / Algorithm 2 Step 1: the sequential block chain: per column of X
+//                        (pair, pipe, general), a team of workgroups per column (team), or 4 / 16 columns per
+//                        workgroup on the matrix cores (quad, tile)
 //   dv_kernel            Algorithm 2 Step 2 as dense products per block (MFMA)
 //   seq_*                the one-reflection-at-a-time comparison
 //   dsigma_kernel        the diagonal step of the SVD layer
-// The kernels live in fasth_factor.h, fasth_chain.h (+ fasth_chain_tile.h), fasth_dv.h and fasth_sequential.h (helpers in
-// fasth_common.h and fasth_device.h); this file holds the host drivers and the C entry points.
+// The kernels live in fasth_factor.h, fasth_chain.h (+ fasth_chain_team.h, fasth_chain_pair.h, fasth_chain_quad.h,
+// fasth_chain_tile.h), fasth_dv.h and fasth_sequential.h (helpers in fasth_common.h and fasth_device.h); this file holds
+// the host drivers and the C entry points.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -72,14 +73,6 @@ static Product bind(int d, int n, int m, int k, void* ws) {
   return P;
 }
 
-// Blocks of up to 32 rows are factored by one kernel; blocks of 64 rows only while d is short, because one
-// workgroup per block then streams 64 d floats alone (measured: d = 256 18.0 -> 13.6 us, d = 1024 19.5 -> 21.5 us,
-// d = 2048 23 -> 34 us against the two kernels that split the Gram product over d).
-#ifndef FASTH_FUSED64_MAX_D
-#define FASTH_FUSED64_MAX_D 512
-#endif
-static bool factor_is_fused(int kp, int d) { return kp <= 32 || (kp == 64 && d <= FASTH_FUSED64_MAX_D); }
-
 static int launch_factor_fused(const FactorPair& fp, int count, int kp, bool vec4, hipStream_t stream) {
   static const std::string names[6] = {variant_name("factor_fused_kernel", {1, 4}), variant_name("factor_fused_kernel", {2, 4}),
                                        variant_name("factor_fused_kernel", {4, 4}), variant_name("factor_fused_kernel", {1, 1}),
@@ -104,64 +97,34 @@ static void set_factor_slot(FactorPair& fp, int slot, const Product& P, const fl
   fp.xch[slot] = P.xch(); fp.xch_words[slot] = (unsigned)P.L.xch_words;
 }
 
-// Blocks of 32 rows stored as merged 64-row factors, built by one launch (both products of a layer at once when
-// count = 2).
-static bool factors_are_merged(const Product& P) { return P.L.kf != P.k; }
-
-static std::atomic<unsigned long long> g_launch_id{0x9e3779b97f4a7c15ull};  // never 0; a new value per launch
-
-static int launch_factor_pairs(const FactorPair& fp, int count, const Product& P0, const Product& P1, hipStream_t stream) {
-  const bool vec4 = P0.d % 4 == 0;
-  const int nbf = std::max(P0.L.nbf, count == 2 ? P1.L.nbf : 0);
-  unsigned long long id = g_launch_id.fetch_add(0x9e3779b97f4a7c15ull, std::memory_order_relaxed);
-  if (id == 0) id = 1;
-  unsigned long long* r0 = reinterpret_cast<unsigned long long*>(P0.ws + P0.L.off_ready);
-  unsigned long long* r1 = reinterpret_cast<unsigned long long*>(P1.ws + P1.L.off_ready);
-  prof::Scope ps_(FASTH_KERNEL_FACTOR, stream, vec4 ? "pair_factor_kernel<4>" : "pair_factor_kernel<1>");
-  const dim3 grid(3 * nbf, count), block(512);
-  if (vec4) hipLaunchKernelGGL(pair_factor_kernel<4>, grid, block, 0, stream, fp, r0, r1, id, wait_limit());
-  else hipLaunchKernelGGL(pair_factor_kernel<1>, grid, block, 0, stream, fp, r0, r1, id, wait_limit());
-  FASTH_HIP(hipGetLastError());
-  return FASTH_OK;
-}
+static std::atomic<unsigned long long> g_launch_id{0x9e3779b97f4a7c15ull};  // a new value per launch, never 0
 
 static int build_factors(const Product& P, const float* V, hipStream_t stream) {
   const int kp = P.L.kpf;
-  if (factors_are_merged(P)) {
-    FactorPair fp;
-    set_factor_slot(fp, 0, P, V);
-    set_factor_slot(fp, 1, P, V);  // unused
-    return launch_factor_pairs(fp, 1, P, P, stream);
-  }
   if (factor_is_fused(kp, P.d)) {
     FactorPair fp;
     set_factor_slot(fp, 0, P, V);
     set_factor_slot(fp, 1, P, V);  // unused
     return launch_factor_fused(fp, 1, kp, P.d % 4 == 0, stream);
   }
-  {
-    const size_t lds = sizeof(float) * (size_t)kp * (kGramChunk + 4);
-    int rc = allow_lds(gram_partial_kernel<4>, lds);
-    if (rc == FASTH_OK) rc = allow_lds(gram_partial_kernel<1>, lds);
-    if (rc != FASTH_OK) return rc;
-    prof::Scope ps_(FASTH_KERNEL_GRAM, stream, P.d % 4 == 0 ? "gram_partial_kernel<4>" : "gram_partial_kernel<1>");
-    const dim3 grid(P.L.gram_split, P.L.nbf);
-    if (P.d % 4 == 0)
-      hipLaunchKernelGGL(gram_partial_kernel<4>, grid, dim3(256), lds, stream, V, P.Spart(), P.d, P.L.kf, kp, P.L.gram_split,
-                         P.xch(), (unsigned)P.L.xch_words);
-    else
-      hipLaunchKernelGGL(gram_partial_kernel<1>, grid, dim3(256), lds, stream, V, P.Spart(), P.d, P.L.kf, kp, P.L.gram_split,
-                         P.xch(), (unsigned)P.L.xch_words);
-    FASTH_HIP(hipGetLastError());
-  }
-  {
-    const size_t lds = t_build_lds(kp);
-    int rc = allow_lds(t_build_kernel, lds);
-    if (rc != FASTH_OK) return rc;
-    prof::Scope ps_(FASTH_KERNEL_TBUILD, stream, "t_build_kernel");
-    hipLaunchKernelGGL(t_build_kernel, dim3(P.L.nbf), dim3(kp >= 128 ? 1024 : kp >= 64 ? 512 : 256), lds, stream, P.Spart(), P.T(), P.L.kf, kp, P.L.gram_split);
-    FASTH_HIP(hipGetLastError());
-  }
+  // blocks of 64 or 128 rows (the caller's, or pairs of blocks of 32 merged for the team chain kernel): the Gram
+  // product split over d, the block's first workgroup inverts
+  TeamFactorArgs a;
+  a.V = V; a.Spart = P.Spart(); a.T = P.T();
+  a.ready = reinterpret_cast<unsigned long long*>(P.ws + P.L.off_ready);
+  a.launch_id = g_launch_id.fetch_add(0x9e3779b97f4a7c15ull, std::memory_order_relaxed);
+  if (a.launch_id == 0) a.launch_id = 1;
+  a.d = P.d; a.k = P.L.kf; a.kp = kp; a.split = P.L.gram_split; a.wait_limit = wait_limit();
+  a.xch = P.xch(); a.xch_words = (unsigned)P.L.xch_words;
+  const size_t lds = std::max(sizeof(float) * (size_t)kp * (kGramChunk + 4), t_build_lds(kp));
+  int rc = allow_lds(team_factor_kernel<4>, lds);
+  if (rc == FASTH_OK) rc = allow_lds(team_factor_kernel<1>, lds);
+  if (rc != FASTH_OK) return rc;
+  prof::Scope ps_(FASTH_KERNEL_TEAM_FACTOR, stream, P.d % 4 == 0 ? "team_factor_kernel<4>" : "team_factor_kernel<1>");
+  const dim3 grid(P.L.gram_split, P.L.nbf), block(8 * kp);
+  if (P.d % 4 == 0) hipLaunchKernelGGL(team_factor_kernel<4>, grid, block, lds, stream, a);
+  else hipLaunchKernelGGL(team_factor_kernel<1>, grid, block, lds, stream, a);
+  FASTH_HIP(hipGetLastError());
   return FASTH_OK;
 }
 
@@ -169,13 +132,7 @@ static int build_factors(const Product& P, const float* V, hipStream_t stream) {
 // kernel with the same template arguments; otherwise one after the other.
 static int build_factors_pair(const Product& P0, const float* V0, const Product& P1, const float* V1,
                               hipStream_t stream) {
-  if (factors_are_merged(P0) && factors_are_merged(P1) && (P0.d % 4 == 0) == (P1.d % 4 == 0)) {
-    FactorPair fp;
-    set_factor_slot(fp, 0, P0, V0);
-    set_factor_slot(fp, 1, P1, V1);
-    return launch_factor_pairs(fp, 2, P0, P1, stream);
-  }
-  if (!factors_are_merged(P0) && !factors_are_merged(P1) && factor_is_fused(P0.L.kpf, P0.d) && factor_is_fused(P1.L.kpf, P1.d) && P0.L.kpf == P1.L.kpf &&
+  if (factor_is_fused(P0.L.kpf, P0.d) && factor_is_fused(P1.L.kpf, P1.d) && P0.L.kpf == P1.L.kpf &&
       (P0.d % 4 == 0) == (P1.d % 4 == 0)) {
     FactorPair fp;
     set_factor_slot(fp, 0, P0, V0);
@@ -485,8 +442,8 @@ int fasth_wait_status(void* stream) {
 
 const char* fasth_kernel_name(int id) {
   switch (id) {
-    case FASTH_KERNEL_GRAM: return "gram_partial_kernel";
-    case FASTH_KERNEL_TBUILD: return "t_build_kernel";
+    case FASTH_KERNEL_TEAM_FACTOR: return "team_factor_kernel";
+    case FASTH_KERNEL_RESERVED: return "";
     case FASTH_KERNEL_CHAIN: return "chain_kernel";
     case FASTH_KERNEL_DV: return "dv_kernel";
     case FASTH_KERNEL_SEQ_FORWARD: return "seq_forward_kernel";

@@ -107,10 +107,19 @@ __global__ void __launch_bounds__(512) chain_team_kernel(ChainArgs p) {
     const float4 t0 = src[0], t1 = src[1];
     t[0] = t0.x; t[1] = t0.y; t[2] = t0.z; t[3] = t0.w; t[4] = t1.x; t[5] = t1.y; t[6] = t1.z; t[7] = t1.w;
   };
-  // Sum over the four lanes of a chunk (lane bits 4 and 5), the same bits in all four: (x + x') + (x'' + x''').
-  auto chunk_sum = [&](float x) {
-    x = swap16_sum(x, x);
-    return swap32_sum(x, x);
+  // Sums of four values over the four lanes of a chunk (lane bits 4 and 5), the same bits in all four lanes. First each
+  // lane ends up with the complete sum of ONE of the values (halving twice: three lane-half swaps and three
+  // additions instead of eight and eight), then the four sums are passed round (three more swaps).
+  auto chunk_sums = [&](float (&x)[4]) {
+    const float s01 = swap32_sum(x[0], x[1]);  // lanes 0..31: x0 over bit 5, lanes 32..63: x1
+    const float s23 = swap32_sum(x[2], x[3]);
+    const float one = swap16_sum(s01, s23);    // rows of lanes 0 / 1 / 2 / 3 hold the sums of x0 / x2 / x1 / x3
+    const u32x2 r = __builtin_amdgcn_permlane16_swap(__float_as_uint(one), __float_as_uint(one), false, false);
+    // r[0]: what the even row of this pair of rows holds, r[1]: what the odd row holds
+    const u32x2 u = __builtin_amdgcn_permlane32_swap(r[0], r[0], false, false);  // lower half's, upper half's
+    const u32x2 w = __builtin_amdgcn_permlane32_swap(r[1], r[1], false, false);
+    x[0] = __uint_as_float(u[0]); x[1] = __uint_as_float(u[1]);
+    x[2] = __uint_as_float(w[0]); x[3] = __uint_as_float(w[1]);
   };
   auto save_input = [&](int block) {
     if (p.save_in && ok && q == 0) store_chunk<4>(p.save_in + ((size_t)block * m + col) * d + x0, a);
@@ -239,22 +248,25 @@ __global__ void __launch_bounds__(512) chain_team_kernel(ChainArgs p) {
       const int first = p.transpose ? 0 : 1;
       Chunk<4> mid = a;
       const bool want_mid = p.save_in != nullptr;
+      float both[4], head[4];
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
-        const float s01 = chunk_sum(acc[0][r] + acc[1][r]);
-        a.e[r] = ok ? a.e[r] - s01 : 0.f;
+        both[r] = acc[0][r] + acc[1][r];
+        head[r] = first ? acc[1][r] : acc[0][r];
       }
-      if (want_mid) {
+      chunk_sums(both);
 #pragma unroll
-        for (int r = 0; r < 4; ++r) mid.e[r] -= chunk_sum(first ? acc[1][r] : acc[0][r]);
+      for (int r = 0; r < 4; ++r) a.e[r] = ok ? a.e[r] - both[r] : 0.f;
+      if (want_mid) {
+        chunk_sums(head);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) mid.e[r] -= head[r];
         if (ok && q == 0) store_chunk<4>(p.save_in + ((size_t)(2 * st + (p.transpose ? 1 : 0)) * m + col) * d + x0, mid);
       }
     } else {
+      chunk_sums(acc[0]);
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const float s0 = chunk_sum(acc[0][r]);
-        a.e[r] = ok ? a.e[r] - s0 : 0.f;
-      }
+      for (int r = 0; r < 4; ++r) a.e[r] = ok ? a.e[r] - acc[0][r] : 0.f;
     }
     ++steps_done;
   };

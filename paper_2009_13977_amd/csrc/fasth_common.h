@@ -89,6 +89,14 @@ static int dv_minibatch_split(int d, int n, int m, int k) {
   return split < 1 ? 1 : split;
 }
 
+// Blocks of up to 32 rows are factored by one workgroup each; blocks of 64 rows only while d is short, because one
+// workgroup per block then streams 64 d floats alone (measured: d = 256 18.0 -> 13.6 us, d = 1024 19.5 -> 21.5 us,
+// d = 2048 23 -> 34 us against a Gram product split over d).
+#ifndef FASTH_FUSED64_MAX_D
+#define FASTH_FUSED64_MAX_D 512
+#endif
+static bool factor_is_fused(int kp, int d) { return kp <= 32 || (kp == 64 && d <= FASTH_FUSED64_MAX_D); }
+
 static Layout make_layout(int d, int n, int m, int k) {
   Layout L;
   L.kp = padded_block(k);
@@ -106,10 +114,10 @@ static Layout make_layout(int d, int n, int m, int k) {
     return o;
   };
   L.off_T = take(2 * (size_t)L.nbf * L.kpf * L.kpf);  // the factors and, behind them, their transposes
-  // partial Gram matrices; merged factors are built without them and the region only serves the dV kernel's
-  // per-block matrices Z later (nb kp^2 floats, which the partial matrices always cover)
-  L.off_Spart = take(L.kf != k ? (size_t)L.nb * L.kp * L.kp : (size_t)L.nbf * L.gram_split * L.kpf * L.kpf);
-  L.off_ready = take(L.kf != k ? (size_t)L.nb * 2 : 0);  // merged factors: an 8-byte "ready" word per block of 32 rows
+  // partial Gram matrices (later the dV kernel's per-block matrices Z, nb kp^2 floats, which they always cover) and,
+  // where the Gram product is split over workgroups, an 8-byte "ready" word per partial matrix
+  L.off_Spart = take((size_t)L.nbf * L.gram_split * L.kpf * L.kpf);
+  L.off_ready = take(factor_is_fused(L.kpf, d) ? 0 : (size_t)L.nbf * L.gram_split * 2);
   L.xch_words = team ? (size_t)m * team_words_per_column(team) : split_pair_serves(d, m, k) ? (size_t)m * kSplitPairWords : 0;
   L.off_xch = take(L.xch_words);
   L.off_saveA = take((size_t)L.nb * m * d);
