@@ -183,6 +183,47 @@ def test_shared_columns_wait_gives_up_and_recovers():
     assert_close(dV.cpu().numpy(), dV0, "dV", rows=True)
 
 
+@pytest.mark.parametrize("d,n,m,k", [(1024, 128, 8, 32), (2048, 128, 5, 64), (1536, 256, 3, 128), (2048, 64, 100, 32)])
+def test_shared_columns_captured_and_replayed(d, n, m, k):
+    """Forward + backward captured into a HIP graph and replayed with new V, X and G each time, with eager work on the
+    same workspace in between: the tags of the hand-offs count on in the workspace, the ready words of the factor
+    kernel are cleared by their reader, and no replay may see anything of the one before."""
+    import torch
+    from paper_2009_13977_amd import binding as B
+    from helpers import to_gpu
+    _say(f"shared columns under graph capture d={d} n={n} m={m} k={k}")
+    probs = [synthetic.householder_problem(d, n, m, seed=6600 + r) for r in range(4)]
+    Vd, Xd, Gd = (to_gpu(probs[0][a]) for a in ("V", "X", "G"))
+    A = torch.empty_like(Xd); dX = torch.empty_like(Xd); dV = torch.empty_like(Vd)
+    ws = B.new_workspace(B.fasth_workspace_bytes(d, n, m, k))
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):  # once eagerly: everything the library sets up on first use is done before capture
+        B.fasth_forward(Vd, Xd, A, ws, k)
+        B.fasth_backward(Vd, Gd, dV, dX, ws, k)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        B.fasth_forward(Vd, Xd, A, ws, k)
+        B.fasth_backward(Vd, Gd, dV, dX, ws, k)
+    for r in (1, 2, 3, 1):
+        p = probs[r]
+        Vd.copy_(to_gpu(p["V"])); Xd.copy_(to_gpu(p["X"])); Gd.copy_(to_gpu(p["G"]))
+        graph.replay()
+        torch.cuda.synchronize()
+        assert B.fasth_wait_status() == B.FASTH_OK
+        A0, dV0, dX0 = orc.product_gradients(p["V"], p["X"], p["G"])
+        assert_close(A.cpu().numpy(), A0, f"A, replay with inputs {r}")
+        assert_close(dX.cpu().numpy(), dX0, f"dX, replay with inputs {r}")
+        assert_close(dV.cpu().numpy(), dV0, f"dV, replay with inputs {r}", rows=True)
+        # eager work on the same workspace between replays (other inputs, transposed order)
+        q = probs[0]
+        A2, dV2, dX2 = gpu_fasth(q["V"], q["X"], q["G"], k, True)
+        B.fasth_forward(to_gpu(q["V"]), to_gpu(q["X"]), torch.empty_like(Xd), ws, k, True)
+        torch.cuda.synchronize()
+
+
 def test_shared_columns_in_the_layers():
     """The SVD layer, a symmetric form (one set of factors serving two products) and the rectangular layer at sizes
     whose chains run two workgroups per column; prepared factors applied repeatedly."""
