@@ -99,6 +99,33 @@ static void set_factor_slot(FactorPair& fp, int slot, const Product& P, const fl
 
 static std::atomic<unsigned long long> g_launch_id{0x9e3779b97f4a7c15ull};  // a new value per launch, never 0
 
+static TeamFactorArgs team_factor_args(const Product& P, const float* V) {
+  TeamFactorArgs a;
+  a.V = V; a.Spart = P.Spart(); a.T = P.T();
+  a.ready = reinterpret_cast<unsigned long long*>(P.ws + P.L.off_ready);
+  a.launch_id = g_launch_id.fetch_add(0x9e3779b97f4a7c15ull, std::memory_order_relaxed);
+  if (a.launch_id == 0) a.launch_id = 1;
+  a.d = P.d; a.k = P.L.kf; a.kp = P.L.kpf; a.split = P.L.gram_split; a.wait_limit = wait_limit();
+  a.xch = P.xch(); a.xch_words = (unsigned)P.L.xch_words;
+  return a;
+}
+
+// Blocks of 64 or 128 rows (the caller's, or pairs of blocks of 32 merged for the team chain kernel): the Gram
+// product split over d, the block's first workgroup inverts. `count` products of the same shape in one launch.
+static int launch_team_factor(const TeamFactorPair& pair, int count, int nbf, hipStream_t stream) {
+  const TeamFactorArgs& a = pair.a[0];
+  const size_t lds = std::max(sizeof(float) * (size_t)a.kp * (kGramChunk + 4), t_build_lds(a.kp));
+  int rc = allow_lds(team_factor_kernel<4>, lds);
+  if (rc == FASTH_OK) rc = allow_lds(team_factor_kernel<1>, lds);
+  if (rc != FASTH_OK) return rc;
+  prof::Scope ps_(FASTH_KERNEL_TEAM_FACTOR, stream, a.d % 4 == 0 ? "team_factor_kernel<4>" : "team_factor_kernel<1>");
+  const dim3 grid(a.split, nbf, count), block(8 * a.kp);
+  if (a.d % 4 == 0) hipLaunchKernelGGL(team_factor_kernel<4>, grid, block, lds, stream, pair);
+  else hipLaunchKernelGGL(team_factor_kernel<1>, grid, block, lds, stream, pair);
+  FASTH_HIP(hipGetLastError());
+  return FASTH_OK;
+}
+
 static int build_factors(const Product& P, const float* V, hipStream_t stream) {
   const int kp = P.L.kpf;
   if (factor_is_fused(kp, P.d)) {
@@ -107,25 +134,10 @@ static int build_factors(const Product& P, const float* V, hipStream_t stream) {
     set_factor_slot(fp, 1, P, V);  // unused
     return launch_factor_fused(fp, 1, kp, P.d % 4 == 0, stream);
   }
-  // blocks of 64 or 128 rows (the caller's, or pairs of blocks of 32 merged for the team chain kernel): the Gram
-  // product split over d, the block's first workgroup inverts
-  TeamFactorArgs a;
-  a.V = V; a.Spart = P.Spart(); a.T = P.T();
-  a.ready = reinterpret_cast<unsigned long long*>(P.ws + P.L.off_ready);
-  a.launch_id = g_launch_id.fetch_add(0x9e3779b97f4a7c15ull, std::memory_order_relaxed);
-  if (a.launch_id == 0) a.launch_id = 1;
-  a.d = P.d; a.k = P.L.kf; a.kp = kp; a.split = P.L.gram_split; a.wait_limit = wait_limit();
-  a.xch = P.xch(); a.xch_words = (unsigned)P.L.xch_words;
-  const size_t lds = std::max(sizeof(float) * (size_t)kp * (kGramChunk + 4), t_build_lds(kp));
-  int rc = allow_lds(team_factor_kernel<4>, lds);
-  if (rc == FASTH_OK) rc = allow_lds(team_factor_kernel<1>, lds);
-  if (rc != FASTH_OK) return rc;
-  prof::Scope ps_(FASTH_KERNEL_TEAM_FACTOR, stream, P.d % 4 == 0 ? "team_factor_kernel<4>" : "team_factor_kernel<1>");
-  const dim3 grid(P.L.gram_split, P.L.nbf), block(8 * kp);
-  if (P.d % 4 == 0) hipLaunchKernelGGL(team_factor_kernel<4>, grid, block, lds, stream, a);
-  else hipLaunchKernelGGL(team_factor_kernel<1>, grid, block, lds, stream, a);
-  FASTH_HIP(hipGetLastError());
-  return FASTH_OK;
+  TeamFactorPair pair;
+  pair.a[0] = team_factor_args(P, V);
+  pair.a[1] = pair.a[0];  // unused
+  return launch_team_factor(pair, 1, P.L.nbf, stream);
 }
 
 // Factors of two products (independent of each other) in one launch when both take the fused
@@ -138,6 +150,13 @@ static int build_factors_pair(const Product& P0, const float* V0, const Product&
     set_factor_slot(fp, 0, P0, V0);
     set_factor_slot(fp, 1, P1, V1);
     return launch_factor_fused(fp, 2, P0.L.kpf, P0.d % 4 == 0, stream);
+  }
+  if (!factor_is_fused(P0.L.kpf, P0.d) && P0.d == P1.d && P0.n == P1.n && P0.L.kf == P1.L.kf &&
+      P0.L.gram_split == P1.L.gram_split) {
+    TeamFactorPair pair;
+    pair.a[0] = team_factor_args(P0, V0);
+    pair.a[1] = team_factor_args(P1, V1);
+    return launch_team_factor(pair, 2, P0.L.nbf, stream);
   }
   const int rc = build_factors(P0, V0, stream);
   return rc != FASTH_OK ? rc : build_factors(P1, V1, stream);

@@ -530,7 +530,7 @@ namespace fasth {
 static bool chain_uses_pipe(const ChainArgs& a) {
   return !chain_uses_tile(a) && !chain_uses_quad(a) && !chain_uses_team(a) && !chain_uses_split_pair(a) && a.d <= 4096;
 }
-static bool chain_takes_side_product(const ChainArgs& a) { return chain_uses_pipe(a); }
+static bool chain_takes_side_product(const ChainArgs& a) { return chain_uses_pipe(a) || chain_uses_team(a); }
 
 static int launch_chain_kernel(const ChainArgs& a, hipStream_t stream) {
   const int d = a.d, k = a.k;

@@ -68,6 +68,12 @@ __global__ void __launch_bounds__(512) chain_team_kernel(ChainArgs p) {
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int m = p.m, d = p.d;
   // workgroups b, b + 8, ... (one XCD) are the parts of column 8 (b / (8 NP)) + b % 8
+  const int chain_wgs = 8 * NP * ((m + 7) / 8);
+  if ((int)blockIdx.x >= chain_wgs) {  // workgroups beyond the chain's: the side product, on compute units the chain leaves idle
+    const int row = ((int)blockIdx.x - chain_wgs) * NW + wave;
+    if (row < p.ds_rows) dsigma_row(p.in, p.ds_z1, p.in_scale, p.ds_out, row, m, p.in_scale_mode);
+    return;
+  }
   const int part = (int)(blockIdx.x >> 3) % NP;
   const int col = (int)(blockIdx.x >> 3) / NP * 8 + (int)(blockIdx.x & 7);
   if (col >= m) return;
@@ -325,7 +331,8 @@ static int launch_chain_team(const ChainArgs& args, hipStream_t stream) {
     return v;
   }();
   prof::Scope ps_(FASTH_KERNEL_CHAIN, stream, names[(a.parts - 2) * 3 + kmode].c_str());
-  const dim3 grid(8 * a.parts * ((a.m + 7) / 8)), block(512);
+  const int side = a.ds_out ? (a.ds_rows + 7) / 8 : 0;  // a row of the side product per wave
+  const dim3 grid(8 * a.parts * ((a.m + 7) / 8) + side), block(512);
   if (kmode == 0) hipLaunchKernelGGL(chain_team_kernel<0>, grid, block, 0, stream, a);
   else if (kmode == 1) hipLaunchKernelGGL(chain_team_kernel<1>, grid, block, 0, stream, a);
   else hipLaunchKernelGGL(chain_team_kernel<2>, grid, block, 0, stream, a);

@@ -192,10 +192,15 @@ struct TeamFactorArgs {
   unsigned* xch;               // hand-off area of the chain kernels, cleared here
   unsigned xch_words;
 };
+// Up to two products of the same shape (the two orthogonal factors of an SVD layer) per launch: blockIdx.z picks.
+struct TeamFactorPair {
+  TeamFactorArgs a[2];
+};
 
 template <int VEC>
-__global__ void __launch_bounds__(1024) team_factor_kernel(TeamFactorArgs p) {
+__global__ void __launch_bounds__(1024) team_factor_kernel(TeamFactorPair pair) {
   extern __shared__ __align__(16) float smem[];
+  const TeamFactorArgs& p = pair.a[blockIdx.z];
   const int LD = kGramChunk + 4;
   const int d = p.d, k = p.k, kp = p.kp, split = p.split;
   const int i = blockIdx.y, s = blockIdx.x;
