@@ -29,6 +29,13 @@ int main() {
   EXPECT(fasth_workspace_bytes(&bad_k), 0);
   EXPECT(fasth_workspace_bytes(nullptr), 0);
   EXPECT(fasth_workspace_bytes(&many_blocks), 0);
+  // shapes whose chains share a column between workgroups carry a hand-off area; the layout code is host code
+  fasth_shape team2 = {1024, 1024, 32, 32, 0}, team8 = {4096, 128, 32, 128, 0}, split2 = {2048, 64, 100, 32, 0};
+  EXPECT(fasth_workspace_bytes(&team2) > fasth_workspace_bytes(&ok), 1);
+  EXPECT(fasth_workspace_bytes(&team8) > (size_t)32 * (256 + 8 * 2 * 8 * 64 * 8), 1);
+  EXPECT(fasth_workspace_bytes(&split2) > 0, 1);
+  EXPECT(fasth_set_wait_limit(0), FASTH_OK);
+  EXPECT(fasth_set_wait_limit(-1), FASTH_OK);
   EXPECT(fasth_forward(&bad_k, p, p, p, p, big, nullptr), FASTH_EINVAL);
   EXPECT(fasth_forward(&bad_m, p, p, p, p, big, nullptr), FASTH_EINVAL);
   EXPECT(fasth_forward(&bad_t, p, p, p, p, big, nullptr), FASTH_EINVAL);

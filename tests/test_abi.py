@@ -44,6 +44,29 @@ def _call_forward(shape, V=256, X=256, A=512, ws=1024, nbytes=1 << 40):
     return B.load_library().fasth_forward(ctypes.byref(shape), V, X, A, ws, nbytes, None)
 
 
+def test_workspace_holds_the_hand_off_area_of_shared_columns():
+    """Few long columns are shared by 2 to 8 workgroups that pass partial sums through the workspace: per column a
+    256-byte head and np * 2 * np * 64 words of 8 bytes, which shapes outside that range do not pay for."""
+    def area(d, n, m, k, np_):
+        return m * (256 + np_ * 2 * np_ * 64 * 8)
+    base = B.fasth_workspace_bytes(1024, 1024, 200, 32)   # too many columns for a team of 2: 400 workgroups
+    team = B.fasth_workspace_bytes(1024, 1024, 100, 32)
+    per_col = 2 * (1024 // 32) * 1024 * 4 + 2 * 1024 * 4  # saved inputs of both chains and both coefficient vectors
+    assert team - (base - 100 * per_col) >= area(1024, 1024, 100, 32, 2)
+    # more parts, more words: d = 4096 takes 8 parts
+    w8 = B.fasth_workspace_bytes(4096, 64, 32, 64)
+    w8_alone = B.fasth_workspace_bytes(4096, 64, 33, 64)  # 33 columns x 8 parts > 256 workgroups: no team
+    assert w8 > area(4096, 64, 32, 64, 8)
+    assert w8_alone < w8 + 2 * (2 * 4096 * 4 + 64 * 4) + 4096  # one more column, no hand-off area
+
+
+def test_wait_limit_is_host_state():
+    B.fasth_set_wait_limit(0)
+    B.fasth_set_wait_limit(-1)  # back to the default
+    assert B.FASTH_ETIMEOUT == -6
+    assert "gave up" in B.load_library().fasth_strerror(B.FASTH_ETIMEOUT).decode()
+
+
 def test_forward_argument_errors_precede_any_gpu_call():
     ok = B.fasth_shape(64, 64, 32, 32, 0)
     assert _call_forward(B.fasth_shape(64, 64, 32, 7, 0)) == B.FASTH_EINVAL
