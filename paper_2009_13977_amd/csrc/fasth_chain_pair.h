@@ -381,9 +381,9 @@ static int launch_chain_pair(const ChainArgs& args, hipStream_t stream) {
   return FASTH_OK;
 }
 
-// Two workgroups per column (SPLIT above): 1024 < d <= 2048, whole 32-row steps, at most split_pair_max_cols columns
+// Two workgroups per column (SPLIT above): 1024 < d <= 2048, whole 32-row steps, at most kSplitPairMaxCols columns
 // so that every workgroup of the launch has a compute unit of its own and no half waits for a partner that has not
-// started.
+// started. (Shapes that chain_team_kernel takes never get here: the launcher asks it first.)
 static bool chain_uses_split_pair(const ChainArgs& a) { return a.xch != nullptr && split_pair_serves(a.d, a.m, a.k); }
 
 template <int SUB>
