@@ -115,10 +115,10 @@ int fasth_apply(const fasth_shape* shape, const float* V, const float* X, float*
  * saved for a backward pass. The call allocates and frees nothing; its first use on a device looks up
  * the array's address. Shapes whose factors, partial Gram matrices and hand-off words need more than the array
  * holds (about 4 n kp (2 + min(16, ceil(d / 128))) bytes, kp = k rounded up to a power of two >= 16; for the
- * shapes of fasth_wait_status's comment up to 65 KiB more per column) return FASTH_EUNSUPPORTED before any
- * GPU call. Every call on one GPU uses the same array: calls that overlap
+ * shapes of fasth_wait_status's comment kp = 64 also for k = 32, and up to 65 KiB more per column: 10 MiB at
+ * d = n = 2048, m = 64) return FASTH_EUNSUPPORTED before any GPU call. Every call on one GPU uses the same array: calls that overlap
  * on one GPU (different streams or threads) race; calls on one stream do not. */
-#define FASTH_STATIC_SCRATCH_BYTES (8u << 20)
+#define FASTH_STATIC_SCRATCH_BYTES (16u << 20)
 int fasth_forward_static(const fasth_shape* shape, const float* V, const float* X, float* A, void* stream);
 
 /* Algorithm 2. Given G = dL/dA [d][m], writes dX = dL/dX [d][m] and
