@@ -115,13 +115,22 @@ static TeamFactorArgs team_factor_args(const Product& P, const float* V) {
 static int launch_team_factor(const TeamFactorPair& pair, int count, int nbf, hipStream_t stream) {
   const TeamFactorArgs& a = pair.a[0];
   const size_t lds = std::max(sizeof(float) * (size_t)a.kp * (kGramChunk + 4), t_build_lds(a.kp));
-  int rc = allow_lds(team_factor_kernel<4>, lds);
-  if (rc == FASTH_OK) rc = allow_lds(team_factor_kernel<1>, lds);
+  const bool vec4 = a.d % 4 == 0;
+  int rc = FASTH_OK;
+  if (a.kp == 64) rc = vec4 ? allow_lds(team_factor_kernel<4, 64>, lds) : allow_lds(team_factor_kernel<1, 64>, lds);
+  else rc = vec4 ? allow_lds(team_factor_kernel<4, 128>, lds) : allow_lds(team_factor_kernel<1, 128>, lds);
   if (rc != FASTH_OK) return rc;
-  prof::Scope ps_(FASTH_KERNEL_TEAM_FACTOR, stream, a.d % 4 == 0 ? "team_factor_kernel<4>" : "team_factor_kernel<1>");
+  static const std::string names[4] = {variant_name("team_factor_kernel", {4, 64}), variant_name("team_factor_kernel", {1, 64}),
+                                       variant_name("team_factor_kernel", {4, 128}), variant_name("team_factor_kernel", {1, 128})};
+  prof::Scope ps_(FASTH_KERNEL_TEAM_FACTOR, stream, names[(a.kp == 64 ? 0 : 2) + (vec4 ? 0 : 1)].c_str());
   const dim3 grid(a.split, nbf, count), block(8 * a.kp);
-  if (a.d % 4 == 0) hipLaunchKernelGGL(team_factor_kernel<4>, grid, block, lds, stream, pair);
-  else hipLaunchKernelGGL(team_factor_kernel<1>, grid, block, lds, stream, pair);
+  if (a.kp == 64) {
+    if (vec4) hipLaunchKernelGGL((team_factor_kernel<4, 64>), grid, block, lds, stream, pair);
+    else hipLaunchKernelGGL((team_factor_kernel<1, 64>), grid, block, lds, stream, pair);
+  } else {
+    if (vec4) hipLaunchKernelGGL((team_factor_kernel<4, 128>), grid, block, lds, stream, pair);
+    else hipLaunchKernelGGL((team_factor_kernel<1, 128>), grid, block, lds, stream, pair);
+  }
   FASTH_HIP(hipGetLastError());
   return FASTH_OK;
 }

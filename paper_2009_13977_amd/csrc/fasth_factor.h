@@ -197,12 +197,13 @@ struct TeamFactorPair {
   TeamFactorArgs a[2];
 };
 
-template <int VEC>
-__global__ void __launch_bounds__(1024) team_factor_kernel(TeamFactorPair pair) {
+template <int VEC, int KP>  // KP: padded rows of a block, 64 or 128; 8 KP threads
+__global__ void __launch_bounds__(8 * KP) team_factor_kernel(TeamFactorPair pair) {
   extern __shared__ __align__(16) float smem[];
   const TeamFactorArgs& p = pair.a[blockIdx.z];
   const int LD = kGramChunk + 4;
-  const int d = p.d, k = p.k, kp = p.kp, split = p.split;
+  constexpr int kp = KP;
+  const int d = p.d, k = p.k, split = p.split;
   const int i = blockIdx.y, s = blockIdx.x;
   const int tid = threadIdx.x, nthreads = blockDim.x, wave = tid >> 6, nwaves = nthreads >> 6, lane = tid & 63;
   clear_exchange_area(p.xch, p.xch_words, blockIdx.y * gridDim.x + blockIdx.x, gridDim.x * gridDim.y);
@@ -323,7 +324,7 @@ __global__ void __launch_bounds__(1024) team_factor_kernel(TeamFactorPair pair) 
   __syncthreads();
   if (tid >= 1 && tid < split) ready[tid] = 0ull;  // the partial matrices are in: the words are cleared for the next launch
   diag_scratch_fill(Ms, Xs, kp, LDM);
-  invert_upper_lds<false>(Ms, Xs, kp, LDM);
+  invert_upper_lds<KP == 64>(Ms, Xs, kp, LDM);  // 512 threads have the registers to fetch a diagonal block at once
   // T_i and, nb factors further on, its transpose: a chain kernel then reads rows of op(T_i) in either direction
   float* Ti = p.T + (size_t)i * kp * kp;
   float* Tti = Ti + (size_t)gridDim.y * kp * kp;
