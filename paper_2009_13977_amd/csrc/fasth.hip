@@ -107,6 +107,7 @@ static TeamFactorArgs team_factor_args(const Product& P, const float* V) {
   if (a.launch_id == 0) a.launch_id = 1;
   a.d = P.d; a.k = P.L.kf; a.kp = P.L.kpf; a.split = P.L.gram_split; a.wait_limit = wait_limit();
   a.xch = P.xch(); a.xch_words = (unsigned)P.L.xch_words;
+  a.S = reinterpret_cast<float*>(P.ws + P.L.off_S); a.nblocks = P.L.nbf; a.npair = P.L.npair;
   return a;
 }
 
@@ -114,7 +115,8 @@ static TeamFactorArgs team_factor_args(const Product& P, const float* V) {
 // product split over d, the block's first workgroup inverts. `count` products of the same shape in one launch.
 static int launch_team_factor(const TeamFactorPair& pair, int count, int nbf, hipStream_t stream) {
   const TeamFactorArgs& a = pair.a[0];
-  const size_t lds = std::max(sizeof(float) * (size_t)a.kp * (kGramChunk + 4), t_build_lds(a.kp));
+  // (a pair's workgroups stage the rows of two blocks)
+  const size_t lds = std::max(sizeof(float) * (size_t)(a.npair > 0 ? 2 : 1) * a.kp * (kGramChunk + 4), t_build_lds(a.kp));
   const bool vec4 = a.d % 4 == 0;
   int rc = FASTH_OK;
   if (a.kp == 64) rc = vec4 ? allow_lds(team_factor_kernel<4, 64>, lds) : allow_lds(team_factor_kernel<1, 64>, lds);
@@ -123,7 +125,7 @@ static int launch_team_factor(const TeamFactorPair& pair, int count, int nbf, hi
   static const std::string names[4] = {variant_name("team_factor_kernel", {4, 64}), variant_name("team_factor_kernel", {1, 64}),
                                        variant_name("team_factor_kernel", {4, 128}), variant_name("team_factor_kernel", {1, 128})};
   prof::Scope ps_(FASTH_KERNEL_TEAM_FACTOR, stream, names[(a.kp == 64 ? 0 : 2) + (vec4 ? 0 : 1)].c_str());
-  const dim3 grid(a.split, nbf, count), block(8 * a.kp);
+  const dim3 grid(a.split, nbf + a.npair, count), block(8 * a.kp);
   if (a.kp == 64) {
     if (vec4) hipLaunchKernelGGL((team_factor_kernel<4, 64>), grid, block, lds, stream, pair);
     else hipLaunchKernelGGL((team_factor_kernel<1, 64>), grid, block, lds, stream, pair);
@@ -161,7 +163,7 @@ static int build_factors_pair(const Product& P0, const float* V0, const Product&
     return launch_factor_fused(fp, 2, P0.L.kpf, P0.d % 4 == 0, stream);
   }
   if (!factor_is_fused(P0.L.kpf, P0.d) && P0.d == P1.d && P0.n == P1.n && P0.L.kf == P1.L.kf &&
-      P0.L.gram_split == P1.L.gram_split) {
+      P0.L.gram_split == P1.L.gram_split && P0.L.npair == P1.L.npair) {
     TeamFactorPair pair;
     pair.a[0] = team_factor_args(P0, V0);
     pair.a[1] = team_factor_args(P1, V1);
@@ -183,6 +185,7 @@ static int run_chain(const Product& P, const float* V, const float* in, float* o
   ChainArgs a;
   a.V = V; a.T = F.T(); a.in = in; a.out = out;
   a.xch = F.xch(); a.wait_limit = wait_limit(); a.parts = 0;
+  a.S = reinterpret_cast<const float*>(F.ws + F.L.off_S);
   a.Tt = a.T + (size_t)F.L.nbf * F.L.kpf * F.L.kpf;
   a.save_in = !save ? nullptr : activation ? P.saveA() : P.saveG();
   a.save_c = !save ? nullptr : activation ? P.saveCa() : P.saveCg();

@@ -55,6 +55,7 @@ struct ChainArgs {
   unsigned* xch;
   int wait_limit;
   int parts;              // chain_team_kernel: workgroups per column (set by its launcher)
+  const float* S;         // chain_team_wide_kernel: [n / 128][2][64][64], V_a V_b^T of each step's two blocks and its transpose
 };
 
 // Gradient of the diagonal step of the SVD layer (Section 2.2), one wave per row: with Z2 = s * Z1 row-wise
@@ -528,14 +529,15 @@ namespace fasth {
 
 // chain_pipe_kernel serves every d up to 4096; it also takes the side product along.
 static bool chain_uses_pipe(const ChainArgs& a) {
-  return !chain_uses_tile(a) && !chain_uses_quad(a) && !chain_uses_team(a) && !chain_uses_split_pair(a) && a.d <= 4096;
+  return !chain_uses_tile(a) && !chain_uses_quad(a) && !chain_uses_team_wide(a) && !chain_uses_team(a) && !chain_uses_split_pair(a) && a.d <= 4096;
 }
-static bool chain_takes_side_product(const ChainArgs& a) { return chain_uses_pipe(a) || chain_uses_team(a); }
+static bool chain_takes_side_product(const ChainArgs& a) { return chain_uses_pipe(a) || chain_uses_team(a) || chain_uses_team_wide(a); }
 
 static int launch_chain_kernel(const ChainArgs& a, hipStream_t stream) {
   const int d = a.d, k = a.k;
   if (chain_uses_tile(a)) return launch_chain_tile(a, stream);
   if (chain_uses_quad(a)) return launch_chain_quad(a, stream);
+  if (chain_uses_team_wide(a)) return launch_chain_team_wide(a, stream);
   if (chain_uses_team(a)) return launch_chain_team(a, stream);
   if (chain_uses_split_pair(a)) {
     // two compute units per column, 32-row steps (d = n = 2048, m = 64: see the measurements at the kernel)

@@ -41,8 +41,10 @@ static int padded_block(int k) {
 
 struct Layout {
   int kp, nb, gram_split, dv_split;
-  int kf, kpf, nbf;  // rows of a factor as stored (two of the caller's blocks when the team kernel merges them), padded; their number
-  size_t off_T, off_Spart, off_ready, off_xch, off_saveA, off_saveCa, off_saveG, off_saveCg, off_dVpart, total;
+  int kf, kpf, nbf;  // rows of a factor as stored (several of the caller's blocks when a team kernel merges them), padded; their number
+  int team_wide;     // parts per column if chain_team_wide_kernel serves the shape (factors stored in its order), else 0
+  int npair;         // pairs of blocks whose rows' product V_a V_b^T is formed beside the factors (chain_team_wide_kernel), else 0
+  size_t off_T, off_S, off_Spart, off_ready, off_xch, off_saveA, off_saveCa, off_saveG, off_saveCg, off_dVpart, total;
   size_t xch_words;  // 32-bit words of the hand-off area between workgroups that share a column (0: none)
 };
 
@@ -67,7 +69,26 @@ constexpr unsigned team_words_per_column(int np) { return (unsigned)(kTeamHeadBy
 #ifndef FASTH_TEAM_MIN_D
 #define FASTH_TEAM_MIN_D (kTeamSlice + 1)
 #endif
+// chain_team_wide_kernel: the same with 256 elements of the column per workgroup and steps of 128 rows, for columns
+// of FASTH_TEAM_WIDE_MIN_D to 2048 elements while every workgroup has a compute unit of its own: half as many
+// sequential steps as with 64 rows. Such a step joins two blocks of 64 rows (the caller's, halves of the caller's
+// blocks of 128, or merged pairs of the caller's blocks of 32) through their 64 x 64 factors and the product
+// V_a V_b^T of their rows, which the factor kernel forms beside the factors. Its hand-off words are 16 bytes
+// {sum, tag, sum, tag}. The matrices of such a shape are stored in the order in which the kernel's threads read them.
+constexpr int kWideRows = 128;
+constexpr int kWideSlice = 256;
+constexpr unsigned team_wide_words_per_column(int np) { return (unsigned)(kTeamHeadBytes + np * 2 * np * (kWideRows / 2) * 16) / 4u; }
+#ifndef FASTH_TEAM_WIDE_MIN_D
+#define FASTH_TEAM_WIDE_MIN_D 769
+#endif
+static int team_wide_parts(int d, int n, int m, int k) {
+  if (d < FASTH_TEAM_WIDE_MIN_D || d > 8 * kWideSlice || d % 4 != 0 || n % kWideRows != 0) return 0;
+  if (!(k == 32 || k == 64 || k == 128)) return 0;
+  const int np = (d + kWideSlice - 1) / kWideSlice;
+  return m * np <= kComputeUnits ? np : 0;
+}
 static int team_parts(int d, int n, int m, int k) {
+  if (team_wide_parts(d, n, m, k)) return 0;
   if (d < FASTH_TEAM_MIN_D || d > 8 * kTeamSlice || d % 4 != 0) return 0;
   if (!(k == 64 || k == 128 || (k == 32 && n % 64 == 0))) return 0;
   const int np = (d + kTeamSlice - 1) / kTeamSlice;
@@ -97,16 +118,23 @@ static int dv_minibatch_split(int d, int n, int m, int k) {
 #endif
 static bool factor_is_fused(int kp, int d) { return kp <= 32 || (kp == 64 && d <= FASTH_FUSED64_MAX_D); }
 
+#ifndef FASTH_GRAM_SPLIT_128
+#define FASTH_GRAM_SPLIT_128 8
+#endif
 static Layout make_layout(int d, int n, int m, int k) {
   Layout L;
   L.kp = padded_block(k);
   L.nb = n / k;
-  const int team = team_parts(d, n, m, k);
-  L.kf = team && k == 32 ? 64 : k;
+  const int team = team_parts(d, n, m, k), wide = team_wide_parts(d, n, m, k);
+  L.kf = wide ? 64 : team && k == 32 ? 64 : k;
+  L.team_wide = wide;
+  L.npair = wide ? n / kWideRows : 0;
   L.kpf = padded_block(L.kf);
   L.nbf = n / L.kf;
   int split = (d + kGramChunk - 1) / kGramChunk;
   L.gram_split = split > kMaxGramSplit ? kMaxGramSplit : split;
+  // factors of 128 rows: the workgroup that adds the partial matrices fetches four of them per trip to memory
+  if (L.kpf == 128 && L.gram_split > FASTH_GRAM_SPLIT_128) L.gram_split = FASTH_GRAM_SPLIT_128;
   size_t off = 256;  // header, reserved
   auto take = [&](size_t floats) {
     size_t o = off;
@@ -116,9 +144,12 @@ static Layout make_layout(int d, int n, int m, int k) {
   L.off_T = take(2 * (size_t)L.nbf * L.kpf * L.kpf);  // the factors and, behind them, their transposes
   // partial Gram matrices (later the dV kernel's per-block matrices Z, nb kp^2 floats, which they always cover) and,
   // where the Gram product is split over workgroups, an 8-byte "ready" word per partial matrix
-  L.off_Spart = take((size_t)L.nbf * L.gram_split * L.kpf * L.kpf);
-  L.off_ready = take(factor_is_fused(L.kpf, d) ? 0 : (size_t)L.nbf * L.gram_split * 2);
-  L.xch_words = team ? (size_t)m * team_words_per_column(team) : split_pair_serves(d, m, k) ? (size_t)m * kSplitPairWords : 0;
+  L.off_Spart = take((size_t)(L.nbf + L.npair) * L.gram_split * L.kpf * L.kpf);
+  L.off_ready = take(factor_is_fused(L.kpf, d) ? 0 : (size_t)(L.nbf + L.npair) * L.gram_split * 2);
+  L.off_S = take(2 * (size_t)L.npair * L.kpf * L.kpf);  // per pair V_a V_b^T and its transpose
+  L.xch_words = wide ? (size_t)m * team_wide_words_per_column(wide)
+              : team ? (size_t)m * team_words_per_column(team)
+              : split_pair_serves(d, m, k) ? (size_t)m * kSplitPairWords : 0;
   L.off_xch = take(L.xch_words);
   L.off_saveA = take((size_t)L.nb * m * d);
   L.off_saveCa = take((size_t)m * n);

@@ -163,6 +163,7 @@ __device__ __forceinline__ float dpp_move(float x) {
   return __uint_as_float(__builtin_amdgcn_update_dpp(0u, __float_as_uint(x), CTRL, 0xF, 0xF, false));
 }
 constexpr int kDppRowMirror = 0x140, kDppRowHalfMirror = 0x141, kDppQuadXor2 = 0x4E, kDppQuadXor1 = 0xB1;
+constexpr int kDppRowRor8 = 0x128;  // row_ror:8, lane i <-> i ^ 8 within a row of 16
 
 template <int MASK>
 __device__ __forceinline__ float partner_value(float x) {

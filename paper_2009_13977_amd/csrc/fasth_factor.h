@@ -191,6 +191,11 @@ struct TeamFactorArgs {
   int d, k, kp, split, wait_limit;
   unsigned* xch;               // hand-off area of the chain kernels, cleared here
   unsigned xch_words;
+  // For chain_team_wide_kernel (kp = 64 only): npair > 0 adds, per pair p of consecutive blocks, the product
+  // S_p = V_2p V_2p+1^T of their rows (workgroups blockIdx.y >= nblocks), and every matrix is stored in the order in
+  // which that kernel's threads read it.
+  float* S;                    // [npair][2][kp][kp]: S_p, then its transpose
+  int nblocks, npair;
 };
 // Up to two products of the same shape (the two orthogonal factors of an SVD layer) per launch: blockIdx.z picks.
 struct TeamFactorPair {
@@ -207,42 +212,60 @@ __global__ void __launch_bounds__(8 * KP) team_factor_kernel(TeamFactorPair pair
   const int i = blockIdx.y, s = blockIdx.x;
   const int tid = threadIdx.x, nthreads = blockDim.x, wave = tid >> 6, nwaves = nthreads >> 6, lane = tid & 63;
   clear_exchange_area(p.xch, p.xch_words, blockIdx.y * gridDim.x + blockIdx.x, gridDim.x * gridDim.y);
+  // A workgroup beyond the blocks' forms a pair's product S = V_a V_b^T instead of a block's Gram matrix: the rows of
+  // both blocks (2 kp consecutive rows of V) in LDS, all kp / 16 squared tiles.
+  const bool pair_job = KP == 64 && i >= p.nblocks;
   {
-    float* Vs = smem;  // [kp][LD]
+    float* Vs = smem;  // [kp][LD], a pair's [2 kp][LD]
     const int chunk = ((d + split - 1) / split + 3) & ~3;
     const int xbeg = s * chunk;
     const int xend = min(d, xbeg + chunk);
     const int kt = kp / 16;
-    const int ntiles = kt * (kt + 1) / 2;
-    constexpr int kMaxTilesPerWave = 3;  // kp = 128: 36 upper tiles over 16 waves; kp = 64: 10 over 8
+    const int ntiles = pair_job ? kt * kt : kt * (kt + 1) / 2;
+    constexpr int kMaxTilesPerWave = 3;  // kp = 128: 36 upper tiles over 16 waves; kp = 64: 10 over 8, a pair's 16 over 8
     f32x4 acc[kMaxTilesPerWave];
 #pragma unroll
     for (int w = 0; w < kMaxTilesPerWave; ++w) acc[w] = f32x4{0.f, 0.f, 0.f, 0.f};
     // the block's k rows as one buffer: rows k .. kp - 1 of the padded block lie beyond it and read as zero
-    const BufferDesc vdesc = make_buffer(p.V + (size_t)i * k * d, (size_t)k * d * sizeof(float));
+    const BufferDesc vdesc = pair_job ? make_buffer(p.V + (size_t)(i - p.nblocks) * 2 * kp * d, (size_t)2 * kp * d * sizeof(float))
+                                      : make_buffer(p.V + (size_t)i * k * d, (size_t)k * d * sizeof(float));
     constexpr int XV = kGramChunk / VEC;  // loads per slab row
-    constexpr int PER = 16 / VEC;         // loads per thread and slab: kp XV / nthreads with nthreads = 8 kp
-    for (int x0 = xbeg; x0 < xend; x0 += kGramChunk) {
-      BufVec<VEC> stage[PER];
+    constexpr int PER1 = 16 / VEC;        // loads per thread and slab: kp XV / nthreads with nthreads = 8 kp
+    constexpr int PER = KP == 64 ? 2 * PER1 : PER1;  // room for a pair's rows; a block's workgroups use the first half
+    const int nper = pair_job ? PER : PER1;
+    // a slab is fetched while the one before it is multiplied
+    BufVec<VEC> stage[PER];
+    auto fetch_slab = [&](int x0) {
 #pragma unroll
       for (int it = 0; it < PER; ++it) {
         const int idx = tid + it * nthreads, j = idx / XV, x = x0 + (idx % XV) * VEC;
-        stage[it] = buffer_load<VEC>(vdesc, x < xend ? (unsigned)(j * d + x) * 4u : kOob, 0);
+        if (it < nper) stage[it] = buffer_load<VEC>(vdesc, x < xend ? (unsigned)(j * d + x) * 4u : kOob, 0);
       }
+    };
+    // tile t of this workgroup: (ti, tj) of the upper triangle, or of a pair's kt x kt tiles (rows of b behind those of a)
+    auto tile_of = [&](int t, int& ti, int& tj) {
+      if (pair_job) { ti = t / kt; tj = t % kt; return; }
+      int rem = t;
+      ti = 0;
+      while (rem >= kt - ti) { rem -= kt - ti; ++ti; }
+      tj = ti + rem;
+    };
+    fetch_slab(xbeg);
+    for (int x0 = xbeg; x0 < xend; x0 += kGramChunk) {
 #pragma unroll
       for (int it = 0; it < PER; ++it) {
         const int idx = tid + it * nthreads;
-        lds_store<VEC>(Vs + (idx / XV) * LD + (idx % XV) * VEC, stage[it]);
+        if (it < nper) lds_store<VEC>(Vs + (idx / XV) * LD + (idx % XV) * VEC, stage[it]);
       }
       __syncthreads();
+      if (x0 + kGramChunk < xend) fetch_slab(x0 + kGramChunk);
 #pragma unroll
       for (int w = 0; w < kMaxTilesPerWave; ++w) {
         const int t = wave + nwaves * w;
         if (t < ntiles) {
-          int ti = 0, rem = t;
-          while (rem >= kt - ti) { rem -= kt - ti; ++ti; }
-          const int tj = ti + rem;
-          acc[w] = tile_mma<true>(Vs + ti * 16 * LD, LD, Vs + tj * 16 * LD, LD, kGramChunk, acc[w]);
+          int ti, tj;
+          tile_of(t, ti, tj);
+          acc[w] = tile_mma<true>(Vs + ti * 16 * LD, LD, Vs + ((pair_job ? kp : 0) + tj * 16) * LD, LD, kGramChunk, acc[w]);
         }
       }
       __syncthreads();
@@ -254,9 +277,8 @@ __global__ void __launch_bounds__(8 * KP) team_factor_kernel(TeamFactorPair pair
     for (int w = 0; w < kMaxTilesPerWave; ++w) {
       const int t = wave + nwaves * w;
       if (t < ntiles) {
-        int ti = 0, rem = t;
-        while (rem >= kt - ti) { rem -= kt - ti; ++ti; }
-        const int tj = ti + rem;
+        int ti, tj;
+        tile_of(t, ti, tj);
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj)
           __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(acc[w][jj]), odesc,
@@ -299,23 +321,40 @@ __global__ void __launch_bounds__(8 * KP) team_factor_kernel(TeamFactorPair pair
     const BufferDesc sdesc = make_buffer(p.Spart + (size_t)i * split * kp * kp, (size_t)split * kp * kp * sizeof(float));
     // Four neighbouring entries of a row at a time (kp is a multiple of 16, so they share a 16 x 16 tile); tiles
     // below the diagonal hold nothing and are not read. All partial sums of an entry are in flight at once.
-    for (int idx4 = tid; idx4 < kp * kp / 4; idx4 += nthreads) {
-      const int j = idx4 / (kp / 4), l0 = (idx4 % (kp / 4)) * 4;
-      f32x4 sum = {0.f, 0.f, 0.f, 0.f};
-      if (j / 16 <= l0 / 16 && j < k) {
-        f32x4 part[kMaxGramSplit];
+    // A trip to memory per batch of fetches: the 8 kp threads take kp / 32 groups of four entries each, and up to 16
+    // fetches are in flight per thread (64 registers), i.e. all groups of a thread at once for up to 16 / (kp / 32)
+    // partial matrices. The sum takes the partial matrices in their order whatever the batches.
+    constexpr int NPOS = KP / 32;       // groups of four per thread
+    constexpr int BATCH = 16 / NPOS;    // partial matrices per batch
+    f32x4 sum[NPOS];
 #pragma unroll
-        for (int sl = 0; sl < kMaxGramSplit; ++sl)
-          part[sl] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(
-                         sdesc, sl < split ? (unsigned)(((size_t)sl * kp * kp + 4 * (size_t)idx4) * 4u) : kOob, 0, 16));
+    for (int it = 0; it < NPOS; ++it) sum[it] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int s0 = 0; s0 < split; s0 += BATCH) {
+      f32x4 part[NPOS][BATCH];
 #pragma unroll
-        for (int sl = 0; sl < kMaxGramSplit; ++sl) sum += part[sl];
+      for (int it = 0; it < NPOS; ++it) {
+        const int idx4 = tid + it * nthreads, j = idx4 / (kp / 4), l0 = (idx4 % (kp / 4)) * 4;
+        const bool wanted = pair_job || (j / 16 <= l0 / 16 && j < k);
+#pragma unroll
+        for (int sb = 0; sb < BATCH; ++sb)
+          part[it][sb] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(
+                             sdesc, wanted && s0 + sb < split ? (unsigned)(((size_t)(s0 + sb) * kp * kp + 4 * (size_t)idx4) * 4u) : kOob, 0, 16));
       }
+#pragma unroll
+      for (int it = 0; it < NPOS; ++it) {
+#pragma unroll
+        for (int sb = 0; sb < BATCH; ++sb) sum[it] += part[it][sb];
+      }
+    }
+#pragma unroll
+    for (int it = 0; it < NPOS; ++it) {
+      const int idx4 = tid + it * nthreads, j = idx4 / (kp / 4), l0 = (idx4 % (kp / 4)) * 4;
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
         const int l = l0 + u;
         float v = 0.f;
-        if (j < k && l < k && j <= l) v = j == l ? 0.5f * sum[u] : sum[u];
+        if (pair_job) v = sum[it][u];
+        else if (j < k && l < k && j <= l) v = j == l ? 0.5f * sum[it][u] : sum[it][u];
         else if (j == l) v = 1.f;
         Ms[j * LDM + l] = v;
       }
@@ -323,11 +362,32 @@ __global__ void __launch_bounds__(8 * KP) team_factor_kernel(TeamFactorPair pair
   }
   __syncthreads();
   if (tid >= 1 && tid < split) ready[tid] = 0ull;  // the partial matrices are in: the words are cleared for the next launch
+  // Order of a 64 x 64 matrix for chain_team_wide_kernel: its thread 16 g + c multiplies entries 4 c .. 4 c + 3 of rows
+  // 2 g and 2 g + 1; those of row 2 g + e are the (512 e + 16 g + c)-th 16 bytes, so a wave's fetch of one e is 1 KiB in a row.
+  auto chain_order_row = [](int idx) { return 2 * (((idx >> 2) & 511) >> 4) + (idx >> 11); };
+  auto chain_order_col = [](int idx) { return 4 * ((idx >> 2) & 15) + (idx & 3); };
+  if (pair_job) {
+    float* Sp = p.S + (size_t)(i - p.nblocks) * 2 * kp * kp;
+    for (int idx = tid; idx < kp * kp; idx += nthreads) {
+      const int j = chain_order_row(idx), l = chain_order_col(idx);
+      Sp[idx] = Ms[j * LDM + l];
+      Sp[kp * kp + idx] = Ms[l * LDM + j];
+    }
+    return;
+  }
   diag_scratch_fill(Ms, Xs, kp, LDM);
   invert_upper_lds<KP == 64>(Ms, Xs, kp, LDM);  // 512 threads have the registers to fetch a diagonal block at once
   // T_i and, nb factors further on, its transpose: a chain kernel then reads rows of op(T_i) in either direction
   float* Ti = p.T + (size_t)i * kp * kp;
-  float* Tti = Ti + (size_t)gridDim.y * kp * kp;
+  float* Tti = Ti + (size_t)p.nblocks * kp * kp;
+  if (KP == 64 && p.npair > 0) {
+    for (int idx = tid; idx < kp * kp; idx += nthreads) {
+      const int j = chain_order_row(idx), l = chain_order_col(idx);
+      Ti[idx] = Ms[j * LDM + l];
+      Tti[idx] = Ms[l * LDM + j];
+    }
+    return;
+  }
   for (int idx = tid; idx < kp * kp; idx += nthreads) {
     Ti[idx] = Ms[(idx / kp) * LDM + idx % kp];
     Tti[idx] = Ms[(idx % kp) * LDM + idx / kp];
