@@ -58,6 +58,12 @@ def test_workspace_holds_the_hand_off_area_of_shared_columns():
     w8_alone = B.fasth_workspace_bytes(4096, 64, 33, 64)  # 33 columns x 8 parts > 256 workgroups: no team
     assert w8 > area(4096, 64, 32, 64, 8)
     assert w8_alone < w8 + 2 * (2 * 4096 * 4 + 64 * 4) + 4096  # one more column, no hand-off area
+    # steps of 128 rows (d = 1024 in four parts of 256): 64 words of 16 bytes per part and step, and per pair of
+    # blocks of 64 rows the product of their rows and its transpose
+    wide = B.fasth_workspace_bytes(1024, 1024, 64, 32)     # 256 workgroups
+    narrow = B.fasth_workspace_bytes(1024, 1024, 65, 32)   # 260: two parts per column instead
+    area_wide = 64 * (256 + 4 * 2 * 4 * 64 * 16)
+    assert wide + per_col - narrow >= area_wide - area(1024, 1024, 65, 32, 2) + (1024 // 128) * 2 * 64 * 64 * 4
 
 
 def test_wait_limit_is_host_state():

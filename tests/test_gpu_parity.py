@@ -125,6 +125,9 @@ def test_fasth_wide_minibatch(d, n, m, k, transpose):
 # through the workspace. A team of 2 to 8 workgroups with steps of 64 rows (blocks of 32 merged in pairs, of 64, of
 # 128 as two steps) while every workgroup has a compute unit of its own: the three block sizes over the team sizes,
 # parts that are full, nearly empty (d = 516, 1028, 2052) and ragged, one column, the most columns a team size takes, n != d;
+# steps of 128 rows (two blocks of 64 joined through the product of their rows) where d is 769 .. 2048 and n a multiple
+# of 128: one to five steps (the kernel's loop takes three at a time), 4 to 8 parts, full, ragged and nearly empty
+# last parts, the most columns;
 # two workgroups per column with steps of 32 rows beyond that (d > 1024, up to 128 columns); and neighbours that stay
 # with one workgroup per column (an odd number of blocks of 32, a block size with a short last step, 129 columns).
 SHARED = [
@@ -134,6 +137,8 @@ SHARED = [
     (2560, 128, 5, 32), (3072, 128, 42, 64), (4096, 256, 32, 128), (3600, 64, 3, 32), (2052, 128, 7, 64), (4096, 64, 33, 32),
     (2044, 96, 128, 32), (2048, 128, 65, 64), (1032, 256, 100, 128),
     (1024, 96, 7, 32), (2048, 64, 129, 32), (2048, 96, 16, 48),
+    (1024, 256, 32, 32), (772, 128, 3, 32), (1792, 384, 9, 64), (2048, 512, 32, 128), (1280, 640, 2, 32), (900, 128, 64, 32),
+    (1024, 384, 64, 64), (2048, 256, 1, 32), (1284, 256, 42, 128), (1000, 512, 7, 64),
 ]
 
 
@@ -151,15 +156,15 @@ def test_fasth_shared_columns(d, n, m, k, transpose):
     assert_close(dV, dV0, "dV", rows=True)
 
 
-def test_shared_columns_wait_gives_up_and_recovers():
-    """A wait between the two workgroups of a column that runs out of polls ends the kernel normally and raises the
+@pytest.mark.parametrize("d,n,m,k", [(2048, 64, 16, 32), (1024, 256, 16, 32)])  # steps of 64 rows, of 128
+def test_shared_columns_wait_gives_up_and_recovers(d, n, m, k):
+    """A wait between the workgroups of a column that runs out of polls ends the kernel normally and raises the
     status word; the next call with the ordinary limit is correct again. The limit is forced to zero from the host,
     so the very first unsuccessful poll gives up: nothing on the GPU hangs or faults."""
     import torch
     from paper_2009_13977_amd import binding as B
     from helpers import to_gpu
-    d, n, m, k = 2048, 64, 16, 32
-    _say("shared columns: wait limit 0")
+    _say(f"shared columns: wait limit 0, d={d} n={n} m={m} k={k}")
     p = synthetic.householder_problem(d, n, m, seed=6100)
     Vd, Xd, Gd = (to_gpu(p[a]) for a in ("V", "X", "G"))
     A = torch.empty_like(Xd); dX = torch.empty_like(Xd); dV = torch.empty_like(Vd)
@@ -252,9 +257,44 @@ def test_shared_columns_in_the_layers():
     for name, g, r in zip(("Y", "dUv", "dsigma", "dVv", "dX"), got,
                           orc.rectangular_gradients(p["Uv"], p["sigma"], p["Vv"], p["X"], p["G"])):
         assert_close(g, r, name, rows=name.startswith("d") and name.endswith("v"))
+    _say("shared columns, steps of 128 rows: svd layer d=1024")
+    p = synthetic.svd_layer_problem(1024, 256, 6, seed=6210)
+    for inverse in (False, True):
+        got = gpu_svd_layer(p["Uv"], p["sigma"], p["Vv"], p["X"], p["G"], 32, inverse)
+        fn = orc.svd_layer_inverse_gradients if inverse else orc.svd_layer_gradients
+        for name, g, r in zip(("Y", "dUv", "dsigma", "dVv", "dX"), got, fn(p["Uv"], p["sigma"], p["Vv"], p["X"], p["G"])):
+            assert_close(g, r, name, rows=name.startswith("d") and name.endswith("v"))
+    _say("shared columns, steps of 128 rows: symmetric form d=1100")
+    rng = np.random.default_rng(6310)
+    Uv = rng.standard_normal((128, 1100)).astype(np.float32)
+    sigma = rng.uniform(-0.8, 0.9, 1100).astype(np.float32)
+    X = rng.standard_normal((1100, 5)).astype(np.float32)
+    G = rng.standard_normal((1100, 5)).astype(np.float32)
+    for name, g, r in zip(("Y", "dUv", "dsigma", "dX"), gpu_svd_sym(Uv, sigma, X, G, 64, "exp"),
+                          orc.symmetric_gradients(Uv, sigma, X, G, "exp")):
+        assert_close(g, r, name, rows=name == "dUv")
+    _say("shared columns, steps of 128 rows: rectangular layer 1024 x 900")
+    p = synthetic.rect_layer_problem(1024, 900, 128, 128, 5, seed=6410)
+    got = gpu_svd_rect(p["Uv"], p["sigma"], p["Vv"], p["X"], p["G"], 32)
+    for name, g, r in zip(("Y", "dUv", "dsigma", "dVv", "dX"), got,
+                          orc.rectangular_gradients(p["Uv"], p["sigma"], p["Vv"], p["X"], p["G"])):
+        assert_close(g, r, name, rows=name.startswith("d") and name.endswith("v"))
     _say("shared columns: prepared factors")
     d, n, m, k = 2048, 64, 24, 32
     p = synthetic.householder_problem(d, n, m, seed=6500)
+    Vd, Xd = to_gpu(p["V"]), to_gpu(p["X"])
+    Y1 = torch.empty_like(Xd); Y2 = torch.empty_like(Xd)
+    ws = B.new_workspace(B.fasth_workspace_bytes(d, n, m, k))
+    B.fasth_prepare(Vd, m, ws, k)
+    for _ in range(3):
+        B.fasth_apply(Vd, Xd, Y1, ws, k)
+        B.fasth_apply(Vd, Y1, Y2, ws, k, transpose=True)
+    assert B.fasth_wait_status() == B.FASTH_OK
+    assert_close(Y1.cpu().numpy(), orc.product_apply(p["V"], p["X"]), "H X")
+    assert_close(Y2.cpu().numpy(), p["X"].astype(np.float64), "H^T H X")
+    _say("shared columns, steps of 128 rows: prepared factors")
+    d, n, m, k = 1536, 384, 20, 64
+    p = synthetic.householder_problem(d, n, m, seed=6510)
     Vd, Xd = to_gpu(p["V"]), to_gpu(p["X"])
     Y1 = torch.empty_like(Xd); Y2 = torch.empty_like(Xd)
     ws = B.new_workspace(B.fasth_workspace_bytes(d, n, m, k))
