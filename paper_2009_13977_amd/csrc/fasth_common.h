@@ -69,6 +69,10 @@ constexpr unsigned team_words_per_column(int np) { return (unsigned)(kTeamHeadBy
 #ifndef FASTH_TEAM_MIN_D
 #define FASTH_TEAM_MIN_D (kTeamSlice + 1)
 #endif
+// A team's workgroups need a compute unit each, all at once: a part that waited for a unit would keep its partners
+// polling until a whole chain elsewhere has ended. The launch places the parts of columns c, c + 8, ... on one XCD
+// (32 of the 256 units), so what must fit is np workgroups for every eight columns begun.
+static bool team_fits(int m, int np) { return 8 * np * ((m + 7) / 8) <= kComputeUnits; }
 // chain_team_wide_kernel: the same with 256 elements of the column per workgroup and steps of 128 rows, for columns
 // of FASTH_TEAM_WIDE_MIN_D to 2048 elements while every workgroup has a compute unit of its own: half as many
 // sequential steps as with 64 rows. Such a step joins two blocks of 64 rows (the caller's, halves of the caller's
@@ -79,20 +83,20 @@ constexpr int kWideRows = 128;
 constexpr int kWideSlice = 256;
 constexpr unsigned team_wide_words_per_column(int np) { return (unsigned)(kTeamHeadBytes + np * 2 * np * (kWideRows / 2) * 16) / 4u; }
 #ifndef FASTH_TEAM_WIDE_MIN_D
-#define FASTH_TEAM_WIDE_MIN_D 769
+#define FASTH_TEAM_WIDE_MIN_D 513
 #endif
 static int team_wide_parts(int d, int n, int m, int k) {
   if (d < FASTH_TEAM_WIDE_MIN_D || d > 8 * kWideSlice || d % 4 != 0 || n % kWideRows != 0) return 0;
   if (!(k == 32 || k == 64 || k == 128)) return 0;
   const int np = (d + kWideSlice - 1) / kWideSlice;
-  return m * np <= kComputeUnits ? np : 0;
+  return team_fits(m, np) ? np : 0;
 }
 static int team_parts(int d, int n, int m, int k) {
   if (team_wide_parts(d, n, m, k)) return 0;
   if (d < FASTH_TEAM_MIN_D || d > 8 * kTeamSlice || d % 4 != 0) return 0;
   if (!(k == 64 || k == 128 || (k == 32 && n % 64 == 0))) return 0;
   const int np = (d + kTeamSlice - 1) / kTeamSlice;
-  return m * np <= kComputeUnits ? np : 0;
+  return team_fits(m, np) ? np : 0;
 }
 
 // The dV kernel has one workgroup per (64-column tile of dV, block). When that is too few to fill the chip and the

@@ -125,7 +125,7 @@ def test_fasth_wide_minibatch(d, n, m, k, transpose):
 # through the workspace. A team of 2 to 8 workgroups with steps of 64 rows (blocks of 32 merged in pairs, of 64, of
 # 128 as two steps) while every workgroup has a compute unit of its own: the three block sizes over the team sizes,
 # parts that are full, nearly empty (d = 516, 1028, 2052) and ragged, one column, the most columns a team size takes, n != d;
-# steps of 128 rows (two blocks of 64 joined through the product of their rows) where d is 769 .. 2048 and n a multiple
+# steps of 128 rows (two blocks of 64 joined through the product of their rows) where d is 513 .. 2048 and n a multiple
 # of 128: one to five steps (the kernel's loop takes three at a time), 4 to 8 parts, full, ragged and nearly empty
 # last parts, the most columns;
 # two workgroups per column with steps of 32 rows beyond that (d > 1024, up to 128 columns); and neighbours that stay
@@ -138,7 +138,7 @@ SHARED = [
     (2044, 96, 128, 32), (2048, 128, 65, 64), (1032, 256, 100, 128),
     (1024, 96, 7, 32), (2048, 64, 129, 32), (2048, 96, 16, 48),
     (1024, 256, 32, 32), (772, 128, 3, 32), (1792, 384, 9, 64), (2048, 512, 32, 128), (1280, 640, 2, 32), (900, 128, 64, 32),
-    (1024, 384, 64, 64), (2048, 256, 1, 32), (1284, 256, 42, 128), (1000, 512, 7, 64),
+    (1024, 384, 64, 64), (2048, 256, 1, 32), (1284, 256, 40, 128), (1000, 512, 7, 64),
 ]
 
 
