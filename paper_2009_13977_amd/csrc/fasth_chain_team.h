@@ -439,8 +439,6 @@ __global__ void __launch_bounds__(512) chain_team_wide_kernel(ChainArgs p) {
 
   unsigned steps_done = 0;
   auto apply_step = [&](int st, TeamRegs& cur, int sf, TeamRegs& dst) {
-    fetch_t(st);
-    __builtin_amdgcn_sched_barrier(0);
     // the input of the caller's block that this step starts with
     save_input(NSUB * st + (p.transpose ? 0 : NSUB - 1));
     float pj[KH];
@@ -455,6 +453,9 @@ __global__ void __launch_bounds__(512) chain_team_wide_kernel(ChainArgs p) {
       for (int r = 0; r < 4; ++r) acc = fmaf(cur.v[jj].e[r], a.e[r], acc);
       pj[jj] = acc;
     }
+    __builtin_amdgcn_sched_barrier(0);
+    fetch_t(st);
+    __builtin_amdgcn_sched_barrier(0);
     auto prefetch = [&](int tt) {
       if (tt % 4 == 0 && tt / 4 < RL) {
         __builtin_amdgcn_sched_barrier(0);

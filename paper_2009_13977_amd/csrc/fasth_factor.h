@@ -192,7 +192,7 @@ struct TeamFactorArgs {
   unsigned* xch;               // hand-off area of the chain kernels, cleared here
   unsigned xch_words;
   // For chain_team_wide_kernel (kp = 64 only): npair > 0 adds, per pair p of consecutive blocks, the product
-  // S_p = V_2p V_2p+1^T of their rows (workgroups blockIdx.y >= nblocks), and every matrix is stored in the order in
+  // S_p = V_2p V_2p+1^T of their rows (workgroups blockIdx.y < npair, the blocks' behind them), and every matrix is stored in the order in
   // which that kernel's threads read it.
   float* S;                    // [npair][2][kp][kp]: S_p, then its transpose
   int nblocks, npair;
@@ -212,9 +212,11 @@ __global__ void __launch_bounds__(8 * KP) team_factor_kernel(TeamFactorPair pair
   const int i = blockIdx.y, s = blockIdx.x;
   const int tid = threadIdx.x, nthreads = blockDim.x, wave = tid >> 6, nwaves = nthreads >> 6, lane = tid & 63;
   clear_exchange_area(p.xch, p.xch_words, blockIdx.y * gridDim.x + blockIdx.x, gridDim.x * gridDim.y);
-  // A workgroup beyond the blocks' forms a pair's product S = V_a V_b^T instead of a block's Gram matrix: the rows of
-  // both blocks (2 kp consecutive rows of V) in LDS, all kp / 16 squared tiles.
-  const bool pair_job = KP == 64 && i >= p.nblocks;
+  // The first npair rows of the grid form a pair's product S = V_a V_b^T instead of a block's Gram matrix: the rows of
+  // both blocks (2 kp consecutive rows of V) in LDS, all kp / 16 squared tiles. They come first because they fetch
+  // twice as much and are the last to start otherwise, when the launch has more workgroups than run at once.
+  const bool pair_job = KP == 64 && i < p.npair;
+  const int bi = i - p.npair;  // a block's workgroups: the block
   {
     float* Vs = smem;  // [kp][LD], a pair's [2 kp][LD]
     const int chunk = ((d + split - 1) / split + 3) & ~3;
@@ -227,8 +229,8 @@ __global__ void __launch_bounds__(8 * KP) team_factor_kernel(TeamFactorPair pair
 #pragma unroll
     for (int w = 0; w < kMaxTilesPerWave; ++w) acc[w] = f32x4{0.f, 0.f, 0.f, 0.f};
     // the block's k rows as one buffer: rows k .. kp - 1 of the padded block lie beyond it and read as zero
-    const BufferDesc vdesc = pair_job ? make_buffer(p.V + (size_t)(i - p.nblocks) * 2 * kp * d, (size_t)2 * kp * d * sizeof(float))
-                                      : make_buffer(p.V + (size_t)i * k * d, (size_t)k * d * sizeof(float));
+    const BufferDesc vdesc = pair_job ? make_buffer(p.V + (size_t)i * 2 * kp * d, (size_t)2 * kp * d * sizeof(float))
+                                      : make_buffer(p.V + (size_t)bi * k * d, (size_t)k * d * sizeof(float));
     constexpr int XV = kGramChunk / VEC;  // loads per slab row
     constexpr int PER1 = 16 / VEC;        // loads per thread and slab: kp XV / nthreads with nthreads = 8 kp
     constexpr int PER = KP == 64 ? 2 * PER1 : PER1;  // room for a pair's rows; a block's workgroups use the first half
@@ -367,7 +369,7 @@ __global__ void __launch_bounds__(8 * KP) team_factor_kernel(TeamFactorPair pair
   auto chain_order_row = [](int idx) { return 2 * (((idx >> 2) & 511) >> 4) + (idx >> 11); };
   auto chain_order_col = [](int idx) { return 4 * ((idx >> 2) & 15) + (idx & 3); };
   if (pair_job) {
-    float* Sp = p.S + (size_t)(i - p.nblocks) * 2 * kp * kp;
+    float* Sp = p.S + (size_t)i * 2 * kp * kp;
     for (int idx = tid; idx < kp * kp; idx += nthreads) {
       const int j = chain_order_row(idx), l = chain_order_col(idx);
       Sp[idx] = Ms[j * LDM + l];
@@ -378,7 +380,7 @@ __global__ void __launch_bounds__(8 * KP) team_factor_kernel(TeamFactorPair pair
   diag_scratch_fill(Ms, Xs, kp, LDM);
   invert_upper_lds<KP == 64>(Ms, Xs, kp, LDM);  // 512 threads have the registers to fetch a diagonal block at once
   // T_i and, nb factors further on, its transpose: a chain kernel then reads rows of op(T_i) in either direction
-  float* Ti = p.T + (size_t)i * kp * kp;
+  float* Ti = p.T + (size_t)bi * kp * kp;
   float* Tti = Ti + (size_t)p.nblocks * kp * kp;
   if (KP == 64 && p.npair > 0) {
     for (int idx = tid; idx < kp * kp; idx += nthreads) {
