@@ -64,8 +64,10 @@ const char* fasth_strerror(int code);
 /* Algorithm 1 Step 2 is sequential over the blocks, but the two products of a block can be shared between compute
  * units. With few columns of more than 512 elements (d <= 4096, a compute unit for every workgroup of the launch:
  * up to 128 columns at d <= 1024, 64 at d = 2048, 32 at d = 4096) two to eight workgroups share each column and hand each other
- * every step's partial inner products through the workspace, and the workgroup that merges two blocks' factors
- * waits for the workgroups that build them: one workgroup waits for another inside a kernel. Every such wait is
+ * every step's partial inner products through the workspace (steps of 128 rows, two blocks of 64 joined, where d <= 2048,
+ * n is a multiple of 128 and a workgroup per 256 elements fits; steps of 64 rows otherwise), and the workgroup that
+ * adds the partial matrices of a block's factor waits for the workgroups that form them: one workgroup waits for
+ * another inside a kernel. Every such wait is
  * bounded: after a number of polls (about a million, a fraction of a second; the wait itself takes a fraction of
  * a microsecond) the waiting wave gives up, raises a status word on the GPU and runs on, so a kernel always ends,
  * but its outputs are then wrong. fasth_wait_status waits for `stream`, reads and clears that word and returns
@@ -115,10 +117,11 @@ int fasth_apply(const fasth_shape* shape, const float* V, const float* X, float*
  * saved for a backward pass. The call allocates and frees nothing; its first use on a device looks up
  * the array's address. Shapes whose factors, partial Gram matrices and hand-off words need more than the array
  * holds (about 4 n kp (2 + min(16, ceil(d / 128))) bytes, kp = k rounded up to a power of two >= 16; for the
- * shapes of fasth_wait_status's comment kp = 64 also for k = 32, and up to 65 KiB more per column: 10 MiB at
- * d = n = 2048, m = 64) return FASTH_EUNSUPPORTED before any GPU call. Every call on one GPU uses the same array: calls that overlap
+ * shapes of fasth_wait_status's comment kp = 64 whatever k, half as much again where a step takes 128 rows, and up
+ * to 129 KiB more per column: 10 MiB at d = n = 2048, m = 64, 17.5 MiB at m = 32) return FASTH_EUNSUPPORTED before
+ * any GPU call. Every call on one GPU uses the same array: calls that overlap
  * on one GPU (different streams or threads) race; calls on one stream do not. */
-#define FASTH_STATIC_SCRATCH_BYTES (16u << 20)
+#define FASTH_STATIC_SCRATCH_BYTES (24u << 20)
 int fasth_forward_static(const fasth_shape* shape, const float* V, const float* X, float* A, void* stream);
 
 /* Algorithm 2. Given G = dL/dA [d][m], writes dX = dL/dX [d][m] and

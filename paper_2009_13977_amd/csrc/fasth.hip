@@ -11,9 +11,10 @@
 //
 // Kernels
 //   factor_fused_kernel  Algorithm 1 Step 1, one workgroup per block (block sizes up to 32; 64 for short vectors)
-//   team_factor_kernel   Algorithm 1 Step 1 with a block's Gram product split over workgroups (MFMA)
+//   team_factor_kernel   Algorithm 1 Step 1 with a block's Gram product split over workgroups (MFMA); also the products
+//                        V_a V_b^T of consecutive blocks' rows for the chain kernel that joins two blocks per step
 //   chain_*_kernel       Algorithm 1 Step 2 / Algorithm 2 Step 1: the sequential block chain: per column of X
-//                        (pair, pipe, general), a team of workgroups per column (team), or 4 / 16 columns per
+//                        (pair, pipe, general), a team of workgroups per column (team, team_wide), or 4 / 16 columns per
 //                        workgroup on the matrix cores (quad, tile)
 //   dv_kernel            Algorithm 2 Step 2 as dense products per block (MFMA)
 //   seq_*                the one-reflection-at-a-time comparison

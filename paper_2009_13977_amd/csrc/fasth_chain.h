@@ -523,7 +523,7 @@ static int launch_chain_pipe(const ChainArgs& args, hipStream_t stream) {
 #include "fasth_chain_tile.h"  // chain_tile_kernel: the same steps on the matrix cores, for wide mini-batches
 #include "fasth_chain_pair.h"  // chain_pair_kernel: the per-column chain with two waves per SIMD
 #include "fasth_chain_quad.h"  // chain_quad_kernel: four columns per workgroup on the matrix cores, 256 < m <= 1024
-#include "fasth_chain_team.h"  // chain_team_kernel: two to eight workgroups per column, steps of 64 rows, few columns
+#include "fasth_chain_team.h"  // chain_team_kernel, chain_team_wide_kernel: two to eight workgroups per column, steps of 64 or 128 rows, few columns
 
 namespace fasth {
 

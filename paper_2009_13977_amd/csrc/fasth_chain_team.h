@@ -1,5 +1,6 @@
 // Algorithm 1 Step 2 and Algorithm 2 Step 1 for few columns of 513 to 4096 elements: chain_team_kernel, in which a
-// team of two to eight workgroups shares a column and a step takes 64 rows.
+// team of two to eight workgroups shares a column and a step takes 64 rows, and chain_team_wide_kernel, in which the
+// parts are half as long and a step takes 128 rows.
 // Included by fasth_chain.h (the library has a single translation unit).
 #pragma once
 #include <hip/hip_runtime.h>

@@ -181,6 +181,13 @@ __device__ __forceinline__ void invert_upper_lds(float* Ms, float* Xs, int kp, i
 // Blocks of 32 rows that the team chain kernel applies in pairs are factored here as blocks of 64: by Lemma 1 the
 // product of two consecutive blocks is a WY block of 64 rows whose factor is the inverse of the 64 x 64 matrix
 // diag(S)/2 + striu(S), [[T1, -T1 S12 T2], [0, T2]] with the two blocks' own factors on its diagonal.
+// For the chain kernel that applies two blocks of 64 rows per step the same launch forms, per pair of consecutive
+// blocks a, b, the product of their rows S = V_a V_b^T (the S12 of Lemma 1, which that kernel applies between the two
+// factors instead of a merged factor of 128 rows): npair more rows of workgroups, first in the grid, which stage the
+// rows of both blocks, form all tiles of their share of d and hand them to the pair's first workgroup as a block's
+// workgroups do; no workgroup waits for a factor.
+// The leader fetches every group of four entries it owns from up to 16 / (KP / 32) partial matrices at once, so the
+// sum costs a trip to memory per eight (four) partial matrices, not one per group.
 // ------------------------------------------------------------------------------------------
 struct TeamFactorArgs {
   const float* V;              // [n][d]
