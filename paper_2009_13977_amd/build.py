@@ -16,7 +16,7 @@ ROOT = os.path.dirname(PKG_DIR)
 LIB_PATH = os.path.join(PKG_DIR, "libfasth.so")
 SOURCES = [os.path.join(PKG_DIR, "csrc", "fasth.hip")]
 HEADERS = [os.path.join(PKG_DIR, "csrc", h) for h in ("fasth_device.h", "fasth_common.h", "fasth_factor.h",
-                                                      "fasth_chain.h", "fasth_chain_tile.h", "fasth_chain_pair.h", "fasth_chain_quad.h", "fasth_chain_team.h", "fasth_dv.h",
+                                                      "fasth_chain.h", "fasth_chain_tile.h", "fasth_chain_pair.h", "fasth_chain_quad.h", "fasth_chain_team.h", "fasth_chain_teamtile.h", "fasth_dv.h",
                                                       "fasth_sequential.h", "fasth_peaks.h")]
 HEADERS.append(os.path.join(ROOT, "include", "fasth.h"))
 

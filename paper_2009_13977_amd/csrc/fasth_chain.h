@@ -524,17 +524,19 @@ static int launch_chain_pipe(const ChainArgs& args, hipStream_t stream) {
 #include "fasth_chain_pair.h"  // chain_pair_kernel: the per-column chain with two waves per SIMD
 #include "fasth_chain_quad.h"  // chain_quad_kernel: four columns per workgroup on the matrix cores, 256 < m <= 1024
 #include "fasth_chain_team.h"  // chain_team_kernel, chain_team_wide_kernel: two to eight workgroups per column, steps of 64 or 128 rows, few columns
+#include "fasth_chain_teamtile.h"  // chain_team_tile_kernel: 16 columns per two to four workgroups on the matrix cores, some hundred columns
 
 namespace fasth {
 
 // chain_pipe_kernel serves every d up to 4096; it also takes the side product along.
 static bool chain_uses_pipe(const ChainArgs& a) {
-  return !chain_uses_tile(a) && !chain_uses_quad(a) && !chain_uses_team_wide(a) && !chain_uses_team(a) && !chain_uses_split_pair(a) && a.d <= 4096;
+  return !chain_uses_tile(a) && !chain_uses_quad(a) && !chain_uses_team_tile(a) && !chain_uses_team_wide(a) && !chain_uses_team(a) && !chain_uses_split_pair(a) && a.d <= 4096;
 }
-static bool chain_takes_side_product(const ChainArgs& a) { return chain_uses_pipe(a) || chain_uses_team(a) || chain_uses_team_wide(a); }
+static bool chain_takes_side_product(const ChainArgs& a) { return chain_uses_pipe(a) || chain_uses_team(a) || chain_uses_team_wide(a) || chain_uses_team_tile(a); }
 
 static int launch_chain_kernel(const ChainArgs& a, hipStream_t stream) {
   const int d = a.d, k = a.k;
+  if (chain_uses_team_tile(a)) return launch_chain_team_tile(a, stream);
   if (chain_uses_tile(a)) return launch_chain_tile(a, stream);
   if (chain_uses_quad(a)) return launch_chain_quad(a, stream);
   if (chain_uses_team_wide(a)) return launch_chain_team_wide(a, stream);
