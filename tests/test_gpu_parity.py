@@ -102,10 +102,16 @@ WIDE = [
     (125, 128, 800, 64), (125, 256, 800, 128),  # odd d: per-column chain in rounds, dV with 4-byte fetches reading Z
     # more columns than compute units, fewer than the matrix-core kernel takes: 16-row steps, several workgroups per unit
     (1024, 64, 300, 32), (768, 128, 260, 64), (1024, 128, 780, 128), (1024, 32, 1024, 32), (516, 96, 770, 32),
-    # 769 .. 1024 columns at 512 < d <= 1024 (from 608 at d > 896): four columns per workgroup on the matrix cores;
+    # 449 .. 1024 columns at 512 < d <= 1024 (897 .. 2048 at 256 < d <= 512) with blocks of 32 (an even number), 64 or 128:
+    # tiles of 16 columns on the matrix cores, each shared by two to four workgroups; other block sizes from 769
+    # columns on (608 at d > 896): four columns per workgroup on the matrix cores;
     # one and several steps per block, ragged d and m, n != d; and neighbours that stay with the per-column kernels
     (1024, 64, 800, 32), (1000, 128, 771, 64), (640, 256, 1023, 128), (900, 64, 610, 32), (516, 64, 1024, 32),
     (1024, 96, 900, 96), (768, 64, 768, 32), (1024, 64, 607, 32),
+    # the shared tiles again: the fewest and the most columns, two, three and four parts, a last part of 4 and of 44
+    # elements, one to four steps, two steps per block of 128, a ragged last tile
+    (1024, 128, 449, 32), (1024, 256, 1024, 64), (512, 128, 2048, 32), (300, 64, 1000, 64), (512, 256, 897, 128),
+    (1020, 192, 500, 64), (768, 64, 1280, 32), (600, 128, 999, 128), (1024, 64, 448, 32),
 ]
 
 
@@ -156,7 +162,7 @@ def test_fasth_shared_columns(d, n, m, k, transpose):
     assert_close(dV, dV0, "dV", rows=True)
 
 
-@pytest.mark.parametrize("d,n,m,k", [(2048, 64, 16, 32), (1024, 256, 16, 32)])  # steps of 64 rows, of 128
+@pytest.mark.parametrize("d,n,m,k", [(2048, 64, 16, 32), (1024, 256, 16, 32), (768, 128, 500, 64)])  # steps of 64 rows, of 128; shared tiles
 def test_shared_columns_wait_gives_up_and_recovers(d, n, m, k):
     """A wait between the workgroups of a column that runs out of polls ends the kernel normally and raises the
     status word; the next call with the ordinary limit is correct again. The limit is forced to zero from the host,
@@ -188,7 +194,7 @@ def test_shared_columns_wait_gives_up_and_recovers(d, n, m, k):
     assert_close(dV.cpu().numpy(), dV0, "dV", rows=True)
 
 
-@pytest.mark.parametrize("d,n,m,k", [(1024, 128, 8, 32), (2048, 128, 5, 64), (1536, 256, 3, 128), (2048, 64, 100, 32)])
+@pytest.mark.parametrize("d,n,m,k", [(1024, 128, 8, 32), (2048, 128, 5, 64), (1536, 256, 3, 128), (2048, 64, 100, 32), (1024, 128, 450, 32)])
 def test_shared_columns_captured_and_replayed(d, n, m, k):
     """Forward + backward captured into a HIP graph and replayed with new V, X and G each time, with eager work on the
     same workspace in between: the tags of the hand-offs count on in the workspace, the ready words of the factor
@@ -275,6 +281,19 @@ def test_shared_columns_in_the_layers():
         assert_close(g, r, name, rows=name == "dUv")
     _say("shared columns, steps of 128 rows: rectangular layer 1024 x 900")
     p = synthetic.rect_layer_problem(1024, 900, 128, 128, 5, seed=6410)
+    got = gpu_svd_rect(p["Uv"], p["sigma"], p["Vv"], p["X"], p["G"], 32)
+    for name, g, r in zip(("Y", "dUv", "dsigma", "dVv", "dX"), got,
+                          orc.rectangular_gradients(p["Uv"], p["sigma"], p["Vv"], p["X"], p["G"])):
+        assert_close(g, r, name, rows=name.startswith("d") and name.endswith("v"))
+    _say("shared tiles of 16 columns: svd layer d=768, 512 columns")
+    p = synthetic.svd_layer_problem(768, 128, 512, seed=6220)
+    for inverse in (False, True):
+        got = gpu_svd_layer(p["Uv"], p["sigma"], p["Vv"], p["X"], p["G"], 64, inverse)
+        fn = orc.svd_layer_inverse_gradients if inverse else orc.svd_layer_gradients
+        for name, g, r in zip(("Y", "dUv", "dsigma", "dVv", "dX"), got, fn(p["Uv"], p["sigma"], p["Vv"], p["X"], p["G"])):
+            assert_close(g, r, name, rows=name.startswith("d") and name.endswith("v"))
+    _say("shared tiles of 16 columns: rectangular layer 1024 x 600, 460 columns")
+    p = synthetic.rect_layer_problem(1024, 600, 128, 64, 460, seed=6420)
     got = gpu_svd_rect(p["Uv"], p["sigma"], p["Vv"], p["X"], p["G"], 32)
     for name, g, r in zip(("Y", "dUv", "dsigma", "dVv", "dX"), got,
                           orc.rectangular_gradients(p["Uv"], p["sigma"], p["Vv"], p["X"], p["G"])):
