@@ -19,8 +19,11 @@ namespace fasth {
 // part forms its share over its 256 elements; the parts hand each other their shares through the workspace (each
 // to every other, 16-byte words {sum, tag, sum, tag}, tagged and bounded as in chain_team_kernel), add them in the
 // order of the parts, and every part forms C = op(T) B (four matrix-core tiles) and updates its rows of A.
+// For columns of 1025 to 2048 elements the parts are 512 elements long and a step takes 32 rows (the same registers
+// and LDS; blocks of more rows as several steps with the diagonal 32 x 32 blocks of their factor).
 //
-// Lanes. Wave w of the 8 owns 32 elements x_w .. x_w + 31 of the part's 256 as two accumulator tiles r = 0, 1:
+// Lanes (for parts of 256 elements: NT = 2 accumulator tiles per wave; parts of 512 have NT = 4, 16 NT elements per
+// wave likewise). Wave w of the 8 owns 32 elements x_w .. x_w + 31 of the part's 256 as two accumulator tiles r = 0, 1:
 // register j of lane (q, i) = (lane / 16, lane % 16) of tile r holds A(x_w + 8 q + 2 j + r, column i). A contraction
 // may run over x in any order, so this layout serves as the B operand of the first product (matrix instruction
 // (j, r) sums over the four x with the lanes' q) and is the output layout of the second (output row 4 q + j of
@@ -31,27 +34,29 @@ namespace fasth {
 // the waves' shares of B meet in LDS (and go out to the other parts), the totals come back into LDS in the layout
 // the matrix cores want, and C goes from the four waves that form it to all eight.
 // ------------------------------------------------------------------------------------------
-constexpr int kTtCols = 16;    // columns per team
-constexpr int kTtRows = 64;    // rows of V per step
-constexpr int kTtSlice = 256;  // elements of the columns per workgroup
-constexpr int kTtLd = 34;      // row stride of a wave's rows in LDS (floats): 8-byte reads of 16 rows hit 16 bank pairs
-constexpr size_t kTtLdsFloats = (size_t)8 * kTtRows * kTtLd + 8 * 1024 + 1024 + 2 * 1024;
+constexpr int kTtCols = 16;  // columns per team
+// NT accumulator tiles (16 NT elements) per wave: 128 NT elements per workgroup, 128 / NT rows per step; row stride of a
+// wave's rows in LDS 34 floats (8-byte reads of 16 rows hit 16 bank pairs) or 68 (16-byte reads, aligned)
+constexpr size_t kTtLdsFloats = (size_t)8 * 64 * 34 + 8 * 1024 + 1024 + 2 * 1024;
+static_assert(8 * 32 * 68 == 8 * 64 * 34, "the rows of a step take the same room in both forms");
 
-// KMODE 0: caller's blocks of 32 rows, two per step (factors stored as 64 x 64 blocks); 1: blocks of 64; 2: blocks of
-// 128, two steps per block. The number of parts is p.parts.
-template <int KMODE>
+// NT = 2: parts of 256 elements, steps of 64 rows; p.sub = 0: the caller's blocks of 32 rows two per step (factors stored
+// as 64 x 64 blocks), else steps per block (1 or 2). NT = 4: parts of 512 elements, steps of 32 rows, p.sub = 1, 2 or 4
+// steps per block. LDT: rows of a stored factor. The number of parts is p.parts.
+template <int NT, int LDT>
 __global__ void __launch_bounds__(512) chain_team_tile_kernel(ChainArgs p) {
   const int NP = p.parts;  // 2 .. 4
-  constexpr int K = kTtRows, LD = kTtLd, LDT = KMODE == 2 ? 128 : 64;
+  constexpr int K = 128 / NT, RT = K / 16, LD = NT == 2 ? 34 : 68, XW = 16 * NT, SLICE = 8 * XW, F = 4 * NT;
+  constexpr int E = RT * 256;  // entries of B per step
   extern __shared__ __align__(16) float smem[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int q = lane >> 4, i = lane & 15;
   float* Vs = smem + (size_t)wave * K * LD;  // this wave's 32 columns of the step's rows: [64][LD]
-  float* Bp = smem + (size_t)8 * K * LD;     // the waves' shares of B: [8][1024], element (row 16 rt + 4 q + jj, column i)
+  float* Bp = smem + (size_t)8 * K * LD;     // the waves' shares of B: [8][E], element (row 16 rt + 4 q + jj, column i)
                                              // of a wave at ((rt * 64 + lane) * 4 + jj)
-  float* Btot = Bp + 8 * 1024;               // B summed over waves and parts, [64][16]
-  float* Cs = Btot + 1024;                   // C in two shares (one per half of the inner index), [2][64][16]
+  float* Btot = Bp + 8 * 1024;               // B summed over waves and parts, [K][16]
+  float* Cs = Btot + 1024;                   // C in two shares (one per half of the inner index), [2][K][16] (second share at 1024)
   const int m = p.m, d = p.d, n = p.n;
   const int tiles = (m + kTtCols - 1) / kTtCols;
   // workgroups b, b + 8, ... (one XCD) are the parts of tile 8 (b / (8 NP)) + b % 8
@@ -66,17 +71,17 @@ __global__ void __launch_bounds__(512) chain_team_tile_kernel(ChainArgs p) {
   if (tile >= tiles) return;
   const int col = tile * kTtCols + i;
   const bool col_ok = col < m;
-  const int x_w = part * kTtSlice + 32 * wave;  // this wave's first element
+  const int x_w = part * SLICE + XW * wave;  // this wave's first element
 
   // the input tile: rows beyond those that exist and columns beyond m read as zero
-  f32x4 A[2];
+  f32x4 A[NT];
   {
     const BufferDesc xdesc = make_buffer(p.in, (size_t)p.in_rows * m * sizeof(float));
 #pragma unroll
-    for (int r = 0; r < 2; ++r) {
+    for (int r = 0; r < NT; ++r) {
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
-        const int x = x_w + 8 * q + 2 * j + r;
+        const int x = x_w + F * q + NT * j + r;
         const unsigned off = col_ok && x < p.in_rows ? ((unsigned)x * (unsigned)m + (unsigned)col) * 4u : kOob;
         A[r][j] = buffer_load<1>(xdesc, off, 0).e[0];
       }
@@ -85,18 +90,18 @@ __global__ void __launch_bounds__(512) chain_team_tile_kernel(ChainArgs p) {
       // all fetches first, then the mode as a compile-time constant: rows that do not exist hold zero in A already;
       // their sigma is replaced by 1 so that the factor stays finite
       const BufferDesc sdesc = make_buffer(p.in_scale, (size_t)p.in_rows * sizeof(float));
-      f32x4 sg[2];
+      f32x4 sg[NT];
 #pragma unroll
-      for (int r = 0; r < 2; ++r) {
+      for (int r = 0; r < NT; ++r) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) sg[r][j] = buffer_load<1>(sdesc, (unsigned)(x_w + 8 * q + 2 * j + r) * 4u, 0).e[0];
+        for (int j = 0; j < 4; ++j) sg[r][j] = buffer_load<1>(sdesc, (unsigned)(x_w + F * q + NT * j + r) * 4u, 0).e[0];
       }
       auto scale_rows = [&](auto mode) {
 #pragma unroll
-        for (int r = 0; r < 2; ++r) {
+        for (int r = 0; r < NT; ++r) {
 #pragma unroll
           for (int j = 0; j < 4; ++j) {
-            const float sv = x_w + 8 * q + 2 * j + r < p.in_rows ? sg[r][j] : 1.f;
+            const float sv = x_w + F * q + NT * j + r < p.in_rows ? sg[r][j] : 1.f;
             A[r][j] *= diag_factor(decltype(mode)::value, sv);
           }
         }
@@ -121,43 +126,58 @@ __global__ void __launch_bounds__(512) chain_team_tile_kernel(ChainArgs p) {
     __builtin_amdgcn_raw_buffer_store_b64(w, hdesc, 32u + (unsigned)part * 8u, 0, 16);
   }
 
-  // staging of a step's 64 rows: lane l fetches 16 bytes at x = x_w + 4 (l % 8) of rows 8 u + l / 8
+  // staging of a step's rows: lane l fetches 16 bytes at x = x_w + 4 (l % F) of rows (64 / F) u + l / F, u < 8
   const BufferDesc vdesc = make_buffer(p.V, (size_t)n * d * sizeof(float));
-  const int srow = lane >> 3, sx = x_w + 4 * (lane & 7);
+  const int srow = lane / F, sx = x_w + 4 * (lane % F);
   const unsigned stage_off = sx < d ? ((unsigned)srow * (unsigned)d + (unsigned)sx) * 4u : kOob;
   BufVec<4> stage[8];
   auto fetch_rows = [&](int row0) {
 #pragma unroll
-    for (int u = 0; u < 8; ++u) stage[u] = buffer_load<4>(vdesc, stage_off, (unsigned)(row0 + 8 * u) * (unsigned)d * 4u);
+    for (int u = 0; u < 8; ++u) stage[u] = buffer_load<4>(vdesc, stage_off, (unsigned)(row0 + (64 / F) * u) * (unsigned)d * 4u);
   };
   auto stash_rows = [&]() {
 #pragma unroll
     for (int u = 0; u < 8; ++u) {
-      float* dst = Vs + (8 * u + srow) * LD + 4 * (lane & 7);
-      *reinterpret_cast<float2*>(dst) = make_float2(stage[u].e[0], stage[u].e[1]);
-      *reinterpret_cast<float2*>(dst + 2) = make_float2(stage[u].e[2], stage[u].e[3]);
+      float* dst = Vs + ((64 / F) * u + srow) * LD + 4 * (lane % F);
+      if constexpr (NT == 4) {
+        *reinterpret_cast<float4*>(dst) = make_float4(stage[u].e[0], stage[u].e[1], stage[u].e[2], stage[u].e[3]);
+      } else {
+        *reinterpret_cast<float2*>(dst) = make_float2(stage[u].e[0], stage[u].e[1]);
+        *reinterpret_cast<float2*>(dst + 2) = make_float2(stage[u].e[2], stage[u].e[3]);
+      }
     }
   };
-  // op(T) of step st as the A operand of C = op(T) B. Wave w forms rows 16 (w % 4) .. + 15 of C from half w / 4 of the
-  // inner index, 8 matrix instructions; instruction kk sums over the inner indices 32 (w / 4) + 8 q + kk (the sum may
-  // run in any order), so lane (q, i) needs 8 consecutive entries of its row: two 16-byte fetches.
-  auto fetch_t = [&](int st, float (&t)[8]) {
+  // op(T) of step st as the A operand of C = op(T) B. Wave w < 2 RT forms rows 16 (w % RT) .. + 15 of C from half w / RT
+  // of the inner index, K / 8 matrix instructions; instruction kk sums over the inner indices
+  // (K / 2) (w / RT) + (K / 8) q + kk (the sum may run in any order), so lane (q, i) needs K / 8 consecutive entries of
+  // its row. (The other waves fetch what wave w % (2 RT) does and do not use it: no branch.)
+  constexpr int TN = K / 8;
+  const int crt = wave % RT, chalf = (wave / RT) & 1;
+  const int sub = p.sub;  // steps per block; 0: two blocks per step
+  auto fetch_t = [&](int st, float (&t)[TN]) {
     const float* opT = p.transpose ? p.Tt : p.T;
-    const float* Ts = KMODE == 2 ? opT + (size_t)(st >> 1) * LDT * LDT + (size_t)(st & 1) * (K * LDT + K)
-                                 : opT + (size_t)st * LDT * LDT;
-    const float4* src = reinterpret_cast<const float4*>(Ts + (16 * (wave & 3) + i) * LDT + 32 * (wave >> 2) + 8 * q);
-    const float4 t0 = src[0], t1 = src[1];
-    t[0] = t0.x; t[1] = t0.y; t[2] = t0.z; t[3] = t0.w; t[4] = t1.x; t[5] = t1.y; t[6] = t1.z; t[7] = t1.w;
+    const int blk = sub > 1 ? st / sub : st, prt = sub > 1 ? st % sub : 0;
+    const float* Ts = opT + (size_t)blk * LDT * LDT + (size_t)prt * (K * LDT + K);
+    const float4* src = reinterpret_cast<const float4*>(Ts + (16 * crt + i) * LDT + (K / 2) * chalf + TN * q);
+#pragma unroll
+    for (int g = 0; g < TN / 4; ++g) {
+      const float4 v = src[g];
+      t[4 * g] = v.x; t[4 * g + 1] = v.y; t[4 * g + 2] = v.z; t[4 * g + 3] = v.w;
+    }
   };
-  // A lane's eight elements of column i are 32 contiguous bytes of the saved input
+  // A lane's 4 NT elements of column i are contiguous in the saved input
   auto save_input = [&](int block) {
     if (!p.save_in) return;
     const BufferDesc adesc = make_buffer(p.save_in + (size_t)block * m * d, (size_t)m * d * sizeof(float));
-    const int x = x_w + 8 * q;
+    const int x = x_w + F * q;
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
+    for (int h = 0; h < NT; ++h) {
       BufVec<4> v;
-      v.e[0] = A[0][2 * h]; v.e[1] = A[1][2 * h]; v.e[2] = A[0][2 * h + 1]; v.e[3] = A[1][2 * h + 1];
+      if constexpr (NT == 4) {
+        v.e[0] = A[0][h]; v.e[1] = A[1][h]; v.e[2] = A[2][h]; v.e[3] = A[3][h];
+      } else {
+        v.e[0] = A[0][2 * h]; v.e[1] = A[1][2 * h]; v.e[2] = A[0][2 * h + 1]; v.e[3] = A[1][2 * h + 1];
+      }
       const unsigned off = col_ok && x + 4 * h < d ? ((unsigned)col * (unsigned)d + (unsigned)(x + 4 * h)) * 4u : kOob;
       buffer_store<4>(adesc, off, 0, v);
     }
@@ -165,7 +185,7 @@ __global__ void __launch_bounds__(512) chain_team_tile_kernel(ChainArgs p) {
 
   const int ns = n / K;
   auto step_of = [&](int s) { return p.transpose ? s : ns - 1 - s; };
-  float tcur[8], tnxt[8];
+  float tcur[TN], tnxt[TN];
   fetch_rows(step_of(0) * K);
   fetch_t(step_of(0), tcur);
   stash_rows();
@@ -187,30 +207,39 @@ __global__ void __launch_bounds__(512) chain_team_tile_kernel(ChainArgs p) {
     fetch_rows(stn * K);
     fetch_t(stn, tnxt);
     // the input of the caller's block that this step starts with
-    if constexpr (KMODE == 0) save_input(2 * st + (p.transpose ? 0 : 1));
-    else if constexpr (KMODE == 1) save_input(st);
-    else if ((st & 1) == (p.transpose ? 0 : 1)) save_input(st >> 1);
+    if (sub == 0) save_input(2 * st + (p.transpose ? 0 : 1));
+    else if (st % sub == (p.transpose ? 0 : sub - 1)) save_input(st / sub);
     // this wave's share of B = V_rows A: rows 16 rt .. 16 rt + 15 in acc[rt]
-    f32x4 acc[4];
+    f32x4 acc[RT];
 #pragma unroll
-    for (int rt = 0; rt < 4; ++rt) {
+    for (int rt = 0; rt < RT; ++rt) {
       acc[rt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
-        const float2 v = *reinterpret_cast<const float2*>(Vs + (16 * rt + i) * LD + 8 * q + 2 * j);
-        acc[rt] = __builtin_amdgcn_mfma_f32_16x16x4f32(v.x, A[0][j], acc[rt], 0, 0, 0);
-        acc[rt] = __builtin_amdgcn_mfma_f32_16x16x4f32(v.y, A[1][j], acc[rt], 0, 0, 0);
+        const float* vp = Vs + (16 * rt + i) * LD + F * q + NT * j;
+        if constexpr (NT == 4) {
+          const float4 v = *reinterpret_cast<const float4*>(vp);
+          acc[rt] = __builtin_amdgcn_mfma_f32_16x16x4f32(v.x, A[0][j], acc[rt], 0, 0, 0);
+          acc[rt] = __builtin_amdgcn_mfma_f32_16x16x4f32(v.y, A[1][j], acc[rt], 0, 0, 0);
+          acc[rt] = __builtin_amdgcn_mfma_f32_16x16x4f32(v.z, A[2][j], acc[rt], 0, 0, 0);
+          acc[rt] = __builtin_amdgcn_mfma_f32_16x16x4f32(v.w, A[3][j], acc[rt], 0, 0, 0);
+        } else {
+          const float2 v = *reinterpret_cast<const float2*>(vp);
+          acc[rt] = __builtin_amdgcn_mfma_f32_16x16x4f32(v.x, A[0][j], acc[rt], 0, 0, 0);
+          acc[rt] = __builtin_amdgcn_mfma_f32_16x16x4f32(v.y, A[1][j], acc[rt], 0, 0, 0);
+        }
       }
     }
 #pragma unroll
-    for (int rt = 0; rt < 4; ++rt) *reinterpret_cast<f32x4*>(Bp + ((size_t)(wave * 4 + rt) * 64 + lane) * 4) = acc[rt];
+    for (int rt = 0; rt < RT; ++rt) *reinterpret_cast<f32x4*>(Bp + ((size_t)(wave * RT + rt) * 64 + lane) * 4) = acc[rt];
     lds_barrier();
-    {
-      // thread t adds entries 2 t, 2 t + 1 of the eight waves' shares, sends the sums to the other parts, receives theirs
+    if (2 * tid < E) {
+      // thread t < E / 2 adds entries 2 t, 2 t + 1 of the eight waves' shares, sends the sums to the other parts, receives
+      // theirs (whole waves: E / 2 is a multiple of 64)
       float2 own = *reinterpret_cast<const float2*>(Bp + 2 * tid);
 #pragma unroll
       for (int w = 1; w < 8; ++w) {
-        const float2 o = *reinterpret_cast<const float2*>(Bp + w * 1024 + 2 * tid);
+        const float2 o = *reinterpret_cast<const float2*>(Bp + w * E + 2 * tid);
         own.x += o.x; own.y += o.y;
       }
       const unsigned tag = tag0 + 1u + (unsigned)s, par = (unsigned)s & 1u;
@@ -263,50 +292,59 @@ __global__ void __launch_bounds__(512) chain_team_tile_kernel(ChainArgs p) {
       Btot[(row + 1) * 16 + c] = total.y;
     }
     lds_barrier();
-    {
-      // this wave's share of C: rows 16 (w % 4) .., inner indices 32 (w / 4) ..; the two shares of a row meet when they are read
+    if (wave < 2 * RT) {
+      // this wave's share of C: rows 16 (w % RT) .., half w / RT of the inner index; the two shares of a row meet when they are read
       f32x4 C0 = {0.f, 0.f, 0.f, 0.f}, C1 = {0.f, 0.f, 0.f, 0.f};
-      const float* bsrc = Btot + (32 * (wave >> 2) + 8 * q) * 16 + i;
+      const float* bsrc = Btot + ((K / 2) * chalf + TN * q) * 16 + i;
 #pragma unroll
-      for (int kk = 0; kk < 8; kk += 2) {
+      for (int kk = 0; kk < TN; kk += 2) {
         C0 = __builtin_amdgcn_mfma_f32_16x16x4f32(tcur[kk], bsrc[kk * 16], C0, 0, 0, 0);
         C1 = __builtin_amdgcn_mfma_f32_16x16x4f32(tcur[kk + 1], bsrc[(kk + 1) * 16], C1, 0, 0, 0);
       }
       const f32x4 C = C0 + C1;
-      float* cdst = Cs + (wave >> 2) * 1024 + (16 * (wave & 3) + 4 * q) * 16 + i;
+      float* cdst = Cs + chalf * 1024 + (16 * crt + 4 * q) * 16 + i;
 #pragma unroll
       for (int jj = 0; jj < 4; ++jj) cdst[jj * 16] = C[jj];
     }
     lds_barrier();
-    if (p.save_c && part == 0 && wave < 4) {
+    if (p.save_c && part == 0 && wave < RT) {
       // wave w saves rows 16 w .. 16 w + 15 of C: lane (q, i) rows 4 q .. 4 q + 3 of column i
       float c4[4];
 #pragma unroll
       for (int jj = 0; jj < 4; ++jj) c4[jj] = Cs[(16 * wave + 4 * q + jj) * 16 + i] + Cs[1024 + (16 * wave + 4 * q + jj) * 16 + i];
       if (col_ok) *reinterpret_cast<float4*>(p.save_c + (size_t)col * n + (size_t)st * K + 16 * wave + 4 * q) = make_float4(c4[0], c4[1], c4[2], c4[3]);
     }
-    // A -= V_rows^T C, the half of the step that is applied first before the other (rows 32 .. 63 first in the plain order)
+    // A -= V_rows^T C, the half of the step that is applied first before the other (the later rows first in the plain order)
 #pragma unroll
     for (int hh = 0; hh < 2; ++hh) {
       const int half = p.transpose ? hh : 1 - hh;
 #pragma unroll
-      for (int rr = 0; rr < 2; ++rr) {
-        const int rt = 2 * half + rr;
+      for (int rr = 0; rr < RT / 2; ++rr) {
+        const int rt = (RT / 2) * half + rr;
 #pragma unroll
         for (int s2 = 0; s2 < 4; ++s2) {
           const int row = 16 * rt + 4 * q + s2;
           const float cneg = -(Cs[row * 16 + i] + Cs[1024 + row * 16 + i]);
-          const float2 v = *reinterpret_cast<const float2*>(Vs + row * LD + 2 * i);
-          A[0] = __builtin_amdgcn_mfma_f32_16x16x4f32(v.x, cneg, A[0], 0, 0, 0);
-          A[1] = __builtin_amdgcn_mfma_f32_16x16x4f32(v.y, cneg, A[1], 0, 0, 0);
+          const float* vp = Vs + row * LD + NT * i;
+          if constexpr (NT == 4) {
+            const float4 v = *reinterpret_cast<const float4*>(vp);
+            A[0] = __builtin_amdgcn_mfma_f32_16x16x4f32(v.x, cneg, A[0], 0, 0, 0);
+            A[1] = __builtin_amdgcn_mfma_f32_16x16x4f32(v.y, cneg, A[1], 0, 0, 0);
+            A[2] = __builtin_amdgcn_mfma_f32_16x16x4f32(v.z, cneg, A[2], 0, 0, 0);
+            A[3] = __builtin_amdgcn_mfma_f32_16x16x4f32(v.w, cneg, A[3], 0, 0, 0);
+          } else {
+            const float2 v = *reinterpret_cast<const float2*>(vp);
+            A[0] = __builtin_amdgcn_mfma_f32_16x16x4f32(v.x, cneg, A[0], 0, 0, 0);
+            A[1] = __builtin_amdgcn_mfma_f32_16x16x4f32(v.y, cneg, A[1], 0, 0, 0);
+          }
         }
       }
-      // blocks of 32: the state between the halves is the input of the pair's other block
-      if (KMODE == 0 && hh == 0) save_input(2 * st + (p.transpose ? 1 : 0));
+      // two blocks of 32 in a step of 64: the state between the halves is the input of the pair's other block
+      if (sub == 0 && hh == 0) save_input(2 * st + (p.transpose ? 1 : 0));
     }
     stash_rows();
 #pragma unroll
-    for (int kk = 0; kk < 8; ++kk) tcur[kk] = tnxt[kk];
+    for (int kk = 0; kk < TN; ++kk) tcur[kk] = tnxt[kk];
   }
   // the next launch on this workspace counts on from here
   if (part == 0 && tid == 0) __builtin_amdgcn_raw_buffer_store_b32(tag0 + (unsigned)ns, hdesc, 0u, 0, 16);
@@ -314,10 +352,10 @@ __global__ void __launch_bounds__(512) chain_team_tile_kernel(ChainArgs p) {
   {
     const BufferDesc odesc = make_buffer(p.out, (size_t)d * m * sizeof(float));
 #pragma unroll
-    for (int r = 0; r < 2; ++r) {
+    for (int r = 0; r < NT; ++r) {
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
-        const int x = x_w + 8 * q + 2 * j + r;
+        const int x = x_w + F * q + NT * j + r;
         BufVec<1> v;
         v.e[0] = A[r][j];
         buffer_store<1>(odesc, col_ok && x < d ? ((unsigned)x * (unsigned)m + (unsigned)col) * 4u : kOob, 0, v);
@@ -332,25 +370,33 @@ static int launch_chain_team_tile(const ChainArgs& args, hipStream_t stream) {
   ChainArgs a = args;
   a.parts = team_tile_parts(a.d, a.n, a.m, a.k);
   if (a.parts == 0 || !a.xch) return FASTH_EINVAL;
-  const int kmode = a.k == 32 ? 0 : a.k == 64 ? 1 : 2;
+  const bool longer = a.d > 1024;  // parts of 512 elements, steps of 32 rows
+  // steps per block (0: two of the caller's blocks of 32 per step of 64 rows) and rows of a stored factor
+  a.sub = longer ? a.k / 32 : a.k == 32 ? 0 : a.k / 64;
+  const int ldt = longer ? a.k : a.k == 128 ? 128 : 64;
   const size_t lds = kTtLdsFloats * sizeof(float);
-  int rc = kmode == 0 ? allow_lds(chain_team_tile_kernel<0>, lds)
-         : kmode == 1 ? allow_lds(chain_team_tile_kernel<1>, lds) : allow_lds(chain_team_tile_kernel<2>, lds);
-  if (rc != FASTH_OK) return rc;
-  static const std::vector<std::string> names = [] {
-    std::vector<std::string> v;
-    for (int np = 2; np <= 4; ++np)
-      for (int km = 0; km < 3; ++km)
-        v.push_back(variant_name("chain_team_tile_kernel", {km}) + " (" + std::to_string(np) + " parts)");
-    return v;
-  }();
-  prof::Scope ps_(FASTH_KERNEL_CHAIN, stream, names[(a.parts - 2) * 3 + kmode].c_str());
   const int side = a.ds_out ? (a.ds_rows + 7) / 8 : 0;
   const int tiles = (a.m + kTtCols - 1) / kTtCols;
   const dim3 grid(8 * a.parts * ((tiles + 7) / 8) + side), block(512);
-  if (kmode == 0) hipLaunchKernelGGL(chain_team_tile_kernel<0>, grid, block, lds, stream, a);
-  else if (kmode == 1) hipLaunchKernelGGL(chain_team_tile_kernel<1>, grid, block, lds, stream, a);
-  else hipLaunchKernelGGL(chain_team_tile_kernel<2>, grid, block, lds, stream, a);
+#define FASTH_LAUNCH_TT(NT_, LDT_)                                                                                   \
+  do {                                                                                                               \
+    int rc_ = allow_lds(chain_team_tile_kernel<NT_, LDT_>, lds);                                                     \
+    if (rc_ != FASTH_OK) return rc_;                                                                                 \
+    static const std::string names_[3] = {variant_name("chain_team_tile_kernel", {NT_, LDT_}) + " (2 parts)",         \
+                                          variant_name("chain_team_tile_kernel", {NT_, LDT_}) + " (3 parts)",         \
+                                          variant_name("chain_team_tile_kernel", {NT_, LDT_}) + " (4 parts)"};        \
+    prof::Scope ps_(FASTH_KERNEL_CHAIN, stream, names_[a.parts - 2].c_str());                                        \
+    hipLaunchKernelGGL((chain_team_tile_kernel<NT_, LDT_>), grid, block, lds, stream, a);                            \
+  } while (0)
+  if (!longer) {
+    if (ldt == 64) FASTH_LAUNCH_TT(2, 64);
+    else FASTH_LAUNCH_TT(2, 128);
+  } else {
+    if (ldt == 32) FASTH_LAUNCH_TT(4, 32);
+    else if (ldt == 64) FASTH_LAUNCH_TT(4, 64);
+    else FASTH_LAUNCH_TT(4, 128);
+  }
+#undef FASTH_LAUNCH_TT
   FASTH_HIP(hipGetLastError());
   return FASTH_OK;
 }

@@ -100,24 +100,29 @@ static int team_parts(int d, int n, int m, int k) {
 }
 
 // chain_team_tile_kernel: tiles of 16 columns on the matrix cores, each shared by a team of ceil(d / 256) workgroups
-// (2 to 4), steps of 64 rows: for mini-batches of FASTH_TEAM_TILE_MIN_COLS columns and more (d > 512; ..._SHORT for
+// (2 to 4; ceil(d / 512) for d > 1024), steps of 64 rows (32 for d > 1024): for mini-batches of FASTH_TEAM_TILE_MIN_COLS columns and more (d > 512; ..._SHORT for
 // shorter columns), as long as every
 // workgroup has a compute unit on its team's XCD. Parts per tile for a shape it serves, else 0. Per tile the
 // workspace holds a 256-byte head and, per receiving part, step parity and sending part, 512 hand-off words of 16 bytes.
 #ifndef FASTH_TEAM_TILE_MIN_COLS
 #define FASTH_TEAM_TILE_MIN_COLS 449        // d > 512: from here on it beats the per-column kernels' rounds (and chain_quad_kernel)
 #endif
+#ifndef FASTH_TEAM_TILE_MIN_COLS_LONG
+#define FASTH_TEAM_TILE_MIN_COLS_LONG 640   // d > 1024 (parts of 512 elements, steps of 32 rows)
+#endif
 #ifndef FASTH_TEAM_TILE_MIN_COLS_SHORT
 #define FASTH_TEAM_TILE_MIN_COLS_SHORT 897  // d <= 512 (two parts)
 #endif
 constexpr unsigned team_tile_words(int np) { return (unsigned)(kTeamHeadBytes + np * 2 * np * 512 * 16) / 4u; }
 static int team_tile_parts(int d, int n, int m, int k) {
-  if (m < (d > 512 ? FASTH_TEAM_TILE_MIN_COLS : FASTH_TEAM_TILE_MIN_COLS_SHORT) || d <= 256 || d > 1024 || d % 4 != 0) return 0;
-  if (!(k == 64 || k == 128 || (k == 32 && n % 64 == 0))) return 0;
+  if (m < (d > 1024 ? FASTH_TEAM_TILE_MIN_COLS_LONG : d > 512 ? FASTH_TEAM_TILE_MIN_COLS : FASTH_TEAM_TILE_MIN_COLS_SHORT) ||
+      d <= 256 || d > 2048 || d % 4 != 0) return 0;
+  // parts of 256 elements take 64 rows per step (blocks of 32 two at a time), parts of 512 (d > 1024) take 32
+  if (!(k == 64 || k == 128 || (k == 32 && (d > 1024 || n % 64 == 0)))) return 0;
   if (team_wide_parts(d, n, m, k) || team_parts(d, n, m, k)) return 0;
   if ((size_t)d * m * sizeof(float) >= 0x80000000u || (size_t)n * d * sizeof(float) >= 0x80000000u) return 0;  // 32-bit byte offsets
-  const int np = (d + 255) / 256;
-  return team_fits((m + 15) / 16, np) ? np : 0;
+  const int np = d > 1024 ? (d + 511) / 512 : (d + 255) / 256;
+  return np >= 2 && team_fits((m + 15) / 16, np) ? np : 0;
 }
 
 // The dV kernel has one workgroup per (64-column tile of dV, block). When that is too few to fill the chip and the
@@ -151,7 +156,7 @@ static Layout make_layout(int d, int n, int m, int k) {
   L.kp = padded_block(k);
   L.nb = n / k;
   const int team = team_parts(d, n, m, k), wide = team_wide_parts(d, n, m, k), ttile = team_tile_parts(d, n, m, k);
-  L.kf = wide ? 64 : (team || ttile) && k == 32 ? 64 : k;
+  L.kf = wide ? 64 : (team || (ttile && d <= 1024)) && k == 32 ? 64 : k;
   L.team_wide = wide;
   L.npair = wide ? n / kWideRows : 0;
   L.kpf = padded_block(L.kf);

@@ -102,8 +102,8 @@ WIDE = [
     (125, 128, 800, 64), (125, 256, 800, 128),  # odd d: per-column chain in rounds, dV with 4-byte fetches reading Z
     # more columns than compute units, fewer than the matrix-core kernel takes: 16-row steps, several workgroups per unit
     (1024, 64, 300, 32), (768, 128, 260, 64), (1024, 128, 780, 128), (1024, 32, 1024, 32), (516, 96, 770, 32),
-    # 449 .. 1024 columns at 512 < d <= 1024 (897 .. 2048 at 256 < d <= 512) with blocks of 32 (an even number), 64 or 128:
-    # tiles of 16 columns on the matrix cores, each shared by two to four workgroups; other block sizes from 769
+    # 449 .. 1024 columns at 512 < d <= 1024 (897 .. 2048 at 256 < d <= 512, 640 .. 1024 at 1024 < d <= 2048) with blocks of
+    # 32 (an even number where d <= 1024), 64 or 128: tiles of 16 columns on the matrix cores, each shared by two to four workgroups; other block sizes from 769
     # columns on (608 at d > 896): four columns per workgroup on the matrix cores;
     # one and several steps per block, ragged d and m, n != d; and neighbours that stay with the per-column kernels
     (1024, 64, 800, 32), (1000, 128, 771, 64), (640, 256, 1023, 128), (900, 64, 610, 32), (516, 64, 1024, 32),
@@ -112,6 +112,9 @@ WIDE = [
     # elements, one to four steps, two steps per block of 128, a ragged last tile
     (1024, 128, 449, 32), (1024, 256, 1024, 64), (512, 128, 2048, 32), (300, 64, 1000, 64), (512, 256, 897, 128),
     (1020, 192, 500, 64), (768, 64, 1280, 32), (600, 128, 999, 128), (1024, 64, 448, 32),
+    # columns of 1025 .. 2048 elements: parts of 512, steps of 32 rows (one, two and four per block), three and four
+    # parts, a last part of 4 elements, the fewest and the most columns
+    (2048, 64, 640, 32), (1536, 128, 1024, 64), (1028, 256, 700, 128), (2044, 96, 1000, 32), (1280, 64, 639, 64),
 ]
 
 
