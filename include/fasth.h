@@ -65,7 +65,9 @@ const char* fasth_strerror(int code);
  * units. With few columns of more than 512 elements (d <= 4096, a compute unit for every workgroup of the launch:
  * up to 128 columns at d <= 1024, 64 at d = 2048, 32 at d = 4096) two to eight workgroups share each column and hand each other
  * every step's partial inner products through the workspace (steps of 128 rows, two blocks of 64 joined, where d <= 2048,
- * n is a multiple of 128 and a workgroup per 256 elements fits; steps of 64 rows otherwise), and the workgroup that
+ * n is a multiple of 128 and a workgroup per 256 elements fits; steps of 64 rows otherwise; with some hundred columns
+ * (449 to 1024, up to 2048 at d <= 512) of 257 to 2048 elements two to four workgroups share each tile of 16 columns in
+ * the same way), and the workgroup that
  * adds the partial matrices of a block's factor waits for the workgroups that form them: one workgroup waits for
  * another inside a kernel. Every such wait is
  * bounded: after a number of polls (about a million, a fraction of a second; the wait itself takes a fraction of
