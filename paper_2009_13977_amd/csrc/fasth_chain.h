@@ -43,7 +43,7 @@ struct ChainArgs {
   int in_rows;            // rows of `in` that exist; rows in_rows..d-1 of the chain's input are zero
   int d, n, m, k, kp, nb;
   int transpose;
-  int sub;                // chain_pipe_kernel: steps per block (set by its launcher)
+  int sub;                // chain_pipe_kernel, chain_quad_kernel, chain_team_tile_kernel: steps per block (set by their launchers)
   // Optional side product of the SVD layers' backward pass, which has the chain's input as one operand:
   // ds_out[r] = s'(in_scale[r]) sum_l in[r][l] ds_z1[r][l] for r < ds_rows (s = diag_factor(in_scale_mode, .)).
   // Null ds_out: not wanted. Kernels that cannot take it along leave it to a launch of dsigma_kernel.

@@ -32,7 +32,7 @@ namespace fasth {
 // Each wave stages only its own 32 columns of the step's 64 rows in LDS (fetched into registers a step ahead,
 // written once its second product has read the old ones), so no barrier guards the rows. Three barriers per step:
 // the waves' shares of B meet in LDS (and go out to the other parts), the totals come back into LDS in the layout
-// the matrix cores want, and C goes from the four waves that form it to all eight.
+// the matrix cores want, and C goes from the waves that form it (each one half of the inner index of some rows) to all.
 // ------------------------------------------------------------------------------------------
 constexpr int kTtCols = 16;  // columns per team
 // NT accumulator tiles (16 NT elements) per wave: 128 NT elements per workgroup, 128 / NT rows per step; row stride of a
@@ -52,7 +52,7 @@ __global__ void __launch_bounds__(512) chain_team_tile_kernel(ChainArgs p) {
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int q = lane >> 4, i = lane & 15;
-  float* Vs = smem + (size_t)wave * K * LD;  // this wave's 32 columns of the step's rows: [64][LD]
+  float* Vs = smem + (size_t)wave * K * LD;  // this wave's 16 NT columns of the step's rows: [K][LD]
   float* Bp = smem + (size_t)8 * K * LD;     // the waves' shares of B: [8][E], element (row 16 rt + 4 q + jj, column i)
                                              // of a wave at ((rt * 64 + lane) * 4 + jj)
   float* Btot = Bp + 8 * 1024;               // B summed over waves and parts, [K][16]
