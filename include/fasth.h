@@ -79,7 +79,10 @@ const char* fasth_strerror(int code);
  * restores the default; 0 makes every wait give up at its first unsuccessful poll, which is how the error path is
  * tested without a kernel that hangs). The kernels assume what HIP provides on this hardware: the workgroups of
  * one launch are started in the order of their indices, and a launch of at most as many workgroups as the GPU
- * has compute units runs them all at once. Two calls that use the same workspace must not overlap on the GPU
+ * has compute units runs them all at once. That holds for calls on one stream; kernels of OTHER streams that run at
+ * the same time (this library's or anyone's) can take compute units that a team needs, and two such launches can
+ * hold each other's units while both wait: the waits then give up and fasth_wait_status says so. Run these shapes
+ * on one stream at a time. Two calls that use the same workspace must not overlap on the GPU
  * (this was already so for calls that save for a backward pass; for these shapes it also holds for fasth_apply
  * without saving). */
 int fasth_wait_status(void* stream);
