@@ -314,6 +314,19 @@ def test_shared_columns_in_the_layers():
     assert B.fasth_wait_status() == B.FASTH_OK
     assert_close(Y1.cpu().numpy(), orc.product_apply(p["V"], p["X"]), "H X")
     assert_close(Y2.cpu().numpy(), p["X"].astype(np.float64), "H^T H X")
+    for (d, n, m, k) in ((1000, 192, 470, 64), (2048, 96, 650, 32)):
+        _say(f"shared tiles of 16 columns: prepared factors d={d} m={m}")
+        p = synthetic.householder_problem(d, n, m, seed=6520 + d)
+        Vd, Xd = to_gpu(p["V"]), to_gpu(p["X"])
+        Y1 = torch.empty_like(Xd); Y2 = torch.empty_like(Xd)
+        ws = B.new_workspace(B.fasth_workspace_bytes(d, n, m, k))
+        B.fasth_prepare(Vd, m, ws, k)
+        for _ in range(2):
+            B.fasth_apply(Vd, Xd, Y1, ws, k)
+            B.fasth_apply(Vd, Y1, Y2, ws, k, transpose=True)
+        assert B.fasth_wait_status() == B.FASTH_OK
+        assert_close(Y1.cpu().numpy(), orc.product_apply(p["V"], p["X"]), "H X")
+        assert_close(Y2.cpu().numpy(), p["X"].astype(np.float64), "H^T H X")
     _say("shared columns, steps of 128 rows: prepared factors")
     d, n, m, k = 1536, 384, 20, 64
     p = synthetic.householder_problem(d, n, m, seed=6510)
