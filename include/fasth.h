@@ -123,8 +123,8 @@ int fasth_apply(const fasth_shape* shape, const float* V, const float* X, float*
  * the array's address. Shapes whose factors, partial Gram matrices and hand-off words need more than the array
  * holds (about 4 n kp (2 + min(16, ceil(d / 128))) bytes, kp = k rounded up to a power of two >= 16; for the
  * shapes of fasth_wait_status's comment kp = 64 whatever k, half as much again where a step takes 128 rows, and up
- * to 129 KiB more per column: 10 MiB at d = n = 2048, m = 64, 17.5 MiB at m = 32) return FASTH_EUNSUPPORTED before
- * any GPU call. Every call on one GPU uses the same array: calls that overlap
+ * to 129 KiB more per column: 10 MiB at d = n = 2048, m = 64, 17.5 MiB at m = 32; where that is too much the call
+ * does without those kernels and needs the first figure only) return FASTH_EUNSUPPORTED before any GPU call. Every call on one GPU uses the same array: calls that overlap
  * on one GPU (different streams or threads) race; calls on one stream do not. */
 #define FASTH_STATIC_SCRATCH_BYTES (24u << 20)
 int fasth_forward_static(const fasth_shape* shape, const float* V, const float* X, float* A, void* stream);

@@ -66,10 +66,10 @@ struct Product {  // one Householder product bound to its slice of a workspace
   float* saveCg() const { return reinterpret_cast<float*>(ws + L.off_saveCg); }
 };
 
-static Product bind(int d, int n, int m, int k, void* ws) {
+static Product bind(int d, int n, int m, int k, void* ws, bool shared = true) {
   Product P;
   P.d = d; P.n = n; P.m = m; P.k = k;
-  P.L = make_layout(d, n, m, k);
+  P.L = make_layout(d, n, m, k, shared);
   P.ws = static_cast<char*>(ws);
   return P;
 }
@@ -581,11 +581,18 @@ int fasth_forward_static(const fasth_shape* shape, const float* V, const float* 
   if (!V || !X || !A) return FASTH_EINVAL;
   if (!aligned16(V) || !aligned16(X) || !aligned16(A)) return FASTH_EALIGN;
   // only the regions Step 1 writes and Step 2 reads: nothing is saved for a backward pass
-  const Layout L = make_layout(shape->d, shape->n, shape->m, shape->k);
+  // (where the kernels in which workgroups share columns would need more room than the array has, the layout without
+  // them: no hand-off area and the caller's own block size, and the chain runs on the other kernels)
+  bool shared = true;
+  Layout L = make_layout(shape->d, shape->n, shape->m, shape->k, true);
+  if (L.off_saveA > FASTH_STATIC_SCRATCH_BYTES) {
+    shared = false;
+    L = make_layout(shape->d, shape->n, shape->m, shape->k, false);
+  }
   if (L.off_saveA > FASTH_STATIC_SCRATCH_BYTES) return FASTH_EUNSUPPORTED;
   void* ws = nullptr;
   if ((rc = static_scratch(&ws)) != FASTH_OK) return rc;
-  const Product P = bind(shape->d, shape->n, shape->m, shape->k, ws);
+  const Product P = bind(shape->d, shape->n, shape->m, shape->k, ws, shared);
   hipStream_t st = static_cast<hipStream_t>(stream);
   if ((rc = build_factors(P, V, st)) != FASTH_OK) return rc;
   return run_chain(P, V, X, A, shape->transpose, true, nullptr, 0, st, false);

@@ -151,11 +151,14 @@ static bool factor_is_fused(int kp, int d) { return kp <= 32 || (kp == 64 && d <
 #ifndef FASTH_GRAM_SPLIT_128
 #define FASTH_GRAM_SPLIT_128 8
 #endif
-static Layout make_layout(int d, int n, int m, int k) {
+// shared = false: the layout without any kernel in which workgroups share columns (no hand-off area, the caller's own
+// block size for the factors), for a caller whose room for factors is limited.
+static Layout make_layout(int d, int n, int m, int k, bool shared = true) {
   Layout L;
   L.kp = padded_block(k);
   L.nb = n / k;
-  const int team = team_parts(d, n, m, k), wide = team_wide_parts(d, n, m, k), ttile = team_tile_parts(d, n, m, k);
+  const int team = shared ? team_parts(d, n, m, k) : 0, wide = shared ? team_wide_parts(d, n, m, k) : 0;
+  const int ttile = shared ? team_tile_parts(d, n, m, k) : 0;
   L.kf = wide ? 64 : (team || (ttile && d <= 1024)) && k == 32 ? 64 : k;
   L.team_wide = wide;
   L.npair = wide ? n / kWideRows : 0;
@@ -180,7 +183,7 @@ static Layout make_layout(int d, int n, int m, int k) {
   L.xch_words = wide ? (size_t)m * team_wide_words_per_column(wide)
               : team ? (size_t)m * team_words_per_column(team)
               : ttile ? (size_t)((m + 15) / 16) * team_tile_words(ttile)
-              : split_pair_serves(d, m, k) ? (size_t)m * kSplitPairWords : 0;
+              : shared && split_pair_serves(d, m, k) ? (size_t)m * kSplitPairWords : 0;
   L.off_xch = take(L.xch_words);
   L.off_saveA = take((size_t)L.nb * m * d);
   L.off_saveCa = take((size_t)m * n);
