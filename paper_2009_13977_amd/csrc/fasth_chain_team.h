@@ -51,13 +51,13 @@ struct TeamRegs {
   Chunk<4> v[16];  // rows 4 jj + q of the step, this lane's chunk
 };
 
-// KMODE 0: caller's blocks of 32 rows, two per step (factors stored as 64 x 64 blocks); 1: blocks of 64; 2: blocks of
-// 128, two steps per block. The number of parts is p.parts.
+// KMODE 0: caller's blocks of 32 rows, two per step; 1: blocks of 64; 2: blocks of 128, two steps per block. The factors
+// are stored as 64 x 64 blocks in every case. The number of parts is p.parts.
 template <int KMODE>
 __global__ void __launch_bounds__(512) chain_team_kernel(ChainArgs p) {
   const int NP = p.parts;  // 2 .. 8: the parts' sums are added within a group of eight lanes
   constexpr int K = kTeamRows, KH = 16, NW = 8, LPT = 8, G = 8;
-  constexpr int LDT = KMODE == 2 ? 128 : 64;
+  constexpr int LDT = 64;  // the factors are stored as 64 x 64 blocks whatever the caller's block size
   // fetches of step s + 2 per lane: P1 during the first product, RL during the reduction, XA behind the hand-off,
   // XC next to the last barrier, the rest during the update
   constexpr int P1 = 4, RL = 4, XA = 3, XC = 2, PR2 = KH - P1 - RL - XA - XC;
@@ -108,8 +108,7 @@ __global__ void __launch_bounds__(512) chain_team_kernel(ChainArgs p) {
   float t[LPT];  // this thread's entries of its row of op(T) of the step being applied
   auto load_t = [&](int st) {
     const float* opT = p.transpose ? p.Tt : p.T;
-    const float* Ts = KMODE == 2 ? opT + (size_t)(st >> 1) * LDT * LDT + (size_t)(st & 1) * (K * LDT + K)
-                                 : opT + (size_t)st * LDT * LDT;
+    const float* Ts = opT + (size_t)st * LDT * LDT;
     const float4* src = reinterpret_cast<const float4*>(Ts + trow * LDT + LPT * tg);
     const float4 t0 = src[0], t1 = src[1];
     t[0] = t0.x; t[1] = t0.y; t[2] = t0.z; t[3] = t0.w; t[4] = t1.x; t[5] = t1.y; t[6] = t1.z; t[7] = t1.w;

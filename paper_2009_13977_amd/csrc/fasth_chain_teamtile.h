@@ -40,9 +40,10 @@ constexpr int kTtCols = 16;  // columns per team
 constexpr size_t kTtLdsFloats = (size_t)8 * 64 * 34 + 8 * 1024 + 1024 + 2 * 1024;
 static_assert(8 * 32 * 68 == 8 * 64 * 34, "the rows of a step take the same room in both forms");
 
-// NT = 2: parts of 256 elements, steps of 64 rows; p.sub = 0: the caller's blocks of 32 rows two per step (factors stored
-// as 64 x 64 blocks), else steps per block (1 or 2). NT = 4: parts of 512 elements, steps of 32 rows, p.sub = 1, 2 or 4
-// steps per block. LDT: rows of a stored factor. The number of parts is p.parts.
+// NT = 2: parts of 256 elements, steps of 64 rows; p.sub = 0: the caller's blocks of 32 rows two per step, else steps per
+// block (1 or 2). NT = 4: parts of 512 elements, steps of 32 rows, p.sub = 1, 2 or 4 steps per block. LDT = 128 / NT: rows
+// of a stored factor, those of a step whatever the caller's block size (the diagonal blocks of a larger block's factor
+// are the factors of its row groups, so only those are built). The number of parts is p.parts.
 template <int NT, int LDT>
 __global__ void __launch_bounds__(512) chain_team_tile_kernel(ChainArgs p) {
   const int NP = p.parts;  // 2 .. 4
@@ -156,8 +157,7 @@ __global__ void __launch_bounds__(512) chain_team_tile_kernel(ChainArgs p) {
   const int sub = p.sub;  // steps per block; 0: two blocks per step
   auto fetch_t = [&](int st, float (&t)[TN]) {
     const float* opT = p.transpose ? p.Tt : p.T;
-    const int blk = sub > 1 ? st / sub : st, prt = sub > 1 ? st % sub : 0;
-    const float* Ts = opT + (size_t)blk * LDT * LDT + (size_t)prt * (K * LDT + K);
+    const float* Ts = opT + (size_t)st * LDT * LDT;  // a stored factor has the rows of a step
     const float4* src = reinterpret_cast<const float4*>(Ts + (16 * crt + i) * LDT + (K / 2) * chalf + TN * q);
 #pragma unroll
     for (int g = 0; g < TN / 4; ++g) {
@@ -371,9 +371,8 @@ static int launch_chain_team_tile(const ChainArgs& args, hipStream_t stream) {
   a.parts = team_tile_parts(a.d, a.n, a.m, a.k);
   if (a.parts == 0 || !a.xch) return FASTH_EINVAL;
   const bool longer = a.d > 1024;  // parts of 512 elements, steps of 32 rows
-  // steps per block (0: two of the caller's blocks of 32 per step of 64 rows) and rows of a stored factor
+  // steps per block (0: two of the caller's blocks of 32 per step of 64 rows)
   a.sub = longer ? a.k / 32 : a.k == 32 ? 0 : a.k / 64;
-  const int ldt = longer ? a.k : a.k == 128 ? 128 : 64;
   const size_t lds = kTtLdsFloats * sizeof(float);
   const int side = a.ds_out ? (a.ds_rows + 7) / 8 : 0;
   const int tiles = (a.m + kTtCols - 1) / kTtCols;
@@ -388,14 +387,8 @@ static int launch_chain_team_tile(const ChainArgs& args, hipStream_t stream) {
     prof::Scope ps_(FASTH_KERNEL_CHAIN, stream, names_[a.parts - 2].c_str());                                        \
     hipLaunchKernelGGL((chain_team_tile_kernel<NT_, LDT_>), grid, block, lds, stream, a);                            \
   } while (0)
-  if (!longer) {
-    if (ldt == 64) FASTH_LAUNCH_TT(2, 64);
-    else FASTH_LAUNCH_TT(2, 128);
-  } else {
-    if (ldt == 32) FASTH_LAUNCH_TT(4, 32);
-    else if (ldt == 64) FASTH_LAUNCH_TT(4, 64);
-    else FASTH_LAUNCH_TT(4, 128);
-  }
+  if (!longer) FASTH_LAUNCH_TT(2, 64);
+  else FASTH_LAUNCH_TT(4, 32);
 #undef FASTH_LAUNCH_TT
   FASTH_HIP(hipGetLastError());
   return FASTH_OK;

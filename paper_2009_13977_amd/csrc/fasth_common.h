@@ -159,7 +159,10 @@ static Layout make_layout(int d, int n, int m, int k, bool shared = true) {
   L.nb = n / k;
   const int team = shared ? team_parts(d, n, m, k) : 0, wide = shared ? team_wide_parts(d, n, m, k) : 0;
   const int ttile = shared ? team_tile_parts(d, n, m, k) : 0;
-  L.kf = wide ? 64 : (team || (ttile && d <= 1024)) && k == 32 ? 64 : k;
+  // The kernels in which workgroups share columns take 64 rows (32: the shared tiles at d > 1024) of factor per step
+  // whatever the caller's block size: two blocks of 32 merged by Lemma 1, or the diagonal blocks of a larger block's
+  // factor, which are the factors of its row groups; so only those are built.
+  L.kf = wide || team ? 64 : ttile ? (d <= 1024 ? 64 : 32) : k;
   L.team_wide = wide;
   L.npair = wide ? n / kWideRows : 0;
   L.kpf = padded_block(L.kf);
